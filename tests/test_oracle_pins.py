@@ -1,0 +1,472 @@
+"""Pins of the CPU oracle against what the paper's equations and plain mathematics fix.
+
+None of these tests needs a GPU and none compares the oracle with itself: expected
+values are hand-worked from Eq. Q / Eq. D / Eq. + / Eq. BN, computed with exact
+Python integers and Fractions (tests/exact.py), by brute-force Python loops, or by an
+independent library routine (torch float64 convolution / pooling on the CPU).
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+from hypothesis import given, settings, strategies as st
+
+import oracle as orc
+from exact import clamp, fl32, fl64, round_half_even
+
+F = Fraction
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. Q: rounding is half-to-even, clamp bounds are -2^p and 2^p - 1
+# ----------------------------------------------------------------------------------------
+def test_Q_handworked_unit_factor():
+    # r/q with q = 1: ties go to the even neighbour; beyond 127 / -128 the clamp acts.
+    r = [0, .5, 1.5, 2.5, -.5, -1.5, -2.5, 3.7, -3.2, 126.5, 127.5, 128.5, 300, -127.5,
+         -128.5, -300]
+    want = [0, 0, 2, 2, 0, -2, -2, 4, -3, 126, 127, 127, 127, -128, -128, -128]
+    assert orc.Q(r, 1.0, 7).tolist() == want
+
+
+def test_Q_handworked_half_factor():
+    # q = 0.5 -> r/q = [.5, 1.5, 2.5, 3.5, -.5, -1.5, 126.5, 127.5, -128, -128.5]
+    r = [.25, .75, 1.25, 1.75, -.25, -.75, 63.25, 63.75, -64, -64.25]
+    want = [0, 2, 2, 4, 0, -2, 126, 127, -128, -128]
+    assert orc.Q(r, 0.5, 7).tolist() == want
+
+
+def test_Q_clamp_bounds_other_precisions():
+    assert orc.Q([255.5, 256, 300, -1, -255.5, -256.5, -400], 1.0, 8).tolist() == \
+        [255, 255, 255, -1, -256, -256, -256]
+    assert orc.Q([7.4, 8.0, -8.0, -9.0, 6.5, 5.5], 1.0, 3).tolist() == [7, 7, -8, -8, 6, 6]
+
+
+def test_Q31_bias_bounds_and_values():
+    # factor = q_x*q_w = 0.25: b/0.25 = [4, 2, -2 (tie 2.5 -> 2), ...]; +-3e9 saturate.
+    z = orc.Q31_bias([1.0, 0.5, -0.625, 0.625, 0.875], 0.5, 0.5)
+    assert z.tolist() == [4, 2, -2, 2, 4]
+    z = orc.Q31_bias([3e9, -3e9], 1.0, 1.0)
+    assert z.tolist() == [2147483647, -2147483648]
+
+
+def test_Q31_bias_matches_exact_rational_fp64():
+    rng = np.random.default_rng(5)
+    b = rng.normal(0, 0.1, 64).astype(np.float32)
+    q_x, q_w = np.float32(0.0137), np.float32(0.00091)
+    got = orc.Q31_bias(b, q_x, q_w)
+    q = fl64(F(float(q_x)) * F(float(q_w)))
+    want = [clamp(round_half_even(fl64(F(float(v)) / q)), -2**31, 2**31 - 1) for v in b]
+    assert got.tolist() == want
+
+
+def test_calibration_example():
+    # max|x| = 2.54, p = 7 -> q = 0.02; the largest element maps to -(2^p - 1)
+    x = np.array([0.1, -2.54, 1.0, 2.0], np.float32)
+    m = orc.maxabs(x)
+    assert m == np.float32(2.54)
+    q = orc.qfactor(m, 7)
+    assert q == np.float32(2.54) / np.float32(127)
+    assert orc.Q(x, q, 7).tolist() == [5, -127, 50, 100]
+    assert orc.qfactor(0.0, 7) == np.float32(1.0)       # all-zero tensor reading
+    assert orc.maxabs(np.zeros(0, np.float32)) == 0.0
+    assert orc.qfactor(255.0, 8) == np.float32(1.0)
+    assert orc.qfactor(np.float32(2**31 - 1), 31) == np.float32(1.0)
+
+
+def test_maxabs_invariants():
+    rng = np.random.default_rng(1)
+    x = rng.normal(size=4099).astype(np.float32)
+    m = orc.maxabs(x)
+    assert m == np.abs(x).max()
+    assert orc.maxabs(rng.permutation(x)) == m
+    assert orc.maxabs(-x) == m
+    parts = np.array_split(x, 7)
+    assert max(orc.maxabs(p) for p in parts) == m      # running max == max of concat
+    q = orc.qfactor(m, 7)
+    z = orc.Q(x, q, 7)
+    assert abs(int(z[np.argmax(np.abs(x))])) == 127 and np.abs(z.astype(int)).max() == 127
+
+
+@settings(max_examples=300, deadline=None)
+@given(st.floats(min_value=2.0**-20, max_value=2.0**20, width=32),
+       st.lists(st.floats(min_value=-1.0, max_value=1.0, width=32), min_size=1, max_size=32),
+       st.sampled_from([3, 7, 8]))
+def test_DQ_error_bound(q, us, p):
+    # Inside the representable range |D(Q(r)) - r| <= q/2, up to the fp32 rounding of r/q.
+    q = np.float32(q)
+    lim = float(q) * (2**p - 1)
+    r = (np.array(us, np.float32) * np.float32(lim)).astype(np.float32)
+    r = r[np.abs(r.astype(np.float64)) <= lim]
+    if r.size == 0:
+        return
+    z = orc.Q(r, q, p).astype(np.int64)
+    err = np.abs(float(q) * z.astype(np.float64) - r.astype(np.float64))
+    assert np.all(err <= float(q) * (0.5 + 2**p * 2.0**-23))
+    assert z.max() <= 2**p - 1 and z.min() >= -2**p
+
+
+def test_Q_matches_exact_rational():
+    rng = np.random.default_rng(11)
+    r = rng.normal(0, 3, 400).astype(np.float32)
+    q = np.float32(0.0371)
+    got = orc.Q(r, q, 7).tolist()
+    want = [clamp(round_half_even(fl32(F(float(v)) / F(float(q)))), -128, 127) for v in r]
+    assert got == want
+
+
+def test_QD_roundtrip_all_codes():
+    z = np.arange(-128, 128).astype(np.int8)
+    rng = np.random.default_rng(2)
+    for q in [1.0, 0.5, 0.02, 3.0] + list(rng.uniform(1e-3, 10, 20)):
+        r = orc.D(z, q)
+        assert r.dtype == np.float32
+        assert np.array_equal(r, np.float32(q) * z.astype(np.float32))
+        assert np.array_equal(orc.Q(r, q, 7), z)
+
+
+def test_D_handworked():
+    assert orc.D(np.array([-128, -1, 0, 3, 127], np.int8), 0.25).tolist() == \
+        [-32.0, -0.25, 0.0, 0.75, 31.75]
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. +  (literal) and the fused epilogue
+# ----------------------------------------------------------------------------------------
+def test_plus_handworked():
+    # q = max(.5, .25) = .5; D-sum = [6, -1, 95.25, .75]; /.5 = [12, -2, 190.5, 1.5]
+    z, q = orc.plus([10, -3, 127, 1], 0.5, [4, 2, 127, 1], 0.25)
+    assert q == np.float32(0.5)
+    assert z.tolist() == [12, -2, 127, 2]
+    # adding the zero tensor at a smaller-or-equal factor leaves z unchanged
+    a = np.arange(-128, 128).astype(np.int8)
+    z, q = orc.plus(a, 0.75, np.zeros_like(a), 0.3)
+    assert q == np.float32(0.75) and np.array_equal(z, a.astype(np.int32))
+    # commutative
+    rng = np.random.default_rng(3)
+    b = rng.integers(-128, 128, 256).astype(np.int8)
+    z1, _ = orc.plus(a, 0.11, b, 0.07)
+    z2, _ = orc.plus(b, 0.07, a, 0.11)
+    assert np.array_equal(z1, z2)
+
+
+def test_requant_handworked():
+    acc = np.array([5, 7, -5, -7, 6, 1000, -1000, 3], np.int32).reshape(1, 8)
+    # x 0.5 -> [2.5, 3.5, -2.5, -3.5, 3, 500, -500, 1.5]: ties to even, saturation
+    assert orc.requant(acc, 0.5, relu=False).ravel().tolist() == \
+        [2, 4, -2, -4, 3, 127, -128, 2]
+    assert orc.requant(acc, 0.5, relu=True).ravel().tolist() == [2, 4, 0, 0, 3, 127, 0, 2]
+
+
+def test_requant_int32_to_fp32_conversion_is_rne():
+    # 2^24+1 is not an fp32 value: ties-to-even gives 2^24; 2^24+3 -> 2^24+4.
+    acc = np.array([16777217, 16777219, -16777217, -16777219], np.int32).reshape(1, 4)
+    m = np.float32(2.0**-18)
+    got = orc.requant(acc, m, relu=False).ravel().tolist()
+    want = [round_half_even(F(v) * F(2)**-18) for v in (16777216, 16777220, -16777216, -16777220)]
+    assert got == want == [64, 64, -64, -64]
+    # a case where the conversion changes the final code: (2^24+2^0)*2^-17 region
+    acc = np.array([2**25 + 2, 2**25 + 6], np.int32).reshape(1, 2)   # -> 2^25, 2^25+8
+    m = np.float32(2.0**-3)            # exact scaling, clamp hides value -> use windowed test below
+    assert orc.requant(acc, m, relu=False).ravel().tolist() == [127, 127]
+
+
+def _requant_exact(acc, m, relu, z_res=None, m_r=None):
+    t = fl32(F(int(acc)))
+    t = fl32(t * F(float(m)))
+    if z_res is not None:
+        u = fl32(F(int(z_res)) * F(float(m_r)))
+        t = fl32(t + u)
+    if relu and t < 0:
+        t = F(0)
+    t = clamp(t, F(-128), F(127))
+    return round_half_even(t)
+
+
+def test_requant_sweep_against_exact_rational():
+    rng = np.random.default_rng(7)
+    for m in [np.float32(0.0123), np.float32(1 / 3), np.float32(2.5e-6), np.float32(0.5)]:
+        centre = int(60 / float(m))
+        lo = max(centre - 300, -2**31)
+        hi = min(centre + 300, 2**31 - 1)
+        accs = np.concatenate([np.arange(lo, hi), -np.arange(lo, hi),
+                               rng.integers(-2**31, 2**31 - 1, 200)]).astype(np.int32)
+        for relu in (False, True):
+            got = orc.requant(accs.reshape(-1, 1), m, relu).ravel().tolist()
+            want = [_requant_exact(a, m, relu) for a in accs]
+            assert got == want
+
+
+def test_requant_residual_against_exact_rational():
+    rng = np.random.default_rng(8)
+    acc = rng.integers(-40000, 40000, size=(50, 8)).astype(np.int32)
+    res = rng.integers(-128, 128, size=(50, 8)).astype(np.int8)
+    m, m_r = np.float32(0.00231), np.float32(0.6180339)
+    for relu in (False, True):
+        got = orc.requant(acc, m, relu, res, m_r)
+        want = [[_requant_exact(acc[i, k], m, relu, res[i, k], m_r) for k in range(8)]
+                for i in range(50)]
+        assert got.tolist() == want
+
+
+def test_requant_scales_are_two_fp32_ops():
+    q_x, q_w, q_o = np.float32(0.0173), np.float32(0.00219), np.float32(0.0411)
+    want = fl32(fl32(F(float(q_x)) * F(float(q_w))) / F(float(q_o)))
+    assert F(float(orc.requant_scale(q_x, q_w, q_o))) == want
+    want = fl32(F(float(q_x)) / F(float(q_o)))
+    assert F(float(orc.residual_scale(q_x, q_o))) == want
+
+
+def test_requant_channel_slice_addressing():
+    rng = np.random.default_rng(9)
+    acc = rng.integers(-3000, 3000, size=(6, 5)).astype(np.int32)
+    res_wide = rng.integers(-128, 128, size=(6, 16)).astype(np.int8)
+    out = np.full((6, 12), 99, np.int8)
+    orc.requant(acc, 0.05, True, res_wide, 0.5, res_c_stride=16, res_c_off=3, out=out,
+                out_c_stride=12, out_c_off=4)
+    dense = orc.requant(acc, 0.05, True, np.ascontiguousarray(res_wide[:, 3:8]), 0.5)
+    assert np.array_equal(out[:, 4:9], dense)
+    assert np.all(out[:, :4] == 99) and np.all(out[:, 9:] == 99)
+
+
+def test_fused_sum_vs_literal_two_step_differs_by_at_most_one():
+    # Fused: one rounding of (acc*m + res*m_r).  Literal: round the conv to int8 at q1,
+    # then apply Eq. + at max(q1, q2).  The arguments of the final Round differ by <= 1/2.
+    rng = np.random.default_rng(10)
+    acc = rng.integers(-60000, 60000, size=(400, 4)).astype(np.int32)
+    res = rng.integers(-128, 128, size=(400, 4)).astype(np.int8)
+    q_x, q_w = np.float32(0.02), np.float32(0.003)
+    for q1, q2 in [(0.9, 0.7), (0.5, 1.1)]:
+        q1, q2 = np.float32(q1), np.float32(q2)
+        q_out = max(q1, q2)
+        fused = orc.requant(acc, orc.requant_scale(q_x, q_w, q_out), False, res,
+                            orc.residual_scale(q2, q_out)).astype(int)
+        z1 = orc.requant(acc, orc.requant_scale(q_x, q_w, q1), False)
+        lit, q = orc.plus(z1, q1, res, q2)
+        assert q == q_out
+        assert np.abs(fused - lit).max() <= 1
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. BN
+# ----------------------------------------------------------------------------------------
+def test_fold_bn_closed_form_and_identity():
+    W = np.arange(24, dtype=np.float32).reshape(2, 2, 2, 3) - 7
+    b = np.array([1.0, -2.0], np.float32)
+    gamma = np.array([3.0, -1.0], np.float32)
+    beta = np.array([0.5, 0.25], np.float32)
+    mu = np.array([0.5, 1.0], np.float32)
+    var = np.array([4.0, 4.0], np.float32)
+    Wf, bf = orc.fold_bn(W, b, gamma, beta, mu, var, eps=0.0)   # s = gamma / 2
+    assert np.array_equal(Wf[0], 1.5 * W[0]) and np.array_equal(Wf[1], -0.5 * W[1])
+    assert bf.tolist() == [1.5 * 0.5 + 0.5, -0.5 * -3.0 + 0.25]
+    Wi, bi = orc.fold_bn(W, b, np.ones(2), np.zeros(2), np.zeros(2), np.ones(2), eps=0.0)
+    assert np.array_equal(Wi, W) and np.array_equal(bi, b)
+    Wn, bn = orc.fold_bn(W, None, gamma, beta, mu, var, eps=0.0)  # missing bias == zero bias
+    W0, b0 = orc.fold_bn(W, np.zeros(2), gamma, beta, mu, var, eps=0.0)
+    assert np.array_equal(Wn, W0) and np.array_equal(bn, b0)
+
+
+def test_fold_bn_equals_conv_then_bn_fp64():
+    rng = np.random.default_rng(12)
+    N, H, Wd, Cc, K, R, S = 2, 6, 5, 3, 4, 3, 3
+    x = rng.normal(size=(N, H, Wd, Cc))
+    W = rng.normal(size=(K, R, S, Cc)).astype(np.float32)
+    b = rng.normal(size=K).astype(np.float32)
+    gamma = rng.uniform(.5, 1.5, K).astype(np.float32)
+    beta = rng.normal(0, .1, K).astype(np.float32)
+    mu = rng.normal(0, .1, K).astype(np.float32)
+    var = rng.uniform(.5, 1.5, K).astype(np.float32)
+    eps = 1e-5
+    Wf, bf = orc.fold_bn(W, b, gamma, beta, mu, var, eps)
+
+    def conv64(w, bias):
+        xt = torch.from_numpy(x).permute(0, 3, 1, 2)
+        wt = torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2)
+        return torch.nn.functional.conv2d(xt, wt, torch.from_numpy(bias.astype(np.float64)),
+                                          padding=1).permute(0, 2, 3, 1).numpy()
+    y = conv64(W, b)
+    bn = gamma.astype(np.float64) * (y - mu) / np.sqrt(var.astype(np.float64) + eps) + beta
+    folded = conv64(Wf, bf)
+    assert np.allclose(folded, bn, rtol=1e-5, atol=1e-5)
+    # a wrong sign on mu or a dropped beta must fail the line above: check the margin
+    assert not np.allclose(conv64(Wf, bf - beta), bn, rtol=1e-5, atol=1e-5)
+
+
+# ----------------------------------------------------------------------------------------
+# x rule: the integer convolution
+# ----------------------------------------------------------------------------------------
+def _brute_conv(g, x, w, b):
+    ics = g.in_c_stride or g.C
+    x = x.reshape(g.N, g.H, g.W, ics)
+    w = w.reshape(g.K, g.R, g.S, g.C)
+    Ho = (g.H + 2 * g.pad_h - g.dil_h * (g.R - 1) - 1) // g.stride_h + 1
+    Wo = (g.W + 2 * g.pad_w - g.dil_w * (g.S - 1) - 1) // g.stride_w + 1
+    out = [[[[0] * g.K for _ in range(Wo)] for _ in range(Ho)] for _ in range(g.N)]
+    for n in range(g.N):
+        for ho in range(Ho):
+            for wo in range(Wo):
+                for k in range(g.K):
+                    a = int(b[k]) if b is not None else 0
+                    for r in range(g.R):
+                        for s in range(g.S):
+                            hi = ho * g.stride_h - g.pad_h + r * g.dil_h
+                            wi = wo * g.stride_w - g.pad_w + s * g.dil_w
+                            if 0 <= hi < g.H and 0 <= wi < g.W:
+                                for c in range(g.C):
+                                    a += int(x[n, hi, wi, c]) * int(w[k, r, s, c])
+                    out[n][ho][wo][k] = a
+    return np.array(out, np.int64).reshape(g.N, Ho, Wo, g.K)
+
+
+def test_conv_toy_handworked():
+    # 3x3 single-channel image 1..9, 2x2 filter [[1,0],[0,-1]], no padding:
+    # every output is x[i,j] - x[i+1,j+1] = -4.
+    g = orc.ConvGeom(N=1, H=3, W=3, C=1, K=1, R=2, S=2)
+    x = np.arange(1, 10, dtype=np.int8)
+    w = np.array([1, 0, 0, -1], np.int8)
+    assert orc.conv_i8(g, x, w).ravel().tolist() == [-4, -4, -4, -4]
+    # with bias 10 and padding 1 the corner output sees only the -1 tap on x[0,0]
+    g = orc.ConvGeom(N=1, H=3, W=3, C=1, K=1, R=2, S=2, pad_h=1, pad_w=1)
+    acc = orc.conv_i8(g, x, w, np.array([10], np.int32))
+    assert acc.shape == (1, 4, 4, 1)
+    assert acc[0, 0, 0, 0] == 10 - 1 and acc[0, 3, 3, 0] == 10 + 9
+    assert acc[0, 1, 1, 0] == 10 + 1 - 5
+
+
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=5, W=4, C=3, K=2, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=1, H=7, W=6, C=2, K=3, R=3, S=2, stride_h=2, stride_w=1, pad_h=0, pad_w=1),
+    dict(N=1, H=9, W=9, C=1, K=2, R=3, S=3, dil_h=2, dil_w=3, pad_h=2, pad_w=3),
+    dict(N=2, H=4, W=4, C=4, K=4, R=1, S=1, stride_h=2, stride_w=2),
+    dict(N=1, H=5, W=8, C=2, K=1, R=1, S=7, pad_w=3),
+    dict(N=1, H=8, W=5, C=2, K=1, R=7, S=1, pad_h=3),
+    dict(N=1, H=6, W=6, C=3, K=2, R=3, S=3, pad_h=1, pad_w=1, in_c_stride=5),
+])
+def test_conv_brute_force_toys(geom):
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(hash(tuple(geom.items())) % 2**32)
+    ics = g.in_c_stride or g.C
+    x = rng.integers(-128, 128, g.N * g.H * g.W * ics).astype(np.int8)
+    w = rng.integers(-128, 128, g.K * g.R * g.S * g.C).astype(np.int8)
+    b = rng.integers(-10**6, 10**6, g.K).astype(np.int32)
+    assert np.array_equal(orc.conv_i8(g, x, w, b), _brute_conv(g, x, w, b))
+    assert np.array_equal(orc.conv_i8(g, x, w, None), _brute_conv(g, x, w, None))
+
+
+def _torch_conv_int(g, x, w, b):
+    xt = torch.from_numpy(x.reshape(g.N, g.H, g.W, g.C).astype(np.float64)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(w.reshape(g.K, g.R, g.S, g.C).astype(np.float64)).permute(0, 3, 1, 2)
+    bt = None if b is None else torch.from_numpy(b.astype(np.float64))
+    y = torch.nn.functional.conv2d(xt, wt, bt, stride=(g.stride_h, g.stride_w),
+                                   padding=(g.pad_h, g.pad_w), dilation=(g.dil_h, g.dil_w))
+    return y.permute(0, 2, 3, 1).numpy().astype(np.int64)
+
+
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=14, W=14, C=32, K=24, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=1, H=17, W=17, C=16, K=20, R=1, S=7, pad_w=3),
+    dict(N=1, H=17, W=17, C=16, K=20, R=7, S=1, pad_h=3),
+    dict(N=1, H=23, W=23, C=3, K=8, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
+    dict(N=1, H=19, W=19, C=8, K=8, R=3, S=3, dil_h=6, dil_w=6, pad_h=6, pad_w=6),
+    dict(N=2, H=10, W=10, C=48, K=64, R=5, S=5, pad_h=2, pad_w=2),
+    dict(N=1, H=35, W=35, C=16, K=12, R=3, S=3, stride_h=2, stride_w=2),
+    dict(N=3, H=8, W=8, C=64, K=16, R=1, S=1, stride_h=2, stride_w=2),
+])
+def test_conv_against_float64_library_convolution(geom):
+    # sums stay far below 2^53, so the float64 library convolution is exact
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(42)
+    x = rng.integers(-128, 128, g.N * g.H * g.W * g.C).astype(np.int8)
+    w = rng.integers(-128, 128, g.K * g.R * g.S * g.C).astype(np.int8)
+    b = rng.integers(-10**5, 10**5, g.K).astype(np.int32)
+    acc = orc.conv_i8(g, x, w, b)
+    ref = _torch_conv_int(g, x, w, b)
+    assert acc.shape == ref.shape
+    assert np.array_equal(acc, ref)
+
+
+def test_conv_1x1_is_matrix_product_and_padding_channels_is_neutral():
+    rng = np.random.default_rng(13)
+    g = orc.ConvGeom(N=2, H=5, W=5, C=24, K=10, R=1, S=1)
+    x = rng.integers(-128, 128, (50, 24)).astype(np.int8)
+    w = rng.integers(-128, 128, (10, 24)).astype(np.int8)
+    acc = orc.conv_i8(g, x, w)
+    assert np.array_equal(acc.reshape(50, 10), x.astype(np.int64) @ w.astype(np.int64).T)
+    # zero-padding the channel axis (C -> C+8) leaves the result unchanged
+    xp = np.concatenate([x, np.zeros((50, 8), np.int8)], 1)
+    wp = np.concatenate([w, rng.integers(-128, 128, (10, 8)).astype(np.int8)], 1)
+    g2 = orc.ConvGeom(N=2, H=5, W=5, C=32, K=10, R=1, S=1)
+    assert np.array_equal(orc.conv_i8(g2, xp, wp), acc)
+
+
+def test_conv_overflow_is_reported():
+    g = orc.ConvGeom(N=1, H=1, W=1, C=4, K=1, R=1, S=1)
+    x = np.full(4, 127, np.int8)
+    w = np.full(4, 127, np.int8)
+    with pytest.raises(OverflowError):
+        orc.conv_i8(g, x, w, np.array([2**31 - 1], np.int32))
+
+
+def test_output_extent_formula():
+    assert (orc.ConvGeom(1, 224, 224, 3, 1, 7, 7, 2, 2, 3, 3).Ho) == 112
+    assert (orc.ConvGeom(1, 19, 19, 8, 1, 3, 3, 1, 1, 6, 6, 6, 6).Ho) == 19
+    assert (orc.ConvGeom(1, 35, 35, 8, 1, 3, 3, 2, 2).Wo) == 17
+    assert (orc.ConvGeom(1, 3, 3, 8, 1, 3, 3).Wo) == 1
+    assert (orc.ConvGeom(1, 2, 2, 8, 1, 3, 3).Wo) == 0
+
+
+# ----------------------------------------------------------------------------------------
+# Whole layer, Eq. A' + fused sum, with power-of-two factors: every fp32 step is exact,
+# so the result equals the exact-rational value of the paper's formula.
+# ----------------------------------------------------------------------------------------
+def test_layer_exact_with_power_of_two_factors():
+    rng = np.random.default_rng(14)
+    g = orc.ConvGeom(N=1, H=6, W=6, C=8, K=5, R=3, S=3, pad_h=1, pad_w=1)
+    z_x = rng.integers(-128, 128, (1, 6, 6, 8)).astype(np.int8)
+    z_w = rng.integers(-128, 128, (5, 3, 3, 8)).astype(np.int8)
+    z_b = rng.integers(-5000, 5000, 5).astype(np.int32)
+    z_r = rng.integers(-128, 128, (1, 6, 6, 5)).astype(np.int8)
+    q_x, q_w, q_r, q_o = 2.0**-5, 2.0**-9, 2.0**-3, 2.0**-2
+    z_y, acc = orc.conv_layer_i8(g, z_x, q_x, z_w, q_w, z_b, q_o, True, z_r, q_r)
+    ref_acc = _brute_conv(g, z_x, z_w, z_b)
+    assert np.array_equal(acc, ref_acc)
+    want = np.empty_like(z_y)
+    for idx in np.ndindex(*ref_acc.shape):
+        real = F(q_x) * F(q_w) * int(ref_acc[idx]) + F(q_r) * int(z_r[idx])
+        real = max(real, F(0))
+        want[idx] = clamp(round_half_even(real / F(q_o)), -128, 127)
+    assert np.array_equal(z_y, want)
+    assert len(np.unique(z_y)) > 20          # the case is not degenerate (all saturated)
+
+
+# ----------------------------------------------------------------------------------------
+# helpers that only chain shapes
+# ----------------------------------------------------------------------------------------
+def test_conv_f32_against_float64_library():
+    rng = np.random.default_rng(15)
+    g = orc.ConvGeom(N=2, H=9, W=8, C=5, K=6, R=3, S=3, stride_h=2, stride_w=1, pad_h=1, pad_w=1)
+    x = rng.normal(size=(2, 9, 8, 5)).astype(np.float32)
+    w = rng.normal(size=(6, 3, 3, 5)).astype(np.float32)
+    b = rng.normal(size=6).astype(np.float32)
+    y = orc.conv_f32(g, x, w, b, None, relu=True)
+    xt = torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2)
+    ref = torch.nn.functional.conv2d(xt, wt, torch.from_numpy(b.astype(np.float64)),
+                                     stride=(2, 1), padding=1).clamp_min(0)
+    ref = ref.permute(0, 2, 3, 1).numpy()
+    assert np.allclose(y, ref, rtol=1e-6, atol=1e-6)
+    res = rng.normal(size=y.shape).astype(np.float32)
+    y2 = orc.conv_f32(g, x, w, b, res, relu=False)
+    ref2 = torch.nn.functional.conv2d(xt, wt, torch.from_numpy(b.astype(np.float64)),
+                                      stride=(2, 1), padding=1).permute(0, 2, 3, 1).numpy() + res
+    assert np.allclose(y2, ref2, rtol=1e-6, atol=1e-6)
+
+
+def test_maxpool_against_library():
+    rng = np.random.default_rng(16)
+    x = rng.integers(-128, 128, (2, 11, 11, 6)).astype(np.int8)
+    y = orc.maxpool_i8(x, 3, 3, 2, 1, 6, 6)
+    ref = torch.nn.functional.max_pool2d(
+        torch.from_numpy(x.astype(np.float32)).permute(0, 3, 1, 2), 3, 2, 1)
+    assert np.array_equal(y, ref.permute(0, 2, 3, 1).numpy().astype(np.int8))
