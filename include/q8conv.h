@@ -1,0 +1,147 @@
+/*
+ * q8conv -- int8 quantised convolution for MI355X (gfx950), C ABI.
+ *
+ * The calls follow the statement of 8-bit inference in arxiv 1805.08691
+ * ("8-bit Low Precision Inference" and "Model Optimization" sections):
+ *   Eq. Q   z = max(min(Round(r/q), 2^p-1), -2^p), Round = round-half-to-even
+ *   Eq. D   r' = q z
+ *   Eq. x   (z1 x z2, q1 q2): integer contraction, the factor is the product
+ *   Eq. +   Q_p(D(z1) + D(z2), max(q1, q2))
+ *   Eq. A'  y_q = Q(ReLU(D(Q(W) x z + Q_31(b)))) -- the quantised layer
+ *   Eq. BN  w' = gamma/sqrt(var+eps) w,  b' = gamma/sqrt(var+eps) (b - mu) + beta
+ *   calibration: q = max|tensor| / (2^p - 1), one factor per tensor.
+ *
+ * Conventions common to every call
+ *   - Every pointer named *_dev, z_*, residual, acc_dump, packed is DEVICE memory
+ *     owned by the caller.  The library never allocates, frees or keeps pointers,
+ *     and holds no state between calls, so calls on different streams are
+ *     independent.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on that stream and return at once.
+ *   - Descriptors (q8_conv_desc) are HOST memory and are read before return.
+ *   - Activations are NHWC, weights KRSC (K output channels, R x S taps, C input
+ *     channels), both dense unless a *_c_stride says otherwise.
+ *   - Return value: Q8_OK (0) or a negative Q8_E* code; q8_strerror names it.
+ *     All argument checks run on the host before anything is launched, so a
+ *     rejected call has touched no device memory.
+ *   - Floating point is IEEE binary32 round-to-nearest-even with no fused
+ *     multiply-add; the int8 results are therefore a pure function of the inputs.
+ */
+#ifndef Q8CONV_H
+#define Q8CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  Q8_OK = 0,
+  Q8_EINVAL = -1,       /* null pointer, negative size, q <= 0 or not finite, bad p   */
+  Q8_EUNSUPPORTED = -2, /* a shape the kernels cannot take (see q8_conv_int8)         */
+  Q8_EALIGN = -3,       /* pointer or channel-stride alignment (see each call)        */
+  Q8_EHIP = -4          /* the HIP runtime refused a launch                            */
+};
+
+const char *q8_strerror(int code);
+
+/* Geometry of one convolution layer and of the tensors it touches. */
+typedef struct q8_conv_desc {
+  int32_t N, H, W, C;     /* input: batch, height, width, channels                   */
+  int32_t K, R, S;        /* output channels, filter height, filter width            */
+  int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+  int32_t relu;           /* 0/1: max(.,0) after the residual sum, before Round      */
+  int32_t in_c_stride;    /* elements between pixels of z_x   (>= C; 0 means C)      */
+  int32_t out_c_stride;   /* elements between pixels of z_y   (>= K; 0 means K)      */
+  int32_t out_c_off;      /* first channel written inside a wider (concat) tensor    */
+  int32_t res_c_stride;   /* same two for the residual tensor (0 means K)            */
+  int32_t res_c_off;
+} q8_conv_desc;
+
+/* Output extent floor((in + 2 pad - dil (k-1) - 1) / stride) + 1, 0 if negative. */
+int q8_conv_out_h(const q8_conv_desc *d);
+int q8_conv_out_w(const q8_conv_desc *d);
+
+/* Calibration (text after Eq. +/x): *maxabs_dev = max(*maxabs_dev, max_i |x_i|).
+ * The caller zeroes *maxabs_dev once; calling it for every calibration batch leaves
+ * the running maximum.  NaNs are ignored.  n may be 0.  x_dev 4-byte aligned.      */
+int q8_calibrate_maxabs(const float *x_dev, size_t n, float *maxabs_dev, void *stream);
+
+/* Host helper: q = maxabs / (2^p - 1) in fp32; an all-zero tensor gets q = 1.      */
+float q8_qfactor(float maxabs, int p);
+
+/* Eq. Q for 1 <= p <= 7: n fp32 values -> n int8 codes.  True fp32 division.       */
+int q8_quantize(const float *r_dev, size_t n, float q, int p, int8_t *z_dev,
+                void *stream);
+
+/* Eq. Q on an NHWC tensor whose channel count grows from C to C_pad (zeros in the
+ * added channels): npix*C fp32 -> npix*C_pad int8.  Used for the 3-channel image.  */
+int q8_quantize_pad_channels(const float *r_dev, size_t npix, int C, int C_pad,
+                             float q, int p, int8_t *z_dev, void *stream);
+
+/* Eq. Q with p = 31 for the bias of Eq. A': z_b = clamp(Round(b / (q_x q_w))), the
+ * factor being that of the accumulator (Eq. x).  Evaluated in fp64.               */
+int q8_quantize_bias(const float *b_dev, size_t n, float q_x, float q_w,
+                     int32_t *z_b_dev, void *stream);
+
+/* Eq. D: n int8 codes -> n fp32 values q*z.                                        */
+int q8_dequantize(const int8_t *z_dev, size_t n, float q, float *r_dev, void *stream);
+
+/* Eq. BN.  W_dev is [K][RSC]; b_dev may be NULL (zero bias); var is the variance.
+ * W_out_dev may alias W_dev.  Op order: s = gamma / sqrt(var + eps); w' = s*w;
+ * b' = (s * (b - mu)) + beta.                                                      */
+int q8_fold_bn(const float *W_dev, const float *b_dev, const float *gamma_dev,
+               const float *beta_dev, const float *mu_dev, const float *var_dev,
+               float eps, int K, int RSC, float *W_out_dev, float *b_out_dev,
+               void *stream);
+
+/* Filter pre-pack.  q8_conv_int8 reads its filters in a layout private to the
+ * library; q8_pack_weights converts dense KRSC int8 into it (d->C, K, R, S are
+ * used).  q8_packed_weight_bytes gives the size of `packed_dev` (16-byte aligned). */
+size_t q8_packed_weight_bytes(const q8_conv_desc *d);
+int q8_pack_weights(const q8_conv_desc *d, const int8_t *z_w_krsc_dev, void *packed_dev,
+                    void *stream);
+
+/* Eq. A' with the fused element-wise sum of the "Model Optimization" section:
+ *   acc[n,ho,wo,k] = bias_i32[k] + sum_{r,s,c} z_x[n,hi,wi,c] * z_w[k,r,s,c]
+ *                    (hi = ho*stride_h - pad_h + r*dil_h, zero outside the image)
+ *   t = fp32(acc) * m                         m   = (q_x * q_w) / q_out
+ *   t = t + fp32(residual) * m_r              m_r = q_res / q_out  (if residual)
+ *   t = max(t, 0)                             (if d->relu)
+ *   z_y = int8(Round(clamp(t, -128, 127)))
+ * The caller passes q_out = max(q1, q_res) for a fused sum (Eq. +).
+ *   z_x        int8 [N][H][W][in_c_stride]; in_c_stride % 4 == 0, 4-byte aligned;
+ *              d->C must match the C the filters were packed with.  C % 16 == 0 and
+ *              in_c_stride % 16 == 0 with a 16-byte aligned pointer take the fast
+ *              path; C == 4 (a padded 3-channel image) is supported for any R, S.
+ *   bias_i32   [K] or NULL.
+ *   residual   int8 [N][Ho][Wo][res_c_stride] or NULL.
+ *   z_y        int8 [N][Ho][Wo][out_c_stride], written at channel out_c_off.
+ *   acc_dump   NULL, or dense int32 [N][Ho][Wo][K] that receives acc (tests).
+ * Accumulation wraps modulo 2^32 (cannot happen below R*S*C = 130 000).           */
+int q8_conv_int8(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
+                 const int32_t *bias_i32, float q_x, float q_w, float q_out,
+                 const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
+                 void *stream);
+
+/* ---- helpers that only chain layers; not part of the paper's method ------------ */
+
+/* fp32 NHWC convolution + bias (+ dense residual) (+ ReLU), used to produce the
+ * real-valued activations that calibration measures.  Dense tensors, weights KRSC. */
+int q8_conv_f32_ref(const q8_conv_desc *d, const float *x_dev, const float *w_dev,
+                    const float *b_dev, const float *res_dev, float *y_dev,
+                    void *stream);
+
+/* int8 max-pool over an R x S window; taps outside the image are ignored.         */
+int q8_maxpool_i8(const int8_t *x_dev, int N, int H, int W, int C, int R, int S,
+                  int stride, int pad, int Ho, int Wo, int8_t *y_dev, void *stream);
+/* The same on fp32 (calibration forward).                                          */
+int q8_maxpool_f32(const float *x_dev, int N, int H, int W, int C, int R, int S,
+                   int stride, int pad, int Ho, int Wo, float *y_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* Q8CONV_H */

@@ -1,0 +1,144 @@
+"""Oracle-side network evaluation (TEST INFRASTRUCTURE): chains the oracle's layer
+functions over a layer list, with its own calibration.  Shares no code with the GPU
+engine; it only reads the same graph description objects (duck-typed: ``ops`` with
+``kind``, ``src``, ``dst``, ... and ``tensors``).
+
+Calibration (text after Eq. +/x): every activation factor is max|tensor| / (2^p - 1) with
+p = 7, the maximum taken over all calibration batches of an fp32 forward of the folded
+network.  For a conv with a fused sum, the + rule sets q_out = max(q1, q_res) where q1 is
+the factor of the branch's own pre-sum output.
+"""
+import numpy as np
+import torch
+
+from . import (ConvGeom, Q, Q31_bias, conv_f32, conv_i8, fold_bn, maxabs, maxpool_i8, qfactor,
+               requant, requant_scale, residual_scale)
+
+P_ACT = 7
+P_W = 7
+
+
+def geom(op, tensors, N):
+    s = tensors[op.src]
+    return ConvGeom(N=N, H=s.H, W=s.W, C=op.C, K=op.K, R=op.R, S=op.S, stride_h=op.stride,
+                    stride_w=op.stride, pad_h=op.pad_h, pad_w=op.pad_w, dil_h=op.dil,
+                    dil_w=op.dil)
+
+
+def fold_all(net, params):
+    """Eq. BN for every conv: name -> (W' KRSC fp32, b' fp32)."""
+    out = {}
+    for op in net.ops:
+        if op.kind != "conv":
+            continue
+        p = params[op.name]
+        out[op.name] = fold_bn(p["W"], p["b"], p["gamma"], p["beta"], p["mu"], p["var"], p["eps"])
+    return out
+
+
+def _conv_f32_lib(op, x, Wf, bf):
+    """fp32 library convolution (a step of the calibration forward, not of the method)."""
+    xt = torch.from_numpy(x).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(Wf).permute(0, 3, 1, 2)
+    y = torch.nn.functional.conv2d(xt, wt, torch.from_numpy(bf), stride=op.stride,
+                                   padding=(op.pad_h, op.pad_w), dilation=op.dil)
+    return np.ascontiguousarray(y.permute(0, 2, 3, 1).numpy())
+
+
+def forward_f32(net, folded, x, use_library=True):
+    """fp32 forward of the folded network.  Returns (tensors, pre_sum) where pre_sum holds,
+    per conv with a fused sum, the branch output before the sum."""
+    t = {net.input: x}
+    pre = {}
+    for op in net.ops:
+        if op.kind == "maxpool":
+            xt = torch.from_numpy(t[op.src]).permute(0, 3, 1, 2)
+            y = torch.nn.functional.max_pool2d(xt, (op.R, op.S), op.stride, op.pad)
+            t[op.dst] = np.ascontiguousarray(y.permute(0, 2, 3, 1).numpy())
+            continue
+        Wf, bf = folded[op.name]
+        xin = t[op.src]
+        if use_library:
+            y = _conv_f32_lib(op, xin, Wf, bf)
+        else:
+            y = conv_f32(geom(op, net.tensors, xin.shape[0]), xin, Wf, bf)
+        if op.res is not None:
+            pre[op.name] = y
+            y = y + t[op.res]
+        if op.relu:
+            y = np.maximum(y, 0)
+        d = net.tensors[op.dst]
+        if d.C == op.K:
+            t[op.dst] = y
+        else:
+            if op.dst not in t:
+                t[op.dst] = np.zeros(y.shape[:3] + (d.C,), np.float32)
+            t[op.dst][..., op.dst_c_off:op.dst_c_off + op.K] = y
+    return t, pre
+
+
+def calibrate(net, folded, batches, use_library=True):
+    """Running max-abs over ``batches`` (iterable of fp32 NHWC inputs) -> factor table
+    {tensor name: q} plus {conv name + ':branch': q1} for fused sums."""
+    mx = {}
+
+    def upd(key, arr):
+        m = maxabs(arr)
+        if m > mx.get(key, np.float32(0)):
+            mx[key] = m
+        mx.setdefault(key, np.float32(0))
+
+    for x in batches:
+        t, pre = forward_f32(net, folded, x, use_library)
+        for name, arr in t.items():
+            upd(name, arr)
+        for name, arr in pre.items():
+            upd(name + ":branch", arr)
+    q = {k: qfactor(v, P_ACT) for k, v in mx.items()}
+    # + rule: a fused sum is re-quantised at max(q1, q2)
+    for op in net.ops:
+        if op.kind == "conv" and op.res is not None:
+            q[op.dst] = max(q[op.name + ":branch"], q[op.res])
+        if op.kind == "maxpool":
+            q[op.dst] = q[op.src]
+    return q
+
+
+def quantize_params(net, folded, q):
+    """name -> dict(z_w int8 KRSC, q_w, z_b int32)."""
+    out = {}
+    for op in net.ops:
+        if op.kind != "conv":
+            continue
+        Wf, bf = folded[op.name]
+        q_w = qfactor(maxabs(Wf), P_W)
+        out[op.name] = dict(z_w=Q(Wf, q_w, P_W), q_w=q_w, z_b=Q31_bias(bf, q[op.src], q_w))
+    return out
+
+
+def forward_i8(net, qparams, q, z_in, keep_acc=False):
+    """int8 forward (Eq. A' per conv).  Returns {tensor: int8 array} (and accumulators)."""
+    t = {net.input: z_in}
+    accs = {}
+    N = z_in.shape[0]
+    for op in net.ops:
+        if op.kind == "maxpool":
+            d = net.tensors[op.dst]
+            t[op.dst] = maxpool_i8(t[op.src], op.R, op.S, op.stride, op.pad, d.H, d.W)
+            continue
+        qp = qparams[op.name]
+        g = geom(op, net.tensors, N)
+        acc = conv_i8(g, t[op.src], qp["z_w"], qp["z_b"])
+        if keep_acc:
+            accs[op.name] = acc
+        q_out = q[op.dst]
+        m = requant_scale(q[op.src], qp["q_w"], q_out)
+        d = net.tensors[op.dst]
+        if op.dst not in t:
+            t[op.dst] = np.zeros((N, d.H, d.W, d.C), np.int8)
+        res, m_r = None, 0.0
+        if op.res is not None:
+            res, m_r = t[op.res], residual_scale(q[op.res], q_out)
+        requant(acc, m, op.relu, res, m_r, out=t[op.dst], out_c_stride=d.C,
+                out_c_off=op.dst_c_off)
+    return (t, accs) if keep_acc else t

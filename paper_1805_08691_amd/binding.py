@@ -1,0 +1,202 @@
+"""ctypes binding of libq8conv.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for
+device memory and streams, nothing else), passes raw pointers and sizes through the C
+ABI of ``include/q8conv.h`` and raises ``Q8Error`` on a non-zero return code.  There is
+no fallback: if the shared library has not been built, importing this module fails.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libq8conv.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_1805_08691_amd.build` "
+        "(there is no CPU fallback)")
+
+lib = C.CDLL(LIB_PATH)
+
+EXPORTS = [
+    "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
+    "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_bias", "q8_dequantize",
+    "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
+    "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32",
+]
+
+
+class Q8Error(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"q8conv error {code}: {lib.q8_strerror(code).decode()}")
+
+
+class ConvDesc(C.Structure):
+    """Mirror of ``q8_conv_desc``."""
+    _fields_ = [(n, C.c_int32) for n in (
+        "N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h",
+        "dil_w", "relu", "in_c_stride", "out_c_stride", "out_c_off", "res_c_stride",
+        "res_c_off")]
+
+    def __init__(self, N, H, W, C, K, R, S, stride_h=1, stride_w=1, pad_h=0, pad_w=0, dil_h=1,
+                 dil_w=1, relu=0, in_c_stride=0, out_c_stride=0, out_c_off=0, res_c_stride=0,
+                 res_c_off=0):
+        super().__init__(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                         int(relu), in_c_stride, out_c_stride, out_c_off, res_c_stride,
+                         res_c_off)
+
+    @property
+    def Ho(self):
+        return lib.q8_conv_out_h(C.byref(self))
+
+    @property
+    def Wo(self):
+        return lib.q8_conv_out_w(C.byref(self))
+
+
+_vp, _sz, _f, _i = C.c_void_p, C.c_size_t, C.c_float, C.c_int
+_dp = C.POINTER(ConvDesc)
+lib.q8_strerror.restype = C.c_char_p
+lib.q8_strerror.argtypes = [_i]
+lib.q8_conv_out_h.argtypes = [_dp]
+lib.q8_conv_out_w.argtypes = [_dp]
+lib.q8_calibrate_maxabs.argtypes = [_vp, _sz, _vp, _vp]
+lib.q8_qfactor.restype = _f
+lib.q8_qfactor.argtypes = [_f, _i]
+lib.q8_quantize.argtypes = [_vp, _sz, _f, _i, _vp, _vp]
+lib.q8_quantize_pad_channels.argtypes = [_vp, _sz, _i, _i, _f, _i, _vp, _vp]
+lib.q8_quantize_bias.argtypes = [_vp, _sz, _f, _f, _vp, _vp]
+lib.q8_dequantize.argtypes = [_vp, _sz, _f, _vp, _vp]
+lib.q8_fold_bn.argtypes = [_vp] * 6 + [_f, _i, _i, _vp, _vp, _vp]
+lib.q8_packed_weight_bytes.restype = _sz
+lib.q8_packed_weight_bytes.argtypes = [_dp]
+lib.q8_pack_weights.argtypes = [_dp, _vp, _vp, _vp]
+lib.q8_conv_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
+lib.q8_conv_f32_ref.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.q8_maxpool_i8.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
+lib.q8_maxpool_f32.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
+
+
+def _check(code):
+    if code != 0:
+        raise Q8Error(code)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors, contiguous"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def calibrate_maxabs(x, maxabs):
+    """maxabs[0] = max(maxabs[0], max|x|); ``maxabs`` is a 1-element fp32 device tensor."""
+    _check(lib.q8_calibrate_maxabs(_ptr(x, torch.float32), x.numel(),
+                                   _ptr(maxabs, torch.float32), _stream()))
+
+
+def qfactor(max_abs, p):
+    return lib.q8_qfactor(float(max_abs), int(p))
+
+
+def quantize(r, q, p, out=None):
+    z = out if out is not None else torch.empty(r.shape, dtype=torch.int8, device=r.device)
+    _check(lib.q8_quantize(_ptr(r, torch.float32), r.numel(), q, p, _ptr(z, torch.int8),
+                           _stream()))
+    return z
+
+
+def quantize_pad_channels(r, c_pad, q, p, out=None):
+    """NHWC fp32 [..., C] -> int8 [..., c_pad] with zero channels appended."""
+    Cc = r.shape[-1]
+    npix = r.numel() // Cc
+    z = out if out is not None else torch.empty(r.shape[:-1] + (c_pad,), dtype=torch.int8,
+                                                device=r.device)
+    _check(lib.q8_quantize_pad_channels(_ptr(r, torch.float32), npix, Cc, c_pad, q, p,
+                                        _ptr(z, torch.int8), _stream()))
+    return z
+
+
+def quantize_bias(b, q_x, q_w, out=None):
+    z = out if out is not None else torch.empty(b.shape, dtype=torch.int32, device=b.device)
+    _check(lib.q8_quantize_bias(_ptr(b, torch.float32), b.numel(), q_x, q_w,
+                                _ptr(z, torch.int32), _stream()))
+    return z
+
+
+def dequantize(z, q, out=None):
+    r = out if out is not None else torch.empty(z.shape, dtype=torch.float32, device=z.device)
+    _check(lib.q8_dequantize(_ptr(z, torch.int8), z.numel(), q, _ptr(r, torch.float32),
+                             _stream()))
+    return r
+
+
+def fold_bn(W, b, gamma, beta, mu, var, eps=1e-5):
+    K = W.shape[0]
+    rsc = W.numel() // K if K else 0
+    W_out = torch.empty_like(W)
+    b_out = torch.empty(K, dtype=torch.float32, device=W.device)
+    _check(lib.q8_fold_bn(_ptr(W, torch.float32), _ptr(b, torch.float32),
+                          _ptr(gamma, torch.float32), _ptr(beta, torch.float32),
+                          _ptr(mu, torch.float32), _ptr(var, torch.float32), eps, K, rsc,
+                          _ptr(W_out), _ptr(b_out), _stream()))
+    return W_out, b_out
+
+
+def packed_weight_bytes(desc):
+    return lib.q8_packed_weight_bytes(C.byref(desc))
+
+
+def pack_weights(desc, z_w):
+    nbytes = packed_weight_bytes(desc)
+    if nbytes == 0:
+        raise Q8Error(-2)
+    packed = torch.empty(nbytes, dtype=torch.int8, device=z_w.device)
+    _check(lib.q8_pack_weights(C.byref(desc), _ptr(z_w, torch.int8), _ptr(packed), _stream()))
+    return packed
+
+
+def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q_res=0.0,
+              out=None, acc_dump=None):
+    if out is None:
+        ocs = desc.out_c_stride or desc.K
+        out = torch.empty((desc.N, desc.Ho, desc.Wo, ocs), dtype=torch.int8, device=z_x.device)
+    _check(lib.q8_conv_int8(C.byref(desc), _ptr(z_x, torch.int8), _ptr(z_w_packed, torch.int8),
+                            _ptr(bias_i32, torch.int32), q_x, q_w, q_out,
+                            _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
+                            _ptr(acc_dump, torch.int32), _stream()))
+    return out
+
+
+def conv_f32_ref(desc, x, w, b=None, res=None, out=None):
+    if out is None:
+        out = torch.empty((desc.N, desc.Ho, desc.Wo, desc.K), dtype=torch.float32,
+                          device=x.device)
+    _check(lib.q8_conv_f32_ref(C.byref(desc), _ptr(x, torch.float32), _ptr(w, torch.float32),
+                               _ptr(b, torch.float32), _ptr(res, torch.float32),
+                               _ptr(out, torch.float32), _stream()))
+    return out
+
+
+def _pool(fn, dtype, x, R, S, stride, pad, Ho, Wo):
+    N, H, W, Cc = x.shape
+    y = torch.empty((N, Ho, Wo, Cc), dtype=dtype, device=x.device)
+    _check(fn(_ptr(x, dtype), N, H, W, Cc, R, S, stride, pad, Ho, Wo, _ptr(y), _stream()))
+    return y
+
+
+def maxpool_i8(x, R, S, stride, pad, Ho, Wo):
+    return _pool(lib.q8_maxpool_i8, torch.int8, x, R, S, stride, pad, Ho, Wo)
+
+
+def maxpool_f32(x, R, S, stride, pad, Ho, Wo):
+    return _pool(lib.q8_maxpool_f32, torch.float32, x, R, S, stride, pad, Ho, Wo)

@@ -1,0 +1,490 @@
+// int8 x int8 -> int32 implicit-GEMM convolution with the fused requantising epilogue
+// (Eq. x, Eq. A' and the conv+ReLU / conv+sum fusions of arxiv 1805.08691), for gfx950.
+//
+// GEMM view: rows = output channels (filters, the MFMA A operand), columns = output
+// pixels n*Ho*Wo (activations, the MFMA B operand), reduction = R*S*C bytes.  With NHWC
+// activations and KRSC filters both operands are contiguous along the reduction, so a
+// 16-byte chunk (16 channels of one tap) is the unit moved from HBM to LDS and from LDS
+// into an MFMA operand register quad.  v_mfma_i32_32x32x32_i8 consumes, per lane, 16
+// reduction bytes of one row/column; integer sums are exact, so any assignment of
+// reduction bytes to lanes is correct as long as A and B use the same one.
+//
+// The accumulator layout of the 32x32 MFMA puts four consecutive rows (= channels) of one
+// column (= pixel) in four consecutive registers of a lane, which is what the epilogue
+// wants: bias, scale, residual, ReLU, Round, clamp on four channels, one packed store.
+#include "q8_common.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
+
+constexpr int kThreads = 256;
+constexpr int kNumXcd = 8;
+
+struct ConvParams {
+  const int8_t* __restrict__ x;
+  const int8_t* __restrict__ w;       // packed filters: [K][red_len] bytes
+  const int32_t* __restrict__ bias;
+  const int8_t* __restrict__ res;
+  int8_t* __restrict__ y;
+  int32_t* __restrict__ acc_dump;
+  int N, H, W, C, K, R, S;
+  int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+  int Ho, Wo;
+  int in_cs, out_cs, out_off, res_cs, res_off;
+  int M;          // N*Ho*Wo
+  int red_len;    // reduction bytes per filter (R*S*C, or R*S4*16 in the 4-channel mode)
+  int S4;         // 4-channel mode: 16-byte chunks per filter row (ceil(S/4))
+  int n_ptiles, n_ctiles;
+  float m, m_r;
+  int relu;
+  int vec_out;    // 1: out/res/dump addresses of 4-channel groups are 4-byte aligned
+};
+
+// 16-byte chunk index -> physical chunk slot inside an LDS row (XOR swizzle so that the
+// 16 rows a quarter-wave reads at one reduction offset fall into distinct bank groups).
+template <int CHUNKS>
+__device__ __forceinline__ int swz(int row, int chunk) {
+  if constexpr (CHUNKS == 4) {
+    int f = (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
+    return chunk ^ f;
+  } else {
+    return chunk ^ ((row >> 1) & (CHUNKS - 1));
+  }
+}
+
+// MODE 0: C % 16 == 0 (a chunk = 16 channels of one tap).
+// MODE 1: 4 stored channels per pixel (a chunk = 4 consecutive taps along the filter row).
+template <int WP, int WC, int TP, int TC, int BK, int MODE>
+__global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
+  constexpr int BP = WP * TP * 32;     // pixels per block
+  constexpr int BC = WC * TC * 32;     // channels per block
+  constexpr int CHUNKS = BK / 16;      // chunks per LDS row
+  constexpr int ROWS_PER_PASS = kThreads / CHUNKS;
+  constexpr int A_LOADS = (BC + ROWS_PER_PASS - 1) / ROWS_PER_PASS;
+  constexpr int B_LOADS = BP / ROWS_PER_PASS;
+  constexpr bool A_RAGGED = (BC % ROWS_PER_PASS) != 0;   // fewer filter rows than loader rows
+  static_assert(WP * WC == 4, "four wavefronts per block");
+  static_assert(BP % ROWS_PER_PASS == 0, "tile/loader mismatch");
+
+  __shared__ __attribute__((aligned(16))) int8_t lds_a[2][BC * BK];
+  __shared__ __attribute__((aligned(16))) int8_t lds_b[2][BP * BK];
+
+  // XCD-aware tile order: consecutive workgroup ids go to different XCDs (each with its
+  // own L2); give every XCD a contiguous run of tiles, channel tile fastest, so the
+  // blocks sharing an activation tile run on the same L2.
+  const int nblk = p.n_ptiles * p.n_ctiles;
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
+    const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
+    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int ctile = bid % p.n_ctiles;
+  const int ptile = bid / p.n_ctiles;
+  const int pix0 = ptile * BP;
+  const int ch0 = ctile * BC;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_p = wave % WP;
+  const int wave_c = wave / WP;
+
+  // ---- loader state: this thread moves chunk column `lchunk` of rows lrow + j*ROWS_PER_PASS
+  const int lchunk = tid % CHUNKS;
+  const int lrow = tid / CHUNKS;
+
+  int b_hi0[B_LOADS], b_wi0[B_LOADS];
+  long b_img[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    int pix = pix0 + lrow + j * ROWS_PER_PASS;
+    if (pix < p.M) {
+      int n = pix / (p.Ho * p.Wo);
+      int rem = pix - n * (p.Ho * p.Wo);
+      int ho = rem / p.Wo;
+      int wo = rem - ho * p.Wo;
+      b_hi0[j] = ho * p.stride_h - p.pad_h;
+      b_wi0[j] = wo * p.stride_w - p.pad_w;
+      b_img[j] = (long)n * p.H * p.W * p.in_cs;
+    } else {
+      b_hi0[j] = -0x40000000;   // never inside the image
+      b_wi0[j] = -0x40000000;
+      b_img[j] = 0;
+    }
+  }
+  // position of this thread's chunk in the reduction
+  int red = lchunk * 16;           // byte offset in the reduction (also the filter offset)
+  int tap_r, tap_s, tap_c;         // MODE 0: tap (r, s) and channel; MODE 1: r and chunk-in-row
+  if constexpr (MODE == 0) {
+    int tap = red / p.C;
+    tap_c = red - tap * p.C;
+    tap_r = tap / p.S;
+    tap_s = tap - tap_r * p.S;
+  } else {
+    int ck = red >> 4;
+    tap_r = ck / p.S4;
+    tap_s = (ck - tap_r * p.S4) * 4;
+    tap_c = 0;
+  }
+
+  v4i a_reg[A_LOADS], b_reg[B_LOADS];
+
+  auto load_global = [&]() {
+    const bool red_ok = red < p.red_len;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) {
+      int ch = ch0 + lrow + j * ROWS_PER_PASS;
+      v4i v = {0, 0, 0, 0};
+      const bool row_ok = !A_RAGGED || (lrow + j * ROWS_PER_PASS < BC);
+      if (red_ok && row_ok && ch < p.K)
+        v = *reinterpret_cast<const v4i*>(p.w + (size_t)ch * p.red_len + red);
+      a_reg[j] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) {
+      v4i v = {0, 0, 0, 0};
+      if constexpr (MODE == 0) {
+        int hi = b_hi0[j] + tap_r * p.dil_h;
+        int wi = b_wi0[j] + tap_s * p.dil_w;
+        if (red_ok && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W)
+          v = *reinterpret_cast<const v4i*>(p.x + b_img[j] +
+                                            ((long)hi * p.W + wi) * p.in_cs + tap_c);
+      } else {
+        int hi = b_hi0[j] + tap_r;          // dilation 1 in this mode
+        int wi = b_wi0[j] + tap_s;
+        if (red_ok && (unsigned)hi < (unsigned)p.H && wi > -4 && wi < p.W) {
+          const int8_t* src = p.x + b_img[j] + ((long)hi * p.W + wi) * 4;
+          if (wi >= 0 && wi + 3 < p.W) {
+            v = *reinterpret_cast<const v4i_a4*>(src);
+          } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+              if ((unsigned)(wi + t) < (unsigned)p.W)
+                v[t] = *reinterpret_cast<const int*>(src + 4 * t);
+          }
+        }
+      }
+      b_reg[j] = v;
+    }
+  };
+  auto advance = [&]() {
+    red += BK;
+    if constexpr (MODE == 0) {
+      tap_c += BK;
+      while (tap_c >= p.C) {
+        tap_c -= p.C;
+        if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+      }
+    } else {
+      int ck = red >> 4;
+      tap_r = ck / p.S4;
+      tap_s = (ck - tap_r * p.S4) * 4;
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) {
+      int row = lrow + j * ROWS_PER_PASS;
+      if (A_RAGGED && row >= BC) continue;
+      *reinterpret_cast<v4i*>(&lds_a[buf][row * BK + swz<CHUNKS>(row, lchunk) * 16]) = a_reg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) {
+      int row = lrow + j * ROWS_PER_PASS;
+      *reinterpret_cast<v4i*>(&lds_b[buf][row * BK + swz<CHUNKS>(row, lchunk) * 16]) = b_reg[j];
+    }
+  };
+
+  v16i acc[TC][TP];
+#pragma unroll
+  for (int i = 0; i < TC; ++i)
+#pragma unroll
+    for (int j = 0; j < TP; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  const int nk = (p.red_len + BK - 1) / BK;
+  const int frag_row = lane & 31;       // row (A) / column (B) of the 32-wide MFMA tile
+  const int frag_half = lane >> 5;      // which 16-byte half of a 32-byte reduction step
+
+  load_global();
+  store_lds(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) {
+      advance();
+      load_global();
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      v4i af[TC], bf[TP];
+      const int chunk = 2 * ks + frag_half;
+#pragma unroll
+      for (int i = 0; i < TC; ++i) {
+        int row = (wave_c * TC + i) * 32 + frag_row;
+        af[i] = *reinterpret_cast<const v4i*>(&lds_a[buf][row * BK + swz<CHUNKS>(row, chunk) * 16]);
+      }
+#pragma unroll
+      for (int j = 0; j < TP; ++j) {
+        int row = (wave_p * TP + j) * 32 + frag_row;
+        bf[j] = *reinterpret_cast<const v4i*>(&lds_b[buf][row * BK + swz<CHUNKS>(row, chunk) * 16]);
+      }
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds, for pixel column (lane & 31), channels 8a + 4*(lane>>5) + b
+  const float m = p.m, m_r = p.m_r;
+#pragma unroll
+  for (int j = 0; j < TP; ++j) {
+    const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
+    if (pix >= p.M) continue;
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int ch = ch0 + (wave_c * TC + i) * 32 + 8 * a + 4 * (lane >> 5);
+        if (ch >= p.K) continue;
+        int v[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) v[b] = acc[i][j][4 * a + b];
+        const bool full = p.vec_out && (ch + 3 < p.K);
+        if (p.bias) {
+          if (full) {
+            v4i bv = *reinterpret_cast<const v4i*>(p.bias + ch);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v[b] += bv[b];
+          } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+              if (ch + b < p.K) v[b] += p.bias[ch + b];
+          }
+        }
+        if (p.acc_dump) {
+          int32_t* d = p.acc_dump + (size_t)pix * p.K + ch;
+          if (full && (p.K & 3) == 0) {
+            *reinterpret_cast<v4i*>(d) = v4i{v[0], v[1], v[2], v[3]};
+          } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+              if (ch + b < p.K) d[b] = v[b];
+          }
+        }
+        float t[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) t[b] = __fmul_rn((float)v[b], m);
+        if (p.res) {
+          const int8_t* r = p.res + (size_t)pix * p.res_cs + p.res_off + ch;
+          int rv[4] = {0, 0, 0, 0};
+          if (full) {
+            int w = *reinterpret_cast<const int*>(r);
+            rv[0] = (int8_t)(w & 0xff);
+            rv[1] = (int8_t)((w >> 8) & 0xff);
+            rv[2] = (int8_t)((w >> 16) & 0xff);
+            rv[3] = (int8_t)(w >> 24);
+          } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+              if (ch + b < p.K) rv[b] = r[b];
+          }
+#pragma unroll
+          for (int b = 0; b < 4; ++b) t[b] = __fadd_rn(t[b], __fmul_rn((float)rv[b], m_r));
+        }
+        int z[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          float u = t[b];
+          if (p.relu) u = fmaxf(u, 0.0f);
+          u = fminf(fmaxf(u, -128.0f), 127.0f);
+          z[b] = (int)rintf(u);
+        }
+        int8_t* o = p.y + (size_t)pix * p.out_cs + p.out_off + ch;
+        if (full) {
+          *reinterpret_cast<unsigned*>(o) = (unsigned)(z[0] & 0xff) | ((unsigned)(z[1] & 0xff) << 8) |
+                                            ((unsigned)(z[2] & 0xff) << 16) |
+                                            ((unsigned)(z[3] & 0xff) << 24);
+        } else {
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (ch + b < p.K) o[b] = (int8_t)z[b];
+        }
+      }
+    }
+  }
+}
+
+// dense KRSC (true C <= 4) -> [K][R][S4][4 taps][4 channels], zero filled
+__global__ void pack_c4_kernel(const int8_t* __restrict__ w, int K, int R, int S, int C, int S4,
+                               int8_t* __restrict__ out) {
+  const int row_len = R * S4 * 16;
+  const size_t total = (size_t)K * row_len;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    int k = (int)(i / row_len);
+    int o = (int)(i - (size_t)k * row_len);
+    int r = o / (S4 * 16);
+    int o2 = o - r * S4 * 16;
+    int s = o2 >> 2, c = o2 & 3;
+    int8_t v = 0;
+    if (s < S && c < C) v = w[(((size_t)k * R + r) * S + s) * C + c];
+    out[i] = v;
+  }
+}
+
+__global__ void copy_bytes_kernel(const int8_t* __restrict__ src, size_t n, int8_t* __restrict__ dst) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+int out_extent(int in, int pad, int dil, int k, int stride) {
+  long span = (long)dil * (k - 1) + 1;
+  long t = (long)in + 2L * pad - span;
+  if (t < 0) return 0;
+  return (int)(t / stride) + 1;
+}
+
+bool desc_sane(const q8_conv_desc* d) {
+  return d && d->N >= 0 && d->H >= 1 && d->W >= 1 && d->C >= 1 && d->K >= 1 && d->R >= 1 &&
+         d->S >= 1 && d->stride_h >= 1 && d->stride_w >= 1 && d->pad_h >= 0 && d->pad_w >= 0 &&
+         d->dil_h >= 1 && d->dil_w >= 1;
+}
+
+// 0: 16-channel chunks; 1: 4-channel pixels; -1: unsupported
+int conv_mode(const q8_conv_desc* d) {
+  if (d->C % 16 == 0) return 0;
+  if (d->C <= 4) return 1;
+  return -1;
+}
+
+template <int WP, int WC, int TP, int TC, int BK>
+int launch(ConvParams& p, int mode, hipStream_t stream) {
+  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
+  p.n_ptiles = (p.M + BP - 1) / BP;
+  p.n_ctiles = (p.K + BC - 1) / BC;
+  long nblk = (long)p.n_ptiles * p.n_ctiles;
+  if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
+  if (mode == 0)
+    hipLaunchKernelGGL((conv_i8_kernel<WP, WC, TP, TC, BK, 0>), dim3((unsigned)nblk), dim3(kThreads),
+                       0, stream, p);
+  else
+    hipLaunchKernelGGL((conv_i8_kernel<WP, WC, TP, TC, BK, 1>), dim3((unsigned)nblk), dim3(kThreads),
+                       0, stream, p);
+  return q8_launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int q8_conv_out_h(const q8_conv_desc* d) {
+  if (!desc_sane(d)) return 0;
+  return out_extent(d->H, d->pad_h, d->dil_h, d->R, d->stride_h);
+}
+int q8_conv_out_w(const q8_conv_desc* d) {
+  if (!desc_sane(d)) return 0;
+  return out_extent(d->W, d->pad_w, d->dil_w, d->S, d->stride_w);
+}
+
+size_t q8_packed_weight_bytes(const q8_conv_desc* d) {
+  if (!desc_sane(d)) return 0;
+  int mode = conv_mode(d);
+  if (mode == 0) return (size_t)d->K * d->R * d->S * d->C;
+  if (mode == 1) return (size_t)d->K * d->R * ((d->S + 3) / 4) * 16;
+  return 0;
+}
+
+int q8_pack_weights(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, void* packed_dev,
+                    void* stream) {
+  Q8_REQUIRE(desc_sane(d) && z_w_krsc_dev && packed_dev, Q8_EINVAL);
+  int mode = conv_mode(d);
+  Q8_REQUIRE(mode >= 0, Q8_EUNSUPPORTED);
+  Q8_REQUIRE(q8_aligned(packed_dev, 16), Q8_EALIGN);
+  size_t bytes = q8_packed_weight_bytes(d);
+  int blocks = (int)((bytes + 255) / 256);
+  if (blocks > 4096) blocks = 4096;
+  if (mode == 0)
+    hipLaunchKernelGGL(copy_bytes_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       z_w_krsc_dev, bytes, (int8_t*)packed_dev);
+  else
+    hipLaunchKernelGGL(pack_c4_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       z_w_krsc_dev, d->K, d->R, d->S, d->C, (d->S + 3) / 4, (int8_t*)packed_dev);
+  return q8_launch_status();
+}
+
+int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                 const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                 const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+                 void* stream) {
+  Q8_REQUIRE(desc_sane(d), Q8_EINVAL);
+  Q8_REQUIRE(q8_finite_pos(q_x) && q8_finite_pos(q_w) && q8_finite_pos(q_out), Q8_EINVAL);
+  Q8_REQUIRE(residual == nullptr || q8_finite_pos(q_res), Q8_EINVAL);
+  const int mode = conv_mode(d);
+  Q8_REQUIRE(mode >= 0, Q8_EUNSUPPORTED);
+
+  ConvParams p{};
+  p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C; p.K = d->K; p.R = d->R; p.S = d->S;
+  p.stride_h = d->stride_h; p.stride_w = d->stride_w; p.pad_h = d->pad_h; p.pad_w = d->pad_w;
+  p.dil_h = d->dil_h; p.dil_w = d->dil_w;
+  p.Ho = q8_conv_out_h(d); p.Wo = q8_conv_out_w(d);
+  p.in_cs = d->in_c_stride ? d->in_c_stride : (mode == 1 ? 4 : d->C);
+  p.out_cs = d->out_c_stride ? d->out_c_stride : d->K;
+  p.out_off = d->out_c_off;
+  p.res_cs = d->res_c_stride ? d->res_c_stride : d->K;
+  p.res_off = d->res_c_off;
+  Q8_REQUIRE(p.in_cs >= d->C && p.out_off >= 0 && p.res_off >= 0, Q8_EINVAL);
+  Q8_REQUIRE(p.out_cs >= p.out_off + d->K, Q8_EINVAL);
+  Q8_REQUIRE(residual == nullptr || p.res_cs >= p.res_off + d->K, Q8_EINVAL);
+
+  const long M = (long)d->N * p.Ho * p.Wo;
+  if (M == 0) return Q8_OK;
+  Q8_REQUIRE(M <= 0x7fffffffL, Q8_EUNSUPPORTED);
+  Q8_REQUIRE((long)d->H * d->W * p.in_cs <= 0x7fffffffL, Q8_EUNSUPPORTED);
+  Q8_REQUIRE(z_x && z_w_packed && z_y, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(z_w_packed, 16), Q8_EALIGN);
+  if (mode == 0) {
+    Q8_REQUIRE(p.in_cs % 16 == 0 && q8_aligned(z_x, 16), Q8_EALIGN);
+    p.red_len = d->R * d->S * d->C;
+    p.S4 = 0;
+  } else {
+    Q8_REQUIRE(p.in_cs == 4 && q8_aligned(z_x, 4), Q8_EALIGN);
+    Q8_REQUIRE(d->dil_w == 1 && d->dil_h == 1, Q8_EUNSUPPORTED);
+    p.S4 = (d->S + 3) / 4;
+    p.red_len = d->R * p.S4 * 16;
+  }
+  Q8_REQUIRE(bias_i32 == nullptr || q8_aligned(bias_i32, 16), Q8_EALIGN);
+  Q8_REQUIRE(acc_dump == nullptr || q8_aligned(acc_dump, 16), Q8_EALIGN);
+
+  p.x = z_x; p.w = (const int8_t*)z_w_packed; p.bias = bias_i32; p.res = residual; p.y = z_y;
+  p.acc_dump = acc_dump;
+  p.M = (int)M;
+  p.relu = d->relu ? 1 : 0;
+  {
+    float prod = q_x * q_w;      // the x rule: factor of the accumulator
+    p.m = prod / q_out;
+    p.m_r = residual ? q_res / q_out : 0.0f;
+  }
+  p.vec_out = (p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(z_y, 4) &&
+               (residual == nullptr ||
+                (p.res_cs % 4 == 0 && p.res_off % 4 == 0 && q8_aligned(residual, 4))))
+                  ? 1 : 0;
+
+  hipStream_t s = (hipStream_t)stream;
+  if (d->K > 64) return launch<2, 2, 2, 2, 64>(p, mode, s);   // 128 pixels x 128 channels
+  if (d->K > 32) return launch<4, 1, 2, 2, 64>(p, mode, s);   // 256 pixels x  64 channels
+  return launch<4, 1, 2, 1, 64>(p, mode, s);                  // 256 pixels x  32 channels
+}
+
+}  // extern "C"

@@ -1,0 +1,326 @@
+// HBM-bound passes of the quantised-convolution path: max-abs calibration, the
+// quantiser Q, the dequantiser D, batch-norm folding and the p = 31 bias quantiser
+// (Eq. Q, Eq. D, Eq. BN and the calibration text of arxiv 1805.08691).
+//
+// All floating point uses the explicitly rounded intrinsics (__fdiv_rn, __fmul_rn, ...)
+// so that no multiply-add is fused and every step is one IEEE binary32 operation.
+#include "q8_common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxBlocks = 256 * 8;   // 256 CUs x 8 resident blocks
+
+inline int blocks_for(size_t work_items) {
+  size_t b = (work_items + kThreads - 1) / kThreads;
+  if (b < 1) b = 1;
+  if (b > (size_t)kMaxBlocks) b = kMaxBlocks;
+  return (int)b;
+}
+
+// ---------------------------------------------------------------- max-abs ----------
+__device__ __forceinline__ float abs4max(float4 v) {
+  return fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));
+}
+
+// One running maximum per tensor.  Each thread folds 16-byte vectors with four
+// independent loads in flight, a wavefront folds with lane shuffles, the four
+// wavefronts of a block fold through LDS, and one atomic per block updates the
+// result.  |x| >= 0, so the IEEE bit pattern orders like an unsigned integer.
+__global__ __launch_bounds__(kThreads) void maxabs_kernel(const float* __restrict__ x,
+                                                          size_t n, size_t head,
+                                                          unsigned* __restrict__ out) {
+  float m = 0.0f;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  // scalar head (until 16-byte alignment) and tail
+  const size_t body = (n - head) / 4;
+  const size_t tail0 = head + body * 4;
+  if (tid < head) m = fabsf(x[tid]);
+  if (tid < n - tail0) m = fmaxf(m, fabsf(x[tail0 + tid]));
+  const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x + head);
+  size_t i = tid;
+  for (; i + 3 * nthreads < body; i += 4 * nthreads) {
+    float4 a = x4[i], b = x4[i + nthreads], c = x4[i + 2 * nthreads], d = x4[i + 3 * nthreads];
+    m = fmaxf(m, fmaxf(fmaxf(abs4max(a), abs4max(b)), fmaxf(abs4max(c), abs4max(d))));
+  }
+  for (; i < body; i += nthreads) m = fmaxf(m, abs4max(x4[i]));
+
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  __shared__ float wave_max[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float b = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+    if (b > 0.0f) atomicMax(out, __float_as_uint(b));
+  }
+}
+
+// ---------------------------------------------------------------- Q ---------------
+__device__ __forceinline__ int quant1(float r, float q, float lo, float hi) {
+  float t = __fdiv_rn(r, q);
+  t = rintf(t);                       // round-half-to-even
+  t = fminf(fmaxf(t, lo), hi);
+  return (int)t;
+}
+
+__device__ __forceinline__ unsigned pack4(int a, int b, int c, int d) {
+  return (unsigned)(a & 0xff) | ((unsigned)(b & 0xff) << 8) | ((unsigned)(c & 0xff) << 16) |
+         ((unsigned)(d & 0xff) << 24);
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const float* __restrict__ r,
+                                                            size_t n, size_t head, float q,
+                                                            float lo, float hi,
+                                                            int8_t* __restrict__ z) {
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  const size_t body = (n - head) / 4;
+  const size_t tail0 = head + body * 4;
+  if (tid < head) z[tid] = (int8_t)quant1(r[tid], q, lo, hi);
+  if (tid < n - tail0) z[tail0 + tid] = (int8_t)quant1(r[tail0 + tid], q, lo, hi);
+  const float4* __restrict__ r4 = reinterpret_cast<const float4*>(r + head);
+  unsigned* __restrict__ z4 = reinterpret_cast<unsigned*>(z + head);
+  size_t i = tid;
+  for (; i + 3 * nthreads < body; i += 4 * nthreads) {
+    float4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = r4[i + j * nthreads];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      z4[i + j * nthreads] = pack4(quant1(v[j].x, q, lo, hi), quant1(v[j].y, q, lo, hi),
+                                   quant1(v[j].z, q, lo, hi), quant1(v[j].w, q, lo, hi));
+  }
+  for (; i < body; i += nthreads) {
+    float4 v = r4[i];
+    z4[i] = pack4(quant1(v.x, q, lo, hi), quant1(v.y, q, lo, hi), quant1(v.z, q, lo, hi),
+                  quant1(v.w, q, lo, hi));
+  }
+}
+
+// NHWC with the channel count padded from C to Cp (Cp == 4 and C <= 4): one thread
+// per pixel, one packed 4-byte store.
+__global__ __launch_bounds__(kThreads) void quantize_pad4_kernel(const float* __restrict__ r,
+                                                                 size_t npix, int C, float q,
+                                                                 float lo, float hi,
+                                                                 unsigned* __restrict__ z) {
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  for (size_t p = (size_t)blockIdx.x * kThreads + threadIdx.x; p < npix; p += nthreads) {
+    int v[4] = {0, 0, 0, 0};
+    for (int c = 0; c < C; ++c) v[c] = quant1(r[p * C + c], q, lo, hi);
+    z[p] = pack4(v[0], v[1], v[2], v[3]);
+  }
+}
+
+// General channel padding (any C <= Cp): one thread per output element.
+__global__ __launch_bounds__(kThreads) void quantize_padc_kernel(const float* __restrict__ r,
+                                                                 size_t npix, int C, int Cp,
+                                                                 float q, float lo, float hi,
+                                                                 int8_t* __restrict__ z) {
+  const size_t total = npix * (size_t)Cp;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += nthreads) {
+    size_t p = i / Cp;
+    int c = (int)(i - p * Cp);
+    z[i] = c < C ? (int8_t)quant1(r[p * C + c], q, lo, hi) : (int8_t)0;
+  }
+}
+
+// Eq. Q with p = 31 in fp64; the factor is the exact-in-fp64 product q_x * q_w.
+__global__ __launch_bounds__(kThreads) void quantize_bias_kernel(const float* __restrict__ b,
+                                                                 size_t n, double q,
+                                                                 int32_t* __restrict__ z) {
+  size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n) return;
+  double t = __ddiv_rn((double)b[i], q);
+  t = rint(t);
+  t = fmin(fmax(t, -2147483648.0), 2147483647.0);
+  z[i] = (int32_t)t;
+}
+
+// ---------------------------------------------------------------- D ---------------
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const int8_t* __restrict__ z,
+                                                              size_t n, size_t head, float q,
+                                                              float* __restrict__ r) {
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  const size_t body = (n - head) / 4;
+  const size_t tail0 = head + body * 4;
+  if (tid < head) r[tid] = __fmul_rn(q, (float)z[tid]);
+  if (tid < n - tail0) r[tail0 + tid] = __fmul_rn(q, (float)z[tail0 + tid]);
+  const unsigned* __restrict__ z4 = reinterpret_cast<const unsigned*>(z + head);
+  for (size_t i = tid; i < body; i += nthreads) {
+    unsigned w = z4[i];
+    float4 o;
+    o.x = __fmul_rn(q, (float)(int8_t)(w & 0xff));
+    o.y = __fmul_rn(q, (float)(int8_t)((w >> 8) & 0xff));
+    o.z = __fmul_rn(q, (float)(int8_t)((w >> 16) & 0xff));
+    o.w = __fmul_rn(q, (float)(int8_t)(w >> 24));
+    // r + head need not be 16-byte aligned when z + head is 4-byte aligned: scalar stores
+    float* dst = r + head + 4 * i;
+    dst[0] = o.x; dst[1] = o.y; dst[2] = o.z; dst[3] = o.w;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void dequantize_vec_kernel(const int8_t* __restrict__ z,
+                                                                  size_t n4, float q,
+                                                                  float4* __restrict__ r) {
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  const unsigned* __restrict__ z4 = reinterpret_cast<const unsigned*>(z);
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += nthreads) {
+    unsigned w = z4[i];
+    float4 o;
+    o.x = __fmul_rn(q, (float)(int8_t)(w & 0xff));
+    o.y = __fmul_rn(q, (float)(int8_t)((w >> 8) & 0xff));
+    o.z = __fmul_rn(q, (float)(int8_t)((w >> 16) & 0xff));
+    o.w = __fmul_rn(q, (float)(int8_t)(w >> 24));
+    r[i] = o;
+  }
+}
+
+// ---------------------------------------------------------------- Eq. BN ----------
+__global__ __launch_bounds__(kThreads) void fold_bn_kernel(
+    const float* __restrict__ W, const float* __restrict__ b, const float* __restrict__ gamma,
+    const float* __restrict__ beta, const float* __restrict__ mu, const float* __restrict__ var,
+    float eps, int K, int RSC, float* __restrict__ W_out, float* __restrict__ b_out) {
+  const int k = blockIdx.y;
+  const float s = __fdiv_rn(gamma[k], __fsqrt_rn(__fadd_rn(var[k], eps)));
+  const size_t row = (size_t)k * RSC;
+  for (int j = blockIdx.x * kThreads + threadIdx.x; j < RSC; j += gridDim.x * kThreads)
+    W_out[row + j] = __fmul_rn(s, W[row + j]);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    float bk = b ? b[k] : 0.0f;
+    b_out[k] = __fadd_rn(__fmul_rn(s, __fsub_rn(bk, mu[k])), beta[k]);
+  }
+}
+
+inline size_t head_elems(const void* p, size_t elem, size_t n) {
+  size_t mis = reinterpret_cast<uintptr_t>(p) & 15;
+  size_t h = mis ? (16 - mis) / elem : 0;
+  return h < n ? h : n;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* q8_strerror(int code) {
+  switch (code) {
+    case Q8_OK: return "ok";
+    case Q8_EINVAL: return "invalid argument (null pointer, bad size, q <= 0 or not finite, bad p)";
+    case Q8_EUNSUPPORTED: return "shape not supported by the kernels";
+    case Q8_EALIGN: return "pointer or channel stride not aligned as the call requires";
+    case Q8_EHIP: return "HIP launch failed";
+    default: return "unknown q8conv error code";
+  }
+}
+
+float q8_qfactor(float maxabs, int p) {
+  if (!(maxabs > 0.0f) || p < 1 || p > 31) return 1.0f;
+  volatile float levels = (float)(((int64_t)1 << p) - 1);
+  volatile float q = maxabs / levels;
+  return q;
+}
+
+int q8_calibrate_maxabs(const float* x_dev, size_t n, float* maxabs_dev, void* stream) {
+  Q8_REQUIRE(maxabs_dev != nullptr, Q8_EINVAL);
+  if (n == 0) return Q8_OK;
+  Q8_REQUIRE(x_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(x_dev, 4) && q8_aligned(maxabs_dev, 4), Q8_EALIGN);
+  size_t head = head_elems(x_dev, 4, n);
+  int blocks = blocks_for((n + 15) / 16);
+  hipLaunchKernelGGL(maxabs_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, x_dev, n,
+                     head, reinterpret_cast<unsigned*>(maxabs_dev));
+  return q8_launch_status();
+}
+
+int q8_quantize(const float* r_dev, size_t n, float q, int p, int8_t* z_dev, void* stream) {
+  Q8_REQUIRE(p >= 1 && p <= 7 && q8_finite_pos(q), Q8_EINVAL);
+  if (n == 0) return Q8_OK;
+  Q8_REQUIRE(r_dev != nullptr && z_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(r_dev, 4), Q8_EALIGN);
+  const float hi = (float)((1 << p) - 1), lo = -(float)(1 << p);
+  // the vector body needs r 16-byte and z 4-byte aligned at the same element
+  size_t head = head_elems(r_dev, 4, n);
+  if (!q8_aligned(z_dev + head, 4)) head = n;   // fully scalar via the head/tail path
+  if (head == n) {
+    hipLaunchKernelGGL(quantize_padc_kernel, dim3(blocks_for(n)), dim3(kThreads), 0,
+                       (hipStream_t)stream, r_dev, n, 1, 1, q, lo, hi, z_dev);
+    return q8_launch_status();
+  }
+  int blocks = blocks_for((n + 15) / 16);
+  hipLaunchKernelGGL(quantize_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, r_dev, n,
+                     head, q, lo, hi, z_dev);
+  return q8_launch_status();
+}
+
+int q8_quantize_pad_channels(const float* r_dev, size_t npix, int C, int C_pad, float q, int p,
+                             int8_t* z_dev, void* stream) {
+  Q8_REQUIRE(p >= 1 && p <= 7 && q8_finite_pos(q), Q8_EINVAL);
+  Q8_REQUIRE(C >= 1 && C_pad >= C, Q8_EINVAL);
+  if (npix == 0) return Q8_OK;
+  Q8_REQUIRE(r_dev != nullptr && z_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(r_dev, 4), Q8_EALIGN);
+  const float hi = (float)((1 << p) - 1), lo = -(float)(1 << p);
+  if (C_pad == 4 && q8_aligned(z_dev, 4)) {
+    hipLaunchKernelGGL(quantize_pad4_kernel, dim3(blocks_for(npix)), dim3(kThreads), 0,
+                       (hipStream_t)stream, r_dev, npix, C, q, lo, hi,
+                       reinterpret_cast<unsigned*>(z_dev));
+  } else {
+    hipLaunchKernelGGL(quantize_padc_kernel, dim3(blocks_for(npix * (size_t)C_pad)), dim3(kThreads),
+                       0, (hipStream_t)stream, r_dev, npix, C, C_pad, q, lo, hi, z_dev);
+  }
+  return q8_launch_status();
+}
+
+int q8_quantize_bias(const float* b_dev, size_t n, float q_x, float q_w, int32_t* z_b_dev,
+                     void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q_x) && q8_finite_pos(q_w), Q8_EINVAL);
+  if (n == 0) return Q8_OK;
+  Q8_REQUIRE(b_dev != nullptr && z_b_dev != nullptr, Q8_EINVAL);
+  const double q = (double)q_x * (double)q_w;
+  Q8_REQUIRE(q > 0.0, Q8_EINVAL);
+  hipLaunchKernelGGL(quantize_bias_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads)),
+                     dim3(kThreads), 0, (hipStream_t)stream, b_dev, n, q, z_b_dev);
+  return q8_launch_status();
+}
+
+int q8_dequantize(const int8_t* z_dev, size_t n, float q, float* r_dev, void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q), Q8_EINVAL);
+  if (n == 0) return Q8_OK;
+  Q8_REQUIRE(z_dev != nullptr && r_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(r_dev, 4), Q8_EALIGN);
+  if (q8_aligned(z_dev, 4) && q8_aligned(r_dev, 16)) {
+    size_t n4 = n / 4;
+    if (n4)
+      hipLaunchKernelGGL(dequantize_vec_kernel, dim3(blocks_for(n4 / 2 + 1)), dim3(kThreads), 0,
+                         (hipStream_t)stream, z_dev, n4, q, reinterpret_cast<float4*>(r_dev));
+    if (n & 3)   // ragged tail: the scalar path of the generic kernel (head = all)
+      hipLaunchKernelGGL(dequantize_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream,
+                         z_dev + 4 * n4, n & 3, n & 3, q, r_dev + 4 * n4);
+    return q8_launch_status();
+  }
+  size_t mis = reinterpret_cast<uintptr_t>(z_dev) & 3;
+  size_t head = mis ? 4 - mis : 0;
+  if (head > n) head = n;
+  hipLaunchKernelGGL(dequantize_kernel, dim3(blocks_for((n + 3) / 4)), dim3(kThreads), 0,
+                     (hipStream_t)stream, z_dev, n, head, q, r_dev);
+  return q8_launch_status();
+}
+
+int q8_fold_bn(const float* W_dev, const float* b_dev, const float* gamma_dev,
+               const float* beta_dev, const float* mu_dev, const float* var_dev, float eps, int K,
+               int RSC, float* W_out_dev, float* b_out_dev, void* stream) {
+  Q8_REQUIRE(K >= 0 && RSC >= 0 && eps >= 0.0f, Q8_EINVAL);
+  if (K == 0) return Q8_OK;
+  Q8_REQUIRE(K <= 65535, Q8_EUNSUPPORTED);
+  Q8_REQUIRE(gamma_dev && beta_dev && mu_dev && var_dev && b_out_dev, Q8_EINVAL);
+  Q8_REQUIRE(RSC == 0 || (W_dev && W_out_dev), Q8_EINVAL);
+  int bx = (RSC + kThreads * 4 - 1) / (kThreads * 4);
+  if (bx < 1) bx = 1;
+  hipLaunchKernelGGL(fold_bn_kernel, dim3(bx, K), dim3(kThreads), 0, (hipStream_t)stream, W_dev,
+                     b_dev, gamma_dev, beta_dev, mu_dev, var_dev, eps, K, RSC, W_out_dev, b_out_dev);
+  return q8_launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,179 @@
+// Helpers that only chain layers or feed calibration; none of them is part of the
+// quantised arithmetic of arxiv 1805.08691.  The fp32 convolution produces the
+// real-valued activations whose max-abs the calibration step measures.
+#include "q8_common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// fp32 NHWC direct convolution, 64 pixels x 64 channels per block, 4 x 4 outputs per
+// thread, reduction staged through LDS 16 values at a time.
+constexpr int TP = 64, TCN = 64, TK = 16;
+
+__global__ __launch_bounds__(kThreads) void conv_f32_kernel(
+    const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ b,
+    const float* __restrict__ res, float* __restrict__ y, int N, int H, int W, int C, int K,
+    int R, int S, int sh, int sw, int ph, int pw, int dh, int dw, int Ho, int Wo, int relu) {
+  __shared__ float xs[TK][TP + 1];
+  __shared__ float ws[TK][TCN + 1];
+  const long M = (long)N * Ho * Wo;
+  const long pix0 = (long)blockIdx.x * TP;
+  const int ch0 = blockIdx.y * TCN;
+  const int tx = threadIdx.x % 16;   // channel group
+  const int ty = threadIdx.x / 16;   // pixel group
+  float acc[4][4] = {};
+  const int RSC = R * S * C;
+  // loader: thread moves element (row = tid / 16 + 16*j, kk = tid % 16)
+  const int lk = threadIdx.x % TK;
+  const int lr = threadIdx.x / TK;
+  for (int k0 = 0; k0 < RSC; k0 += TK) {
+    const int kidx = k0 + lk;
+    int r = 0, s = 0, c = 0;
+    const bool kok = kidx < RSC;
+    if (kok) {
+      int tap = kidx / C;
+      c = kidx - tap * C;
+      r = tap / S;
+      s = tap - r * S;
+    }
+#pragma unroll
+    for (int j = 0; j < TP / 16; ++j) {
+      int row = lr + 16 * j;
+      long pix = pix0 + row;
+      float v = 0.f;
+      if (kok && pix < M) {
+        int n = (int)(pix / ((long)Ho * Wo));
+        int rem = (int)(pix - (long)n * Ho * Wo);
+        int ho = rem / Wo, wo = rem - ho * Wo;
+        int hi = ho * sh - ph + r * dh, wi = wo * sw - pw + s * dw;
+        if ((unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W)
+          v = x[(((long)n * H + hi) * W + wi) * C + c];
+      }
+      xs[lk][row] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < TCN / 16; ++j) {
+      int row = lr + 16 * j;
+      int ch = ch0 + row;
+      ws[lk][row] = (kok && ch < K) ? w[(long)ch * RSC + kidx] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < TK; ++kk) {
+      float xv[4], wv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) xv[i] = xs[kk][ty * 4 + i];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) wv[i] = ws[kk][tx * 4 + i];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(xv[i], wv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    long pix = pix0 + ty * 4 + i;
+    if (pix >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int ch = ch0 + tx * 4 + j;
+      if (ch >= K) continue;
+      float v = acc[i][j];
+      if (b) v += b[ch];
+      if (res) v += res[pix * K + ch];
+      if (relu) v = fmaxf(v, 0.f);
+      y[pix * K + ch] = v;
+    }
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ T lowest();
+template <>
+__device__ __forceinline__ int8_t lowest<int8_t>() { return -128; }
+template <>
+__device__ __forceinline__ float lowest<float>() { return -3.402823466e38f; }
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool_kernel(const T* __restrict__ x, int N, int H,
+                                                           int W, int C, int R, int S, int stride,
+                                                           int pad, int Ho, int Wo,
+                                                           T* __restrict__ y) {
+  const size_t total = (size_t)N * Ho * Wo * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * kThreads) {
+    int c = (int)(i % C);
+    size_t t = i / C;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    T best = lowest<T>();
+    for (int r = 0; r < R; ++r) {
+      int hi = ho * stride - pad + r;
+      if ((unsigned)hi >= (unsigned)H) continue;
+      for (int s = 0; s < S; ++s) {
+        int wi = wo * stride - pad + s;
+        if ((unsigned)wi >= (unsigned)W) continue;
+        T v = x[(((size_t)n * H + hi) * W + wi) * C + c];
+        best = v > best ? v : best;
+      }
+    }
+    y[i] = best;
+  }
+}
+
+template <typename T>
+int maxpool_launch(const T* x, int N, int H, int W, int C, int R, int S, int stride, int pad,
+                   int Ho, int Wo, T* y, void* stream) {
+  Q8_REQUIRE(N >= 0 && H >= 1 && W >= 1 && C >= 1 && R >= 1 && S >= 1 && stride >= 1 && pad >= 0 &&
+                 Ho >= 0 && Wo >= 0, Q8_EINVAL);
+  // every window must hold at least one in-image tap
+  Q8_REQUIRE(pad < R && pad < S, Q8_EINVAL);
+  Q8_REQUIRE(Ho == 0 || (long)(Ho - 1) * stride - pad < H, Q8_EINVAL);
+  Q8_REQUIRE(Wo == 0 || (long)(Wo - 1) * stride - pad < W, Q8_EINVAL);
+  size_t total = (size_t)N * Ho * Wo * C;
+  if (total == 0) return Q8_OK;
+  Q8_REQUIRE(x && y, Q8_EINVAL);
+  size_t blocks = (total + kThreads - 1) / kThreads;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(maxpool_kernel<T>, dim3((unsigned)blocks), dim3(kThreads), 0,
+                     (hipStream_t)stream, x, N, H, W, C, R, S, stride, pad, Ho, Wo, y);
+  return q8_launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int q8_conv_f32_ref(const q8_conv_desc* d, const float* x_dev, const float* w_dev,
+                    const float* b_dev, const float* res_dev, float* y_dev, void* stream) {
+  Q8_REQUIRE(d && d->N >= 0 && d->H >= 1 && d->W >= 1 && d->C >= 1 && d->K >= 1 && d->R >= 1 &&
+                 d->S >= 1 && d->stride_h >= 1 && d->stride_w >= 1 && d->pad_h >= 0 &&
+                 d->pad_w >= 0 && d->dil_h >= 1 && d->dil_w >= 1, Q8_EINVAL);
+  const int Ho = q8_conv_out_h(d), Wo = q8_conv_out_w(d);
+  const long M = (long)d->N * Ho * Wo;
+  if (M == 0) return Q8_OK;
+  Q8_REQUIRE(x_dev && w_dev && y_dev, Q8_EINVAL);
+  const long bx = (M + TP - 1) / TP;
+  const int by = (d->K + TCN - 1) / TCN;
+  Q8_REQUIRE(bx <= 0x7fffffffL && by <= 65535, Q8_EUNSUPPORTED);
+  hipLaunchKernelGGL(conv_f32_kernel, dim3((unsigned)bx, by), dim3(kThreads), 0, (hipStream_t)stream,
+                     x_dev, w_dev, b_dev, res_dev, y_dev, d->N, d->H, d->W, d->C, d->K, d->R, d->S,
+                     d->stride_h, d->stride_w, d->pad_h, d->pad_w, d->dil_h, d->dil_w, Ho, Wo,
+                     d->relu ? 1 : 0);
+  return q8_launch_status();
+}
+
+int q8_maxpool_i8(const int8_t* x_dev, int N, int H, int W, int C, int R, int S, int stride, int pad,
+                  int Ho, int Wo, int8_t* y_dev, void* stream) {
+  return maxpool_launch<int8_t>(x_dev, N, H, W, C, R, S, stride, pad, Ho, Wo, y_dev, stream);
+}
+int q8_maxpool_f32(const float* x_dev, int N, int H, int W, int C, int R, int S, int stride, int pad,
+                   int Ho, int Wo, float* y_dev, void* stream) {
+  return maxpool_launch<float>(x_dev, N, H, W, C, R, S, stride, pad, Ho, Wo, y_dev, stream);
+}
+
+}  // extern "C"

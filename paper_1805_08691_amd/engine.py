@@ -1,0 +1,190 @@
+"""Runs a layer list on the GPU through the C-ABI calls of ``binding``.
+
+Host-side orchestration only: which call follows which, which buffer a layer reads and
+writes, which factor goes with which tensor.  All arithmetic happens inside libq8conv.so.
+Offline steps (in the paper's flow, Fig. "steps to generate the optimized model"):
+  fold()               Eq. BN on every conv
+  calibrate(batches)   fp32 forward of the folded net + running max-abs per tensor
+  quantize_weights()   per-tensor q_w, int8 filters (packed), int32 bias at q_x * q_w
+Online step:
+  forward(x)           Q on the input image, then one fused conv launch per layer (Eq. A').
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+
+P_ACT = 7
+P_W = 7
+
+
+def _pad_c(c):
+    """Stored channel count of an activation tensor (3-channel images are stored as 4)."""
+    return 4 if c < 4 else c
+
+
+class Engine:
+    def __init__(self, net, batch, device="cuda"):
+        self.net = net
+        self.N = batch
+        self.dev = torch.device(device)
+        self.params = {}      # conv name -> dict of fp32 device tensors
+        self.folded = {}      # conv name -> (W', b')
+        self.q = {}           # tensor name -> activation factor (host float)
+        self.qw = {}          # conv name -> weight factor
+        self.wq = {}          # conv name -> (packed int8 filters, int32 bias)
+        self.act = {}         # tensor name -> int8 device buffer [N, H, W, C_stored]
+        self.desc = {}        # conv name -> ConvDesc
+        self.graph = None
+        for op in net.ops:
+            if op.kind == "conv":
+                self.desc[op.name] = self._desc(op, batch)
+
+    # ------------------------------------------------------------------ descriptors
+    def _desc(self, op, N):
+        s, d = self.net.tensors[op.src], self.net.tensors[op.dst]
+        res_cs = _pad_c(self.net.tensors[op.res].C) if op.res else 0
+        return B.ConvDesc(N, s.H, s.W, op.C, op.K, op.R, op.S, op.stride, op.stride, op.pad_h,
+                          op.pad_w, op.dil, op.dil, relu=op.relu, in_c_stride=_pad_c(s.C),
+                          out_c_stride=_pad_c(d.C), out_c_off=op.dst_c_off, res_c_stride=res_cs)
+
+    # ------------------------------------------------------------------ offline steps
+    def load_params(self, params):
+        for name, p in params.items():
+            self.params[name] = {k: (torch.from_numpy(v).to(self.dev) if isinstance(v, np.ndarray)
+                                     else v) for k, v in p.items()}
+
+    def fold(self):
+        for op in self.net.convs():
+            p = self.params[op.name]
+            self.folded[op.name] = B.fold_bn(p["W"], p["b"], p["gamma"], p["beta"], p["mu"],
+                                             p["var"], p["eps"])
+
+    def forward_f32(self, x, observe=None):
+        """fp32 forward of the folded network; ``observe(key, tensor)`` sees every activation."""
+        t = {self.net.input: x}
+        N = x.shape[0]
+        for op in self.net.ops:
+            d = self.net.tensors[op.dst]
+            if op.kind == "maxpool":
+                t[op.dst] = B.maxpool_f32(t[op.src], op.R, op.S, op.stride, op.pad, d.H, d.W)
+            else:
+                Wf, bf = self.folded[op.name]
+                desc = self._desc(op, N)
+                desc.in_c_stride = desc.out_c_stride = desc.res_c_stride = 0
+                if op.res is not None and observe:
+                    desc.relu = 0                  # the branch's own output, before the sum
+                    observe(op.name + ":branch", B.conv_f32_ref(desc, t[op.src], Wf, bf))
+                desc.relu = int(op.relu)
+                y = B.conv_f32_ref(desc, t[op.src], Wf, bf, t[op.res] if op.res else None)
+                if d.C == op.K:
+                    t[op.dst] = y
+                else:
+                    if op.dst not in t:
+                        t[op.dst] = torch.zeros((N, d.H, d.W, d.C), dtype=torch.float32,
+                                                device=self.dev)
+                    t[op.dst][..., op.dst_c_off:op.dst_c_off + op.K] = y
+            if observe and op.dst in t and (op.kind != "conv" or d.C == op.K):
+                observe(op.dst, t[op.dst])
+        if observe:
+            for op in self.net.convs():         # concat targets: observe once complete
+                d = self.net.tensors[op.dst]
+                if d.C != op.K:
+                    observe(op.dst, t[op.dst])
+        return t
+
+    def calibrate(self, batches):
+        """Running max-abs over fp32 forwards of ``batches`` (device fp32 NHWC tensors)."""
+        slots = {}
+
+        def observe(key, tensor):
+            if key not in slots:
+                slots[key] = torch.zeros(1, dtype=torch.float32, device=self.dev)
+            B.calibrate_maxabs(tensor.contiguous(), slots[key])
+
+        for x in batches:
+            observe(self.net.input, x)
+            self.forward_f32(x, observe)
+        keys = list(slots)
+        vals = torch.cat([slots[k] for k in keys]).cpu().numpy()
+        q = {k: B.qfactor(float(v), P_ACT) for k, v in zip(keys, vals)}
+        for op in self.net.ops:
+            if op.kind == "conv" and op.res is not None:
+                q[op.dst] = max(q[op.name + ":branch"], q[op.res])   # the + rule
+            if op.kind == "maxpool":
+                q[op.dst] = q[op.src]
+        self.q = q
+        return q
+
+    def set_factors(self, q):
+        self.q = {k: float(v) for k, v in q.items()}
+
+    def quantize_weights(self):
+        slots = {}
+        for op in self.net.convs():
+            Wf, _ = self.folded[op.name]
+            slots[op.name] = torch.zeros(1, dtype=torch.float32, device=self.dev)
+            B.calibrate_maxabs(Wf, slots[op.name])
+        names = list(slots)
+        vals = torch.cat([slots[k] for k in names]).cpu().numpy()
+        self.zw_dense = {}
+        for name, v in zip(names, vals):
+            op = next(o for o in self.net.convs() if o.name == name)
+            Wf, bf = self.folded[name]
+            q_w = B.qfactor(float(v), P_W)
+            z_w = B.quantize(Wf, q_w, P_W)
+            self.zw_dense[name] = z_w
+            self.qw[name] = q_w
+            self.wq[name] = (B.pack_weights(self.desc[name], z_w),
+                             B.quantize_bias(bf, self.q[op.src], q_w))
+
+    # ------------------------------------------------------------------ online step
+    def allocate(self):
+        for name, t in self.net.tensors.items():
+            self.act[name] = torch.zeros((self.N, t.H, t.W, _pad_c(t.C)), dtype=torch.int8,
+                                         device=self.dev)
+
+    def quantize_input(self, x):
+        t = self.net.tensors[self.net.input]
+        if _pad_c(t.C) != t.C:
+            B.quantize_pad_channels(x, _pad_c(t.C), self.q[self.net.input], P_ACT,
+                                    out=self.act[self.net.input])
+        else:
+            B.quantize(x, self.q[self.net.input], P_ACT, out=self.act[self.net.input])
+
+    def run_layers(self, acc_dump=None):
+        for op in self.net.ops:
+            d = self.net.tensors[op.dst]
+            if op.kind == "maxpool":
+                s = self.net.tensors[op.src]
+                B._check(B.lib.q8_maxpool_i8(self.act[op.src].data_ptr(), self.N, s.H, s.W,
+                                             _pad_c(s.C), op.R, op.S, op.stride, op.pad, d.H, d.W,
+                                             self.act[op.dst].data_ptr(), B._stream()))
+                continue
+            packed, bias = self.wq[op.name]
+            res = self.act[op.res] if op.res else None
+            q_res = self.q[op.res] if op.res else 0.0
+            dump = acc_dump.get(op.name) if acc_dump else None
+            B.conv_int8(self.desc[op.name], self.act[op.src], packed, bias, self.q[op.src],
+                        self.qw[op.name], self.q[op.dst], res, q_res, out=self.act[op.dst],
+                        acc_dump=dump)
+
+    def forward(self, x):
+        """x: fp32 NHWC device tensor of the network input.  Returns the int8 outputs."""
+        if not self.act:
+            self.allocate()
+        self.quantize_input(x)
+        self.run_layers()
+        return [self.act[o] for o in self.net.outputs]
+
+    def capture(self, x):
+        """Record forward(x) into a HIP graph (x's storage is read at every replay)."""
+        if not self.act:
+            self.allocate()
+        self.forward(x)                     # warm-up outside capture
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.forward(x)
+        self.graph = g
+        return g

@@ -1,0 +1,82 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments before anything is launched (so these run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+B = pytest.importorskip("paper_1805_08691_amd.binding")
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "q8conv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(q8_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 16
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+
+
+def test_strerror():
+    assert B.lib.q8_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(B.lib.q8_strerror(code)) > 3
+
+
+def test_qfactor_and_extents():
+    assert B.qfactor(0.0, 7) == 1.0
+    assert B.qfactor(127.0, 7) == 1.0
+    assert B.ConvDesc(1, 224, 224, 3, 64, 7, 7, 2, 2, 3, 3).Ho == 112
+    assert B.ConvDesc(1, 19, 19, 512, 1024, 3, 3, 1, 1, 6, 6, 6, 6).Wo == 19
+    assert B.ConvDesc(1, 2, 2, 16, 16, 3, 3).Ho == 0
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    fake = C.c_void_p(0x1000)      # never dereferenced: every call below fails validation first
+    L = B.lib
+    assert L.q8_calibrate_maxabs(fake, 10, None, None) == -1
+    assert L.q8_calibrate_maxabs(None, 10, fake, None) == -1
+    assert L.q8_calibrate_maxabs(C.c_void_p(0x1002), 10, fake, None) == -3
+    assert L.q8_calibrate_maxabs(None, 0, fake, None) == 0            # empty tensor: no-op
+    assert L.q8_quantize(fake, 10, 0.0, 7, fake, None) == -1          # q <= 0
+    assert L.q8_quantize(fake, 10, float("nan"), 7, fake, None) == -1
+    assert L.q8_quantize(fake, 10, float("inf"), 7, fake, None) == -1
+    assert L.q8_quantize(fake, 10, 1.0, 8, fake, None) == -1          # p outside 1..7
+    assert L.q8_quantize(fake, 10, 1.0, 0, fake, None) == -1
+    assert L.q8_quantize(None, 10, 1.0, 7, fake, None) == -1
+    assert L.q8_quantize(None, 0, 1.0, 7, None, None) == 0
+    assert L.q8_quantize_pad_channels(fake, 10, 5, 4, 1.0, 7, fake, None) == -1
+    assert L.q8_quantize_bias(fake, 4, -1.0, 1.0, fake, None) == -1
+    assert L.q8_dequantize(fake, 4, 0.0, fake, None) == -1
+    assert L.q8_dequantize(None, 4, 1.0, fake, None) == -1
+    assert L.q8_fold_bn(fake, None, fake, fake, fake, fake, 1e-5, -1, 4, fake, fake, None) == -1
+    assert L.q8_fold_bn(fake, None, None, fake, fake, fake, 1e-5, 2, 4, fake, fake, None) == -1
+    assert L.q8_fold_bn(fake, None, fake, fake, fake, fake, 1e-5, 0, 4, fake, fake, None) == 0
+
+    d = B.ConvDesc(1, 8, 8, 16, 16, 3, 3, pad_h=1, pad_w=1)
+    ok = (fake, fake, None, 1.0, 1.0, 1.0, None, 0.0, fake, None, None)
+    assert L.q8_conv_int8(None, *ok) == -1
+    bad = B.ConvDesc(1, 8, 8, 16, 16, 3, 3, stride_h=0)
+    assert L.q8_conv_int8(C.byref(bad), *ok) == -1
+    odd = B.ConvDesc(1, 8, 8, 24, 16, 3, 3)          # C neither <= 4 nor a multiple of 16
+    assert L.q8_conv_int8(C.byref(odd), *ok) == -2
+    assert B.packed_weight_bytes(odd) == 0
+    assert L.q8_conv_int8(C.byref(d), fake, fake, None, 0.0, 1.0, 1.0, None, 0.0, fake, None,
+                          None) == -1
+    assert L.q8_conv_int8(C.byref(d), None, fake, None, 1.0, 1.0, 1.0, None, 0.0, fake, None,
+                          None) == -1
+    assert L.q8_conv_int8(C.byref(d), C.c_void_p(0x1004), fake, None, 1.0, 1.0, 1.0, None, 0.0,
+                          fake, None, None) == -3     # activations not 16-byte aligned
+    narrow = B.ConvDesc(1, 8, 8, 16, 16, 3, 3, out_c_stride=8)
+    assert L.q8_conv_int8(C.byref(narrow), *ok) == -1  # K does not fit the output stride
+    resq = (fake, fake, None, 1.0, 1.0, 1.0, fake, 0.0, fake, None, None)
+    assert L.q8_conv_int8(C.byref(d), *resq) == -1     # residual with q_res <= 0
+    empty = B.ConvDesc(0, 8, 8, 16, 16, 3, 3)
+    assert L.q8_conv_int8(C.byref(empty), None, None, None, 1.0, 1.0, 1.0, None, 0.0, None, None,
+                          None) == 0                   # empty batch: nothing to do
+    assert B.packed_weight_bytes(d) == 16 * 3 * 3 * 16
+    assert B.packed_weight_bytes(B.ConvDesc(1, 8, 8, 3, 64, 7, 7)) == 64 * 7 * 2 * 16
+    assert L.q8_maxpool_i8(fake, 1, 8, 8, 4, 3, 3, 2, 3, 4, 4, fake, None) == -1   # pad >= window

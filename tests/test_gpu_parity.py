@@ -1,0 +1,307 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact for int8 codes, int32 accumulators, int32 bias, max-abs and the folded fp32
+weights (each is a fixed sequence of IEEE operations); dequantised values within 1e-5
+relative (they are in fact bit-equal: one fp32 multiply).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from oracle import net as onet
+from paper_1805_08691_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_1805_08691_amd.binding as b
+    assert torch.cuda.is_available()
+    return b
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------ calibration / Q / D
+@pytest.mark.parametrize("n", [0, 1, 3, 5, 63, 1024, 4099, 1_000_003, 8_388_608 + 7])
+@pytest.mark.parametrize("offset", [0, 1, 3])
+def test_maxabs(B, n, offset):
+    rng = np.random.default_rng(n + offset)
+    x = rng.standard_normal(n + offset).astype(np.float32)
+    if n > 10:
+        x[offset + int(rng.integers(0, n))] = -7.25     # a single extreme, negative
+    xd = dev(x)[offset:]
+    slot = torch.zeros(1, device="cuda")
+    B.calibrate_maxabs(xd, slot)
+    assert host(slot)[0] == orc.maxabs(x[offset:])
+    # running maximum over a second batch
+    x2 = (x * np.float32(0.5)).astype(np.float32)
+    x2[-1:] = 9.5
+    B.calibrate_maxabs(dev(x2)[offset:], slot)
+    assert host(slot)[0] == max(orc.maxabs(x[offset:]), orc.maxabs(x2[offset:]))
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 7, 1023, 65536 + 5, 3_000_001])
+@pytest.mark.parametrize("offset", [0, 1, 2])
+@pytest.mark.parametrize("p", [7, 4])
+def test_quantize(B, n, offset, p):
+    rng = np.random.default_rng(100 + n + offset)
+    x = (rng.standard_normal(n + offset) * 2).astype(np.float32)
+    q = np.float32(0.0371)
+    if n > 64:      # exact ties and saturating values
+        k = np.arange(-40, 24)
+        x[offset:offset + 64] = (k.astype(np.float32) + np.float32(0.5)) * q
+        x[offset + 64 - 4:offset + 64] = [1e6, -1e6, 127.5 * q, -128.5 * q]
+    z = B.quantize(dev(x)[offset:], float(q), p)
+    assert np.array_equal(host(z), orc.Q(x[offset:], q, p))
+
+
+def test_quantize_pad_channels(B):
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((2, 9, 11, 3)).astype(np.float32)
+    q = orc.qfactor(orc.maxabs(x), 7)
+    z = host(B.quantize_pad_channels(dev(x), 4, float(q), 7))
+    assert z.shape == (2, 9, 11, 4)
+    assert np.array_equal(z[..., :3], orc.Q(x, q, 7)) and np.all(z[..., 3] == 0)
+    z = host(B.quantize_pad_channels(dev(x), 16, float(q), 7))
+    assert np.array_equal(z[..., :3], orc.Q(x, q, 7)) and np.all(z[..., 3:] == 0)
+
+
+@pytest.mark.parametrize("n", [0, 1, 5, 1024, 1_000_003])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_dequantize(B, n, offset):
+    rng = np.random.default_rng(200 + n)
+    z = rng.integers(-128, 128, n + offset).astype(np.int8)
+    q = np.float32(0.0123)
+    r = host(B.dequantize(dev(z)[offset:], float(q)))
+    want = orc.D(z[offset:], q)
+    assert np.array_equal(r, want)
+    assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want))
+
+
+def test_quantize_bias(B):
+    rng = np.random.default_rng(9)
+    b = (rng.standard_normal(1000) * 0.1).astype(np.float32)
+    b[:4] = [1e9, -1e9, 0.0, 1e-12]
+    for q_x, q_w in [(0.0137, 0.00091), (1.0, 1.0), (3e-3, 2.5e-4)]:
+        z = host(B.quantize_bias(dev(b), q_x, q_w))
+        assert np.array_equal(z, orc.Q31_bias(b, q_x, q_w))
+
+
+@pytest.mark.parametrize("K,RSC", [(1, 1), (3, 7), (64, 576), (130, 1030)])
+def test_fold_bn(B, K, RSC):
+    rng = np.random.default_rng(K * 1000 + RSC)
+    W = rng.standard_normal((K, RSC)).astype(np.float32)
+    b = rng.standard_normal(K).astype(np.float32)
+    gamma = rng.uniform(.5, 1.5, K).astype(np.float32)
+    beta = (rng.standard_normal(K) * .1).astype(np.float32)
+    mu = (rng.standard_normal(K) * .1).astype(np.float32)
+    var = rng.uniform(.5, 1.5, K).astype(np.float32)
+    Wf, bf = B.fold_bn(dev(W), dev(b), dev(gamma), dev(beta), dev(mu), dev(var), 1e-5)
+    Wo, bo = orc.fold_bn(W, b, gamma, beta, mu, var, 1e-5)
+    assert np.array_equal(host(Wf), Wo) and np.array_equal(host(bf), bo)
+    Wf, bf = B.fold_bn(dev(W), None, dev(gamma), dev(beta), dev(mu), dev(var), 1e-5)
+    Wo, bo = orc.fold_bn(W, None, gamma, beta, mu, var, 1e-5)
+    assert np.array_equal(host(Wf), Wo) and np.array_equal(host(bf), bo)
+
+
+# ------------------------------------------------------------------ convolution
+CONV_CASES = [
+    # several tiles and ragged tails in pixels, channels and reduction
+    dict(N=2, H=14, W=14, C=32, K=48, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=3, H=13, W=11, C=64, K=64, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=1, H=56, W=56, C=64, K=64, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=2, H=28, W=28, C=128, K=160, R=1, S=1),
+    dict(N=2, H=28, W=28, C=256, K=128, R=1, S=1, stride_h=2, stride_w=2),
+    dict(N=1, H=17, W=17, C=128, K=192, R=1, S=7, pad_w=3),
+    dict(N=1, H=17, W=17, C=128, K=192, R=7, S=1, pad_h=3),
+    dict(N=1, H=19, W=19, C=64, K=96, R=3, S=3, dil_h=6, dil_w=6, pad_h=6, pad_w=6),
+    dict(N=2, H=12, W=12, C=48, K=64, R=5, S=5, pad_h=2, pad_w=2),
+    dict(N=1, H=35, W=35, C=80, K=24, R=3, S=3, stride_h=2, stride_w=2),
+    dict(N=1, H=10, W=10, C=16, K=126, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=2, H=9, W=9, C=16, K=17, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=1, H=3, W=3, C=256, K=16, R=3, S=3),
+    dict(N=4, H=1, W=1, C=256, K=84, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=2, H=37, W=41, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
+    dict(N=1, H=20, W=20, C=3, K=32, R=3, S=3, stride_h=2, stride_w=2),
+    dict(N=1, H=16, W=16, C=4, K=8, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=1, H=7, W=7, C=512, K=2048 // 8, R=1, S=1),
+]
+
+
+def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=0):
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(seed)
+    Cs = 4 if g.C < 4 else g.C                      # stored channels of the input
+    x = rng.integers(-128, 128, (g.N, g.H, g.W, Cs)).astype(np.int8)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, g.K).astype(np.int32) if with_bias else None
+    Ho, Wo = g.Ho, g.Wo
+    q_x, q_w = np.float32(0.021), np.float32(0.0017)
+    fan = g.R * g.S * g.C
+    # accumulators have std ~ 74^2 sqrt(fan): aim at ~40 output codes std, a few saturate
+    q_out = np.float32(q_x * q_w * 5476.0 * np.sqrt(fan) / 40.0)
+    q_res = np.float32(0.3) * q_out
+    res = rng.integers(-128, 128, (g.N, Ho, Wo, g.K)).astype(np.int8) if with_res else None
+
+    go = orc.ConvGeom(**{**geom, "in_c_stride": Cs})
+    acc_o = orc.conv_i8(go, x, w, b)
+    m = orc.requant_scale(q_x, q_w, q_out)
+    m_r = orc.residual_scale(q_res, q_out) if with_res else 0.0
+    out_cs = g.K + out_pad
+    want = np.full((g.N, Ho, Wo, out_cs), 77, np.int8)
+    orc.requant(acc_o, m, relu, res, m_r, out=want, out_c_stride=out_cs, out_c_off=out_off)
+
+    d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                   g.dil_h, g.dil_w, relu=relu, in_c_stride=Cs, out_c_stride=out_cs,
+                   out_c_off=out_off)
+    packed = B.pack_weights(d, dev(w))
+    out = torch.full((g.N, Ho, Wo, out_cs), 77, dtype=torch.int8, device="cuda")
+    dump = torch.zeros((g.N, Ho, Wo, g.K), dtype=torch.int32, device="cuda")
+    B.conv_int8(d, dev(x), packed, None if b is None else dev(b), float(q_x), float(q_w),
+                float(q_out), None if res is None else dev(res), float(q_res), out=out,
+                acc_dump=dump)
+    assert np.array_equal(host(dump), acc_o), "int32 accumulators differ"
+    got = host(out)
+    assert np.array_equal(got, want), "int8 outputs differ"
+    frac_sat = np.mean(np.abs(want[..., out_off:out_off + g.K].astype(int)) >= 127)
+    assert frac_sat < 0.5
+
+
+@pytest.mark.parametrize("idx", range(len(CONV_CASES)))
+def test_conv_shapes(B, idx):
+    geom = CONV_CASES[idx]
+    _run_conv_case(B, geom, relu=True, with_res=False, with_bias=True, seed=idx)
+    _run_conv_case(B, geom, relu=(idx % 2 == 0), with_res=True, with_bias=(idx % 3 != 0),
+                   seed=1000 + idx)
+
+
+@pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
+def test_conv_channel_slice_of_concat(B, out_pad, out_off):
+    geom = dict(N=2, H=9, W=9, C=32, K=40, R=3, S=3, pad_h=1, pad_w=1)
+    _run_conv_case(B, geom, relu=True, with_res=False, with_bias=True, seed=5,
+                   out_pad=out_pad, out_off=out_off)
+
+
+def test_conv_input_channel_stride(B):
+    # a conv that reads the first 32 channels of a 48-channel tensor
+    rng = np.random.default_rng(3)
+    g = orc.ConvGeom(N=2, H=10, W=10, C=32, K=32, R=3, S=3, pad_h=1, pad_w=1, in_c_stride=48)
+    x = rng.integers(-128, 128, (2, 10, 10, 48)).astype(np.int8)
+    w = rng.integers(-128, 128, (32, 3, 3, 32)).astype(np.int8)
+    acc_o = orc.conv_i8(g, x, w)
+    d = B.ConvDesc(2, 10, 10, 32, 32, 3, 3, pad_h=1, pad_w=1, in_c_stride=48)
+    dump = torch.zeros((2, 10, 10, 32), dtype=torch.int32, device="cuda")
+    B.conv_int8(d, dev(x), B.pack_weights(d, dev(w)), None, 1.0, 1.0, 1000.0, acc_dump=dump)
+    assert np.array_equal(host(dump), acc_o)
+
+
+def test_conv_batch_elements_are_independent(B):
+    rng = np.random.default_rng(4)
+    x = rng.integers(-128, 128, (5, 14, 14, 64)).astype(np.int8)
+    w = rng.integers(-128, 128, (64, 3, 3, 64)).astype(np.int8)
+    d5 = B.ConvDesc(5, 14, 14, 64, 64, 3, 3, pad_h=1, pad_w=1, relu=1)
+    d1 = B.ConvDesc(1, 14, 14, 64, 64, 3, 3, pad_h=1, pad_w=1, relu=1)
+    wp = B.pack_weights(d5, dev(w))
+    full = host(B.conv_int8(d5, dev(x), wp, None, 0.02, 0.002, 0.08))
+    for i in (0, 2, 4):
+        one = host(B.conv_int8(d1, dev(x[i:i + 1]), wp, None, 0.02, 0.002, 0.08))
+        assert np.array_equal(one[0], full[i])
+
+
+# ------------------------------------------------------------------ whole configurations
+def _oracle_pipeline(cfg_id, batch, calib_library):
+    cfg = wl.CONFIGS[cfg_id]
+    net = cfg["make"]()
+    params = {op.name: wl.conv_params(cfg_id, i, op) for i, op in enumerate(net.convs())}
+    x = wl.input_batch(cfg_id, net, batch, 0, relu=cfg["relu_input"])
+    folded = onet.fold_all(net, params)
+    q = onet.calibrate(net, folded, [x], use_library=calib_library)
+    qparams = onet.quantize_params(net, folded, q)
+    z_in = orc.Q(x, q[net.input], 7)
+    acts, accs = onet.forward_i8(net, qparams, q, z_in, keep_acc=True)
+    return net, params, x, folded, q, qparams, z_in, acts, accs
+
+
+def _gpu_pipeline_checks(B, cfg_id, batch, calib_library):
+    from paper_1805_08691_amd.engine import Engine
+    net, params, x, folded, q, qparams, z_in, acts, accs = _oracle_pipeline(
+        cfg_id, batch, calib_library)
+    eng = Engine(net, batch)
+    eng.load_params(params)
+    eng.fold()
+    for name, (Wf, bf) in folded.items():          # Eq. BN: bit-exact
+        assert np.array_equal(host(eng.folded[name][0]), Wf)
+        assert np.array_equal(host(eng.folded[name][1]), bf)
+    eng.set_factors(q)                             # frozen factor table from the oracle side
+    eng.quantize_weights()
+    for name, qp in qparams.items():               # q_w, int8 filters, int32 bias: bit-exact
+        assert np.float32(eng.qw[name]) == qp["q_w"]
+        assert np.array_equal(host(eng.zw_dense[name]), qp["z_w"])
+        assert np.array_equal(host(eng.wq[name][1]), qp["z_b"])
+    eng.allocate()
+    xd = dev(x)
+    slot = torch.zeros(1, device="cuda")           # the input factor from the GPU's own max-abs
+    B.calibrate_maxabs(xd, slot)
+    assert np.float32(B.qfactor(float(host(slot)[0]), 7)) == q[net.input]
+    eng.quantize_input(xd)
+    assert np.array_equal(host(eng.act[net.input]), z_in)
+    dumps = {op.name: torch.zeros((batch, net.tensors[op.dst].H, net.tensors[op.dst].W, op.K),
+                                  dtype=torch.int32, device="cuda") for op in net.convs()}
+    eng.run_layers(acc_dump=dumps)
+    for op in net.convs():
+        assert np.array_equal(host(dumps[op.name]), accs[op.name]), op.name
+        assert np.array_equal(host(eng.act[op.dst]), acts[op.dst]), op.name
+    for o in net.outputs:                          # Eq. D on what leaves the int8 domain
+        r = host(B.dequantize(eng.act[o], float(q[o])))
+        want = orc.D(acts[o], q[o])
+        assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want))
+        assert len(np.unique(acts[o])) > 32        # not degenerate
+    return eng, net, xd, acts
+
+
+def test_config1_single_conv(B):
+    _gpu_pipeline_checks(B, 1, 1, calib_library=False)
+
+
+def test_config2_bottleneck_block(B):
+    eng, net, xd, acts = _gpu_pipeline_checks(B, 2, 32, calib_library=True)
+    # the same through a captured HIP graph, replayed with eager work in between
+    eng.capture(xd)
+    for _ in range(3):
+        for t in eng.act.values():
+            if t is not eng.act[net.input]:
+                t.fill_(55)
+        torch.cuda.synchronize()
+        eng.graph.replay()
+        for o in net.outputs:
+            assert np.array_equal(host(eng.act[o]), acts[o])
+
+
+def test_gpu_calibration_matches_oracle_closely(B):
+    # the GPU's own calibration (fp32 forward in a different summation order) gives
+    # factors equal to the oracle's up to fp32 rounding of the activations
+    from paper_1805_08691_amd.engine import Engine
+    cfg_id, batch = 2, 4
+    cfg = wl.CONFIGS[cfg_id]
+    net = cfg["make"]()
+    params = {op.name: wl.conv_params(cfg_id, i, op) for i, op in enumerate(net.convs())}
+    xs = [wl.input_batch(cfg_id, net, batch, i, relu=True) for i in range(2)]
+    folded = onet.fold_all(net, params)
+    q_o = onet.calibrate(net, folded, xs, use_library=False)
+    eng = Engine(net, batch)
+    eng.load_params(params)
+    eng.fold()
+    q_g = eng.calibrate([dev(x) for x in xs])
+    assert set(q_g) == set(q_o)
+    for k in q_o:
+        assert abs(q_g[k] - float(q_o[k])) <= 1e-5 * float(q_o[k]), k
