@@ -13,6 +13,7 @@
 // column (= pixel) in four consecutive registers of a lane, which is what the epilogue
 // wants: bias, scale, residual, ReLU, Round, clamp on four channels, one packed store.
 #include "q8_common.h"
+#pragma clang fp contract(off)   // the epilogue's op order is part of the result
 
 namespace {
 

@@ -2,9 +2,13 @@
 // quantiser Q, the dequantiser D, batch-norm folding and the p = 31 bias quantiser
 // (Eq. Q, Eq. D, Eq. BN and the calibration text of arxiv 1805.08691).
 //
-// All floating point uses the explicitly rounded intrinsics (__fdiv_rn, __fmul_rn, ...)
-// so that no multiply-add is fused and every step is one IEEE binary32 operation.
+// Every floating-point step is one IEEE binary32 (or binary64) operation: contraction
+// into fused multiply-adds is switched off for this file, and division and square root
+// are the correctly rounded ones (hipcc -fhip-fp32-correctly-rounded-divide-sqrt, the
+// default).  __fsqrt_rn is NOT used: without OCML_BASIC_ROUNDED_OPERATIONS it maps to the
+// approximate native square root.
 #include "q8_common.h"
+#pragma clang fp contract(off)
 
 namespace {
 
@@ -184,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void fold_bn_kernel(
     const float* __restrict__ beta, const float* __restrict__ mu, const float* __restrict__ var,
     float eps, int K, int RSC, float* __restrict__ W_out, float* __restrict__ b_out) {
   const int k = blockIdx.y;
-  const float s = __fdiv_rn(gamma[k], __fsqrt_rn(__fadd_rn(var[k], eps)));
+  const float s = __fdiv_rn(gamma[k], sqrtf(__fadd_rn(var[k], eps)));
   const size_t row = (size_t)k * RSC;
   for (int j = blockIdx.x * kThreads + threadIdx.x; j < RSC; j += gridDim.x * kThreads)
     W_out[row + j] = __fmul_rn(s, W[row + j]);
