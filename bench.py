@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the int8 quantised-convolution path on one MI355X.
+
+A step = one pass of the online hot path over one resident batch: Q on the fp32 input
+image, every fused int8 convolution of the network (bias, ReLU, residual sum, requantise
+in the epilogue), D on the output that leaves the int8 domain.  The offline steps (BN
+fold, max-abs calibration, weight/bias quantisation) are run once before the timed
+region and timed separately (reported under "offline").  Default workload: the full
+ResNet-50 conv stack at batch 64 (config 3), the configuration the headline metric names.
+
+Prints ONE JSON line on stdout; per-layer detail goes to stderr (and --layers-out).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, POP/s -> TOP/s
+PEAK_HBM_GBS = 8000.0
+RIDGE = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def conv_work(net, op, N):
+    """Algorithmic int8 ops and HBM bytes of one conv launch (true C and K, no padding)."""
+    s, d = net.tensors[op.src], net.tensors[op.dst]
+    npix = N * d.H * d.W
+    ops = 2 * npix * op.K * op.C * op.R * op.S
+    if op.R == 1 and op.S == 1 and op.stride > 1:
+        in_bytes = npix * op.C                     # only the pixels a strided 1x1 touches
+    else:
+        in_bytes = N * s.H * s.W * op.C
+    byts = in_bytes + npix * op.K + op.K * op.R * op.S * op.C + 4 * op.K
+    if op.res:
+        byts += npix * op.K
+    return ops, byts
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload: 1, 2 or 3 (BASELINE configs)")
+    ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
+    ap.add_argument("--layers-out", default="", help="write the per-layer table (JSON) here")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (batch data-parallel sharding is a "
+              "design note, not code); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1805_08691_amd import binding as B, workloads as wl
+    from paper_1805_08691_amd.engine import Engine
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    net = cfg["make"]()
+    N = args.batch or cfg["batch"]
+    convs = net.convs()
+    log(f"workload: {net.name} batch {N}: {len(convs)} convs, "
+        f"{net.macs_per_image() / 1e9:.3f} GMAC/image")
+
+    # ---------------- offline: parameters, fold, calibrate, quantise weights ---------------
+    params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
+    eng = Engine(net, N)
+    eng.load_params(params)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.fold()
+    torch.cuda.synchronize()
+    t_fold = time.perf_counter() - t0
+    if args.config == 3:
+        calib = [torch.from_numpy(wl.input_batch(args.config, net, 8, 100 + i)).cuda()
+                 for i in range(8)]                       # 8 seeded batches of 8 images
+    else:
+        calib = [torch.from_numpy(wl.input_batch(args.config, net, N, 0,
+                                                 relu=cfg["relu_input"])).cuda()]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.calibrate(calib)
+    torch.cuda.synchronize()
+    t_cal = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    eng.quantize_weights()
+    torch.cuda.synchronize()
+    t_qw = time.perf_counter() - t0
+    del calib
+    eng.allocate()
+
+    x = torch.from_numpy(wl.input_batch(args.config, net, N, 0, relu=cfg["relu_input"])).cuda()
+    out_name = net.outputs[0]
+    out_f32 = torch.empty(eng.act[out_name].shape, dtype=torch.float32, device="cuda")
+
+    def step():
+        eng.quantize_input(x)
+        eng.run_layers()
+        B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
+
+    step()
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+    run = graph.replay if graph is not None else step
+
+    # ---------------- timed region ---------------------------------------------------------
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    images_per_s = N * args.steps / elapsed
+
+    # ---------------- per-launch durations with HIP events on the launch stream ------------
+    # The host enqueues a whole chained pass behind a spin kernel so the GPU runs the
+    # layers back to back; events between launches give each kernel's duration.
+    ops_list = [o for o in net.ops]
+    reps = 7
+    dur = np.zeros((reps, len(ops_list) + 2))
+    for r in range(reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(ops_list) + 3)]
+        torch.cuda._sleep(20_000_000)
+        ev[0].record()
+        eng.quantize_input(x)
+        ev[1].record()
+        for i, op in enumerate(ops_list):
+            if op.kind == "maxpool":
+                s, d = net.tensors[op.src], net.tensors[op.dst]
+                B._check(B.lib.q8_maxpool_i8(eng.act[op.src].data_ptr(), N, s.H, s.W,
+                                             max(s.C, 4), op.R, op.S, op.stride, op.pad, d.H, d.W,
+                                             eng.act[op.dst].data_ptr(), B._stream()))
+            else:
+                packed, bias = eng.wq[op.name]
+                res = eng.act[op.res] if op.res else None
+                B.conv_int8(eng.desc[op.name], eng.act[op.src], packed, bias, eng.q[op.src],
+                            eng.qw[op.name], eng.q[op.dst], res, eng.q[op.res] if op.res else 0.0,
+                            out=eng.act[op.dst])
+            ev[i + 2].record()
+        B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
+        ev[-1].record()
+        torch.cuda.synchronize()
+        for i in range(len(ops_list) + 2):
+            dur[r, i] = ev[i].elapsed_time(ev[i + 1]) * 1e3      # us
+    med = np.median(dur, axis=0)
+
+    layers = []
+    by_variant = {}
+    tot_ops = tot_us = tot_bytes = 0.0
+    roof_us = 0.0
+    for i, op in enumerate(ops_list):
+        if op.kind != "conv":
+            continue
+        ops, byts = conv_work(net, op, N)
+        us = float(med[i + 1])
+        variant = B.conv_variant(eng.desc[op.name])
+        bound = "mfma" if ops / byts > RIDGE else "hbm"
+        t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)) * 1e6
+        layers.append(dict(name=op.name, C=op.C, K=op.K, R=op.R, S=op.S, stride=op.stride,
+                           H=net.tensors[op.src].H, variant=variant, us=round(us, 2),
+                           tops=round(ops / us / 1e6, 1), gbs=round(byts / us / 1e3, 1),
+                           bound=bound, roof_us=round(t_roof, 2), frac=round(t_roof / us, 3)))
+        v = by_variant.setdefault(variant, dict(ops=0.0, us=0.0, bytes=0.0, launches=0))
+        v["ops"] += ops; v["us"] += us; v["bytes"] += byts; v["launches"] += 1
+        tot_ops += ops; tot_us += us; tot_bytes += byts; roof_us += t_roof
+    for L in layers:
+        log("{name:22s} C={C:<4d} K={K:<4d} {R}x{S}/{stride} H={H:<3d} {variant:30s} {us:8.2f} us "
+            "{tops:7.1f} TOP/s {gbs:7.1f} GB/s  {bound:4s} roof {roof_us:6.2f} us frac {frac:.3f}"
+            .format(**L))
+    dom_name, dom = max(by_variant.items(), key=lambda kv: kv[1]["us"])
+    for k, v in by_variant.items():
+        log(f"variant {k}: {v['launches']} launches, avg {v['us'] / v['launches']:.2f} us, "
+            f"{v['ops'] / v['us'] / 1e6:.1f} TOP/s")
+    agg_tops = tot_ops / tot_us / 1e6
+    log(f"conv kernels: sum {tot_us:.1f} us per pass, {agg_tops:.1f} TOP/s aggregate "
+        f"({100 * agg_tops / PEAK_INT8_TOPS:.1f}% of int8 MFMA peak), "
+        f"roofline sum {roof_us:.1f} us; quantize {med[0]:.1f} us; dequantize {med[-1]:.1f} us; "
+        f"graph step {ms_per_step * 1e3:.1f} us")
+
+    dom_tops = dom["ops"] / dom["us"] / 1e6
+    roofline = dict(bound="mfma", kernel=dom_name, launches_per_step=dom["launches"],
+                    avg_launch_us=round(dom["us"] / dom["launches"], 3),
+                    achieved=round(dom_tops, 2), peak=PEAK_INT8_TOPS, unit="TOP/s",
+                    frac=round(dom_tops / PEAK_INT8_TOPS, 4), traffic=None,
+                    hbm_gbs=round(dom["bytes"] / dom["us"] / 1e3, 1),
+                    hbm_frac=round(dom["bytes"] / dom["us"] / 1e3 / PEAK_HBM_GBS, 4))
+
+    # ---------------- the oracle on the host cores, bounded sample --------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        from oracle import net as onet
+        sample = {1: 1, 2: 4, 3: 2}[args.config]
+        sample = min(sample, N)
+        xs = x[:sample].cpu().numpy()
+        folded = onet.fold_all(net, params)
+        q = {k: np.float32(v) for k, v in eng.q.items()}
+        qparams = onet.quantize_params(net, folded, q)
+        t0 = time.perf_counter()
+        z_in = orc.Q(xs, q[net.input], 7)
+        acts = onet.forward_i8(net, qparams, q, z_in)
+        orc.D(acts[out_name], q[out_name])
+        t_cpu = time.perf_counter() - t0
+        same = bool(np.array_equal(acts[out_name], eng.act[out_name][:sample].cpu().numpy()))
+        log(f"oracle: {sample} image(s) in {t_cpu:.2f} s on {orc.num_threads()} threads; "
+            f"output equals the GPU's: {same}")
+        cpu = dict(value=round(sample / t_cpu, 3), unit="images/s", cores=orc.num_threads(),
+                   kind="oracle", sample=f"{sample} image(s) of the same batch, whole conv stack",
+                   matches_gpu=same)
+
+    result = {
+        "metric": "ResNet-50 int8 images/sec at batch 64" if args.config == 3
+                  else f"{net.name} int8 images/sec at batch {N}",
+        "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{net.name} conv stack, batch {N}, NHWC int8, "
+                               f"{len(convs)} fused convs", "batch": N,
+                   "launch": "eager" if graph is None else "hip_graph"},
+        "int8_conv_tops": round(agg_tops, 1),
+        "pct_of_mfma_int8_peak": round(100 * agg_tops / PEAK_INT8_TOPS, 2),
+        "conv_kernel_us_per_step": round(tot_us, 1),
+        "conv_roofline_us_per_step": round(roof_us, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "offline": {"fold_bn_ms": round(t_fold * 1e3, 2), "calibrate_ms": round(t_cal * 1e3, 2),
+                    "quantize_weights_ms": round(t_qw * 1e3, 2)},
+    }
+    if args.layers_out:
+        with open(args.layers_out, "w") as f:
+            json.dump(dict(result=result, layers=layers, variants=by_variant), f, indent=1)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,11 @@ int q8_conv_int8(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packe
                  const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
                  void *stream);
 
+/* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
+ * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.
+ * For measurement code that groups launches by kernel.                              */
+const char *q8_conv_variant(const q8_conv_desc *d);
+
 /* ---- helpers that only chain layers; not part of the paper's method ------------ */
 
 /* fp32 NHWC convolution + bias (+ dense residual) (+ ReLU), used to produce the

@@ -370,6 +370,13 @@ int conv_mode(const q8_conv_desc* d) {
   return -1;
 }
 
+// tile shape by output-channel count: 0 = 128x128, 1 = 256 pixels x 64, 2 = 256 x 32
+int pick_variant(const q8_conv_desc* d) {
+  if (d->K > 64) return 0;
+  if (d->K > 32) return 1;
+  return 2;
+}
+
 template <int WP, int WC, int TP, int TC, int BK>
 int launch(ConvParams& p, int mode, hipStream_t stream) {
   constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
@@ -483,9 +490,19 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
                   ? 1 : 0;
 
   hipStream_t s = (hipStream_t)stream;
-  if (d->K > 64) return launch<2, 2, 2, 2, 64>(p, mode, s);   // 128 pixels x 128 channels
-  if (d->K > 32) return launch<4, 1, 2, 2, 64>(p, mode, s);   // 256 pixels x  64 channels
-  return launch<4, 1, 2, 1, 64>(p, mode, s);                  // 256 pixels x  32 channels
+  switch (pick_variant(d)) {
+    case 0: return launch<2, 2, 2, 2, 64>(p, mode, s);   // 128 pixels x 128 channels
+    case 1: return launch<4, 1, 2, 2, 64>(p, mode, s);   // 256 pixels x  64 channels
+    default: return launch<4, 1, 2, 1, 64>(p, mode, s);  // 256 pixels x  32 channels
+  }
+}
+
+const char* q8_conv_variant(const q8_conv_desc* d) {
+  if (!desc_sane(d) || conv_mode(d) < 0) return "unsupported";
+  static const char* names[2][3] = {
+      {"conv_i8_kernel<2,2,2,2,64,0>", "conv_i8_kernel<4,1,2,2,64,0>", "conv_i8_kernel<4,1,2,1,64,0>"},
+      {"conv_i8_kernel<2,2,2,2,64,1>", "conv_i8_kernel<4,1,2,2,64,1>", "conv_i8_kernel<4,1,2,1,64,1>"}};
+  return names[conv_mode(d)][pick_variant(d)];
 }
 
 }  // extern "C"
