@@ -41,8 +41,105 @@ struct ConvParams {
   int n_ptiles, n_ctiles;
   float m, m_r;
   int relu;
-  int vec_out;    // 1: out/res/dump addresses of 4-channel groups are 4-byte aligned
+  int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
+  int vec16;      // 1: out/res addresses of 16-channel groups are 16-byte aligned
 };
+
+// A 16-byte block of zeros in device memory: the source of every chunk that lies in the
+// zero padding, beyond the last pixel / channel, or beyond the end of the reduction when
+// chunks are copied straight from global memory to LDS.
+__device__ __attribute__((aligned(16))) const int q8_zero_chunk[4] = {0, 0, 0, 0};
+
+// Filter row (within a 32-row MFMA tile) -> output channel.  The 32x32 MFMA leaves, in
+// accumulator register 4a+b of a lane in half g, row 8a+4g+b.  Feeding channel 16g+4a+b
+// as that row makes the 16 accumulators of a lane 16 CONSECUTIVE channels of one pixel,
+// so the epilogue needs one 16-byte residual load and one 16-byte store per lane.
+__device__ __forceinline__ int row_to_channel(int row) {
+  return (((row >> 2) & 1) << 4) | ((row >> 3) << 2) | (row & 3);
+}
+
+// Epilogue for 16 consecutive channels [ch, ch+16) of pixel `pix` (Eq. A' tail + fused sum):
+// bias, fp32 scale, residual, ReLU, clamp, Round, int8 pack, store.
+__device__ __forceinline__ void epilogue16(const ConvParams& p, int pix, int ch, int (&v)[16]) {
+  const int nvalid = p.K - ch;          // > 0 guaranteed by the caller
+  const bool full = nvalid >= 16;
+  if (p.bias) {
+    if (full) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        v4i bv = *reinterpret_cast<const v4i*>(p.bias + ch + 4 * a);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) v[4 * a + b] += bv[b];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e < nvalid) v[e] += p.bias[ch + e];
+    }
+  }
+  if (p.acc_dump) {
+    int32_t* d = p.acc_dump + (size_t)pix * p.K + ch;
+    if (full && (p.K & 3) == 0) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        *reinterpret_cast<v4i*>(d + 4 * a) = v4i{v[4 * a], v[4 * a + 1], v[4 * a + 2], v[4 * a + 3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e < nvalid) d[e] = v[e];
+    }
+  }
+  float t[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * p.m;
+  if (p.res) {
+    const int8_t* r = p.res + (size_t)pix * p.res_cs + p.res_off + ch;
+    int rw[4] = {0, 0, 0, 0};
+    if (full && p.vec16) {
+      v4i q = *reinterpret_cast<const v4i*>(r);
+      rw[0] = q[0]; rw[1] = q[1]; rw[2] = q[2]; rw[3] = q[3];
+    } else {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        if (p.vec4 && 4 * a + 3 < nvalid) {
+          rw[a] = *reinterpret_cast<const int*>(r + 4 * a);
+        } else {
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (4 * a + b < nvalid) rw[a] |= ((int)(uint8_t)r[4 * a + b]) << (8 * b);
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float u = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) * p.m_r;
+      t[e] = t[e] + u;
+    }
+  }
+  unsigned zw[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    float u = t[e];
+    if (p.relu) u = fmaxf(u, 0.0f);
+    u = fminf(fmaxf(u, -128.0f), 127.0f);
+    zw[e >> 2] |= ((unsigned)((int)rintf(u)) & 0xffu) << (8 * (e & 3));
+  }
+  int8_t* o = p.y + (size_t)pix * p.out_cs + p.out_off + ch;
+  if (full && p.vec16) {
+    *reinterpret_cast<v4i*>(o) = v4i{(int)zw[0], (int)zw[1], (int)zw[2], (int)zw[3]};
+  } else {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      if (p.vec4 && 4 * a + 3 < nvalid) {
+        *reinterpret_cast<unsigned*>(o + 4 * a) = zw[a];
+      } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          if (4 * a + b < nvalid) o[4 * a + b] = (int8_t)((zw[a] >> (8 * b)) & 0xff);
+      }
+    }
+  }
+}
 
 // 16-byte chunk index -> physical chunk slot inside an LDS row (XOR swizzle so that the
 // 16 rows a quarter-wave reads at one reduction offset fall into distinct bank groups).
@@ -138,9 +235,10 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
     const bool red_ok = red < p.red_len;
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
-      int ch = ch0 + lrow + j * ROWS_PER_PASS;
+      const int arow = lrow + j * ROWS_PER_PASS;            // LDS row <- permuted channel
+      int ch = ch0 + (arow & ~31) + row_to_channel(arow & 31);
       v4i v = {0, 0, 0, 0};
-      const bool row_ok = !A_RAGGED || (lrow + j * ROWS_PER_PASS < BC);
+      const bool row_ok = !A_RAGGED || (arow < BC);
       if (red_ok && row_ok && ch < p.K)
         v = *reinterpret_cast<const v4i*>(p.w + (size_t)ch * p.red_len + red);
       a_reg[j] = v;
@@ -246,82 +344,19 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
     __syncthreads();
   }
 
-  // ---- epilogue: lane holds, for pixel column (lane & 31), channels 8a + 4*(lane>>5) + b
-  const float m = p.m, m_r = p.m_r;
+  // ---- epilogue: a lane holds 16 consecutive channels of pixel column (lane & 31)
 #pragma unroll
   for (int j = 0; j < TP; ++j) {
     const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
     if (pix >= p.M) continue;
 #pragma unroll
     for (int i = 0; i < TC; ++i) {
+      const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+      if (ch >= p.K) continue;
+      int v[16];
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int ch = ch0 + (wave_c * TC + i) * 32 + 8 * a + 4 * (lane >> 5);
-        if (ch >= p.K) continue;
-        int v[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) v[b] = acc[i][j][4 * a + b];
-        const bool full = p.vec_out && (ch + 3 < p.K);
-        if (p.bias) {
-          if (full) {
-            v4i bv = *reinterpret_cast<const v4i*>(p.bias + ch);
-#pragma unroll
-            for (int b = 0; b < 4; ++b) v[b] += bv[b];
-          } else {
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-              if (ch + b < p.K) v[b] += p.bias[ch + b];
-          }
-        }
-        if (p.acc_dump) {
-          int32_t* d = p.acc_dump + (size_t)pix * p.K + ch;
-          if (full && (p.K & 3) == 0) {
-            *reinterpret_cast<v4i*>(d) = v4i{v[0], v[1], v[2], v[3]};
-          } else {
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-              if (ch + b < p.K) d[b] = v[b];
-          }
-        }
-        float t[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) t[b] = __fmul_rn((float)v[b], m);
-        if (p.res) {
-          const int8_t* r = p.res + (size_t)pix * p.res_cs + p.res_off + ch;
-          int rv[4] = {0, 0, 0, 0};
-          if (full) {
-            int w = *reinterpret_cast<const int*>(r);
-            rv[0] = (int8_t)(w & 0xff);
-            rv[1] = (int8_t)((w >> 8) & 0xff);
-            rv[2] = (int8_t)((w >> 16) & 0xff);
-            rv[3] = (int8_t)(w >> 24);
-          } else {
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-              if (ch + b < p.K) rv[b] = r[b];
-          }
-#pragma unroll
-          for (int b = 0; b < 4; ++b) t[b] = __fadd_rn(t[b], __fmul_rn((float)rv[b], m_r));
-        }
-        int z[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          float u = t[b];
-          if (p.relu) u = fmaxf(u, 0.0f);
-          u = fminf(fmaxf(u, -128.0f), 127.0f);
-          z[b] = (int)rintf(u);
-        }
-        int8_t* o = p.y + (size_t)pix * p.out_cs + p.out_off + ch;
-        if (full) {
-          *reinterpret_cast<unsigned*>(o) = (unsigned)(z[0] & 0xff) | ((unsigned)(z[1] & 0xff) << 8) |
-                                            ((unsigned)(z[2] & 0xff) << 16) |
-                                            ((unsigned)(z[3] & 0xff) << 24);
-        } else {
-#pragma unroll
-          for (int b = 0; b < 4; ++b)
-            if (ch + b < p.K) o[b] = (int8_t)z[b];
-        }
-      }
+      for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+      epilogue16(p, pix, ch, v);
     }
   }
 }
@@ -484,10 +519,13 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
     p.m = prod / q_out;
     p.m_r = residual ? q_res / q_out : 0.0f;
   }
-  p.vec_out = (p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(z_y, 4) &&
-               (residual == nullptr ||
-                (p.res_cs % 4 == 0 && p.res_off % 4 == 0 && q8_aligned(residual, 4))))
-                  ? 1 : 0;
+  auto aligned_to = [&](int a) {
+    return p.out_cs % a == 0 && p.out_off % a == 0 && q8_aligned(z_y, a) &&
+           (residual == nullptr ||
+            (p.res_cs % a == 0 && p.res_off % a == 0 && q8_aligned(residual, a)));
+  };
+  p.vec4 = aligned_to(4) ? 1 : 0;
+  p.vec16 = aligned_to(16) ? 1 : 0;
 
   hipStream_t s = (hipStream_t)stream;
   switch (pick_variant(d)) {

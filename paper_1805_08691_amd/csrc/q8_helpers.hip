@@ -125,6 +125,44 @@ __global__ __launch_bounds__(kThreads) void maxpool_kernel(const T* __restrict__
   }
 }
 
+// int8 max-pool, 16 channels per thread (C % 16 == 0): 16-byte loads and stores.
+typedef int v4i __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* __restrict__ x, int N,
+                                                                  int H, int W, int C16, int R, int S,
+                                                                  int stride, int pad, int Ho, int Wo,
+                                                                  int8_t* __restrict__ y) {
+  const size_t total = (size_t)N * Ho * Wo * C16;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * kThreads) {
+    int c = (int)(i % C16);
+    size_t t = i / C16;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    int best[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) best[e] = -128;
+    for (int r = 0; r < R; ++r) {
+      int hi = ho * stride - pad + r;
+      if ((unsigned)hi >= (unsigned)H) continue;
+      for (int s = 0; s < S; ++s) {
+        int wi = wo * stride - pad + s;
+        if ((unsigned)wi >= (unsigned)W) continue;
+        v4i v = *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          int b = (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
+          best[e] = b > best[e] ? b : best[e];
+        }
+      }
+    }
+    v4i o = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[e >> 2] |= (best[e] & 0xff) << (8 * (e & 3));
+    *reinterpret_cast<v4i*>(y + i * 16) = o;
+  }
+}
+
 template <typename T>
 int maxpool_launch(const T* x, int N, int H, int W, int C, int R, int S, int stride, int pad,
                    int Ho, int Wo, T* y, void* stream) {
@@ -137,6 +175,17 @@ int maxpool_launch(const T* x, int N, int H, int W, int C, int R, int S, int str
   size_t total = (size_t)N * Ho * Wo * C;
   if (total == 0) return Q8_OK;
   Q8_REQUIRE(x && y, Q8_EINVAL);
+  if constexpr (sizeof(T) == 1) {
+    if (C % 16 == 0 && q8_aligned(x, 16) && q8_aligned(y, 16)) {
+      size_t items = total / 16;
+      size_t vb = (items + kThreads - 1) / kThreads;
+      if (vb > 65536) vb = 65536;
+      hipLaunchKernelGGL(maxpool_i8_vec_kernel, dim3((unsigned)vb), dim3(kThreads), 0,
+                         (hipStream_t)stream, (const int8_t*)x, N, H, W, C / 16, R, S, stride, pad, Ho,
+                         Wo, (int8_t*)y);
+      return q8_launch_status();
+    }
+  }
   size_t blocks = (total + kThreads - 1) / kThreads;
   if (blocks > 65536) blocks = 65536;
   hipLaunchKernelGGL(maxpool_kernel<T>, dim3((unsigned)blocks), dim3(kThreads), 0,

@@ -218,6 +218,18 @@ def test_conv_batch_elements_are_independent(B):
         assert np.array_equal(one[0], full[i])
 
 
+@pytest.mark.parametrize("shape,win", [((2, 23, 23, 64), (3, 2, 1)), ((1, 10, 9, 48), (2, 2, 0)),
+                                       ((2, 11, 11, 6), (3, 2, 1)), ((1, 19, 19, 32), (3, 1, 1))])
+def test_maxpool_helper(B, shape, win):
+    R, stride, pad = win
+    rng = np.random.default_rng(sum(shape))
+    x = rng.integers(-128, 128, shape).astype(np.int8)
+    Ho = (shape[1] + 2 * pad - R) // stride + 1
+    Wo = (shape[2] + 2 * pad - R) // stride + 1
+    got = host(B.maxpool_i8(dev(x), R, R, stride, pad, Ho, Wo))
+    assert np.array_equal(got, orc.maxpool_i8(x, R, R, stride, pad, Ho, Wo))
+
+
 # ------------------------------------------------------------------ whole configurations
 def _oracle_pipeline(cfg_id, batch, calib_library):
     cfg = wl.CONFIGS[cfg_id]
