@@ -153,6 +153,14 @@ __device__ __forceinline__ int swz(int row, int chunk) {
   }
 }
 
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
 // MODE 0: C % 16 == 0 (a chunk = 16 channels of one tap).
 // MODE 1: 4 stored channels per pixel (a chunk = 4 consecutive taps along the filter row).
 template <int WP, int WC, int TP, int TC, int BK, int MODE>
@@ -361,6 +369,195 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Main kernel (C % 16 == 0): chunks go from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging), through a ring of STAGES buffers, so
+// several reduction steps of loads are in flight per workgroup while the MFMAs of the
+// current step run.  One barrier per reduction step.
+//
+// A wavefront-wide direct load writes 64 x 16 bytes to consecutive LDS addresses, i.e. 16
+// rows of 64 bytes.  Which global chunk lands in which slot is chosen on the global side:
+// lane l fills row l/4, physical slot l%4, and therefore fetches logical chunk
+// (l%4) ^ swz(row) of that row.  Chunks that must read as zero fetch q8_zero_chunk.
+template <int WP, int WC, int TP, int TC, int STAGES>
+__global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams p) {
+  constexpr int BK = 64, CHUNKS = 4;
+  constexpr int BP = WP * TP * 32;
+  constexpr int BC = WC * TC * 32;
+  constexpr int A_GROUPS = BC / 16, B_GROUPS = BP / 16;     // 16-row groups = one wave-load
+  constexpr int A_LOADS = A_GROUPS / 4, B_LOADS = B_GROUPS / 4;
+  constexpr int LOADS = A_LOADS + B_LOADS;                   // per lane per stage
+  constexpr int A_BYTES = BC * BK, STAGE_BYTES = (BC + BP) * BK;
+  static_assert(WP * WC == 4, "four wavefronts per block");
+  static_assert(A_GROUPS % 4 == 0 && B_GROUPS % 4 == 0, "every wave issues the same loads");
+  static_assert(STAGES >= 2 && STAGES <= 4, "ring depth");
+  static_assert(STAGES * STAGE_BYTES <= 65536, "static LDS limit");
+
+  __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES];
+
+  const int nblk = p.n_ptiles * p.n_ctiles;
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
+    const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
+    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int ctile = bid % p.n_ctiles;
+  const int ptile = bid / p.n_ctiles;
+  const int pix0 = ptile * BP;
+  const int ch0 = ctile * BC;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_p = wave % WP;
+  const int wave_c = wave / WP;
+
+  // ---- loader state
+  const int lrow16 = lane >> 2;                              // row inside a 16-row group
+  const int lchunk = (lane & 3) ^ swz<CHUNKS>(lrow16, 0);    // logical chunk this lane fetches
+  const int8_t* const zero_src = reinterpret_cast<const int8_t*>(q8_zero_chunk);
+
+  const int8_t* a_row[A_LOADS];        // filter row base (or null when the channel is a tail)
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int row = (wave + 4 * j) * 16 + lrow16;
+    const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
+    a_row[j] = ch < p.K ? p.w + (size_t)ch * p.red_len : nullptr;
+  }
+  int b_hi0[B_LOADS], b_wi0[B_LOADS];
+  const int8_t* b_img[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    const int pix = pix0 + (wave + 4 * j) * 16 + lrow16;
+    if (pix < p.M) {
+      int n = pix / (p.Ho * p.Wo);
+      int rem = pix - n * (p.Ho * p.Wo);
+      int ho = rem / p.Wo;
+      int wo = rem - ho * p.Wo;
+      b_hi0[j] = ho * p.stride_h - p.pad_h;
+      b_wi0[j] = wo * p.stride_w - p.pad_w;
+      b_img[j] = p.x + (size_t)n * p.H * p.W * p.in_cs;
+    } else {
+      b_hi0[j] = -0x40000000;
+      b_wi0[j] = -0x40000000;
+      b_img[j] = p.x;
+    }
+  }
+  int red = lchunk * 16;
+  int tap_r, tap_s, tap_c;
+  {
+    int tap = red / p.C;
+    tap_c = red - tap * p.C;
+    tap_r = tap / p.S;
+    tap_s = tap - tap_r * p.S;
+  }
+
+  auto issue_stage = [&](int buf) {
+    int8_t* stage = lds + buf * STAGE_BYTES;
+    const bool red_ok = red < p.red_len;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) {
+      const int8_t* src = (red_ok && a_row[j]) ? a_row[j] + red : zero_src;
+      asm volatile("" : "+v"(src));   // one load instruction for all lanes (vmcnt bookkeeping)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)src,
+          (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) {
+      const int hi = b_hi0[j] + tap_r * p.dil_h;
+      const int wi = b_wi0[j] + tap_s * p.dil_w;
+      const bool ok = red_ok && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
+      const int8_t* src = ok ? b_img[j] + ((long)hi * p.W + wi) * p.in_cs + tap_c : zero_src;
+      asm volatile("" : "+v"(src));
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)src,
+          (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16, 0,
+          0);
+    }
+    // advance this lane's chunk to the next reduction step
+    red += BK;
+    tap_c += BK;
+    while (tap_c >= p.C) {
+      tap_c -= p.C;
+      if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+    }
+  };
+
+  v16i acc[TC][TP];
+#pragma unroll
+  for (int i = 0; i < TC; ++i)
+#pragma unroll
+    for (int j = 0; j < TP; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  const int nk = (p.red_len + BK - 1) / BK;
+  const int frag_row = lane & 31;
+  const int frag_half = lane >> 5;
+
+  // prologue: STAGES-1 reduction steps in flight
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nk) issue_stage(s);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // wait for this lane's loads of step kt: at most the loads of the later steps already
+    // issued (min(STAGES-2, nk-1-kt) steps) may still be outstanding
+    {
+      const int later = nk - 1 - kt;
+      if (STAGES >= 4 && later >= 2) wait_vmcnt<2 * LOADS>();
+      else if (STAGES >= 3 && later >= 1) wait_vmcnt<LOADS>();
+      else wait_vmcnt<0>();
+    }
+    // Bare barrier (no fence: a fence would drain the loads of the later steps too).
+    // Step kt is now visible to all waves, and everyone is done reading step kt-1.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt + STAGES - 1 < nk) issue_stage((kt + STAGES - 1) % STAGES);
+
+    const int8_t* sa = lds + (kt % STAGES) * STAGE_BYTES;
+    const int8_t* sb = sa + A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      v4i af[TC], bf[TP];
+      const int chunk = 2 * ks + frag_half;
+#pragma unroll
+      for (int i = 0; i < TC; ++i) {
+        int row = (wave_c * TC + i) * 32 + frag_row;
+        af[i] = *reinterpret_cast<const v4i*>(sa + row * BK + swz<CHUNKS>(row, chunk) * 16);
+      }
+#pragma unroll
+      for (int j = 0; j < TP; ++j) {
+        int row = (wave_p * TP + j) * 32 + frag_row;
+        bf[j] = *reinterpret_cast<const v4i*>(sb + row * BK + swz<CHUNKS>(row, chunk) * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < TP; ++j) {
+    const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
+    if (pix >= p.M) continue;
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+      const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+      if (ch >= p.K) continue;
+      int v[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+      epilogue16(p, pix, ch, v);
+    }
+  }
+}
+
 // dense KRSC (true C <= 4) -> [K][R][S4][4 taps][4 channels], zero filled
 __global__ void pack_c4_kernel(const int8_t* __restrict__ w, int K, int R, int S, int C, int S4,
                                int8_t* __restrict__ out) {
@@ -405,27 +602,50 @@ int conv_mode(const q8_conv_desc* d) {
   return -1;
 }
 
-// tile shape by output-channel count: 0 = 128x128, 1 = 256 pixels x 64, 2 = 256 x 32
+// Kernel variants.  "dma" = direct-to-LDS ring kernel (C % 16 == 0 and K > 32); "reg" =
+// register-staged kernel (4-channel images, and K <= 32 where a 32-channel tile is used).
+enum Variant {
+  V_DMA_128x128_S2, V_DMA_128x128_S3, V_DMA_128x128_S4, V_DMA_256x64_S2, V_DMA_256x64_S3,
+  V_REG_256x32, V_REG4_128x128, V_REG4_256x64, V_REG4_256x32, V_COUNT
+};
+const char* const kVariantNames[V_COUNT] = {
+    "conv_i8_dma_kernel<2,2,2,2,2>", "conv_i8_dma_kernel<2,2,2,2,3>", "conv_i8_dma_kernel<2,2,2,2,4>",
+    "conv_i8_dma_kernel<4,1,2,2,2>", "conv_i8_dma_kernel<4,1,2,2,3>",
+    "conv_i8_kernel<4,1,2,1,64,0>", "conv_i8_kernel<2,2,2,2,64,1>", "conv_i8_kernel<4,1,2,2,64,1>",
+    "conv_i8_kernel<4,1,2,1,64,1>"};
+
 int pick_variant(const q8_conv_desc* d) {
-  if (d->K > 64) return 0;
-  if (d->K > 32) return 1;
-  return 2;
+  const int mode = conv_mode(d);
+  if (mode == 1) return d->K > 64 ? V_REG4_128x128 : d->K > 32 ? V_REG4_256x64 : V_REG4_256x32;
+  if (d->K <= 32) return V_REG_256x32;
+  const int nk = (d->R * d->S * d->C + 63) / 64;     // reduction steps of 64 bytes
+  if (d->K > 64) return nk <= 1 ? V_DMA_128x128_S2 : nk <= 4 ? V_DMA_128x128_S3 : V_DMA_128x128_S4;
+  return nk <= 1 ? V_DMA_256x64_S2 : V_DMA_256x64_S3;
 }
 
-template <int WP, int WC, int TP, int TC, int BK>
-int launch(ConvParams& p, int mode, hipStream_t stream) {
-  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
+template <int BP, int BC, typename F>
+int launch_tiles(ConvParams& p, F&& launch_fn) {
   p.n_ptiles = (p.M + BP - 1) / BP;
   p.n_ctiles = (p.K + BC - 1) / BC;
   long nblk = (long)p.n_ptiles * p.n_ctiles;
   if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
-  if (mode == 0)
-    hipLaunchKernelGGL((conv_i8_kernel<WP, WC, TP, TC, BK, 0>), dim3((unsigned)nblk), dim3(kThreads),
-                       0, stream, p);
-  else
-    hipLaunchKernelGGL((conv_i8_kernel<WP, WC, TP, TC, BK, 1>), dim3((unsigned)nblk), dim3(kThreads),
-                       0, stream, p);
+  launch_fn(dim3((unsigned)nblk));
   return q8_launch_status();
+}
+
+template <int WP, int WC, int TP, int TC, int MODE>
+int launch_reg(ConvParams& p, hipStream_t stream) {
+  return launch_tiles<WP * TP * 32, WC * TC * 32>(p, [&](dim3 grid) {
+    hipLaunchKernelGGL((conv_i8_kernel<WP, WC, TP, TC, 64, MODE>), grid, dim3(kThreads), 0, stream, p);
+  });
+}
+
+template <int WP, int WC, int TP, int TC, int STAGES>
+int launch_dma(ConvParams& p, hipStream_t stream) {
+  return launch_tiles<WP * TP * 32, WC * TC * 32>(p, [&](dim3 grid) {
+    hipLaunchKernelGGL((conv_i8_dma_kernel<WP, WC, TP, TC, STAGES>), grid, dim3(kThreads), 0, stream,
+                       p);
+  });
 }
 
 }  // namespace
@@ -529,18 +749,21 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
 
   hipStream_t s = (hipStream_t)stream;
   switch (pick_variant(d)) {
-    case 0: return launch<2, 2, 2, 2, 64>(p, mode, s);   // 128 pixels x 128 channels
-    case 1: return launch<4, 1, 2, 2, 64>(p, mode, s);   // 256 pixels x  64 channels
-    default: return launch<4, 1, 2, 1, 64>(p, mode, s);  // 256 pixels x  32 channels
+    case V_DMA_128x128_S2: return launch_dma<2, 2, 2, 2, 2>(p, s);
+    case V_DMA_128x128_S3: return launch_dma<2, 2, 2, 2, 3>(p, s);
+    case V_DMA_128x128_S4: return launch_dma<2, 2, 2, 2, 4>(p, s);
+    case V_DMA_256x64_S2: return launch_dma<4, 1, 2, 2, 2>(p, s);
+    case V_DMA_256x64_S3: return launch_dma<4, 1, 2, 2, 3>(p, s);
+    case V_REG_256x32: return launch_reg<4, 1, 2, 1, 0>(p, s);
+    case V_REG4_128x128: return launch_reg<2, 2, 2, 2, 1>(p, s);
+    case V_REG4_256x64: return launch_reg<4, 1, 2, 2, 1>(p, s);
+    default: return launch_reg<4, 1, 2, 1, 1>(p, s);
   }
 }
 
 const char* q8_conv_variant(const q8_conv_desc* d) {
   if (!desc_sane(d) || conv_mode(d) < 0) return "unsupported";
-  static const char* names[2][3] = {
-      {"conv_i8_kernel<2,2,2,2,64,0>", "conv_i8_kernel<4,1,2,2,64,0>", "conv_i8_kernel<4,1,2,1,64,0>"},
-      {"conv_i8_kernel<2,2,2,2,64,1>", "conv_i8_kernel<4,1,2,2,64,1>", "conv_i8_kernel<4,1,2,1,64,1>"}};
-  return names[conv_mode(d)][pick_variant(d)];
+  return kVariantNames[pick_variant(d)];
 }
 
 }  // extern "C"
