@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libq8conv.so")
+LIB_PATH = os.environ.get("Q8CONV_LIB") or os.path.join(_HERE, "libq8conv.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

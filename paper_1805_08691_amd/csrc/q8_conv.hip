@@ -12,6 +12,7 @@
 // The accumulator layout of the 32x32 MFMA puts four consecutive rows (= channels) of one
 // column (= pixel) in four consecutive registers of a lane, which is what the epilogue
 // wants: bias, scale, residual, ReLU, Round, clamp on four channels, one packed store.
+#include <type_traits>
 #include "q8_common.h"
 #pragma clang fp contract(off)   // the epilogue's op order is part of the result
 
@@ -39,16 +40,12 @@ struct ConvParams {
   int red_len;    // reduction bytes per filter (R*S*C, or R*S4*16 in the 4-channel mode)
   int S4;         // 4-channel mode: 16-byte chunks per filter row (ceil(S/4))
   int n_ptiles, n_ctiles;
+  int x_bytes, w_bytes;   // sizes of the activation and filter tensors (buffer descriptors)
   float m, m_r;
   int relu;
   int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
   int vec16;      // 1: out/res addresses of 16-channel groups are 16-byte aligned
 };
-
-// A 16-byte block of zeros in device memory: the source of every chunk that lies in the
-// zero padding, beyond the last pixel / channel, or beyond the end of the reduction when
-// chunks are copied straight from global memory to LDS.
-__device__ __attribute__((aligned(16))) const int q8_zero_chunk[4] = {0, 0, 0, 0};
 
 // Filter row (within a 32-row MFMA tile) -> output channel.  The 32x32 MFMA leaves, in
 // accumulator register 4a+b of a lane in half g, row 8a+4g+b.  Feeding channel 16g+4a+b
@@ -58,25 +55,57 @@ __device__ __forceinline__ int row_to_channel(int row) {
   return (((row >> 2) & 1) << 4) | ((row >> 3) << 2) | (row & 3);
 }
 
-// Epilogue for 16 consecutive channels [ch, ch+16) of pixel `pix` (Eq. A' tail + fused sum):
-// bias, fp32 scale, residual, ReLU, clamp, Round, int8 pack, store.
-__device__ __forceinline__ void epilogue16(const ConvParams& p, int pix, int ch, int (&v)[16]) {
-  const int nvalid = p.K - ch;          // > 0 guaranteed by the caller
-  const bool full = nvalid >= 16;
-  if (p.bias) {
-    if (full) {
+// ---- Epilogue pieces, all for 16 consecutive channels [ch, ch+16) of one pixel ------------
+
+// Bias of the 16 channels (zero where there is no bias or the channel is beyond K).
+__device__ __forceinline__ void load_bias16(const ConvParams& p, int ch, int (&b)[16]) {
+  const int nvalid = p.K - ch;
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        v4i bv = *reinterpret_cast<const v4i*>(p.bias + ch + 4 * a);
+  for (int e = 0; e < 16; ++e) b[e] = 0;
+  if (!p.bias || nvalid <= 0) return;
+  if (nvalid >= 16) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) v[4 * a + b] += bv[b];
+    for (int a = 0; a < 4; ++a) {
+      v4i bv = *reinterpret_cast<const v4i*>(p.bias + ch + 4 * a);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) b[4 * a + k] = bv[k];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      if (e < nvalid) b[e] = p.bias[ch + e];
+  }
+}
+
+// The 16 residual codes, packed four to a word (zero where absent).
+__device__ __forceinline__ void load_res16(const ConvParams& p, int pix, int ch, int (&rw)[4]) {
+  rw[0] = rw[1] = rw[2] = rw[3] = 0;
+  const int nvalid = p.K - ch;
+  if (!p.res || nvalid <= 0 || pix >= p.M) return;
+  const int8_t* r = p.res + (size_t)pix * p.res_cs + p.res_off + ch;
+  if (nvalid >= 16 && p.vec16) {
+    v4i q = *reinterpret_cast<const v4i*>(r);
+    rw[0] = q[0]; rw[1] = q[1]; rw[2] = q[2]; rw[3] = q[3];
+  } else {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      if (p.vec4 && 4 * a + 3 < nvalid) {
+        rw[a] = *reinterpret_cast<const int*>(r + 4 * a);
+      } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          if (4 * a + b < nvalid) rw[a] |= ((int)(uint8_t)r[4 * a + b]) << (8 * b);
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 16; ++e)
-        if (e < nvalid) v[e] += p.bias[ch + e];
     }
   }
+}
+
+// Tail of Eq. A' with the fused sum: v = accumulators (bias included), rw = residual codes.
+// fp32 scale, residual term, ReLU, clamp, Round, int8 pack, store (and the accumulator dump).
+__device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, const int (&v)[16],
+                                         const int (&rw)[4]) {
+  const int nvalid = p.K - ch;          // > 0 guaranteed by the caller
+  const bool full = nvalid >= 16;
   if (p.acc_dump) {
     int32_t* d = p.acc_dump + (size_t)pix * p.K + ch;
     if (full && (p.K & 3) == 0) {
@@ -93,23 +122,6 @@ __device__ __forceinline__ void epilogue16(const ConvParams& p, int pix, int ch,
 #pragma unroll
   for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * p.m;
   if (p.res) {
-    const int8_t* r = p.res + (size_t)pix * p.res_cs + p.res_off + ch;
-    int rw[4] = {0, 0, 0, 0};
-    if (full && p.vec16) {
-      v4i q = *reinterpret_cast<const v4i*>(r);
-      rw[0] = q[0]; rw[1] = q[1]; rw[2] = q[2]; rw[3] = q[3];
-    } else {
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        if (p.vec4 && 4 * a + 3 < nvalid) {
-          rw[a] = *reinterpret_cast<const int*>(r + 4 * a);
-        } else {
-#pragma unroll
-          for (int b = 0; b < 4; ++b)
-            if (4 * a + b < nvalid) rw[a] |= ((int)(uint8_t)r[4 * a + b]) << (8 * b);
-        }
-      }
-    }
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       float u = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) * p.m_r;
@@ -139,6 +151,16 @@ __device__ __forceinline__ void epilogue16(const ConvParams& p, int pix, int ch,
       }
     }
   }
+}
+
+// Whole epilogue in one go (register-staged kernel).
+__device__ __forceinline__ void epilogue16(const ConvParams& p, int pix, int ch, int (&v)[16]) {
+  int b[16], rw[4];
+  load_bias16(p, ch, b);
+  load_res16(p, pix, ch, rw);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) v[e] += b[e];
+  finish16(p, pix, ch, v, rw);
 }
 
 // 16-byte chunk index -> physical chunk slot inside an LDS row (XOR swizzle so that the
@@ -370,17 +392,30 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Main kernel (C % 16 == 0): chunks go from global memory straight into LDS
-// (global_load_lds_dwordx4, no register staging), through a ring of STAGES buffers, so
+// Main kernel (C % 16 == 0, R*S <= 32): chunks go from global memory straight into LDS
+// (buffer_load_dwordx4 ... lds, no register staging) through a ring of STAGES buffers, so
 // several reduction steps of loads are in flight per workgroup while the MFMAs of the
-// current step run.  One barrier per reduction step.
+// current step run.  One bare barrier per reduction step.
 //
 // A wavefront-wide direct load writes 64 x 16 bytes to consecutive LDS addresses, i.e. 16
 // rows of 64 bytes.  Which global chunk lands in which slot is chosen on the global side:
 // lane l fills row l/4, physical slot l%4, and therefore fetches logical chunk
-// (l%4) ^ swz(row) of that row.  Chunks that must read as zero fetch q8_zero_chunk.
-template <int WP, int WC, int TP, int TC, int STAGES>
+// (l%4) ^ swz(row) of that row.
+//
+// Addressing uses raw buffer descriptors: a per-lane 32-bit offset that is computed once,
+// plus a wave-uniform offset per reduction step, so a load costs a handful of VALU
+// instructions.  A chunk that must read as zero (padding, pixel or channel beyond the
+// tensor, reduction tail) gets an offset beyond the descriptor's size: the hardware's
+// range check then returns zeros.
+//
+// UNIFORM (C % 64 == 0): every lane of the block is in the same filter tap during one
+// reduction step, so the tap offset is a scalar.  Otherwise each lane tracks its own tap.
+constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
+
+template <int WP, int WC, int TP, int TC, int STAGES, int UNIFORM>
 __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
+                                      // descriptor types exist for the device target alone
   constexpr int BK = 64, CHUNKS = 4;
   constexpr int BP = WP * TP * 32;
   constexpr int BC = WC * TC * 32;
@@ -413,134 +448,257 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
   const int wave_p = wave % WP;
   const int wave_c = wave / WP;
 
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, p.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, p.x_bytes, 0x00020000);
+
   // ---- loader state
   const int lrow16 = lane >> 2;                              // row inside a 16-row group
   const int lchunk = (lane & 3) ^ swz<CHUNKS>(lrow16, 0);    // logical chunk this lane fetches
-  const int8_t* const zero_src = reinterpret_cast<const int8_t*>(q8_zero_chunk);
 
-  const int8_t* a_row[A_LOADS];        // filter row base (or null when the channel is a tail)
+  int a_off[A_LOADS];                  // filter row offset + chunk, or out of range
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const int row = (wave + 4 * j) * 16 + lrow16;
     const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
-    a_row[j] = ch < p.K ? p.w + (size_t)ch * p.red_len : nullptr;
+    a_off[j] = ch < p.K ? ch * p.red_len + lchunk * 16 : kOobOffset;
   }
-  int b_hi0[B_LOADS], b_wi0[B_LOADS];
-  const int8_t* b_img[B_LOADS];
+  int b_off[B_LOADS];                  // offset of tap (0,0), channel 0 (+ chunk if UNIFORM)
+  unsigned b_mask[B_LOADS];            // bit t: tap t of this pixel lies inside the image
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) {
     const int pix = pix0 + (wave + 4 * j) * 16 + lrow16;
+    unsigned mask = 0;
+    int off = 0;
     if (pix < p.M) {
-      int n = pix / (p.Ho * p.Wo);
-      int rem = pix - n * (p.Ho * p.Wo);
-      int ho = rem / p.Wo;
-      int wo = rem - ho * p.Wo;
-      b_hi0[j] = ho * p.stride_h - p.pad_h;
-      b_wi0[j] = wo * p.stride_w - p.pad_w;
-      b_img[j] = p.x + (size_t)n * p.H * p.W * p.in_cs;
-    } else {
-      b_hi0[j] = -0x40000000;
-      b_wi0[j] = -0x40000000;
-      b_img[j] = p.x;
+      const int n = pix / (p.Ho * p.Wo);
+      const int rem = pix - n * (p.Ho * p.Wo);
+      const int ho = rem / p.Wo;
+      const int wo = rem - ho * p.Wo;
+      const int hi0 = ho * p.stride_h - p.pad_h;
+      const int wi0 = wo * p.stride_w - p.pad_w;
+      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + (UNIFORM ? lchunk * 16 : 0);
+      int t = 0;
+      for (int r = 0; r < p.R; ++r) {
+        const bool hok = (unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H;
+        for (int s2 = 0; s2 < p.S; ++s2, ++t)
+          if (hok && (unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) mask |= 1u << t;
+      }
     }
+    b_off[j] = off;
+    b_mask[j] = mask;
   }
-  int red = lchunk * 16;
-  int tap_r, tap_s, tap_c;
-  {
-    int tap = red / p.C;
+
+  // ---- position in the reduction
+  const int dw_step = p.dil_w * p.in_cs;                     // offset step of one tap along S
+  const int dh_step = p.dil_h * p.W * p.in_cs - p.S * dw_step;   // extra step when a row wraps
+  // UNIFORM: scalars shared by the block.  Otherwise: this lane's own chunk.
+  int step_base = 0;                     // reduction byte offset of the next step to issue
+  int tap = 0, tap_s = 0, tap_c = 0, tap_delta = 0;
+  if (!UNIFORM) {
+    const int red = lchunk * 16;
+    tap = red / p.C;
     tap_c = red - tap * p.C;
-    tap_r = tap / p.S;
-    tap_s = tap - tap_r * p.S;
+    const int r = tap / p.S;
+    tap_s = tap - r * p.S;
+    tap_delta = (r * p.dil_h * p.W + tap_s * p.dil_w) * p.in_cs;
   }
 
   auto issue_stage = [&](int buf) {
     int8_t* stage = lds + buf * STAGE_BYTES;
-    const bool red_ok = red < p.red_len;
+    if constexpr (UNIFORM) {
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-      const int8_t* src = (red_ok && a_row[j]) ? a_row[j] + red : zero_src;
-      asm volatile("" : "+v"(src));   // one load instruction for all lanes (vmcnt bookkeeping)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)src,
-          (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16, 0, 0);
-    }
+      for (int j = 0; j < A_LOADS; ++j)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16,
+            a_off[j], step_base, 0, 0);
+      const int delta = tap_delta + tap_c;
 #pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) {
-      const int hi = b_hi0[j] + tap_r * p.dil_h;
-      const int wi = b_wi0[j] + tap_s * p.dil_w;
-      const bool ok = red_ok && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
-      const int8_t* src = ok ? b_img[j] + ((long)hi * p.W + wi) * p.in_cs + tap_c : zero_src;
-      asm volatile("" : "+v"(src));
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)src,
-          (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16, 0,
-          0);
-    }
-    // advance this lane's chunk to the next reduction step
-    red += BK;
-    tap_c += BK;
-    while (tap_c >= p.C) {
-      tap_c -= p.C;
-      if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
+      for (int j = 0; j < B_LOADS; ++j) {
+        const int voff = ((b_mask[j] >> tap) & 1u) ? b_off[j] + delta : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_x,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16,
+            voff, 0, 0, 0);
+      }
+      step_base += BK;
+      // advance (branch-free, so the whole step stays one scheduling region)
+      tap_c += BK;
+      const int wrap_c = tap_c >= p.C ? 1 : 0;
+      tap_c = wrap_c ? 0 : tap_c;
+      tap += wrap_c;
+      tap_s += wrap_c;
+      tap_delta += wrap_c ? dw_step : 0;
+      const int wrap_s = tap_s == p.S ? 1 : 0;
+      tap_s = wrap_s ? 0 : tap_s;
+      tap_delta += wrap_s ? dh_step : 0;
+    } else {
+      const bool red_ok = step_base + lchunk * 16 < p.red_len;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        const int voff = red_ok ? a_off[j] : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16,
+            voff, step_base, 0, 0);
+      }
+      const int delta = tap_delta + tap_c;
+#pragma unroll
+      for (int j = 0; j < B_LOADS; ++j) {
+        const bool ok = red_ok && ((b_mask[j] >> tap) & 1u);
+        const int voff = ok ? b_off[j] + delta : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_x,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16,
+            voff, 0, 0, 0);
+      }
+      step_base += BK;
+      tap_c += BK;
+      while (tap_c >= p.C) {
+        tap_c -= p.C;
+        ++tap;
+        tap_delta += dw_step;
+        if (++tap_s == p.S) { tap_s = 0; tap_delta += dh_step; }
+      }
     }
   };
 
+  // Accumulators start at the bias (Eq. A': the int32 bias shares the accumulator's factor).
+  // These loads are issued before any stage load, so the in-order vmcnt bookkeeping of
+  // the ring is unaffected, and their latency hides behind the first stages.
   v16i acc[TC][TP];
 #pragma unroll
-  for (int i = 0; i < TC; ++i)
+  for (int i = 0; i < TC; ++i) {
+    int b[16];
+    load_bias16(p, ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
 #pragma unroll
     for (int j = 0; j < TP; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = b[v];
+  }
+  int res_w[TC][TP][4];
 
   const int nk = (p.red_len + BK - 1) / BK;
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
 
-  // prologue: STAGES-1 reduction steps in flight
+  // Operand fragments of the two 32-byte halves of a reduction step.  The loop is
+  // software-pipelined inside one wavefront: the LDS reads of a half are issued one phase
+  // before the MFMAs that consume them, and the MFMAs of the second half of step kt-1 run
+  // after the barrier of step kt, so LDS latency, the barrier and the issue of the global
+  // loads all overlap matrix work.
+  v4i af[2][TC], bf[2][TP];
+  int a_foff[2][TC], b_foff[2][TP];          // LDS offsets inside a stage, per half
 #pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s)
-    if (s < nk) issue_stage(s);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    // wait for this lane's loads of step kt: at most the loads of the later steps already
-    // issued (min(STAGES-2, nk-1-kt) steps) may still be outstanding
-    {
-      const int later = nk - 1 - kt;
-      if (STAGES >= 4 && later >= 2) wait_vmcnt<2 * LOADS>();
-      else if (STAGES >= 3 && later >= 1) wait_vmcnt<LOADS>();
-      else wait_vmcnt<0>();
+  for (int h = 0; h < 2; ++h) {
+    const int chunk = 2 * h + frag_half;
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+      const int row = (wave_c * TC + i) * 32 + frag_row;
+      a_foff[h][i] = row * BK + swz<CHUNKS>(row, chunk) * 16;
+      asm volatile("" : "+v"(a_foff[h][i]));     // keep in a register, do not recompute
+      af[h][i] = v4i{0, 0, 0, 0};
     }
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+      const int row = (wave_p * TP + j) * 32 + frag_row;
+      b_foff[h][j] = A_BYTES + row * BK + swz<CHUNKS>(row, chunk) * 16;
+      asm volatile("" : "+v"(b_foff[h][j]));
+      bf[h][j] = v4i{0, 0, 0, 0};
+    }
+  }
+  auto load_frags = [&](const int8_t* stage, int h) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i) af[h][i] = *reinterpret_cast<const v4i*>(stage + a_foff[h][i]);
+#pragma unroll
+    for (int j = 0; j < TP; ++j) bf[h][j] = *reinterpret_cast<const v4i*>(stage + b_foff[h][j]);
+  };
+  auto mma = [&](int h) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h][i], bf[h][j], acc[i][j], 0, 0, 0);
+  };
+
+  // One reduction step.  LATER = steps issued after step kt that may still be in flight
+  // when step kt must have landed; ISSUE = whether a further step is issued; LAST = whether
+  // the residual codes are fetched (no stage load follows, so vmcnt bookkeeping is over).
+  auto step = [&](int kt, auto later_c, auto issue_c, auto last_c) {
+    constexpr int LATER = decltype(later_c)::value;
+    wait_vmcnt<LATER * LOADS>();
     // Bare barrier (no fence: a fence would drain the loads of the later steps too).
-    // Step kt is now visible to all waves, and everyone is done reading step kt-1.
+    // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS
+    // (its second-half fragments are in registers already).
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + STAGES - 1 < nk) issue_stage((kt + STAGES - 1) % STAGES);
-
-    const int8_t* sa = lds + (kt % STAGES) * STAGE_BYTES;
-    const int8_t* sb = sa + A_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < BK / 32; ++ks) {
-      v4i af[TC], bf[TP];
-      const int chunk = 2 * ks + frag_half;
-#pragma unroll
-      for (int i = 0; i < TC; ++i) {
-        int row = (wave_c * TC + i) * 32 + frag_row;
-        af[i] = *reinterpret_cast<const v4i*>(sa + row * BK + swz<CHUNKS>(row, chunk) * 16);
-      }
-#pragma unroll
-      for (int j = 0; j < TP; ++j) {
-        int row = (wave_p * TP + j) * 32 + frag_row;
-        bf[j] = *reinterpret_cast<const v4i*>(sb + row * BK + swz<CHUNKS>(row, chunk) * 16);
-      }
+    const int8_t* stage = lds + (kt % STAGES) * STAGE_BYTES;
+    load_frags(stage, 0);
+    if constexpr (decltype(issue_c)::value) issue_stage((kt + STAGES - 1) % STAGES);
+    if constexpr (decltype(last_c)::value) {
 #pragma unroll
       for (int i = 0; i < TC; ++i)
 #pragma unroll
         for (int j = 0; j < TP; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+          load_res16(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31),
+                     ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), res_w[i][j]);
+    }
+    mma(1);                             // second half of step kt-1 (zeros on the first step)
+    load_frags(stage, 1);
+    mma(0);
+    // Instruction order inside the step (one scheduling region): the four LDS reads of the
+    // first half, then the MFMAs of the previous second half with one global->LDS load
+    // after each (a wavefront issues in order: spreading the loads lets a load that waits
+    // for queue space hide behind a running MFMA), then the MFMAs of the first half with
+    // the LDS reads of the second half between them.
+    if constexpr (!decltype(last_c)::value) {
+      __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // DS reads, half 0
+      constexpr int kMma = TC * TP;
+      constexpr int kVmem = decltype(issue_c)::value ? LOADS : 0;
+#pragma unroll
+      for (int g = 0; g < kMma; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // one MFMA
+        if (g < kVmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); // one VMEM read
+      }
+      if (kVmem > kMma) __builtin_amdgcn_sched_group_barrier(0x020, kVmem - kMma, 0);
+#pragma unroll
+      for (int g = 0; g < kMma; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // one MFMA
+        if (g < TC + TP) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using std::integral_constant;
+
+  // prologue: up to STAGES-1 reduction steps in flight
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nk) issue_stage(s);
+  // steady state: every step finds STAGES-2 later steps in flight and issues one more
+  int kt = 0;
+  for (; kt + STAGES - 1 < nk; ++kt)
+    step(kt, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
+         integral_constant<bool, false>{});
+  // drain: the last min(STAGES-1, nk) steps, with fewer and fewer loads behind them
+  if constexpr (STAGES >= 4) {
+    if (nk - kt == 3) {
+      step(kt, integral_constant<int, 2>{}, integral_constant<bool, false>{},
+           integral_constant<bool, false>{});
+      ++kt;
     }
   }
+  if constexpr (STAGES >= 3) {
+    if (nk - kt == 2) {
+      step(kt, integral_constant<int, 1>{}, integral_constant<bool, false>{},
+           integral_constant<bool, false>{});
+      ++kt;
+    }
+  }
+  step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
+       integral_constant<bool, true>{});
+  mma(1);
 
 #pragma unroll
   for (int j = 0; j < TP; ++j) {
@@ -553,9 +711,10 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
       int v[16];
 #pragma unroll
       for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
-      epilogue16(p, pix, ch, v);
+      finish16(p, pix, ch, v, res_w[i][j]);
     }
   }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 // dense KRSC (true C <= 4) -> [K][R][S4][4 taps][4 channels], zero filled
@@ -606,11 +765,12 @@ int conv_mode(const q8_conv_desc* d) {
 // register-staged kernel (4-channel images, and K <= 32 where a 32-channel tile is used).
 enum Variant {
   V_DMA_128x128_S2, V_DMA_128x128_S3, V_DMA_128x128_S4, V_DMA_256x64_S2, V_DMA_256x64_S3,
-  V_REG_256x32, V_REG4_128x128, V_REG4_256x64, V_REG4_256x32, V_COUNT
+  V_REG_128x128, V_REG_256x64, V_REG_256x32, V_REG4_128x128, V_REG4_256x64, V_REG4_256x32, V_COUNT
 };
 const char* const kVariantNames[V_COUNT] = {
     "conv_i8_dma_kernel<2,2,2,2,2>", "conv_i8_dma_kernel<2,2,2,2,3>", "conv_i8_dma_kernel<2,2,2,2,4>",
     "conv_i8_dma_kernel<4,1,2,2,2>", "conv_i8_dma_kernel<4,1,2,2,3>",
+    "conv_i8_kernel<2,2,2,2,64,0>", "conv_i8_kernel<4,1,2,2,64,0>",
     "conv_i8_kernel<4,1,2,1,64,0>", "conv_i8_kernel<2,2,2,2,64,1>", "conv_i8_kernel<4,1,2,2,64,1>",
     "conv_i8_kernel<4,1,2,1,64,1>"};
 
@@ -618,6 +778,7 @@ int pick_variant(const q8_conv_desc* d) {
   const int mode = conv_mode(d);
   if (mode == 1) return d->K > 64 ? V_REG4_128x128 : d->K > 32 ? V_REG4_256x64 : V_REG4_256x32;
   if (d->K <= 32) return V_REG_256x32;
+  if (d->R * d->S > 32) return d->K > 64 ? V_REG_128x128 : V_REG_256x64;   // tap mask is 32 bits
   const int nk = (d->R * d->S * d->C + 63) / 64;     // reduction steps of 64 bytes
   if (d->K > 64) return nk <= 1 ? V_DMA_128x128_S2 : nk <= 4 ? V_DMA_128x128_S3 : V_DMA_128x128_S4;
   return nk <= 1 ? V_DMA_256x64_S2 : V_DMA_256x64_S3;
@@ -640,12 +801,24 @@ int launch_reg(ConvParams& p, hipStream_t stream) {
   });
 }
 
+template <int WP, int WC, int TP, int TC, int STAGES, int UNIFORM>
+void launch_dma_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((conv_i8_dma_kernel<WP, WC, TP, TC, STAGES, UNIFORM>), grid, dim3(kThreads), 0,
+                     stream, p);
+}
+
 template <int WP, int WC, int TP, int TC, int STAGES>
 int launch_dma(ConvParams& p, hipStream_t stream) {
-  return launch_tiles<WP * TP * 32, WC * TC * 32>(p, [&](dim3 grid) {
-    hipLaunchKernelGGL((conv_i8_dma_kernel<WP, WC, TP, TC, STAGES>), grid, dim3(kThreads), 0, stream,
-                       p);
-  });
+  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
+  p.n_ptiles = (p.M + BP - 1) / BP;
+  p.n_ctiles = (p.K + BC - 1) / BC;
+  long nblk = (long)p.n_ptiles * p.n_ctiles;
+  if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
+  if (p.C % 64 == 0)
+    launch_dma_grid<WP, WC, TP, TC, STAGES, 1>(p, dim3((unsigned)nblk), stream);
+  else
+    launch_dma_grid<WP, WC, TP, TC, STAGES, 0>(p, dim3((unsigned)nblk), stream);
+  return q8_launch_status();
 }
 
 }  // namespace
@@ -730,6 +903,12 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
   Q8_REQUIRE(bias_i32 == nullptr || q8_aligned(bias_i32, 16), Q8_EALIGN);
   Q8_REQUIRE(acc_dump == nullptr || q8_aligned(acc_dump, 16), Q8_EALIGN);
 
+  {
+    const long xb = (long)d->N * d->H * d->W * p.in_cs, wb = (long)d->K * p.red_len;
+    Q8_REQUIRE(xb < 0x7fffffffL && wb < 0x7fffffffL, Q8_EUNSUPPORTED);   // 32-bit buffer offsets
+    p.x_bytes = (int)xb;
+    p.w_bytes = (int)wb;
+  }
   p.x = z_x; p.w = (const int8_t*)z_w_packed; p.bias = bias_i32; p.res = residual; p.y = z_y;
   p.acc_dump = acc_dump;
   p.M = (int)M;
@@ -754,6 +933,8 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
     case V_DMA_128x128_S4: return launch_dma<2, 2, 2, 2, 4>(p, s);
     case V_DMA_256x64_S2: return launch_dma<4, 1, 2, 2, 2>(p, s);
     case V_DMA_256x64_S3: return launch_dma<4, 1, 2, 2, 3>(p, s);
+    case V_REG_128x128: return launch_reg<2, 2, 2, 2, 0>(p, s);
+    case V_REG_256x64: return launch_reg<4, 1, 2, 2, 0>(p, s);
     case V_REG_256x32: return launch_reg<4, 1, 2, 1, 0>(p, s);
     case V_REG4_128x128: return launch_reg<2, 2, 2, 2, 1>(p, s);
     case V_REG4_256x64: return launch_reg<4, 1, 2, 2, 1>(p, s);
