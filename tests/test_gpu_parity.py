@@ -299,6 +299,47 @@ def test_config2_bottleneck_block(B):
             assert np.array_equal(host(eng.act[o]), acts[o])
 
 
+def test_config3_resnet50_batch64_sampled_images(B):
+    """Full ResNet-50 conv stack at batch 64 in the launch configuration the benchmark
+    times; the oracle evaluates images 0, 32 and 63 (batch elements are independent once
+    the factor table is frozen) and every tensor of the chain is compared bit for bit."""
+    from paper_1805_08691_amd.engine import Engine
+    cfg_id, batch, picks = 3, 64, [0, 32, 63]
+    net = wl.resnet50()
+    params = {op.name: wl.conv_params(cfg_id, i, op) for i, op in enumerate(net.convs())}
+    folded = onet.fold_all(net, params)
+    q = onet.calibrate(net, folded, (wl.input_batch(cfg_id, net, 8, 100 + i) for i in range(8)))
+    qparams = onet.quantize_params(net, folded, q)
+    x = wl.input_batch(cfg_id, net, batch, 0)
+    z_in = orc.Q(x[picks], q[net.input], 7)
+    acts = onet.forward_i8(net, qparams, q, z_in)
+
+    eng = Engine(net, batch)
+    eng.load_params(params)
+    eng.fold()
+    eng.set_factors(q)
+    eng.quantize_weights()
+    for name, qp in qparams.items():
+        assert np.float32(eng.qw[name]) == qp["q_w"], name
+        assert np.array_equal(host(eng.wq[name][1]), qp["z_b"]), name
+    xd = dev(x)
+    out = eng.forward(xd)[0]
+    zi = host(eng.act[net.input])
+    assert np.array_equal(zi[picks][..., :3], z_in) and np.all(zi[..., 3] == 0)
+    for op in net.ops:
+        got = host(eng.act[op.dst])[picks]
+        assert np.array_equal(got, acts[op.dst]), op.name
+    o = net.outputs[0]
+    r = host(B.dequantize(out, float(q[o])))[picks]
+    want = orc.D(acts[o], q[o])
+    assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want))
+    # replay through a HIP graph: same bits
+    eng.capture(xd)
+    eng.act[o].fill_(3)
+    eng.graph.replay()
+    assert np.array_equal(host(eng.act[o])[picks], acts[o])
+
+
 def test_gpu_calibration_matches_oracle_closely(B):
     # the GPU's own calibration (fp32 forward in a different summation order) gives
     # factors equal to the oracle's up to fp32 rounding of the activations
