@@ -131,6 +131,12 @@ int q8_conv_int8(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packe
  * For measurement code that groups launches by kernel.                              */
 const char *q8_conv_variant(const q8_conv_desc *d);
 
+/* Tests and tuning only: force tile/ring variant `index` (0 .. 8, in the order of the
+ * library's variant table) for every later q8_conv_int8 call whose geometry the main
+ * kernel can take (C % 16 == 0, K > 32, R*S <= 32); -1 restores automatic selection.
+ * Process-wide, not thread-safe; results are identical for every variant.             */
+int q8_conv_force_variant(int index);
+
 /* ---- helpers that only chain layers; not part of the paper's method ------------ */
 
 /* fp32 NHWC convolution + bias (+ dense residual) (+ ReLU), used to produce the

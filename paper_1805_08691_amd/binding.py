@@ -24,7 +24,7 @@ EXPORTS = [
     "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
     "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_bias", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
-    "q8_conv_variant",
+    "q8_conv_variant", "q8_conv_force_variant",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32",
 ]
 
@@ -78,6 +78,7 @@ lib.q8_pack_weights.argtypes = [_dp, _vp, _vp, _vp]
 lib.q8_conv_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
 lib.q8_conv_variant.argtypes = [_dp]
+lib.q8_conv_force_variant.argtypes = [_i]
 lib.q8_conv_f32_ref.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.q8_maxpool_i8.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
 lib.q8_maxpool_f32.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
@@ -182,6 +183,10 @@ def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q
 
 def conv_variant(desc):
     return lib.q8_conv_variant(C.byref(desc)).decode()
+
+
+def conv_force_variant(index):
+    _check(lib.q8_conv_force_variant(int(index)))
 
 
 def conv_f32_ref(desc, x, w, b=None, res=None, out=None):

@@ -171,6 +171,8 @@ __device__ __forceinline__ int swz(int row, int chunk) {
     int f = (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
     return chunk ^ f;
   } else {
+    // 128-byte rows: two rows share a 256-byte bank line, so the slot must differ for the
+    // eight row pairs a quarter-wave touches
     return chunk ^ ((row >> 1) & (CHUNKS - 1));
   }
 }
@@ -412,23 +414,26 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
 // reduction step, so the tap offset is a scalar.  Otherwise each lane tracks its own tap.
 constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
 
-template <int WP, int WC, int TP, int TC, int STAGES, int UNIFORM>
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
 __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
                                       // descriptor types exist for the device target alone
-  constexpr int BK = 64, CHUNKS = 4;
+  constexpr int CHUNKS = BK / 16;          // 16-byte chunks per LDS row
+  constexpr int RPW = 64 / CHUNKS;         // rows filled by one wavefront-wide load (1 KB)
+  constexpr int NH = BK / 32;              // MFMA sub-steps (32 reduction bytes) per step
   constexpr int BP = WP * TP * 32;
   constexpr int BC = WC * TC * 32;
-  constexpr int A_GROUPS = BC / 16, B_GROUPS = BP / 16;     // 16-row groups = one wave-load
+  constexpr int A_GROUPS = BC / RPW, B_GROUPS = BP / RPW;
   constexpr int A_LOADS = A_GROUPS / 4, B_LOADS = B_GROUPS / 4;
   constexpr int LOADS = A_LOADS + B_LOADS;                   // per lane per stage
   constexpr int A_BYTES = BC * BK, STAGE_BYTES = (BC + BP) * BK;
+  static_assert(BK == 64 || BK == 128, "reduction bytes per step");
   static_assert(WP * WC == 4, "four wavefronts per block");
   static_assert(A_GROUPS % 4 == 0 && B_GROUPS % 4 == 0, "every wave issues the same loads");
   static_assert(STAGES >= 2 && STAGES <= 4, "ring depth");
-  static_assert(STAGES * STAGE_BYTES <= 65536, "static LDS limit");
+  static_assert((STAGES - 2) * LOADS < 64, "vmcnt is 6 bits");
 
-  __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES];
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // STAGES * STAGE_BYTES
 
   const int nblk = p.n_ptiles * p.n_ctiles;
   int bid = blockIdx.x;
@@ -453,14 +458,16 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, p.x_bytes, 0x00020000);
 
-  // ---- loader state
-  const int lrow16 = lane >> 2;                              // row inside a 16-row group
-  const int lchunk = (lane & 3) ^ swz<CHUNKS>(lrow16, 0);    // logical chunk this lane fetches
+  // ---- loader state: lane l of wave w fills, in its j-th load, row (w + 4j)*RPW + l/CHUNKS,
+  // physical slot l % CHUNKS.  The swizzle term only depends on row bits that do not change
+  // with j, so the logical chunk a lane fetches is fixed.
+  const int lrow = lane / CHUNKS;
+  const int lchunk = (lane % CHUNKS) ^ swz<CHUNKS>(wave * RPW + lrow, 0);
 
   int a_off[A_LOADS];                  // filter row offset + chunk, or out of range
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
-    const int row = (wave + 4 * j) * 16 + lrow16;
+    const int row = (wave + 4 * j) * RPW + lrow;
     const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
     a_off[j] = ch < p.K ? ch * p.red_len + lchunk * 16 : kOobOffset;
   }
@@ -468,7 +475,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
   unsigned b_mask[B_LOADS];            // bit t: tap t of this pixel lies inside the image
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) {
-    const int pix = pix0 + (wave + 4 * j) * 16 + lrow16;
+    const int pix = pix0 + (wave + 4 * j) * RPW + lrow;
     unsigned mask = 0;
     int off = 0;
     if (pix < p.M) {
@@ -576,49 +583,70 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = b[v];
   }
-  int res_w[TC][TP][4];
-
   const int nk = (p.red_len + BK - 1) / BK;
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
 
-  // Operand fragments of the two 32-byte halves of a reduction step.  The loop is
-  // software-pipelined inside one wavefront: the LDS reads of a half are issued one phase
-  // before the MFMAs that consume them, and the MFMAs of the second half of step kt-1 run
-  // after the barrier of step kt, so LDS latency, the barrier and the issue of the global
-  // loads all overlap matrix work.
-  v4i af[2][TC], bf[2][TP];
-  int a_foff[2][TC], b_foff[2][TP];          // LDS offsets inside a stage, per half
+  // Residual codes (fused element-wise sum).  With a short reduction (every step fits in
+  // the prologue) they are requested first of all, so one memory latency covers bias,
+  // residual and operands; otherwise they are requested in the last step.
+  int res_w[TC][TP][4];
+  auto fetch_residual = [&]() {
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+        load_res16(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31),
+                   ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), res_w[i][j]);
+  };
+  const bool early_residual = nk <= STAGES - 1;
+  if (early_residual) fetch_residual();
+
+  // Operand fragments of the 32-byte sub-steps of a reduction step, double-buffered in
+  // registers.  The loop is software-pipelined inside one wavefront: the LDS reads of a
+  // sub-step are issued one phase before the MFMAs that consume them, and the MFMAs of the
+  // last sub-step of step kt-1 run after the barrier of step kt, so LDS latency, the
+  // barrier and the issue of the global loads all overlap matrix work.
+  v4i af[2][TC], bf[2][TP];
+  int a_foff[NH][TC], b_foff[NH][TP];        // LDS offsets inside a stage, per sub-step
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
     const int chunk = 2 * h + frag_half;
 #pragma unroll
     for (int i = 0; i < TC; ++i) {
       const int row = (wave_c * TC + i) * 32 + frag_row;
       a_foff[h][i] = row * BK + swz<CHUNKS>(row, chunk) * 16;
       asm volatile("" : "+v"(a_foff[h][i]));     // keep in a register, do not recompute
-      af[h][i] = v4i{0, 0, 0, 0};
     }
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
       const int row = (wave_p * TP + j) * 32 + frag_row;
       b_foff[h][j] = A_BYTES + row * BK + swz<CHUNKS>(row, chunk) * 16;
       asm volatile("" : "+v"(b_foff[h][j]));
-      bf[h][j] = v4i{0, 0, 0, 0};
     }
+  }
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i) af[b][i] = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < TP; ++j) bf[b][j] = v4i{0, 0, 0, 0};
   }
   auto load_frags = [&](const int8_t* stage, int h) {
 #pragma unroll
-    for (int i = 0; i < TC; ++i) af[h][i] = *reinterpret_cast<const v4i*>(stage + a_foff[h][i]);
+    for (int i = 0; i < TC; ++i)
+      af[h & 1][i] = *reinterpret_cast<const v4i*>(stage + a_foff[h][i]);
 #pragma unroll
-    for (int j = 0; j < TP; ++j) bf[h][j] = *reinterpret_cast<const v4i*>(stage + b_foff[h][j]);
+    for (int j = 0; j < TP; ++j)
+      bf[h & 1][j] = *reinterpret_cast<const v4i*>(stage + b_foff[h][j]);
   };
   auto mma = [&](int h) {
 #pragma unroll
     for (int i = 0; i < TC; ++i)
 #pragma unroll
       for (int j = 0; j < TP; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h][i], bf[h][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
+                                                          0, 0, 0);
   };
 
   // One reduction step.  LATER = steps issued after step kt that may still be in flight
@@ -629,7 +657,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
     wait_vmcnt<LATER * LOADS>();
     // Bare barrier (no fence: a fence would drain the loads of the later steps too).
     // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS
-    // (its second-half fragments are in registers already).
+    // (its last fragments are in registers already).
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -637,35 +665,35 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
     load_frags(stage, 0);
     if constexpr (decltype(issue_c)::value) issue_stage((kt + STAGES - 1) % STAGES);
     if constexpr (decltype(last_c)::value) {
-#pragma unroll
-      for (int i = 0; i < TC; ++i)
-#pragma unroll
-        for (int j = 0; j < TP; ++j)
-          load_res16(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31),
-                     ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), res_w[i][j]);
+      if (!early_residual) fetch_residual();
     }
-    mma(1);                             // second half of step kt-1 (zeros on the first step)
-    load_frags(stage, 1);
-    mma(0);
-    // Instruction order inside the step (one scheduling region): the four LDS reads of the
-    // first half, then the MFMAs of the previous second half with one global->LDS load
-    // after each (a wavefront issues in order: spreading the loads lets a load that waits
-    // for queue space hide behind a running MFMA), then the MFMAs of the first half with
-    // the LDS reads of the second half between them.
+    mma(NH - 1);                        // last sub-step of step kt-1 (zeros on the first step)
+#pragma unroll
+    for (int h = 1; h < NH; ++h) {
+      load_frags(stage, h);
+      mma(h - 1);
+    }
+    // Instruction order inside the step (one scheduling region): the LDS reads of the
+    // first sub-step; then MFMAs with one global->LDS load after each (a wavefront issues
+    // in order: spreading the loads lets a load that waits for queue space hide behind a
+    // running MFMA); the LDS reads of sub-step h are spread between the MFMAs of h-1.
     if constexpr (!decltype(last_c)::value) {
-      __builtin_amdgcn_sched_group_barrier(0x100, TC + TP, 0);            // DS reads, half 0
-      constexpr int kMma = TC * TP;
+      constexpr int kMma = TC * TP, kFrag = TC + TP;
       constexpr int kVmem = decltype(issue_c)::value ? LOADS : 0;
+      __builtin_amdgcn_sched_group_barrier(0x100, kFrag, 0);              // DS reads, sub-step 0
+      int vmem_left = kVmem;
 #pragma unroll
-      for (int g = 0; g < kMma; ++g) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // one MFMA
-        if (g < kVmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); // one VMEM read
-      }
-      if (kVmem > kMma) __builtin_amdgcn_sched_group_barrier(0x020, kVmem - kMma, 0);
+      for (int h = 0; h < NH; ++h) {
 #pragma unroll
-      for (int g = 0; g < kMma; ++g) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // one MFMA
-        if (g < TC + TP) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
+        for (int g = 0; g < kMma; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
+          if (vmem_left > 0) {
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);            // one VMEM read
+            --vmem_left;
+          }
+          if (h + 1 < NH && g < kFrag)
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // one DS read
+        }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -698,7 +726,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_dma_kernel(const ConvParams 
   }
   step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
        integral_constant<bool, true>{});
-  mma(1);
+  mma(NH - 1);
 
 #pragma unroll
   for (int j = 0; j < TP; ++j) {
@@ -761,27 +789,45 @@ int conv_mode(const q8_conv_desc* d) {
   return -1;
 }
 
-// Kernel variants.  "dma" = direct-to-LDS ring kernel (C % 16 == 0 and K > 32); "reg" =
-// register-staged kernel (4-channel images, and K <= 32 where a 32-channel tile is used).
+// Kernel variants.  "dma" = direct-to-LDS ring kernel (C % 16 == 0, K > 32, R*S <= 32);
+// "reg" = register-staged kernel (4-channel images, K <= 32, R*S > 32).
 enum Variant {
-  V_DMA_128x128_S2, V_DMA_128x128_S3, V_DMA_128x128_S4, V_DMA_256x64_S2, V_DMA_256x64_S3,
+  V_DMA64_128x128_S2, V_DMA64_128x128_S3, V_DMA64_128x128_S4, V_DMA64_256x64_S2, V_DMA64_256x64_S3,
+  V_DMA128_128x128_S2, V_DMA128_128x128_S3, V_DMA128_256x64_S2, V_DMA128_256x64_S3,
   V_REG_128x128, V_REG_256x64, V_REG_256x32, V_REG4_128x128, V_REG4_256x64, V_REG4_256x32, V_COUNT
 };
 const char* const kVariantNames[V_COUNT] = {
-    "conv_i8_dma_kernel<2,2,2,2,2>", "conv_i8_dma_kernel<2,2,2,2,3>", "conv_i8_dma_kernel<2,2,2,2,4>",
-    "conv_i8_dma_kernel<4,1,2,2,2>", "conv_i8_dma_kernel<4,1,2,2,3>",
+    "conv_i8_dma_kernel<2,2,2,2,64,2>", "conv_i8_dma_kernel<2,2,2,2,64,3>",
+    "conv_i8_dma_kernel<2,2,2,2,64,4>", "conv_i8_dma_kernel<4,1,2,2,64,2>",
+    "conv_i8_dma_kernel<4,1,2,2,64,3>",
+    "conv_i8_dma_kernel<2,2,2,2,128,2>", "conv_i8_dma_kernel<2,2,2,2,128,3>",
+    "conv_i8_dma_kernel<4,1,2,2,128,2>", "conv_i8_dma_kernel<4,1,2,2,128,3>",
     "conv_i8_kernel<2,2,2,2,64,0>", "conv_i8_kernel<4,1,2,2,64,0>",
     "conv_i8_kernel<4,1,2,1,64,0>", "conv_i8_kernel<2,2,2,2,64,1>", "conv_i8_kernel<4,1,2,2,64,1>",
     "conv_i8_kernel<4,1,2,1,64,1>"};
 
+int g_variant_override = -1;   // tests / tuning: force a "dma" variant where it is applicable
+
 int pick_variant(const q8_conv_desc* d) {
   const int mode = conv_mode(d);
+  if (g_variant_override >= 0 && g_variant_override < V_REG_128x128 && mode == 0 && d->K > 32 &&
+      d->R * d->S <= 32)
+    return g_variant_override;
   if (mode == 1) return d->K > 64 ? V_REG4_128x128 : d->K > 32 ? V_REG4_256x64 : V_REG4_256x32;
   if (d->K <= 32) return V_REG_256x32;
   if (d->R * d->S > 32) return d->K > 64 ? V_REG_128x128 : V_REG_256x64;   // tap mask is 32 bits
-  const int nk = (d->R * d->S * d->C + 63) / 64;     // reduction steps of 64 bytes
-  if (d->K > 64) return nk <= 1 ? V_DMA_128x128_S2 : nk <= 4 ? V_DMA_128x128_S3 : V_DMA_128x128_S4;
-  return nk <= 1 ? V_DMA_256x64_S2 : V_DMA_256x64_S3;
+  const int red = d->R * d->S * d->C;
+  const bool wide = d->K > 64;
+  if (d->C % 128 == 0) {
+    // full 128-byte lines per row and step: the L2 -> LDS path is ~1.6x faster than with
+    // 64-byte segments, and there are half as many barriers
+    const int nk = red / 128;
+    if (wide) return nk <= 2 ? V_DMA128_128x128_S2 : V_DMA128_128x128_S3;
+    return nk <= 2 ? V_DMA128_256x64_S2 : V_DMA128_256x64_S3;
+  }
+  const int nk = (red + 63) / 64;     // reduction steps of 64 bytes
+  if (wide) return nk <= 1 ? V_DMA64_128x128_S2 : nk <= 4 ? V_DMA64_128x128_S3 : V_DMA64_128x128_S4;
+  return nk <= 1 ? V_DMA64_256x64_S2 : V_DMA64_256x64_S3;
 }
 
 template <int BP, int BC, typename F>
@@ -801,24 +847,30 @@ int launch_reg(ConvParams& p, hipStream_t stream) {
   });
 }
 
-template <int WP, int WC, int TP, int TC, int STAGES, int UNIFORM>
-void launch_dma_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
-  hipLaunchKernelGGL((conv_i8_dma_kernel<WP, WC, TP, TC, STAGES, UNIFORM>), grid, dim3(kThreads), 0,
-                     stream, p);
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
+int launch_dma_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
+  constexpr int kLdsBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
+  auto kernel = conv_i8_dma_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM>;
+  if constexpr (kLdsBytes > 65536) {
+    // more than 64 KB of LDS per workgroup has to be requested once per kernel
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr != hipSuccess) return Q8_EHIP;
+  }
+  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, stream, p);
+  return q8_launch_status();
 }
 
-template <int WP, int WC, int TP, int TC, int STAGES>
+template <int WP, int WC, int TP, int TC, int BK, int STAGES>
 int launch_dma(ConvParams& p, hipStream_t stream) {
   constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
   p.n_ptiles = (p.M + BP - 1) / BP;
   p.n_ctiles = (p.K + BC - 1) / BC;
   long nblk = (long)p.n_ptiles * p.n_ctiles;
   if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
-  if (p.C % 64 == 0)
-    launch_dma_grid<WP, WC, TP, TC, STAGES, 1>(p, dim3((unsigned)nblk), stream);
-  else
-    launch_dma_grid<WP, WC, TP, TC, STAGES, 0>(p, dim3((unsigned)nblk), stream);
-  return q8_launch_status();
+  if (p.C % BK == 0)
+    return launch_dma_grid<WP, WC, TP, TC, BK, STAGES, 1>(p, dim3((unsigned)nblk), stream);
+  return launch_dma_grid<WP, WC, TP, TC, BK, STAGES, 0>(p, dim3((unsigned)nblk), stream);
 }
 
 }  // namespace
@@ -928,11 +980,15 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
 
   hipStream_t s = (hipStream_t)stream;
   switch (pick_variant(d)) {
-    case V_DMA_128x128_S2: return launch_dma<2, 2, 2, 2, 2>(p, s);
-    case V_DMA_128x128_S3: return launch_dma<2, 2, 2, 2, 3>(p, s);
-    case V_DMA_128x128_S4: return launch_dma<2, 2, 2, 2, 4>(p, s);
-    case V_DMA_256x64_S2: return launch_dma<4, 1, 2, 2, 2>(p, s);
-    case V_DMA_256x64_S3: return launch_dma<4, 1, 2, 2, 3>(p, s);
+    case V_DMA64_128x128_S2: return launch_dma<2, 2, 2, 2, 64, 2>(p, s);
+    case V_DMA64_128x128_S3: return launch_dma<2, 2, 2, 2, 64, 3>(p, s);
+    case V_DMA64_128x128_S4: return launch_dma<2, 2, 2, 2, 64, 4>(p, s);
+    case V_DMA64_256x64_S2: return launch_dma<4, 1, 2, 2, 64, 2>(p, s);
+    case V_DMA64_256x64_S3: return launch_dma<4, 1, 2, 2, 64, 3>(p, s);
+    case V_DMA128_128x128_S2: return launch_dma<2, 2, 2, 2, 128, 2>(p, s);
+    case V_DMA128_128x128_S3: return launch_dma<2, 2, 2, 2, 128, 3>(p, s);
+    case V_DMA128_256x64_S2: return launch_dma<4, 1, 2, 2, 128, 2>(p, s);
+    case V_DMA128_256x64_S3: return launch_dma<4, 1, 2, 2, 128, 3>(p, s);
     case V_REG_128x128: return launch_reg<2, 2, 2, 2, 0>(p, s);
     case V_REG_256x64: return launch_reg<4, 1, 2, 2, 0>(p, s);
     case V_REG_256x32: return launch_reg<4, 1, 2, 1, 0>(p, s);
@@ -940,6 +996,12 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
     case V_REG4_256x64: return launch_reg<4, 1, 2, 2, 1>(p, s);
     default: return launch_reg<4, 1, 2, 1, 1>(p, s);
   }
+}
+
+int q8_conv_force_variant(int index) {
+  if (index < -1 || index >= V_REG_128x128) return Q8_EINVAL;
+  g_variant_override = index;
+  return Q8_OK;
 }
 
 const char* q8_conv_variant(const q8_conv_desc* d) {
