@@ -14,12 +14,16 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libq8conv.so")
-SOURCES = ["q8_elementwise.hip", "q8_conv.hip", "q8_helpers.hip"]
+SOURCES = ["q8_elementwise.hip", "q8_conv.hip", "q8_conv_ring.hip", "q8_conv_reg.hip",
+           "q8_helpers.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # accumulators that are also read by ordinary vector code (the in-loop epilogue of the
+         # persistent kernel) stay in VGPRs: no per-step copies between VGPRs and AGPRs
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-function",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -1,0 +1,216 @@
+// Device-side pieces shared by the convolution kernels: parameter block, the
+// filter-row permutation, the fused epilogue (Eq. A' tail, Eq. +, conv+ReLU / conv+sum
+// fusion of arxiv 1805.08691), the LDS slot swizzle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#pragma clang fp contract(off)   // the epilogue's op order is part of the result
+
+namespace q8 {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
+
+constexpr int kThreads = 256;
+constexpr int kNumXcd = 8;
+
+struct ConvParams {
+  const int8_t* __restrict__ x;
+  const int8_t* __restrict__ w;       // packed filters: [K][red_len] bytes
+  const int32_t* __restrict__ bias;
+  const int8_t* __restrict__ res;
+  int8_t* __restrict__ y;
+  int32_t* __restrict__ acc_dump;
+  int N, H, W, C, K, R, S;
+  int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+  int Ho, Wo;
+  int in_cs, out_cs, out_off, res_cs, res_off;
+  int M;          // N*Ho*Wo
+  int red_len;    // reduction bytes per filter (R*S*C, or R*S4*16 in the 4-channel mode)
+  int S4;         // 4-channel mode: 16-byte chunks per filter row (ceil(S/4))
+  int n_ptiles, n_ctiles;
+  int x_bytes, w_bytes;   // sizes of the activation and filter tensors (buffer descriptors)
+  float m, m_r;
+  int relu;
+  int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
+  int vec16;      // 1: out/res addresses of 16-channel groups are 16-byte aligned
+};
+
+// Filter row (within a 32-row MFMA tile) -> output channel.  The 32x32 MFMA leaves, in
+// accumulator register 4a+b of a lane in half g, row 8a+4g+b.  Feeding channel 16g+4a+b
+// as that row makes the 16 accumulators of a lane 16 CONSECUTIVE channels of one pixel,
+// so the epilogue needs one 16-byte residual load and one 16-byte store per lane.
+__device__ __forceinline__ int row_to_channel(int row) {
+  return (((row >> 2) & 1) << 4) | ((row >> 3) << 2) | (row & 3);
+}
+
+// ---- Epilogue pieces, all for 16 consecutive channels [ch, ch+16) of one pixel ------------
+
+// Bias of the 16 channels (zero where there is no bias or the channel is beyond K).
+__device__ __forceinline__ void load_bias16(const ConvParams& p, int ch, int (&b)[16]) {
+  const int nvalid = p.K - ch;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) b[e] = 0;
+  if (!p.bias || nvalid <= 0) return;
+  if (nvalid >= 16) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      v4i bv = *reinterpret_cast<const v4i*>(p.bias + ch + 4 * a);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) b[4 * a + k] = bv[k];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      if (e < nvalid) b[e] = p.bias[ch + e];
+  }
+}
+
+// The 16 residual codes, packed four to a word (zero where absent).
+__device__ __forceinline__ void load_res16(const ConvParams& p, int pix, int ch, int (&rw)[4]) {
+  rw[0] = rw[1] = rw[2] = rw[3] = 0;
+  const int nvalid = p.K - ch;
+  if (!p.res || nvalid <= 0 || pix >= p.M) return;
+  const int8_t* r = p.res + (size_t)pix * p.res_cs + p.res_off + ch;
+  if (nvalid >= 16 && p.vec16) {
+    v4i q = *reinterpret_cast<const v4i*>(r);
+    rw[0] = q[0]; rw[1] = q[1]; rw[2] = q[2]; rw[3] = q[3];
+  } else {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      if (p.vec4 && 4 * a + 3 < nvalid) {
+        rw[a] = *reinterpret_cast<const int*>(r + 4 * a);
+      } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          if (4 * a + b < nvalid) rw[a] |= ((int)(uint8_t)r[4 * a + b]) << (8 * b);
+      }
+    }
+  }
+}
+
+// Tail of Eq. A' with the fused sum: v = accumulators (bias included), rw = residual codes.
+// fp32 scale, residual term, ReLU, clamp, Round, int8 pack, store (and the accumulator dump).
+__device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, const int (&v)[16],
+                                         const int (&rw)[4]) {
+  const int nvalid = p.K - ch;          // > 0 guaranteed by the caller
+  const bool full = nvalid >= 16;
+  if (p.acc_dump) {
+    int32_t* d = p.acc_dump + (size_t)pix * p.K + ch;
+    if (full && (p.K & 3) == 0) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        *reinterpret_cast<v4i*>(d + 4 * a) = v4i{v[4 * a], v[4 * a + 1], v[4 * a + 2], v[4 * a + 3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e < nvalid) d[e] = v[e];
+    }
+  }
+  float t[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * p.m;
+  if (p.res) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float u = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) * p.m_r;
+      t[e] = t[e] + u;
+    }
+  }
+  unsigned zw[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    float u = t[e];
+    if (p.relu) u = fmaxf(u, 0.0f);
+    u = fminf(fmaxf(u, -128.0f), 127.0f);
+    zw[e >> 2] |= ((unsigned)((int)rintf(u)) & 0xffu) << (8 * (e & 3));
+  }
+  int8_t* o = p.y + (size_t)pix * p.out_cs + p.out_off + ch;
+  if (full && p.vec16) {
+    *reinterpret_cast<v4i*>(o) = v4i{(int)zw[0], (int)zw[1], (int)zw[2], (int)zw[3]};
+  } else {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      if (p.vec4 && 4 * a + 3 < nvalid) {
+        *reinterpret_cast<unsigned*>(o + 4 * a) = zw[a];
+      } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          if (4 * a + b < nvalid) o[4 * a + b] = (int8_t)((zw[a] >> (8 * b)) & 0xff);
+      }
+    }
+  }
+}
+
+// The same tail for a COMPLETE group (all 16 channels valid, 16-byte aligned addresses, no
+// accumulator dump), branch-free and with as few vector instructions per element as the
+// fixed arithmetic allows: convert, scale, (residual: convert, scale, add), one median for
+// ReLU + clamp, and Round by adding 1.5 * 2^23 -- for |t| <= 128 the fp32 sum is the
+// round-half-to-even integer and its low byte is the two's-complement int8 code -- then
+// byte permutes to pack four codes per word.  Bit-identical to finish16.
+template <bool HAS_RES>
+__device__ __forceinline__ void finish16_fast(const ConvParams& p, int pix, int ch,
+                                              const int (&v)[16], const int (&rw)[4]) {
+  const float lo = p.relu ? 0.0f : -128.0f;     // ReLU folded into the lower clamp bound
+  unsigned r[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    float t = (float)v[e] * p.m;
+    if (HAS_RES) {
+      const float u = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) * p.m_r;
+      t = t + u;
+    }
+    t = __builtin_amdgcn_fmed3f(t, lo, 127.0f);
+    r[e] = __float_as_uint(t + 12582912.0f);
+  }
+  v4i out;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const unsigned w01 = __builtin_amdgcn_perm(r[4 * a + 1], r[4 * a], 0x0c0c0400u);
+    const unsigned w23 = __builtin_amdgcn_perm(r[4 * a + 3], r[4 * a + 2], 0x0c0c0400u);
+    out[a] = (int)__builtin_amdgcn_perm(w23, w01, 0x05040100u);
+  }
+  *reinterpret_cast<v4i*>(p.y + (size_t)pix * p.out_cs + p.out_off + ch) = out;
+}
+
+// Whole epilogue in one go (register-staged kernel).
+__device__ __forceinline__ void epilogue16(const ConvParams& p, int pix, int ch, int (&v)[16]) {
+  int b[16], rw[4];
+  load_bias16(p, ch, b);
+  load_res16(p, pix, ch, rw);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) v[e] += b[e];
+  finish16(p, pix, ch, v, rw);
+}
+
+// 16-byte chunk index -> physical chunk slot inside an LDS row (XOR swizzle so that the
+// 16 rows a quarter-wave reads at one reduction offset fall into distinct bank groups).
+template <int CHUNKS>
+__device__ __forceinline__ int swz(int row, int chunk) {
+  if constexpr (CHUNKS == 4) {
+    int f = (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
+    return chunk ^ f;
+  } else {
+    // 128-byte rows: two rows share a 256-byte bank line, so the slot must differ for the
+    // eight row pairs a quarter-wave touches
+    return chunk ^ ((row >> 1) & (CHUNKS - 1));
+  }
+}
+
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+
+// Entry points of the kernel translation units (host side).
+int launch_reg_variant(int variant, ConvParams& p, hipStream_t stream);      // q8_conv_reg.hip
+int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream);   // q8_conv_ring.hip
+const char* stream_variant_name(int variant);
+const char* reg_variant_name(int variant);
+
+}  // namespace q8

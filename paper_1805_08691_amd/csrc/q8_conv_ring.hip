@@ -1,0 +1,430 @@
+// Main int8 implicit-GEMM convolution kernel (Eq. x / Eq. A' of arxiv 1805.08691) for
+// gfx950: C % 16 == 0, more than 32 output channels, at most 32 filter taps.
+//
+// One workgroup (4 wavefronts) per output tile.  Chunks go from global memory straight into
+// LDS (buffer_load_dwordx4 ... lds, no register staging) through a ring of STAGES buffers,
+// so several reduction steps of loads are in flight per workgroup while the MFMAs of the
+// current step run.  One bare s_barrier per reduction step.
+//
+// A wavefront-wide direct load writes 64 x 16 bytes to consecutive LDS addresses, i.e. RPW
+// rows of BK bytes.  Which global chunk lands in which slot is chosen on the global side:
+// lane l fills row l / CHUNKS, physical slot l % CHUNKS, and therefore fetches logical chunk
+// (l % CHUNKS) ^ swz(row) of that row (XOR swizzle: conflict-free ds_read_b128 operand reads).
+//
+// Addressing uses raw buffer descriptors: a per-lane 32-bit offset that is computed once,
+// plus a wave-uniform offset per reduction step, so a load costs a handful of VALU
+// instructions.  A chunk that must read as zero (padding, pixel or channel beyond the
+// tensor, reduction tail) gets an offset beyond the descriptor's size: the hardware's
+// range check then returns zeros.
+//
+// UNIFORM (C % BK == 0): every lane of the block is in the same filter tap during one
+// reduction step, so the tap offset is a scalar.  Otherwise each lane tracks its own tap.
+#include <type_traits>
+#include "q8_common.h"
+#include "q8_conv_common.h"
+
+namespace q8 {
+namespace {
+
+constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
+
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
+__global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
+                                      // descriptor types exist for the device target alone
+  constexpr int CHUNKS = BK / 16;          // 16-byte chunks per LDS row
+  constexpr int RPW = 64 / CHUNKS;         // rows filled by one wavefront-wide load (1 KB)
+  constexpr int NH = BK / 32;              // MFMA sub-steps (32 reduction bytes) per step
+  constexpr int BP = WP * TP * 32;
+  constexpr int BC = WC * TC * 32;
+  constexpr int A_GROUPS = BC / RPW, B_GROUPS = BP / RPW;
+  constexpr int A_LOADS = A_GROUPS / 4, B_LOADS = B_GROUPS / 4;
+  constexpr int LOADS = A_LOADS + B_LOADS;                   // per lane per stage
+  constexpr int A_BYTES = BC * BK, STAGE_BYTES = (BC + BP) * BK;
+  static_assert(BK == 64 || BK == 128, "reduction bytes per step");
+  static_assert(WP * WC == 4, "four wavefronts per block");
+  static_assert(A_GROUPS % 4 == 0 && B_GROUPS % 4 == 0, "every wave issues the same loads");
+  static_assert(STAGES >= 2 && STAGES <= 4, "ring depth");
+  static_assert((STAGES - 2) * LOADS < 64, "vmcnt is 6 bits");
+
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // STAGES * STAGE_BYTES
+
+  const int nblk = p.n_ptiles * p.n_ctiles;
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
+    const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
+    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int ctile = bid % p.n_ctiles;
+  const int ptile = bid / p.n_ctiles;
+  const int pix0 = ptile * BP;
+  const int ch0 = ctile * BC;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_p = wave % WP;
+  const int wave_c = wave / WP;
+
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, p.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, p.x_bytes, 0x00020000);
+
+  // ---- loader state: lane l of wave w fills, in its j-th load, row (w + 4j)*RPW + l/CHUNKS,
+  // physical slot l % CHUNKS.  The swizzle term only depends on row bits that do not change
+  // with j, so the logical chunk a lane fetches is fixed.
+  const int lrow = lane / CHUNKS;
+  const int lchunk = (lane % CHUNKS) ^ swz<CHUNKS>(wave * RPW + lrow, 0);
+
+  int a_off[A_LOADS];                  // filter row offset + chunk, or out of range
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int row = (wave + 4 * j) * RPW + lrow;
+    const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
+    a_off[j] = ch < p.K ? ch * p.red_len + lchunk * 16 : kOobOffset;
+  }
+  int b_off[B_LOADS];                  // offset of tap (0,0), channel 0 (+ chunk if UNIFORM)
+  unsigned b_mask[B_LOADS];            // bit t: tap t of this pixel lies inside the image
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    const int pix = pix0 + (wave + 4 * j) * RPW + lrow;
+    unsigned mask = 0;
+    int off = 0;
+    if (pix < p.M) {
+      const int n = pix / (p.Ho * p.Wo);
+      const int rem = pix - n * (p.Ho * p.Wo);
+      const int ho = rem / p.Wo;
+      const int wo = rem - ho * p.Wo;
+      const int hi0 = ho * p.stride_h - p.pad_h;
+      const int wi0 = wo * p.stride_w - p.pad_w;
+      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + (UNIFORM ? lchunk * 16 : 0);
+      int t = 0;
+      for (int r = 0; r < p.R; ++r) {
+        const bool hok = (unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H;
+        for (int s2 = 0; s2 < p.S; ++s2, ++t)
+          if (hok && (unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) mask |= 1u << t;
+      }
+    }
+    b_off[j] = off;
+    b_mask[j] = mask;
+  }
+
+  // ---- position in the reduction
+  const int dw_step = p.dil_w * p.in_cs;                     // offset step of one tap along S
+  const int dh_step = p.dil_h * p.W * p.in_cs - p.S * dw_step;   // extra step when a row wraps
+  // UNIFORM: scalars shared by the block.  Otherwise: this lane's own chunk.
+  int step_base = 0;                     // reduction byte offset of the next step to issue
+  int tap = 0, tap_s = 0, tap_c = 0, tap_delta = 0;
+  if (!UNIFORM) {
+    const int red = lchunk * 16;
+    tap = red / p.C;
+    tap_c = red - tap * p.C;
+    const int r = tap / p.S;
+    tap_s = tap - r * p.S;
+    tap_delta = (r * p.dil_h * p.W + tap_s * p.dil_w) * p.in_cs;
+  }
+
+  auto issue_stage = [&](int buf) {
+    int8_t* stage = lds + buf * STAGE_BYTES;
+    if constexpr (UNIFORM) {
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16,
+            a_off[j], step_base, 0, 0);
+      const int delta = tap_delta + tap_c;
+#pragma unroll
+      for (int j = 0; j < B_LOADS; ++j) {
+        const int voff = ((b_mask[j] >> tap) & 1u) ? b_off[j] + delta : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_x,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16,
+            voff, 0, 0, 0);
+      }
+      step_base += BK;
+      // advance (branch-free, so the whole step stays one scheduling region)
+      tap_c += BK;
+      const int wrap_c = tap_c >= p.C ? 1 : 0;
+      tap_c = wrap_c ? 0 : tap_c;
+      tap += wrap_c;
+      tap_s += wrap_c;
+      tap_delta += wrap_c ? dw_step : 0;
+      const int wrap_s = tap_s == p.S ? 1 : 0;
+      tap_s = wrap_s ? 0 : tap_s;
+      tap_delta += wrap_s ? dh_step : 0;
+    } else {
+      const bool red_ok = step_base + lchunk * 16 < p.red_len;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        const int voff = red_ok ? a_off[j] : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16,
+            voff, step_base, 0, 0);
+      }
+      const int delta = tap_delta + tap_c;
+#pragma unroll
+      for (int j = 0; j < B_LOADS; ++j) {
+        const bool ok = red_ok && ((b_mask[j] >> tap) & 1u);
+        const int voff = ok ? b_off[j] + delta : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_x,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16,
+            voff, 0, 0, 0);
+      }
+      step_base += BK;
+      tap_c += BK;
+      while (tap_c >= p.C) {
+        tap_c -= p.C;
+        ++tap;
+        tap_delta += dw_step;
+        if (++tap_s == p.S) { tap_s = 0; tap_delta += dh_step; }
+      }
+    }
+  };
+
+  // Accumulators start at the bias (Eq. A': the int32 bias shares the accumulator's factor).
+  // These loads are issued before any stage load, so the in-order vmcnt bookkeeping of
+  // the ring is unaffected, and their latency hides behind the first stages.
+  v16i acc[TC][TP];
+#pragma unroll
+  for (int i = 0; i < TC; ++i) {
+    int b[16];
+    load_bias16(p, ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
+#pragma unroll
+    for (int j = 0; j < TP; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = b[v];
+  }
+  const int nk = (p.red_len + BK - 1) / BK;
+  const int frag_row = lane & 31;
+  const int frag_half = lane >> 5;
+
+  // Residual codes (fused element-wise sum).  With a short reduction (every step fits in
+  // the prologue) they are requested first of all, so one memory latency covers bias,
+  // residual and operands; otherwise they are requested in the last step.
+  int res_w[TC][TP][4];
+  auto fetch_residual = [&]() {
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+        load_res16(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31),
+                   ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), res_w[i][j]);
+  };
+  const bool early_residual = nk <= STAGES - 1;
+  if (early_residual) fetch_residual();
+
+  // Operand fragments of the 32-byte sub-steps of a reduction step, double-buffered in
+  // registers.  The loop is software-pipelined inside one wavefront: the LDS reads of a
+  // sub-step are issued one phase before the MFMAs that consume them, and the MFMAs of the
+  // last sub-step of step kt-1 run after the barrier of step kt, so LDS latency, the
+  // barrier and the issue of the global loads all overlap matrix work.
+  v4i af[2][TC], bf[2][TP];
+  int a_foff[NH][TC], b_foff[NH][TP];        // LDS offsets inside a stage, per sub-step
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    const int chunk = 2 * h + frag_half;
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+      const int row = (wave_c * TC + i) * 32 + frag_row;
+      a_foff[h][i] = row * BK + swz<CHUNKS>(row, chunk) * 16;
+      asm volatile("" : "+v"(a_foff[h][i]));     // keep in a register, do not recompute
+    }
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+      const int row = (wave_p * TP + j) * 32 + frag_row;
+      b_foff[h][j] = A_BYTES + row * BK + swz<CHUNKS>(row, chunk) * 16;
+      asm volatile("" : "+v"(b_foff[h][j]));
+    }
+  }
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i) af[b][i] = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < TP; ++j) bf[b][j] = v4i{0, 0, 0, 0};
+  }
+  auto load_frags = [&](const int8_t* stage, int h) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+      af[h & 1][i] = *reinterpret_cast<const v4i*>(stage + a_foff[h][i]);
+#pragma unroll
+    for (int j = 0; j < TP; ++j)
+      bf[h & 1][j] = *reinterpret_cast<const v4i*>(stage + b_foff[h][j]);
+  };
+  auto mma = [&](int h) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
+                                                          0, 0, 0);
+  };
+
+  // One reduction step.  LATER = steps issued after step kt that may still be in flight
+  // when step kt must have landed; ISSUE = whether a further step is issued; LAST = whether
+  // the residual codes are fetched (no stage load follows, so vmcnt bookkeeping is over).
+  auto step = [&](int kt, auto later_c, auto issue_c, auto last_c) {
+    constexpr int LATER = decltype(later_c)::value;
+    wait_vmcnt<LATER * LOADS>();
+    // Bare barrier (no fence: a fence would drain the loads of the later steps too).
+    // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS
+    // (its last fragments are in registers already).
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const int8_t* stage = lds + (kt % STAGES) * STAGE_BYTES;
+    load_frags(stage, 0);
+    if constexpr (decltype(issue_c)::value) issue_stage((kt + STAGES - 1) % STAGES);
+    if constexpr (decltype(last_c)::value) {
+      if (!early_residual) fetch_residual();
+    }
+    mma(NH - 1);                        // last sub-step of step kt-1 (zeros on the first step)
+#pragma unroll
+    for (int h = 1; h < NH; ++h) {
+      load_frags(stage, h);
+      mma(h - 1);
+    }
+    // Instruction order inside the step (one scheduling region): the LDS reads of the
+    // first sub-step; then MFMAs with one global->LDS load after each (a wavefront issues
+    // in order: spreading the loads lets a load that waits for queue space hide behind a
+    // running MFMA); the LDS reads of sub-step h are spread between the MFMAs of h-1.
+    if constexpr (!decltype(last_c)::value) {
+      constexpr int kMma = TC * TP, kFrag = TC + TP;
+      constexpr int kVmem = decltype(issue_c)::value ? LOADS : 0;
+      __builtin_amdgcn_sched_group_barrier(0x100, kFrag, 0);              // DS reads, sub-step 0
+      int vmem_left = kVmem;
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+#pragma unroll
+        for (int g = 0; g < kMma; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
+          if (vmem_left > 0) {
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);            // one VMEM read
+            --vmem_left;
+          }
+          if (h + 1 < NH && g < kFrag)
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // one DS read
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using std::integral_constant;
+
+  // prologue: up to STAGES-1 reduction steps in flight
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nk) issue_stage(s);
+  // steady state: every step finds STAGES-2 later steps in flight and issues one more
+  int kt = 0;
+  for (; kt + STAGES - 1 < nk; ++kt)
+    step(kt, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
+         integral_constant<bool, false>{});
+  // drain: the last min(STAGES-1, nk) steps, with fewer and fewer loads behind them
+  if constexpr (STAGES >= 4) {
+    if (nk - kt == 3) {
+      step(kt, integral_constant<int, 2>{}, integral_constant<bool, false>{},
+           integral_constant<bool, false>{});
+      ++kt;
+    }
+  }
+  if constexpr (STAGES >= 3) {
+    if (nk - kt == 2) {
+      step(kt, integral_constant<int, 1>{}, integral_constant<bool, false>{},
+           integral_constant<bool, false>{});
+      ++kt;
+    }
+  }
+  step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
+       integral_constant<bool, true>{});
+  mma(NH - 1);
+
+  // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
+  const bool fast_tile = p.vec16 && !p.acc_dump && ch0 + BC <= p.K && pix0 + BP <= p.M;
+  auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
+    constexpr int MODE = decltype(mode_c)::value;     // 0 general, 1 fast, 2 fast + residual
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+      const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
+      if (MODE == 0 && pix >= p.M) continue;
+#pragma unroll
+      for (int i = 0; i < TC; ++i) {
+        const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+        if (MODE == 0 && ch >= p.K) continue;
+        int v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+        if constexpr (MODE == 0) finish16(p, pix, ch, v, res_w[i][j]);
+        else finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j]);
+      }
+    }
+  };
+  if (!fast_tile) finish_all(std::integral_constant<int, 0>{});
+  else if (p.res) finish_all(std::integral_constant<int, 2>{});
+  else finish_all(std::integral_constant<int, 1>{});
+#endif  // __HIP_DEVICE_COMPILE__
+}
+
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
+int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
+  constexpr int kLdsBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
+  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM>;
+  if constexpr (kLdsBytes > 65536) {
+    // more than 64 KB of LDS per workgroup has to be requested once per kernel
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr != hipSuccess) return Q8_EHIP;
+  }
+  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, stream, p);
+  return q8_launch_status();
+}
+
+template <int WP, int WC, int TP, int TC, int BK, int STAGES>
+int launch_ring(ConvParams& p, hipStream_t stream) {
+  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
+  p.n_ptiles = (p.M + BP - 1) / BP;
+  p.n_ctiles = (p.K + BC - 1) / BC;
+  long nblk = (long)p.n_ptiles * p.n_ctiles;
+  if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
+  if (p.C % BK == 0)
+    return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1>(p, dim3((unsigned)nblk), stream);
+  return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 0>(p, dim3((unsigned)nblk), stream);
+}
+
+struct RingVariant {
+  const char* name;
+  int (*launch)(ConvParams&, hipStream_t);
+};
+#define Q8_RING_VARIANT(WP, WC, TP, TC, BK, ST) \
+  { "conv_i8_ring_kernel<" #WP "," #WC "," #TP "," #TC "," #BK "," #ST ">", \
+    &launch_ring<WP, WC, TP, TC, BK, ST> }
+// pixels x channels per tile = (WP*TP*32) x (WC*TC*32); BK bytes per step; ring depth
+const RingVariant kRingVariants[] = {
+    Q8_RING_VARIANT(2, 2, 2, 2, 64, 2),    //  0: 128 x 128
+    Q8_RING_VARIANT(2, 2, 2, 2, 64, 3),    //  1
+    Q8_RING_VARIANT(2, 2, 2, 2, 64, 4),    //  2
+    Q8_RING_VARIANT(4, 1, 2, 2, 64, 3),    //  3: 256 x 64
+    Q8_RING_VARIANT(2, 2, 1, 2, 64, 2),    //  4:  64 x 128
+    Q8_RING_VARIANT(2, 2, 1, 2, 64, 4),    //  5
+    Q8_RING_VARIANT(2, 2, 1, 1, 64, 2),    //  6:  64 x 64
+    Q8_RING_VARIANT(2, 2, 1, 1, 64, 4),    //  7
+    Q8_RING_VARIANT(2, 2, 2, 1, 64, 2),    //  8: 128 x 64
+    Q8_RING_VARIANT(2, 2, 2, 1, 64, 4),    //  9
+};
+constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]);
+
+}  // namespace
+
+int num_stream_variants() { return kNumRingVariants; }
+int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
+  if (variant < 0 || variant >= kNumRingVariants) return Q8_EINVAL;
+  return kRingVariants[variant].launch(p, stream);
+}
+const char* stream_variant_name(int variant) {
+  return variant >= 0 && variant < kNumRingVariants ? kRingVariants[variant].name : "unsupported";
+}
+
+}  // namespace q8
