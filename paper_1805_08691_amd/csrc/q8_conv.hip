@@ -88,14 +88,17 @@ int pick_variant(const q8_conv_desc* d) {
   const long M = (long)d->N * out_extent(d->H, d->pad_h, d->dil_h, d->R, d->stride_h) *
                  out_extent(d->W, d->pad_w, d->dil_w, d->S, d->stride_w);
   const long tiles128 = ((M + 127) / 128) * ((d->K + 127) / 128);
-  // Variant numbers: see kRingVariants.  Measured on ResNet-50 shapes at batch 64: the
-  // short-reduction, large-M layers are bound by memory latency and epilogue work per
-  // workgroup, and smaller tiles with more workgroups per CU win; layers with few
-  // 128x128 tiles also take 64x64 tiles to fill the chip.
-  if (d->K <= 64) return nk <= 2 ? 6 : 7;                 // 64 x 64
-  if (nk <= 2) return 4;                                  // 64 pixels x 128 channels
-  if (tiles128 < 2 * 256) return 7;                       // 64 x 64, ring of 4
-  return nk <= 4 ? 1 : 2;                                 // 128 x 128, ring of 3 or 4
+  // Variant numbers: see kRingVariants.  Rules fitted to a sweep of every variant over the
+  // ResNet-50 shapes at batch 64 (56x56 ... 7x7 maps, 64 ... 2048 channels):
+  //  - few output channels: 128 pixels x 64 channels, more workgroups per CU;
+  //  - very few tiles: 128 x 64 tiles with a deep ring (the chip is not filled anyway);
+  //  - short reductions (bound by memory latency and epilogue work per workgroup):
+  //    64 pixels x 128 channels, ring of 2, three or more workgroups per CU;
+  //  - otherwise 128 x 128, ring of 3, or 4 when at most one workgroup per CU exists.
+  if (d->K <= 64) return 8;
+  if (tiles128 <= 128) return 9;
+  if (nk <= 4) return 4;
+  return tiles128 <= 256 ? 2 : 1;
 }
 
 }  // namespace
