@@ -94,11 +94,12 @@ int pick_variant(const q8_conv_desc* d) {
   //  - very few tiles: 128 x 64 tiles with a deep ring (the chip is not filled anyway);
   //  - short reductions (bound by memory latency and epilogue work per workgroup):
   //    64 pixels x 128 channels, ring of 2, three or more workgroups per CU;
-  //  - otherwise 128 x 128, ring of 3, or 4 when at most one workgroup per CU exists.
+  //  - otherwise 128 x 128 with a ring of 3; when at most one workgroup per CU exists,
+  //    eight wavefronts share the tile (more waves to hide LDS latency) with a ring of 4.
   if (d->K <= 64) return 8;
   if (tiles128 <= 128) return 9;
   if (nk <= 4) return 4;
-  return tiles128 <= 256 ? 2 : 1;
+  return tiles128 <= 256 ? 11 : 1;    // 11: eight wavefronts on a 128 x 128 tile, ring of 4
 }
 
 }  // namespace

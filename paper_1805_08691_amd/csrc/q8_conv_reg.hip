@@ -200,7 +200,9 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
     __syncthreads();
   }
 
-  // ---- epilogue: a lane holds 16 consecutive channels of pixel column (lane & 31)
+  // ---- epilogue: a lane holds 16 consecutive channels of pixel column (lane & 31).
+  // A complete tile with aligned rows takes the branch-free path.
+  const bool fast_tile = p.vec16 && !p.acc_dump && ch0 + BC <= p.K && pix0 + BP <= p.M;
 #pragma unroll
   for (int j = 0; j < TP; ++j) {
     const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
@@ -212,11 +214,20 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
       int v[16];
 #pragma unroll
       for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
-      epilogue16(p, pix, ch, v);
+      if (fast_tile) {
+        int b[16], rw[4];
+        load_bias16(p, ch, b);
+        load_res16(p, pix, ch, rw);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] += b[e];
+        if (p.res) finish16_fast<true>(p, pix, ch, v, rw);
+        else finish16_fast<false>(p, pix, ch, v, rw);
+      } else {
+        epilogue16(p, pix, ch, v);
+      }
     }
   }
 }
-
 
 template <int WP, int WC, int TP, int TC, int MODE>
 int launch_reg(ConvParams& p, hipStream_t stream) {

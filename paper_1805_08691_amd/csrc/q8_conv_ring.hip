@@ -29,7 +29,7 @@ namespace {
 constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
 
 template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
-__global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams p) {
+__global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
                                       // descriptor types exist for the device target alone
   constexpr int CHUNKS = BK / 16;          // 16-byte chunks per LDS row
@@ -38,13 +38,14 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
   constexpr int BP = WP * TP * 32;
   constexpr int BC = WC * TC * 32;
   constexpr int A_GROUPS = BC / RPW, B_GROUPS = BP / RPW;
-  constexpr int A_LOADS = A_GROUPS / 4, B_LOADS = B_GROUPS / 4;
+  constexpr int NW = WP * WC;              // wavefronts per workgroup (4 or 8)
+  constexpr int A_LOADS = A_GROUPS / NW, B_LOADS = B_GROUPS / NW;
   constexpr int LOADS = A_LOADS + B_LOADS;                   // per lane per stage
   constexpr int A_BYTES = BC * BK, STAGE_BYTES = (BC + BP) * BK;
   static_assert(BK == 64 || BK == 128, "reduction bytes per step");
-  static_assert(WP * WC == 4, "four wavefronts per block");
-  static_assert(A_GROUPS % 4 == 0 && B_GROUPS % 4 == 0, "every wave issues the same loads");
-  static_assert(STAGES >= 2 && STAGES <= 4, "ring depth");
+  static_assert(NW == 4 || NW == 8, "four or eight wavefronts per block");
+  static_assert(A_GROUPS % NW == 0 && B_GROUPS % NW == 0, "every wave issues the same loads");
+  static_assert(STAGES >= 2 && STAGES <= 8, "ring depth");
   static_assert((STAGES - 2) * LOADS < 64, "vmcnt is 6 bits");
 
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // STAGES * STAGE_BYTES
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
   int a_off[A_LOADS];                  // filter row offset + chunk, or out of range
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
-    const int row = (wave + 4 * j) * RPW + lrow;
+    const int row = (wave + NW * j) * RPW + lrow;
     const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
     a_off[j] = ch < p.K ? ch * p.red_len + lchunk * 16 : kOobOffset;
   }
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
   unsigned b_mask[B_LOADS];            // bit t: tap t of this pixel lies inside the image
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) {
-    const int pix = pix0 + (wave + 4 * j) * RPW + lrow;
+    const int pix = pix0 + (wave + NW * j) * RPW + lrow;
     unsigned mask = 0;
     int off = 0;
     if (pix < p.M) {
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
 #pragma unroll
       for (int j = 0; j < A_LOADS; ++j)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16,
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
             a_off[j], step_base, 0, 0);
       const int delta = tap_delta + tap_c;
 #pragma unroll
@@ -140,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
         const int voff = ((b_mask[j] >> tap) & 1u) ? b_off[j] + delta : kOobOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rsrc_x,
-            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
             voff, 0, 0, 0);
       }
       step_base += BK;
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
       for (int j = 0; j < A_LOADS; ++j) {
         const int voff = red_ok ? a_off[j] : kOobOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + 4 * j) * 1024), 16,
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
             voff, step_base, 0, 0);
       }
       const int delta = tap_delta + tap_c;
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
         const int voff = ok ? b_off[j] + delta : kOobOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rsrc_x,
-            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + 4 * j) * 1024), 16,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
             voff, 0, 0, 0);
       }
       step_base += BK;
@@ -324,20 +325,21 @@ __global__ __launch_bounds__(kThreads) void conv_i8_ring_kernel(const ConvParams
     step(kt, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
          integral_constant<bool, false>{});
   // drain: the last min(STAGES-1, nk) steps, with fewer and fewer loads behind them
-  if constexpr (STAGES >= 4) {
-    if (nk - kt == 3) {
-      step(kt, integral_constant<int, 2>{}, integral_constant<bool, false>{},
-           integral_constant<bool, false>{});
-      ++kt;
-    }
+#define Q8_DRAIN_STEP(L)                                                              \
+  if constexpr (STAGES >= (L) + 2) {                                                  \
+    if (nk - kt == (L) + 1) {                                                         \
+      step(kt, integral_constant<int, (L)>{}, integral_constant<bool, false>{},       \
+           integral_constant<bool, false>{});                                         \
+      ++kt;                                                                           \
+    }                                                                                 \
   }
-  if constexpr (STAGES >= 3) {
-    if (nk - kt == 2) {
-      step(kt, integral_constant<int, 1>{}, integral_constant<bool, false>{},
-           integral_constant<bool, false>{});
-      ++kt;
-    }
-  }
+  Q8_DRAIN_STEP(6)
+  Q8_DRAIN_STEP(5)
+  Q8_DRAIN_STEP(4)
+  Q8_DRAIN_STEP(3)
+  Q8_DRAIN_STEP(2)
+  Q8_DRAIN_STEP(1)
+#undef Q8_DRAIN_STEP
   step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
        integral_constant<bool, true>{});
   mma(NH - 1);
@@ -378,7 +380,7 @@ int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
         reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return Q8_EHIP;
   }
-  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, stream, p);
+  hipLaunchKernelGGL(kernel, grid, dim3(WP * WC * 64), kLdsBytes, stream, p);
   return q8_launch_status();
 }
 
@@ -413,6 +415,15 @@ const RingVariant kRingVariants[] = {
     Q8_RING_VARIANT(2, 2, 1, 1, 64, 4),    //  7
     Q8_RING_VARIANT(2, 2, 2, 1, 64, 2),    //  8: 128 x 64
     Q8_RING_VARIANT(2, 2, 2, 1, 64, 4),    //  9
+    Q8_RING_VARIANT(2, 4, 2, 1, 64, 3),    // 10: 128 x 128, eight wavefronts of 64 x 32
+    Q8_RING_VARIANT(2, 4, 2, 1, 64, 4),    // 11
+    Q8_RING_VARIANT(4, 2, 1, 2, 64, 3),    // 12: 128 x 128, eight wavefronts of 32 x 64
+    Q8_RING_VARIANT(4, 2, 2, 2, 64, 3),    // 13: 256 x 128, eight wavefronts of 64 x 64
+    Q8_RING_VARIANT(2, 4, 2, 2, 64, 3),    // 14: 128 x 256, eight wavefronts of 64 x 64
+    Q8_RING_VARIANT(2, 2, 2, 2, 64, 6),    // 15: 128 x 128, deep rings for one workgroup per CU
+    Q8_RING_VARIANT(2, 2, 2, 2, 64, 8),    // 16
+    Q8_RING_VARIANT(2, 4, 2, 1, 64, 8),    // 17: the same with eight wavefronts
+    Q8_RING_VARIANT(2, 2, 2, 1, 64, 8),    // 18: 128 x 64, deep ring
 };
 constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]);
 

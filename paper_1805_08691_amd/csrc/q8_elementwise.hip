@@ -116,6 +116,23 @@ __global__ __launch_bounds__(kThreads) void quantize_pad4_kernel(const float* __
   }
 }
 
+// The 3-channel image case: four pixels per thread = three aligned 16-byte loads (12
+// floats) and one 16-byte store.  r 16-byte aligned, z 16-byte aligned, npix4 = npix / 4.
+__global__ __launch_bounds__(kThreads) void quantize_rgb_pad4_kernel(const float4* __restrict__ r,
+                                                                     size_t npix4, float q, float lo,
+                                                                     float hi, uint4* __restrict__ z) {
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < npix4; g += nthreads) {
+    const float4 a = r[3 * g], b = r[3 * g + 1], c = r[3 * g + 2];
+    uint4 o;
+    o.x = pack4(quant1(a.x, q, lo, hi), quant1(a.y, q, lo, hi), quant1(a.z, q, lo, hi), 0);
+    o.y = pack4(quant1(a.w, q, lo, hi), quant1(b.x, q, lo, hi), quant1(b.y, q, lo, hi), 0);
+    o.z = pack4(quant1(b.z, q, lo, hi), quant1(b.w, q, lo, hi), quant1(c.x, q, lo, hi), 0);
+    o.w = pack4(quant1(c.y, q, lo, hi), quant1(c.z, q, lo, hi), quant1(c.w, q, lo, hi), 0);
+    z[g] = o;
+  }
+}
+
 // General channel padding (any C <= Cp): one thread per output element.
 __global__ __launch_bounds__(kThreads) void quantize_padc_kernel(const float* __restrict__ r,
                                                                  size_t npix, int C, int Cp,
@@ -266,7 +283,17 @@ int q8_quantize_pad_channels(const float* r_dev, size_t npix, int C, int C_pad, 
   Q8_REQUIRE(r_dev != nullptr && z_dev != nullptr, Q8_EINVAL);
   Q8_REQUIRE(q8_aligned(r_dev, 4), Q8_EALIGN);
   const float hi = (float)((1 << p) - 1), lo = -(float)(1 << p);
-  if (C_pad == 4 && q8_aligned(z_dev, 4)) {
+  if (C_pad == 4 && C == 3 && q8_aligned(z_dev, 16) && q8_aligned(r_dev, 16)) {
+    const size_t npix4 = npix / 4, tail = npix - 4 * npix4;
+    if (npix4)
+      hipLaunchKernelGGL(quantize_rgb_pad4_kernel, dim3(blocks_for(npix4)), dim3(kThreads), 0,
+                         (hipStream_t)stream, reinterpret_cast<const float4*>(r_dev), npix4, q, lo,
+                         hi, reinterpret_cast<uint4*>(z_dev));
+    if (tail)
+      hipLaunchKernelGGL(quantize_pad4_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream,
+                         r_dev + 12 * npix4, tail, C, q, lo, hi,
+                         reinterpret_cast<unsigned*>(z_dev) + 4 * npix4);
+  } else if (C_pad == 4 && q8_aligned(z_dev, 4)) {
     hipLaunchKernelGGL(quantize_pad4_kernel, dim3(blocks_for(npix)), dim3(kThreads), 0,
                        (hipStream_t)stream, r_dev, npix, C, q, lo, hi,
                        reinterpret_cast<unsigned*>(z_dev));

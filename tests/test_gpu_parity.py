@@ -185,6 +185,31 @@ def test_conv_shapes(B, idx):
                    seed=1000 + idx)
 
 
+VARIANT_CASES = [
+    dict(N=2, H=14, W=14, C=64, K=160, R=3, S=3, pad_h=1, pad_w=1),      # uniform taps, tails
+    dict(N=1, H=17, W=17, C=48, K=272, R=1, S=7, pad_w=3),               # per-lane taps, tails
+    dict(N=3, H=28, W=28, C=128, K=64, R=1, S=1, stride_h=2, stride_w=2),
+    dict(N=1, H=33, W=31, C=256, K=384, R=1, S=1),                       # complete + ragged tiles
+]
+
+
+def test_conv_every_kernel_variant(B):
+    """Every tile / ring variant of the main kernel gives the same bits (integer sums are
+    order-independent; the epilogue is one fixed fp32 sequence)."""
+    n = 0
+    while B.lib.q8_conv_force_variant(n) == 0:
+        n += 1
+    assert n >= 10
+    try:
+        for v in range(n):
+            B.conv_force_variant(v)
+            for k, geom in enumerate(VARIANT_CASES):
+                _run_conv_case(B, geom, relu=bool(k % 2), with_res=bool((k + v) % 2),
+                               with_bias=True, seed=100 * v + k)
+    finally:
+        B.conv_force_variant(-1)
+
+
 @pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
 def test_conv_channel_slice_of_concat(B, out_pad, out_off):
     geom = dict(N=2, H=9, W=9, C=32, K=40, R=3, S=3, pad_h=1, pad_w=1)
