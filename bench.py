@@ -145,11 +145,8 @@ def main():
         eng.quantize_input(x)
         ev[1].record()
         for i, op in enumerate(ops_list):
-            if op.kind == "maxpool":
-                s, d = net.tensors[op.src], net.tensors[op.dst]
-                B._check(B.lib.q8_maxpool_i8(eng.act[op.src].data_ptr(), N, s.H, s.W,
-                                             max(s.C, 4), op.R, op.S, op.stride, op.pad, d.H, d.W,
-                                             eng.act[op.dst].data_ptr(), B._stream()))
+            if op.kind == "pool":
+                eng.run_pool(op)
             else:
                 packed, bias = eng.wq[op.name]
                 res = eng.act[op.res] if op.res else None

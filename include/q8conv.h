@@ -152,6 +152,20 @@ int q8_maxpool_i8(const int8_t *x_dev, int N, int H, int W, int C, int R, int S,
 int q8_maxpool_f32(const float *x_dev, int N, int H, int W, int C, int R, int S,
                    int stride, int pad, int Ho, int Wo, float *y_dev, void *stream);
 
+/* General int8 pooling into channels [out_c_off, out_c_off + C) of a tensor with pixel
+ * stride out_c_stride, with a change of quantisation factor.  mode 0: v = max over the taps
+ * inside the image, t = fp32(v).  mode 1: v = sum over the taps inside the image,
+ * t = fp32(v) * (1 / fp32(R*S)) (padding counts as zeros).  Then t = t * m with
+ * m = q_in / q_out (formed by the caller in fp32), z = int8(Round(clamp(t, -128, 127))).
+ * With m = 1 max-pooling is exact.  x is dense [N][H][W][C].                           */
+int q8_pool_i8(const int8_t *x_dev, int N, int H, int W, int C, int mode, int R, int S,
+               int stride, int pad, int Ho, int Wo, float m, int8_t *y_dev,
+               int out_c_stride, int out_c_off, void *stream);
+/* fp32 twin for the calibration forward: max, or mean with padding counted as zeros.   */
+int q8_pool_f32(const float *x_dev, int N, int H, int W, int C, int mode, int R, int S,
+                int stride, int pad, int Ho, int Wo, float *y_dev, int out_c_stride,
+                int out_c_off, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -94,6 +94,8 @@ _lib.orc_conv_f32.argtypes = [C.POINTER(_Geom), _f32p, _f32p, C.c_void_p, C.c_vo
                               C.c_int, _f32p]
 _lib.orc_maxpool_i8.restype = None
 _lib.orc_maxpool_i8.argtypes = [_i8p] + [C.c_int] * 10 + [_i8p]
+_lib.orc_pool_i8.restype = None
+_lib.orc_pool_i8.argtypes = [_i8p] + [C.c_int] * 11 + [C.c_float, _i8p, C.c_int, C.c_int]
 _lib.orc_num_threads.restype = C.c_int
 
 
@@ -229,6 +231,19 @@ def maxpool_i8(x, R, S, stride, pad, Ho, Wo):
     y = np.empty((N, Ho, Wo, Cc), np.int8)
     _lib.orc_maxpool_i8(x.ravel(), N, H, W, Cc, R, S, stride, pad, Ho, Wo, y.reshape(-1))
     return y
+
+
+def pool_i8(x, mode, R, S, stride, pad, Ho, Wo, m=1.0, out=None, out_c_off=0):
+    """mode 'max' or 'avg'; writes channels [out_c_off, out_c_off + C) of ``out``."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    N, H, W, Cc = x.shape
+    if out is None:
+        out = np.zeros((N, Ho, Wo, Cc), np.int8)
+    assert out.dtype == np.int8 and out.flags.c_contiguous and out.shape[:3] == (N, Ho, Wo)
+    assert out_c_off + Cc <= out.shape[3]
+    _lib.orc_pool_i8(x.ravel(), N, H, W, Cc, 0 if mode == "max" else 1, R, S, stride, pad, Ho, Wo,
+                     np.float32(m), out.reshape(-1), out.shape[3], out_c_off)
+    return out
 
 
 def conv_layer_i8(g, z_x, q_x, z_w, q_w, z_b, q_out, relu, z_res=None, q_res=None):

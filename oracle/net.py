@@ -11,7 +11,7 @@ the factor of the branch's own pre-sum output.
 import numpy as np
 import torch
 
-from . import (ConvGeom, Q, Q31_bias, conv_f32, conv_i8, fold_bn, maxabs, maxpool_i8, qfactor,
+from . import (ConvGeom, Q, Q31_bias, conv_f32, conv_i8, fold_bn, maxabs, pool_i8, qfactor,
                requant, requant_scale, residual_scale)
 
 P_ACT = 7
@@ -51,10 +51,24 @@ def forward_f32(net, folded, x, use_library=True):
     t = {net.input: x}
     pre = {}
     for op in net.ops:
-        if op.kind == "maxpool":
+        if op.kind == "pool":
+            d = net.tensors[op.dst]
             xt = torch.from_numpy(t[op.src]).permute(0, 3, 1, 2)
-            y = torch.nn.functional.max_pool2d(xt, (op.R, op.S), op.stride, op.pad)
-            t[op.dst] = np.ascontiguousarray(y.permute(0, 2, 3, 1).numpy())
+            ceil = d.H != (xt.shape[2] + 2 * op.pad - op.R) // op.stride + 1
+            if op.mode == "max":
+                y = torch.nn.functional.max_pool2d(xt, (op.R, op.S), op.stride, op.pad,
+                                                   ceil_mode=ceil)
+            else:
+                y = torch.nn.functional.avg_pool2d(xt, (op.R, op.S), op.stride, op.pad,
+                                                   count_include_pad=True)
+            y = np.ascontiguousarray(y.permute(0, 2, 3, 1).numpy())
+            assert y.shape[1:3] == (d.H, d.W), (op.name, y.shape, d)
+            if d.C == y.shape[3]:
+                t[op.dst] = y
+            else:
+                if op.dst not in t:
+                    t[op.dst] = np.zeros(y.shape[:3] + (d.C,), np.float32)
+                t[op.dst][..., op.dst_c_off:op.dst_c_off + y.shape[3]] = y
             continue
         Wf, bf = folded[op.name]
         xin = t[op.src]
@@ -99,8 +113,8 @@ def calibrate(net, folded, batches, use_library=True):
     for op in net.ops:
         if op.kind == "conv" and op.res is not None:
             q[op.dst] = max(q[op.name + ":branch"], q[op.res])
-        if op.kind == "maxpool":
-            q[op.dst] = q[op.src]
+        if op.kind == "pool" and net.tensors[op.dst].C == net.tensors[op.src].C:
+            q[op.dst] = q[op.src]          # a stand-alone pool keeps its input's factor
     return q
 
 
@@ -122,9 +136,13 @@ def forward_i8(net, qparams, q, z_in, keep_acc=False):
     accs = {}
     N = z_in.shape[0]
     for op in net.ops:
-        if op.kind == "maxpool":
+        if op.kind == "pool":
             d = net.tensors[op.dst]
-            t[op.dst] = maxpool_i8(t[op.src], op.R, op.S, op.stride, op.pad, d.H, d.W)
+            if op.dst not in t:
+                t[op.dst] = np.zeros((N, d.H, d.W, d.C), np.int8)
+            m = residual_scale(q[op.src], q[op.dst])        # q_in / q_out in fp32 (1 if equal)
+            pool_i8(t[op.src], op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W, m,
+                    out=t[op.dst], out_c_off=op.dst_c_off)
             continue
         qp = qparams[op.name]
         g = geom(op, net.tensors, N)

@@ -271,6 +271,49 @@ void orc_maxpool_i8(const int8_t *x, int N, int H, int W, int C, int R, int S,
         }
 }
 
+/* Helper (shape chaining, not the paper's method): int8 pooling into a channel slice
+ * of a possibly wider tensor, with a change of factor.
+ *   mode 0 (max): v = max over the taps inside the image (as an integer)
+ *   mode 1 (avg): v = sum over the taps inside the image; t = fp32(v) * inv_count, where
+ *                 inv_count = fp32(1) / fp32(R*S) (padding counts as zeros)
+ *   t = fp32(v) for max; then t = t * m (m = q_in / q_out, formed by the caller in fp32);
+ *   z = int8(Round(clamp(t, -128, 127))).  With m = 1 max-pooling is exact.            */
+void orc_pool_i8(const int8_t *x, int N, int H, int W, int C, int mode, int R, int S,
+                 int stride, int pad, int Ho, int Wo, float m, int8_t *y,
+                 int out_c_stride, int out_c_off) {
+  const float inv_count = 1.0f / (float)(R * S);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int ho = 0; ho < Ho; ++ho)
+      for (int wo = 0; wo < Wo; ++wo)
+        for (int c = 0; c < C; ++c) {
+          int best = -128, sum = 0;
+          for (int r = 0; r < R; ++r) {
+            int hi = ho * stride - pad + r;
+            if (hi < 0 || hi >= H) continue;
+            for (int s = 0; s < S; ++s) {
+              int wi = wo * stride - pad + s;
+              if (wi < 0 || wi >= W) continue;
+              int v = x[(((size_t)n * H + hi) * W + wi) * C + c];
+              if (v > best) best = v;
+              sum += v;
+            }
+          }
+          float t;
+          if (mode == 0) {
+            t = (float)best;
+          } else {
+            t = (float)sum;
+            t = t * inv_count;
+          }
+          t = t * m;
+          if (t > 127.0f) t = 127.0f;
+          if (t < -128.0f) t = -128.0f;
+          t = rintf(t);
+          y[(((size_t)n * Ho + ho) * Wo + wo) * out_c_stride + out_c_off + c] = (int8_t)t;
+        }
+}
+
 /* Number of OpenMP threads the loops above will use. */
 int orc_num_threads(void) {
 #ifdef _OPENMP

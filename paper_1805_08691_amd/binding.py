@@ -25,7 +25,7 @@ EXPORTS = [
     "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_bias", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_variant", "q8_conv_force_variant",
-    "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32",
+    "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
 
 
@@ -82,6 +82,10 @@ lib.q8_conv_force_variant.argtypes = [_i]
 lib.q8_conv_f32_ref.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.q8_maxpool_i8.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
 lib.q8_maxpool_f32.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
+
+
+lib.q8_pool_i8.argtypes = [_vp] + [_i] * 11 + [_f, _vp, _i, _i, _vp]
+lib.q8_pool_f32.argtypes = [_vp] + [_i] * 11 + [_vp, _i, _i, _vp]
 
 
 def _check(code):
@@ -212,3 +216,24 @@ def maxpool_i8(x, R, S, stride, pad, Ho, Wo):
 
 def maxpool_f32(x, R, S, stride, pad, Ho, Wo):
     return _pool(lib.q8_maxpool_f32, torch.float32, x, R, S, stride, pad, Ho, Wo)
+
+
+def pool_i8(x, mode, R, S, stride, pad, Ho, Wo, m=1.0, out=None, out_c_off=0):
+    """mode 'max' or 'avg'; writes channels [out_c_off, out_c_off + C) of ``out``."""
+    N, H, W, Cc = x.shape
+    if out is None:
+        out = torch.zeros((N, Ho, Wo, Cc), dtype=torch.int8, device=x.device)
+    _check(lib.q8_pool_i8(_ptr(x, torch.int8), N, H, W, Cc, 0 if mode == "max" else 1, R, S, stride,
+                          pad, Ho, Wo, m, _ptr(out, torch.int8), out.shape[3], out_c_off,
+                          _stream()))
+    return out
+
+
+def pool_f32(x, mode, R, S, stride, pad, Ho, Wo, out=None, out_c_off=0):
+    N, H, W, Cc = x.shape
+    if out is None:
+        out = torch.zeros((N, Ho, Wo, Cc), dtype=torch.float32, device=x.device)
+    _check(lib.q8_pool_f32(_ptr(x, torch.float32), N, H, W, Cc, 0 if mode == "max" else 1, R, S,
+                           stride, pad, Ho, Wo, _ptr(out, torch.float32), out.shape[3], out_c_off,
+                           _stream()))
+    return out

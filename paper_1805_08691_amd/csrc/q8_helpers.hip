@@ -163,6 +163,72 @@ __global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* 
   }
 }
 
+// General int8 pooling into a channel slice with a change of factor (see q8_pool_i8).
+#pragma clang fp contract(off)
+__global__ __launch_bounds__(kThreads) void pool_i8_kernel(const int8_t* __restrict__ x, int N, int H,
+                                                           int W, int C, int mode, int R, int S,
+                                                           int stride, int pad, int Ho, int Wo,
+                                                           float m, float inv_count,
+                                                           int8_t* __restrict__ y, int out_cs,
+                                                           int out_off) {
+  const size_t total = (size_t)N * Ho * Wo * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * kThreads) {
+    int c = (int)(i % C);
+    size_t t = i / C;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    int best = -128, sum = 0;
+    for (int r = 0; r < R; ++r) {
+      int hi = ho * stride - pad + r;
+      if ((unsigned)hi >= (unsigned)H) continue;
+      for (int s2 = 0; s2 < S; ++s2) {
+        int wi = wo * stride - pad + s2;
+        if ((unsigned)wi >= (unsigned)W) continue;
+        int v = x[(((size_t)n * H + hi) * W + wi) * C + c];
+        best = v > best ? v : best;
+        sum += v;
+      }
+    }
+    float f = mode == 0 ? (float)best : (float)sum * inv_count;
+    f = f * m;
+    f = fminf(fmaxf(f, -128.0f), 127.0f);
+    y[(((size_t)n * Ho + ho) * Wo + wo) * out_cs + out_off + c] = (int8_t)(int)rintf(f);
+  }
+}
+
+// fp32 twin for the calibration forward (max, or mean with padding counted as zeros).
+__global__ __launch_bounds__(kThreads) void pool_f32_kernel(const float* __restrict__ x, int N, int H,
+                                                            int W, int C, int mode, int R, int S,
+                                                            int stride, int pad, int Ho, int Wo,
+                                                            float* __restrict__ y, int out_cs,
+                                                            int out_off) {
+  const size_t total = (size_t)N * Ho * Wo * C;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * kThreads) {
+    int c = (int)(i % C);
+    size_t t = i / C;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    float best = -3.402823466e38f, sum = 0.f;
+    for (int r = 0; r < R; ++r) {
+      int hi = ho * stride - pad + r;
+      if ((unsigned)hi >= (unsigned)H) continue;
+      for (int s2 = 0; s2 < S; ++s2) {
+        int wi = wo * stride - pad + s2;
+        if ((unsigned)wi >= (unsigned)W) continue;
+        float v = x[(((size_t)n * H + hi) * W + wi) * C + c];
+        best = fmaxf(best, v);
+        sum += v;
+      }
+    }
+    y[(((size_t)n * Ho + ho) * Wo + wo) * out_cs + out_off + c] =
+        mode == 0 ? best : sum / (float)(R * S);
+  }
+}
+
 template <typename T>
 int maxpool_launch(const T* x, int N, int H, int W, int C, int R, int S, int stride, int pad,
                    int Ho, int Wo, T* y, void* stream) {
@@ -220,6 +286,46 @@ int q8_maxpool_i8(const int8_t* x_dev, int N, int H, int W, int C, int R, int S,
                   int Ho, int Wo, int8_t* y_dev, void* stream) {
   return maxpool_launch<int8_t>(x_dev, N, H, W, C, R, S, stride, pad, Ho, Wo, y_dev, stream);
 }
+int q8_pool_i8(const int8_t* x_dev, int N, int H, int W, int C, int mode, int R, int S, int stride,
+               int pad, int Ho, int Wo, float m, int8_t* y_dev, int out_c_stride, int out_c_off,
+               void* stream) {
+  Q8_REQUIRE(N >= 0 && H >= 1 && W >= 1 && C >= 1 && R >= 1 && S >= 1 && stride >= 1 && pad >= 0 &&
+                 Ho >= 0 && Wo >= 0 && (mode == 0 || mode == 1), Q8_EINVAL);
+  Q8_REQUIRE(pad < R && pad < S && q8_finite_pos(m), Q8_EINVAL);
+  Q8_REQUIRE(Ho == 0 || (long)(Ho - 1) * stride - pad < H, Q8_EINVAL);
+  Q8_REQUIRE(Wo == 0 || (long)(Wo - 1) * stride - pad < W, Q8_EINVAL);
+  Q8_REQUIRE(out_c_off >= 0 && out_c_stride >= out_c_off + C, Q8_EINVAL);
+  size_t total = (size_t)N * Ho * Wo * C;
+  if (total == 0) return Q8_OK;
+  Q8_REQUIRE(x_dev && y_dev, Q8_EINVAL);
+  size_t blocks = (total + kThreads - 1) / kThreads;
+  if (blocks > 65536) blocks = 65536;
+  const float inv_count = 1.0f / (float)(R * S);
+  hipLaunchKernelGGL(pool_i8_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                     x_dev, N, H, W, C, mode, R, S, stride, pad, Ho, Wo, m, inv_count, y_dev,
+                     out_c_stride, out_c_off);
+  return q8_launch_status();
+}
+
+int q8_pool_f32(const float* x_dev, int N, int H, int W, int C, int mode, int R, int S, int stride,
+                int pad, int Ho, int Wo, float* y_dev, int out_c_stride, int out_c_off, void* stream) {
+  Q8_REQUIRE(N >= 0 && H >= 1 && W >= 1 && C >= 1 && R >= 1 && S >= 1 && stride >= 1 && pad >= 0 &&
+                 Ho >= 0 && Wo >= 0 && (mode == 0 || mode == 1), Q8_EINVAL);
+  Q8_REQUIRE(pad < R && pad < S, Q8_EINVAL);
+  Q8_REQUIRE(Ho == 0 || (long)(Ho - 1) * stride - pad < H, Q8_EINVAL);
+  Q8_REQUIRE(Wo == 0 || (long)(Wo - 1) * stride - pad < W, Q8_EINVAL);
+  Q8_REQUIRE(out_c_off >= 0 && out_c_stride >= out_c_off + C, Q8_EINVAL);
+  size_t total = (size_t)N * Ho * Wo * C;
+  if (total == 0) return Q8_OK;
+  Q8_REQUIRE(x_dev && y_dev, Q8_EINVAL);
+  size_t blocks = (total + kThreads - 1) / kThreads;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(pool_f32_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                     x_dev, N, H, W, C, mode, R, S, stride, pad, Ho, Wo, y_dev, out_c_stride,
+                     out_c_off);
+  return q8_launch_status();
+}
+
 int q8_maxpool_f32(const float* x_dev, int N, int H, int W, int C, int R, int S, int stride, int pad,
                    int Ho, int Wo, float* y_dev, void* stream) {
   return maxpool_launch<float>(x_dev, N, H, W, C, R, S, stride, pad, Ho, Wo, y_dev, stream);

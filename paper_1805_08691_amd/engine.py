@@ -66,8 +66,16 @@ class Engine:
         N = x.shape[0]
         for op in self.net.ops:
             d = self.net.tensors[op.dst]
-            if op.kind == "maxpool":
-                t[op.dst] = B.maxpool_f32(t[op.src], op.R, op.S, op.stride, op.pad, d.H, d.W)
+            if op.kind == "pool":
+                if d.C == self.net.tensors[op.src].C:
+                    t[op.dst] = B.pool_f32(t[op.src], op.mode, op.R, op.S, op.stride, op.pad, d.H,
+                                           d.W)
+                else:
+                    if op.dst not in t:
+                        t[op.dst] = torch.zeros((N, d.H, d.W, d.C), dtype=torch.float32,
+                                                device=self.dev)
+                    B.pool_f32(t[op.src], op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W,
+                               out=t[op.dst], out_c_off=op.dst_c_off)
             else:
                 Wf, bf = self.folded[op.name]
                 desc = self._desc(op, N)
@@ -84,12 +92,16 @@ class Engine:
                         t[op.dst] = torch.zeros((N, d.H, d.W, d.C), dtype=torch.float32,
                                                 device=self.dev)
                     t[op.dst][..., op.dst_c_off:op.dst_c_off + op.K] = y
-            if observe and op.dst in t and (op.kind != "conv" or d.C == op.K):
+            width = op.K if op.kind == "conv" else self.net.tensors[op.src].C
+            if observe and d.C == width:
                 observe(op.dst, t[op.dst])
         if observe:
-            for op in self.net.convs():         # concat targets: observe once complete
+            seen = set()
+            for op in self.net.ops:             # concat targets: observe once complete
                 d = self.net.tensors[op.dst]
-                if d.C != op.K:
+                width = op.K if op.kind == "conv" else self.net.tensors[op.src].C
+                if d.C != width and op.dst not in seen:
+                    seen.add(op.dst)
                     observe(op.dst, t[op.dst])
         return t
 
@@ -111,8 +123,8 @@ class Engine:
         for op in self.net.ops:
             if op.kind == "conv" and op.res is not None:
                 q[op.dst] = max(q[op.name + ":branch"], q[op.res])   # the + rule
-            if op.kind == "maxpool":
-                q[op.dst] = q[op.src]
+            if op.kind == "pool" and self.net.tensors[op.dst].C == self.net.tensors[op.src].C:
+                q[op.dst] = q[op.src]       # a stand-alone pool keeps its input's factor
         self.q = q
         return q
 
@@ -152,14 +164,28 @@ class Engine:
         else:
             B.quantize(x, self.q[self.net.input], P_ACT, out=self.act[self.net.input])
 
+    def run_pool(self, op):
+        s, d = self.net.tensors[op.src], self.net.tensors[op.dst]
+        q_in, q_out = self.q[op.src], self.q[op.dst]
+        if op.mode == "max" and q_in == q_out and _pad_c(d.C) == _pad_c(s.C):
+            # exact copy of the maximum: the vectorised kernel
+            B._check(B.lib.q8_maxpool_i8(self.act[op.src].data_ptr(), self.N, s.H, s.W,
+                                         _pad_c(s.C), op.R, op.S, op.stride, op.pad, d.H, d.W,
+                                         self.act[op.dst].data_ptr(), B._stream()))
+        else:
+            B.pool_i8(self.act[op.src], op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W,
+                      self.scale32(q_in, q_out), out=self.act[op.dst], out_c_off=op.dst_c_off)
+
+    @staticmethod
+    def scale32(q_in, q_out):
+        """q_in / q_out rounded once to fp32 (both factors are fp32 values)."""
+        return float(np.float32(q_in) / np.float32(q_out))
+
     def run_layers(self, acc_dump=None):
         for op in self.net.ops:
             d = self.net.tensors[op.dst]
-            if op.kind == "maxpool":
-                s = self.net.tensors[op.src]
-                B._check(B.lib.q8_maxpool_i8(self.act[op.src].data_ptr(), self.N, s.H, s.W,
-                                             _pad_c(s.C), op.R, op.S, op.stride, op.pad, d.H, d.W,
-                                             self.act[op.dst].data_ptr(), B._stream()))
+            if op.kind == "pool":
+                self.run_pool(op)
                 continue
             packed, bias = self.wq[op.name]
             res = self.act[op.res] if op.res else None

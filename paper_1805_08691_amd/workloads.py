@@ -61,7 +61,9 @@ class PoolSpec:
     S: int
     stride: int
     pad: int
-    kind: str = "maxpool"
+    mode: str = "max"              # "max" or "avg" (mean over R*S, padding counted as zeros)
+    dst_c_off: int = 0             # channel offset inside dst (pooled branch of a concat)
+    kind: str = "pool"
 
 
 @dataclass
@@ -110,13 +112,25 @@ def _conv(net, name, src, K, R, S, stride=1, pad_h=None, pad_w=None, dil=1, relu
     return dst
 
 
-def _maxpool(net, name, src, R, stride, pad):
+def _pool(net, name, src, R, stride, pad, mode="max", ceil=False, dst=None, dst_c_off=0):
     s = net.tensors[src]
-    Ho = out_extent(s.H, R, stride, pad)
-    Wo = out_extent(s.W, R, stride, pad)
-    dst = net.tensor(name, Ho, Wo, s.C)
-    net.ops.append(PoolSpec(name, src, dst, R, R, stride, pad))
+    if ceil:
+        Ho = -((s.H + 2 * pad - R) // -stride) + 1
+        Wo = -((s.W + 2 * pad - R) // -stride) + 1
+    else:
+        Ho = out_extent(s.H, R, stride, pad)
+        Wo = out_extent(s.W, R, stride, pad)
+    if dst is None:
+        dst = net.tensor(name, Ho, Wo, s.C)
+    else:
+        d = net.tensors[dst]
+        assert (d.H, d.W) == (Ho, Wo) and dst_c_off + s.C <= d.C
+    net.ops.append(PoolSpec(name, src, dst, R, R, stride, pad, mode, dst_c_off))
     return dst
+
+
+def _maxpool(net, name, src, R, stride, pad):
+    return _pool(net, name, src, R, stride, pad)
 
 
 def single_conv3x3():
@@ -161,6 +175,118 @@ def resnet50(image=224):
     return net
 
 
+def inception_v3(image=299):
+    """Config 4: the 94 convolutions of Inception-v3 (1x1, 3x3, 5x5, 1x7/7x1, 1x3/3x1,
+    stride-2 reductions); the branches of a block write channel slices of one concat tensor."""
+    net = Network("inception_v3", "image")
+    net.tensor("image", image, image, 3)
+    t = _conv(net, "conv1a", "image", 32, 3, 3, stride=2, pad_h=0, pad_w=0)
+    t = _conv(net, "conv2a", t, 32, 3, 3, pad_h=0, pad_w=0)
+    t = _conv(net, "conv2b", t, 64, 3, 3)
+    t = _pool(net, "pool1", t, 3, 2, 0)
+    t = _conv(net, "conv3b", t, 80, 1, 1)
+    t = _conv(net, "conv4a", t, 192, 3, 3, pad_h=0, pad_w=0)
+    t = _pool(net, "pool2", t, 3, 2, 0)
+
+    def concat(name, src, width):
+        s = net.tensors[src]
+        return net.tensor(name, s.H, s.W, width)
+
+    for i, pf in enumerate((32, 64, 64)):                       # 35 x 35
+        n = f"mixed5{'bcd'[i]}"
+        out = concat(n, t, 64 + 64 + 96 + pf)
+        _conv(net, n + "_1x1", t, 64, 1, 1, dst=out, dst_c_off=0)
+        a = _conv(net, n + "_5x5a", t, 48, 1, 1)
+        _conv(net, n + "_5x5b", a, 64, 5, 5, dst=out, dst_c_off=64)
+        a = _conv(net, n + "_dbla", t, 64, 1, 1)
+        a = _conv(net, n + "_dblb", a, 96, 3, 3)
+        _conv(net, n + "_dblc", a, 96, 3, 3, dst=out, dst_c_off=128)
+        a = _pool(net, n + "_pool", t, 3, 1, 1, mode="avg")
+        _conv(net, n + "_poolproj", a, pf, 1, 1, dst=out, dst_c_off=224)
+        t = out
+    s = net.tensors[t]
+    out = net.tensor("mixed6a", out_extent(s.H, 3, 2, 0), out_extent(s.W, 3, 2, 0), 384 + 96 + 288)
+    _conv(net, "mixed6a_3x3", t, 384, 3, 3, stride=2, pad_h=0, pad_w=0, dst=out, dst_c_off=0)
+    a = _conv(net, "mixed6a_dbla", t, 64, 1, 1)
+    a = _conv(net, "mixed6a_dblb", a, 96, 3, 3)
+    _conv(net, "mixed6a_dblc", a, 96, 3, 3, stride=2, pad_h=0, pad_w=0, dst=out, dst_c_off=384)
+    _pool(net, "mixed6a_pool", t, 3, 2, 0, dst=out, dst_c_off=480)
+    t = out
+    for i, c7 in enumerate((128, 160, 160, 192)):               # 17 x 17
+        n = f"mixed6{'bcde'[i]}"
+        out = concat(n, t, 768)
+        _conv(net, n + "_1x1", t, 192, 1, 1, dst=out, dst_c_off=0)
+        a = _conv(net, n + "_7a", t, c7, 1, 1)
+        a = _conv(net, n + "_7b", a, c7, 1, 7)
+        _conv(net, n + "_7c", a, 192, 7, 1, dst=out, dst_c_off=192)
+        a = _conv(net, n + "_77a", t, c7, 1, 1)
+        a = _conv(net, n + "_77b", a, c7, 7, 1)
+        a = _conv(net, n + "_77c", a, c7, 1, 7)
+        a = _conv(net, n + "_77d", a, c7, 7, 1)
+        _conv(net, n + "_77e", a, 192, 1, 7, dst=out, dst_c_off=384)
+        a = _pool(net, n + "_pool", t, 3, 1, 1, mode="avg")
+        _conv(net, n + "_poolproj", a, 192, 1, 1, dst=out, dst_c_off=576)
+        t = out
+    s = net.tensors[t]
+    out = net.tensor("mixed7a", out_extent(s.H, 3, 2, 0), out_extent(s.W, 3, 2, 0), 320 + 192 + 768)
+    a = _conv(net, "mixed7a_3a", t, 192, 1, 1)
+    _conv(net, "mixed7a_3b", a, 320, 3, 3, stride=2, pad_h=0, pad_w=0, dst=out, dst_c_off=0)
+    a = _conv(net, "mixed7a_7a", t, 192, 1, 1)
+    a = _conv(net, "mixed7a_7b", a, 192, 1, 7)
+    a = _conv(net, "mixed7a_7c", a, 192, 7, 1)
+    _conv(net, "mixed7a_7d", a, 192, 3, 3, stride=2, pad_h=0, pad_w=0, dst=out, dst_c_off=320)
+    _pool(net, "mixed7a_pool", t, 3, 2, 0, dst=out, dst_c_off=512)
+    t = out
+    for i in range(2):                                          # 8 x 8
+        n = f"mixed7{'bc'[i]}"
+        out = concat(n, t, 320 + 768 + 768 + 192)
+        _conv(net, n + "_1x1", t, 320, 1, 1, dst=out, dst_c_off=0)
+        a = _conv(net, n + "_3a", t, 384, 1, 1)
+        _conv(net, n + "_3b1", a, 384, 1, 3, dst=out, dst_c_off=320)
+        _conv(net, n + "_3b2", a, 384, 3, 1, dst=out, dst_c_off=704)
+        a = _conv(net, n + "_d3a", t, 448, 1, 1)
+        a = _conv(net, n + "_d3b", a, 384, 3, 3)
+        _conv(net, n + "_d3c1", a, 384, 1, 3, dst=out, dst_c_off=1088)
+        _conv(net, n + "_d3c2", a, 384, 3, 1, dst=out, dst_c_off=1472)
+        a = _pool(net, n + "_pool", t, 3, 1, 1, mode="avg")
+        _conv(net, n + "_poolproj", a, 192, 1, 1, dst=out, dst_c_off=1856)
+        t = out
+    net.outputs = [t]
+    return net
+
+
+def ssd300_vgg16(image=300, classes=21):
+    """Config 5: SSD-300 backbone (VGG-16 with a dilated fc6), extra layers and the 3x3
+    multibox heads on six feature maps (location 4a and confidence classes*a channels)."""
+    net = Network("ssd300_vgg16", "image")
+    net.tensor("image", image, image, 3)
+    t = "image"
+    plan = [(64, 2), (128, 2), (256, 3), (512, 3), (512, 3)]
+    for b, (k, n) in enumerate(plan, 1):
+        for i in range(1, n + 1):
+            t = _conv(net, f"conv{b}_{i}", t, k, 3, 3)
+        if b == 4:
+            conv4_3 = t
+        if b < 5:
+            t = _pool(net, f"pool{b}", t, 2, 2, 0, ceil=(b == 3))
+        else:
+            t = _pool(net, "pool5", t, 3, 1, 1)
+    t = _conv(net, "fc6", t, 1024, 3, 3, dil=6)
+    fc7 = t = _conv(net, "fc7", t, 1024, 1, 1)
+    t = _conv(net, "conv6_1", t, 256, 1, 1)
+    c6 = t = _conv(net, "conv6_2", t, 512, 3, 3, stride=2)
+    t = _conv(net, "conv7_1", t, 128, 1, 1)
+    c7 = t = _conv(net, "conv7_2", t, 256, 3, 3, stride=2)
+    t = _conv(net, "conv8_1", t, 128, 1, 1)
+    c8 = t = _conv(net, "conv8_2", t, 256, 3, 3, pad_h=0, pad_w=0)
+    t = _conv(net, "conv9_1", t, 128, 1, 1)
+    c9 = t = _conv(net, "conv9_2", t, 256, 3, 3, pad_h=0, pad_w=0)
+    for src, anchors in ((conv4_3, 4), (fc7, 6), (c6, 6), (c7, 6), (c8, 4), (c9, 4)):
+        net.outputs.append(_conv(net, src + "_loc", src, 4 * anchors, 3, 3, relu=False))
+        net.outputs.append(_conv(net, src + "_conf", src, classes * anchors, 3, 3, relu=False))
+    return net
+
+
 # ------------------------------------------------------------------------------------------
 # seeded parameters and inputs
 # ------------------------------------------------------------------------------------------
@@ -195,4 +321,6 @@ CONFIGS = {
     1: dict(make=single_conv3x3, batch=1, relu_input=True),
     2: dict(make=bottleneck_block, batch=32, relu_input=True),
     3: dict(make=resnet50, batch=64, relu_input=False),
+    4: dict(make=inception_v3, batch=64, relu_input=False),
+    5: dict(make=ssd300_vgg16, batch=64, relu_input=False),
 }

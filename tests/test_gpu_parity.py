@@ -256,6 +256,41 @@ def test_maxpool_helper(B, shape, win):
 
 
 # ------------------------------------------------------------------ whole configurations
+@pytest.mark.parametrize("mode", ["max", "avg"])
+@pytest.mark.parametrize("shape,win,m,slice_", [
+    ((2, 35, 35, 192), (3, 1, 1), 1.0, (0, 0)),        # Inception pooled branch
+    ((1, 17, 17, 768), (3, 2, 0), 0.73, (1280, 512)),  # into a concatenation, rescaled
+    ((2, 9, 10, 20), (2, 2, 0), 1.9, (23, 3)),         # odd widths, saturating scale
+    ((1, 8, 8, 3), (8, 8, 0), 1.0, (0, 0)),            # whole-image window
+    ((1, 19, 19, 64), (3, 1, 1), 0.5, (64, 0)),        # ties of .5 after the scale
+])
+def test_pool_i8(B, mode, shape, win, m, slice_):
+    rng = np.random.default_rng(sum(shape) + win[0])
+    x = rng.integers(-128, 128, size=shape, dtype=np.int8)
+    R, stride, pad = win
+    Ho = (shape[1] + 2 * pad - R) // stride + 1
+    Wo = (shape[2] + 2 * pad - R) // stride + 1
+    Cd, off = slice_
+    Cd = Cd or shape[3]
+    base = rng.integers(-128, 128, size=(shape[0], Ho, Wo, Cd), dtype=np.int8)
+    want = orc.pool_i8(x, mode, R, R, stride, pad, Ho, Wo, m, out=base.copy(), out_c_off=off)
+    got = B.pool_i8(dev(x), mode, R, R, stride, pad, Ho, Wo, float(np.float32(m)),
+                    out=dev(base), out_c_off=off)
+    assert np.array_equal(host(got), want)
+
+
+def test_pool_f32(B):
+    import torch
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((2, 17, 15, 24)).astype(np.float32)
+    xt = torch.from_numpy(x).permute(0, 3, 1, 2)
+    for mode, ref in (("max", torch.nn.functional.max_pool2d(xt, 3, 2, 1)),
+                      ("avg", torch.nn.functional.avg_pool2d(xt, 3, 2, 1, count_include_pad=True))):
+        got = host(B.pool_f32(dev(x), mode, 3, 3, 2, 1, 9, 8))
+        want = ref.permute(0, 2, 3, 1).numpy()
+        assert np.allclose(got, want, rtol=1e-6, atol=1e-6), mode
+
+
 def _oracle_pipeline(cfg_id, batch, calib_library):
     cfg = wl.CONFIGS[cfg_id]
     net = cfg["make"]()
@@ -324,16 +359,16 @@ def test_config2_bottleneck_block(B):
             assert np.array_equal(host(eng.act[o]), acts[o])
 
 
-def test_config3_resnet50_batch64_sampled_images(B):
-    """Full ResNet-50 conv stack at batch 64 in the launch configuration the benchmark
-    times; the oracle evaluates images 0, 32 and 63 (batch elements are independent once
-    the factor table is frozen) and every tensor of the chain is compared bit for bit."""
+def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch):
+    """Whole network at ``batch`` in the launch configuration the benchmark times; the
+    oracle evaluates the images in ``picks`` (batch elements are independent once the
+    factor table is frozen) and every tensor of the chain is compared bit for bit."""
     from paper_1805_08691_amd.engine import Engine
-    cfg_id, batch, picks = 3, 64, [0, 32, 63]
-    net = wl.resnet50()
+    net = wl.CONFIGS[cfg_id]["make"]()
     params = {op.name: wl.conv_params(cfg_id, i, op) for i, op in enumerate(net.convs())}
     folded = onet.fold_all(net, params)
-    q = onet.calibrate(net, folded, (wl.input_batch(cfg_id, net, 8, 100 + i) for i in range(8)))
+    q = onet.calibrate(net, folded, (wl.input_batch(cfg_id, net, cal_batch, 100 + i)
+                                     for i in range(n_cal)))
     qparams = onet.quantize_params(net, folded, q)
     x = wl.input_batch(cfg_id, net, batch, 0)
     z_in = orc.Q(x[picks], q[net.input], 7)
@@ -348,21 +383,40 @@ def test_config3_resnet50_batch64_sampled_images(B):
         assert np.float32(eng.qw[name]) == qp["q_w"], name
         assert np.array_equal(host(eng.wq[name][1]), qp["z_b"]), name
     xd = dev(x)
-    out = eng.forward(xd)[0]
+    outs = eng.forward(xd)
     zi = host(eng.act[net.input])
     assert np.array_equal(zi[picks][..., :3], z_in) and np.all(zi[..., 3] == 0)
     for op in net.ops:
         got = host(eng.act[op.dst])[picks]
         assert np.array_equal(got, acts[op.dst]), op.name
-    o = net.outputs[0]
-    r = host(B.dequantize(out, float(q[o])))[picks]
-    want = orc.D(acts[o], q[o])
-    assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want))
+    for o, out in zip(net.outputs, outs):
+        r = host(B.dequantize(out, float(q[o])))[picks]
+        want = orc.D(acts[o], q[o])
+        assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want)), o
     # replay through a HIP graph: same bits
     eng.capture(xd)
-    eng.act[o].fill_(3)
+    for o in net.outputs:
+        eng.act[o].fill_(3)
     eng.graph.replay()
-    assert np.array_equal(host(eng.act[o])[picks], acts[o])
+    for o in net.outputs:
+        assert np.array_equal(host(eng.act[o])[picks], acts[o]), o
+
+
+def test_config3_resnet50_batch64_sampled_images(B):
+    _sampled_images_check(B, 3, 64, [0, 32, 63], n_cal=8, cal_batch=8)
+
+
+def test_config4_inception_v3_batch64_sampled_images(B):
+    # odd extents (299 -> 149 -> 147 -> 73 -> 71 -> 35 -> 17 -> 8), 1x7 / 7x1 filters,
+    # pooled branches, channel-slice writes into concatenations
+    _sampled_images_check(B, 4, 64, [0, 21, 63], n_cal=4, cal_batch=8)
+
+
+@pytest.mark.parametrize("batch,picks", [(1, [0]), (64, [0, 63])])
+def test_config5_ssd300_vgg16_sampled_images(B, batch, picks):
+    # 3x3 stack at 300x300, ceil-mode pooling, dilation 6, head convolutions with
+    # K in {16, 24, 84, 126}, twelve int8 outputs
+    _sampled_images_check(B, 5, batch, picks, n_cal=2, cal_batch=4)
 
 
 def test_gpu_calibration_matches_oracle_closely(B):

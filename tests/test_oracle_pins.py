@@ -470,3 +470,64 @@ def test_maxpool_against_library():
     ref = torch.nn.functional.max_pool2d(
         torch.from_numpy(x.astype(np.float32)).permute(0, 3, 1, 2), 3, 2, 1)
     assert np.array_equal(y, ref.permute(0, 2, 3, 1).numpy().astype(np.int8))
+
+
+def _pool_exact(x, mode, R, stride, pad, Ho, Wo, m):
+    """Pooling written out with Python integers and exact fractions: window max / window
+    sum, the stated fp32 roundings (1/(R*S), sum * that, * m), clamp, round half to even."""
+    N, H, W, Cc = x.shape
+    inv = fl32(Fraction(1, R * R))
+    mf = Fraction(float(np.float32(m)))
+    out = np.zeros((N, Ho, Wo, Cc), np.int64)
+    for n in range(N):
+        for ho in range(Ho):
+            for wo in range(Wo):
+                for c in range(Cc):
+                    vals = [int(x[n, hi, wi, c])
+                            for hi in range(ho * stride - pad, ho * stride - pad + R)
+                            for wi in range(wo * stride - pad, wo * stride - pad + R)
+                            if 0 <= hi < H and 0 <= wi < W]
+                    if mode == "max":
+                        t = Fraction(max(vals))
+                    else:
+                        t = fl32(Fraction(sum(vals)) * inv)
+                    t = fl32(t * mf)
+                    out[n, ho, wo, c] = round_half_even(clamp(t, Fraction(-128), Fraction(127)))
+    return out
+
+
+@pytest.mark.parametrize("mode", ["max", "avg"])
+@pytest.mark.parametrize("m", [1.0, 0.5, 0.737, 1.9])
+def test_pool_i8_against_exact_arithmetic(mode, m):
+    rng = np.random.default_rng(31)
+    x = rng.integers(-128, 128, (2, 7, 6, 3)).astype(np.int8)
+    for R, stride, pad in ((3, 1, 1), (3, 2, 0), (2, 2, 0)):
+        Ho = (7 + 2 * pad - R) // stride + 1
+        Wo = (6 + 2 * pad - R) // stride + 1
+        got = orc.pool_i8(x, mode, R, R, stride, pad, Ho, Wo, m)
+        assert np.array_equal(got, _pool_exact(x, mode, R, stride, pad, Ho, Wo, m)), (R, stride)
+
+
+def test_pool_i8_against_library_and_slices():
+    rng = np.random.default_rng(32)
+    x = rng.integers(-128, 128, (2, 12, 11, 5)).astype(np.int8)
+    xt = torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2)
+    # max with m = 1 is the library's max pooling exactly, ceil-mode extent included
+    ref = torch.nn.functional.max_pool2d(xt, 2, 2, 0, ceil_mode=True).permute(0, 2, 3, 1).numpy()
+    assert ref.shape[1:3] == (6, 6)
+    assert np.array_equal(orc.pool_i8(x, "max", 2, 2, 2, 0, 6, 6), ref.astype(np.int8))
+    # avg: within half a code (+ fp32 slack) of the library's real-valued average,
+    # padding counted in the divisor
+    ref = torch.nn.functional.avg_pool2d(xt, 3, 1, 1, count_include_pad=True)
+    ref = ref.permute(0, 2, 3, 1).numpy()
+    got = orc.pool_i8(x, "avg", 3, 3, 1, 1, 12, 11)
+    assert np.max(np.abs(got - ref)) <= 0.5 + 1e-4
+    # channel-slice write leaves the other channels alone
+    base = rng.integers(-128, 128, (2, 12, 11, 9)).astype(np.int8)
+    out = orc.pool_i8(x, "avg", 3, 3, 1, 1, 12, 11, out=base.copy(), out_c_off=3)
+    assert np.array_equal(out[..., 3:8], got)
+    assert np.array_equal(out[..., :3], base[..., :3]) and np.array_equal(out[..., 8:], base[..., 8:])
+    # saturation on both sides
+    big = np.full((1, 3, 3, 1), 127, np.int8)
+    assert orc.pool_i8(big, "max", 3, 3, 1, 0, 1, 1, 2.0)[0, 0, 0, 0] == 127
+    assert orc.pool_i8(-big - 1, "avg", 3, 3, 1, 0, 1, 1, 2.0)[0, 0, 0, 0] == -128
