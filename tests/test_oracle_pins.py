@@ -12,6 +12,7 @@ import pytest
 import torch
 from hypothesis import given, settings, strategies as st
 
+import golden_io
 import oracle as orc
 from exact import clamp, fl32, fl64, round_half_even
 
@@ -21,25 +22,11 @@ F = Fraction
 # ----------------------------------------------------------------------------------------
 # Eq. Q: rounding is half-to-even, clamp bounds are -2^p and 2^p - 1
 # ----------------------------------------------------------------------------------------
-def test_Q_handworked_unit_factor():
-    # r/q with q = 1: ties go to the even neighbour; beyond 127 / -128 the clamp acts.
-    r = [0, .5, 1.5, 2.5, -.5, -1.5, -2.5, 3.7, -3.2, 126.5, 127.5, 128.5, 300, -127.5,
-         -128.5, -300]
-    want = [0, 0, 2, 2, 0, -2, -2, 4, -3, 126, 127, 127, 127, -128, -128, -128]
-    assert orc.Q(r, 1.0, 7).tolist() == want
-
-
-def test_Q_handworked_half_factor():
-    # q = 0.5 -> r/q = [.5, 1.5, 2.5, 3.5, -.5, -1.5, 126.5, 127.5, -128, -128.5]
-    r = [.25, .75, 1.25, 1.75, -.25, -.75, 63.25, 63.75, -64, -64.25]
-    want = [0, 2, 2, 4, 0, -2, 126, 127, -128, -128]
-    assert orc.Q(r, 0.5, 7).tolist() == want
-
-
-def test_Q_clamp_bounds_other_precisions():
-    assert orc.Q([255.5, 256, 300, -1, -255.5, -256.5, -400], 1.0, 8).tolist() == \
-        [255, 255, 255, -1, -256, -256, -256]
-    assert orc.Q([7.4, 8.0, -8.0, -9.0, 6.5, 5.5], 1.0, 3).tolist() == [7, 7, -8, -8, 6, 6]
+@pytest.mark.parametrize("case", ["unit_factor", "half_factor", "p8_bounds", "p3_bounds",
+                                  "calibration"])
+def test_Q_handworked(case):
+    c = golden_io.load("eq_Q.txt")[case]
+    assert orc.Q(c["r"], c["q"], int(c["p"])).tolist() == [int(v) for v in c["z"]]
 
 
 def test_Q31_bias_bounds_and_values():
@@ -134,10 +121,10 @@ def test_D_handworked():
 # Eq. +  (literal) and the fused epilogue
 # ----------------------------------------------------------------------------------------
 def test_plus_handworked():
-    # q = max(.5, .25) = .5; D-sum = [6, -1, 95.25, .75]; /.5 = [12, -2, 190.5, 1.5]
-    z, q = orc.plus([10, -3, 127, 1], 0.5, [4, 2, 127, 1], 0.25)
-    assert q == np.float32(0.5)
-    assert z.tolist() == [12, -2, 127, 2]
+    c = golden_io.load("eq_plus.txt")["two_factors"]
+    z, q = orc.plus([int(v) for v in c["z1"]], c["q1"], [int(v) for v in c["z2"]], c["q2"])
+    assert q == np.float32(c["q"])
+    assert z.tolist() == [int(v) for v in c["z"]]
     # adding the zero tensor at a smaller-or-equal factor leaves z unchanged
     a = np.arange(-128, 128).astype(np.int8)
     z, q = orc.plus(a, 0.75, np.zeros_like(a), 0.3)
@@ -151,11 +138,10 @@ def test_plus_handworked():
 
 
 def test_requant_handworked():
-    acc = np.array([5, 7, -5, -7, 6, 1000, -1000, 3], np.int32).reshape(1, 8)
-    # x 0.5 -> [2.5, 3.5, -2.5, -3.5, 3, 500, -500, 1.5]: ties to even, saturation
-    assert orc.requant(acc, 0.5, relu=False).ravel().tolist() == \
-        [2, 4, -2, -4, 3, 127, -128, 2]
-    assert orc.requant(acc, 0.5, relu=True).ravel().tolist() == [2, 4, 0, 0, 3, 127, 0, 2]
+    c = golden_io.load("eq_Aprime_tail.txt")["half_scale"]
+    acc = np.array(c["acc"], np.int32).reshape(1, -1)
+    assert orc.requant(acc, c["m"], relu=False).ravel().tolist() == [int(v) for v in c["z"]]
+    assert orc.requant(acc, c["m"], relu=True).ravel().tolist() == [int(v) for v in c["z_relu"]]
 
 
 def test_requant_int32_to_fp32_conversion_is_rne():
