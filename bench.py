@@ -43,16 +43,34 @@ def conv_work(net, op, N):
     return ops, byts
 
 
+def measured_traffic(kernel, net_name, batch):
+    """HBM bytes per launch of ``kernel`` from the committed counter summary (rocprofv3 --pmc
+    FETCH_SIZE and WRITE_SIZE, scaled by a plain copy), or None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"conv_i8_{net_name}_b{batch}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split("|")
+            if len(f) >= 3 and f[0].strip() == "traffic_bytes_per_launch" and f[1].strip() == kernel:
+                return int(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload: 1, 2 or 3 (BASELINE configs)")
+    ap.add_argument("--config", type=int, default=3, help="workload: 1..5 (BASELINE configs)")
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
     ap.add_argument("--layers-out", default="", help="write the per-layer table (JSON) here")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="one eager pass plus one plain 256 MiB device copy, then exit: the "
+                         "program to run under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the copy "
+                         "gives the counters' scale)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (batch data-parallel sharding is a "
@@ -84,7 +102,7 @@ def main():
     eng.fold()
     torch.cuda.synchronize()
     t_fold = time.perf_counter() - t0
-    if args.config == 3:
+    if args.config >= 3:
         calib = [torch.from_numpy(wl.input_batch(args.config, net, 8, 100 + i)).cuda()
                  for i in range(8)]                       # 8 seeded batches of 8 images
     else:
@@ -113,6 +131,15 @@ def main():
 
     step()
     torch.cuda.synchronize()
+    if args.pmc_probe:
+        src = torch.ones(256 << 20, dtype=torch.int8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        step()
+        dst.copy_(src)                      # 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        log("pmc probe pass done")
+        return
     graph = None
     if not args.no_graph:
         graph = torch.cuda.CUDAGraph()
@@ -137,6 +164,14 @@ def main():
     # layers back to back; events between launches give each kernel's duration.
     ops_list = [o for o in net.ops]
     reps = 7
+    # an event record costs GPU time of its own: measure the interval between back-to-back
+    # records on the busy stream and take it off every interval below
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(33)]
+    torch.cuda._sleep(20_000_000)
+    for e in evs:
+        e.record()
+    torch.cuda.synchronize()
+    ev_cost = float(np.median([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(32)]))
     dur = np.zeros((reps, len(ops_list) + 2))
     for r in range(reps):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(ops_list) + 3)]
@@ -159,7 +194,13 @@ def main():
         torch.cuda.synchronize()
         for i in range(len(ops_list) + 2):
             dur[r, i] = ev[i].elapsed_time(ev[i + 1]) * 1e3      # us
-    med = np.median(dur, axis=0)
+    raw = np.median(dur, axis=0)
+    # between busy kernels a record costs less than between empty ones: take off the amount
+    # that makes the intervals add up to the timed step (never more than the measured cost)
+    ev_take = float(np.clip((raw.sum() - ms_per_step * 1e3) / len(raw), 0.0, ev_cost))
+    med = np.maximum(raw - ev_take, 0.0)
+    log(f"event record cost {ev_cost:.2f} us between empty intervals; {ev_take:.2f} us taken off "
+        f"each launch interval: sum {med.sum():.1f} us vs timed step {ms_per_step * 1e3:.1f} us")
 
     layers = []
     by_variant = {}
@@ -194,20 +235,30 @@ def main():
         f"roofline sum {roof_us:.1f} us; quantize {med[0]:.1f} us; dequantize {med[-1]:.1f} us; "
         f"graph step {ms_per_step * 1e3:.1f} us")
 
+    # the kernel with the largest share of the step; its launches together decide which
+    # roofline bounds it (algorithmic ops / algorithmic bytes against the ridge)
     dom_tops = dom["ops"] / dom["us"] / 1e6
-    roofline = dict(bound="mfma", kernel=dom_name, launches_per_step=dom["launches"],
+    dom_gbs = dom["bytes"] / dom["us"] / 1e3
+    traffic = measured_traffic(dom_name, net.name, N)
+    if dom["ops"] / dom["bytes"] > RIDGE:
+        roofline = dict(bound="mfma", achieved=round(dom_tops, 2), peak=PEAK_INT8_TOPS,
+                        unit="TOP/s", frac=round(dom_tops / PEAK_INT8_TOPS, 4))
+    else:
+        roofline = dict(bound="hbm", achieved=round(dom_gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(dom_gbs / PEAK_HBM_GBS, 4))
+    roofline.update(traffic=traffic, kernel=dom_name, launches_per_step=dom["launches"],
                     avg_launch_us=round(dom["us"] / dom["launches"], 3),
-                    achieved=round(dom_tops, 2), peak=PEAK_INT8_TOPS, unit="TOP/s",
-                    frac=round(dom_tops / PEAK_INT8_TOPS, 4), traffic=None,
-                    hbm_gbs=round(dom["bytes"] / dom["us"] / 1e3, 1),
-                    hbm_frac=round(dom["bytes"] / dom["us"] / 1e3 / PEAK_HBM_GBS, 4))
+                    algorithmic_bytes_per_launch=round(dom["bytes"] / dom["launches"]),
+                    algorithmic_ops_per_launch=round(dom["ops"] / dom["launches"]),
+                    tops=round(dom_tops, 2), pct_of_mfma_int8_peak=round(100 * dom_tops / PEAK_INT8_TOPS, 2),
+                    hbm_gbs=round(dom_gbs, 1))
 
     # ---------------- the oracle on the host cores, bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as orc
         from oracle import net as onet
-        sample = {1: 1, 2: 4, 3: 2}[args.config]
+        sample = {1: 1, 2: 32, 3: 64, 4: 32, 5: 4}[args.config]
         sample = min(sample, N)
         xs = x[:sample].cpu().numpy()
         folded = onet.fold_all(net, params)
