@@ -193,6 +193,12 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
   p.x = z_x; p.w = (const int8_t*)z_w_packed; p.bias = bias_i32; p.res = residual; p.y = z_y;
   p.acc_dump = acc_dump;
   p.M = (int)M;
+  {
+    const q8::FastDiv img = q8::make_fast_div((unsigned)(p.Ho * p.Wo));
+    const q8::FastDiv row = q8::make_fast_div((unsigned)p.Wo);
+    p.div_img_m = img.m; p.div_img_s = img.s;
+    p.div_row_m = row.m; p.div_row_s = row.s;
+  }
   p.relu = d->relu ? 1 : 0;
   {
     float prod = q_x * q_w;      // the x rule: factor of the accumulator

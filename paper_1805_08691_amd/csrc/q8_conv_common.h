@@ -31,11 +31,34 @@ struct ConvParams {
   int S4;         // 4-channel mode: 16-byte chunks per filter row (ceil(S/4))
   int n_ptiles, n_ctiles;
   int x_bytes, w_bytes;   // sizes of the activation and filter tensors (buffer descriptors)
+  unsigned div_img_m, div_img_s;   // division of a pixel index by Ho*Wo (see fast_div)
+  unsigned div_row_m, div_row_s;   // division by Wo
   float m, m_r;
   int relu;
   int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
   int vec16;      // 1: out/res addresses of 16-channel groups are 16-byte aligned
 };
+
+// x / d for 0 <= x < 2^31 with host-made constants s = ceil(log2 d), m = ceil(2^(31+s) / d):
+// m * d exceeds 2^(31+s) by less than d <= 2^s, so x * m / 2^(31+s) exceeds x / d by less
+// than 1/d and has the same integer part.
+struct FastDiv {
+  unsigned m, s;
+};
+inline FastDiv make_fast_div(unsigned d) {      // host side, 1 <= d < 2^31
+  unsigned s = 0;
+  while ((1ull << s) < d) ++s;
+  const unsigned long long pw = 1ull << (31 + s);
+  return FastDiv{(unsigned)((pw + d - 1) / d), s};
+}
+__device__ __forceinline__ int fast_div(int x, unsigned m, unsigned s) {
+  return (int)(__umulhi((unsigned)x << 1, m) >> s);
+}
+
+// Bits [0, k) set, for any k (negative: none, 32 or more: all).
+__device__ __forceinline__ unsigned bits_below(int k) {
+  return k <= 0 ? 0u : (k >= 32 ? 0xffffffffu : (1u << k) - 1u);
+}
 
 // Filter row (within a 32-row MFMA tile) -> output channel.  The 32x32 MFMA leaves, in
 // accumulator register 4a+b of a lane in half g, row 8a+4g+b.  Feeding channel 16g+4a+b

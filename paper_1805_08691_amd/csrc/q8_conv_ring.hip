@@ -94,18 +94,26 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     unsigned mask = 0;
     int off = 0;
     if (pix < p.M) {
-      const int n = pix / (p.Ho * p.Wo);
+      const int n = fast_div(pix, p.div_img_m, p.div_img_s);
       const int rem = pix - n * (p.Ho * p.Wo);
-      const int ho = rem / p.Wo;
+      const int ho = fast_div(rem, p.div_row_m, p.div_row_s);
       const int wo = rem - ho * p.Wo;
       const int hi0 = ho * p.stride_h - p.pad_h;
       const int wi0 = wo * p.stride_w - p.pad_w;
       off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + (UNIFORM ? lchunk * 16 : 0);
-      int t = 0;
-      for (int r = 0; r < p.R; ++r) {
-        const bool hok = (unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H;
-        for (int s2 = 0; s2 < p.S; ++s2, ++t)
-          if (hok && (unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) mask |= 1u << t;
+      if (p.dil_h == 1 && p.dil_w == 1) {
+        // taps inside the image: rows [r_lo, r_hi), columns [s_lo, s_hi)
+        const unsigned cols = bits_below(min(p.S, p.W - wi0)) & ~bits_below(-wi0);
+        const int r_lo = -hi0, r_hi = p.H - hi0;
+        for (int r = 0; r < p.R; ++r)
+          if (r >= r_lo && r < r_hi) mask |= cols << (r * p.S);
+      } else {
+        int t = 0;
+        for (int r = 0; r < p.R; ++r) {
+          const bool hok = (unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H;
+          for (int s2 = 0; s2 < p.S; ++s2, ++t)
+            if (hok && (unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) mask |= 1u << t;
+        }
       }
     }
     b_off[j] = off;
@@ -319,6 +327,10 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
     if (s < nk) issue_stage(s);
+  // Scalar loads still outstanding here would make every LDS wait inside the loop a full
+  // one (scalar and LDS results share a counter but return in no fixed order): settle them
+  // now, so the loop waits for exactly the fragments it needs.
+  __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0), other counters untouched
   // steady state: every step finds STAGES-2 later steps in flight and issues one more
   int kt = 0;
   for (; kt + STAGES - 1 < nk; ++kt)
