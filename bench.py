@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: the layers behind the first pooling op run as two concurrent "
+                         "half-batch pipelines")
     ap.add_argument("--layers-out", default="", help="write the per-layer table (JSON) here")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="one eager pass plus one plain 256 MiB device copy, then exit: the "
@@ -95,7 +98,7 @@ def main():
 
     # ---------------- offline: parameters, fold, calibrate, quantise weights ---------------
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
-    eng = Engine(net, N)
+    eng = Engine(net, N, n_streams=args.streams)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -159,6 +162,26 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     images_per_s = N * args.steps / elapsed
 
+    # the same launches on ONE stream (the half-batch pipelines one after the other): the
+    # total the per-launch intervals below must add up to
+    serial_us = ms_per_step * 1e3
+    if graph is not None and eng.n_streams > 1:
+        def serial_step():
+            eng.quantize_input(x)
+            eng.run_layers(serial=True)
+            B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
+        g1 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g1):
+            serial_step()
+        for _ in range(3):
+            g1.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            g1.replay()
+        torch.cuda.synchronize()
+        serial_us = (time.perf_counter() - t0) / 20 * 1e6
+
     # ---------------- per-launch durations with HIP events on the launch stream ------------
     # The host enqueues a whole chained pass behind a spin kernel so the GPU runs the
     # layers back to back; events between launches give each kernel's duration.
@@ -180,14 +203,10 @@ def main():
         eng.quantize_input(x)
         ev[1].record()
         for i, op in enumerate(ops_list):
-            if op.kind == "pool":
-                eng.run_pool(op)
-            else:
-                packed, bias = eng.wq[op.name]
-                res = eng.act[op.res] if op.res else None
-                B.conv_int8(eng.desc[op.name], eng.act[op.src], packed, bias, eng.q[op.src],
-                            eng.qw[op.name], eng.q[op.dst], res, eng.q[op.res] if op.res else 0.0,
-                            out=eng.act[op.dst])
+            # the launches of one layer (one per half-batch when split) back to back on
+            # this stream; the interval is divided by their number below
+            for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
+                eng.run_ops([op], lo, n)
             ev[i + 2].record()
         B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
         ev[-1].record()
@@ -197,10 +216,11 @@ def main():
     raw = np.median(dur, axis=0)
     # between busy kernels a record costs less than between empty ones: take off the amount
     # that makes the intervals add up to the timed step (never more than the measured cost)
-    ev_take = float(np.clip((raw.sum() - ms_per_step * 1e3) / len(raw), 0.0, ev_cost))
+    ev_take = float(np.clip((raw.sum() - serial_us) / len(raw), 0.0, ev_cost))
     med = np.maximum(raw - ev_take, 0.0)
     log(f"event record cost {ev_cost:.2f} us between empty intervals; {ev_take:.2f} us taken off "
-        f"each launch interval: sum {med.sum():.1f} us vs timed step {ms_per_step * 1e3:.1f} us")
+        f"each launch interval: sum {med.sum():.1f} us vs one-stream step {serial_us:.1f} us "
+        f"(timed step, {eng.n_streams} stream(s): {ms_per_step * 1e3:.1f} us)")
 
     layers = []
     by_variant = {}
@@ -209,9 +229,12 @@ def main():
     for i, op in enumerate(ops_list):
         if op.kind != "conv":
             continue
+        n_launch = len(eng.parts) if i >= eng.n_unsplit else 1
+        n_img = eng.parts[0][1] if i >= eng.n_unsplit else N
         ops, byts = conv_work(net, op, N)
-        us = float(med[i + 1])
-        variant = B.conv_variant(eng.desc[op.name])
+        ops, byts = ops / n_launch, byts / n_launch          # per launch
+        us = float(med[i + 1]) / n_launch
+        variant = B.conv_variant(eng.conv_desc(op, n_img))
         bound = "mfma" if ops / byts > RIDGE else "hbm"
         t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)) * 1e6
         layers.append(dict(name=op.name, C=op.C, K=op.K, R=op.R, S=op.S, stride=op.stride,
@@ -219,8 +242,10 @@ def main():
                            tops=round(ops / us / 1e6, 1), gbs=round(byts / us / 1e3, 1),
                            bound=bound, roof_us=round(t_roof, 2), frac=round(t_roof / us, 3)))
         v = by_variant.setdefault(variant, dict(ops=0.0, us=0.0, bytes=0.0, launches=0))
-        v["ops"] += ops; v["us"] += us; v["bytes"] += byts; v["launches"] += 1
-        tot_ops += ops; tot_us += us; tot_bytes += byts; roof_us += t_roof
+        v["ops"] += ops * n_launch; v["us"] += us * n_launch; v["bytes"] += byts * n_launch
+        v["launches"] += n_launch
+        tot_ops += ops * n_launch; tot_us += us * n_launch; tot_bytes += byts * n_launch
+        roof_us += t_roof * n_launch
     for L in layers:
         log("{name:22s} C={C:<4d} K={K:<4d} {R}x{S}/{stride} H={H:<3d} {variant:30s} {us:8.2f} us "
             "{tops:7.1f} TOP/s {gbs:7.1f} GB/s  {bound:4s} roof {roof_us:6.2f} us frac {frac:.3f}"
@@ -284,10 +309,12 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{net.name} conv stack, batch {N}, NHWC int8, "
                                f"{len(convs)} fused convs", "batch": N,
-                   "launch": "eager" if graph is None else "hip_graph"},
+                   "launch": "eager" if graph is None else "hip_graph",
+                   "streams": eng.n_streams},
         "int8_conv_tops": round(agg_tops, 1),
         "pct_of_mfma_int8_peak": round(100 * agg_tops / PEAK_INT8_TOPS, 2),
         "conv_kernel_us_per_step": round(tot_us, 1),
+        "one_stream_step_us": round(serial_us, 1),
         "conv_roofline_us_per_step": round(roof_us, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -24,10 +24,24 @@ def _pad_c(c):
 
 
 class Engine:
-    def __init__(self, net, batch, device="cuda"):
+    """``n_streams`` = 2 runs the layers behind the first pooling op as two concurrent
+    half-batch pipelines (batch elements are independent once the factor table is frozen):
+    one on the caller's stream, one on a side stream of the same (default) priority, joined
+    again before forward() returns.  A layer's launch latency and its tail then overlap the
+    other half's work.  Results are the same bits as with one stream."""
+
+    def __init__(self, net, batch, device="cuda", n_streams=1):
         self.net = net
         self.N = batch
         self.dev = torch.device(device)
+        assert n_streams in (1, 2)
+        self.n_streams = n_streams if batch >= 2 else 1
+        self.side = torch.cuda.Stream(device=self.dev) if self.n_streams == 2 else None
+        half = (batch + 1) // 2
+        self.parts = [(0, half), (half, batch - half)] if self.n_streams == 2 else [(0, batch)]
+        first_pool = next((i for i, o in enumerate(net.ops) if o.kind == "pool"), -1)
+        self.n_unsplit = first_pool + 1 if self.n_streams == 2 else len(net.ops)
+        self.part_desc = {}   # (conv name, images) -> ConvDesc
         self.params = {}      # conv name -> dict of fp32 device tensors
         self.folded = {}      # conv name -> (W', b')
         self.q = {}           # tensor name -> activation factor (host float)
@@ -164,36 +178,71 @@ class Engine:
         else:
             B.quantize(x, self.q[self.net.input], P_ACT, out=self.act[self.net.input])
 
-    def run_pool(self, op):
+    def run_pool(self, op, lo=0, n=None):
+        n = self.N if n is None else n
         s, d = self.net.tensors[op.src], self.net.tensors[op.dst]
         q_in, q_out = self.q[op.src], self.q[op.dst]
+        src, dst = self.act[op.src][lo:lo + n], self.act[op.dst][lo:lo + n]
         if op.mode == "max" and q_in == q_out and _pad_c(d.C) == _pad_c(s.C):
             # exact copy of the maximum: the vectorised kernel
-            B._check(B.lib.q8_maxpool_i8(self.act[op.src].data_ptr(), self.N, s.H, s.W,
-                                         _pad_c(s.C), op.R, op.S, op.stride, op.pad, d.H, d.W,
-                                         self.act[op.dst].data_ptr(), B._stream()))
+            B._check(B.lib.q8_maxpool_i8(src.data_ptr(), n, s.H, s.W, _pad_c(s.C), op.R, op.S,
+                                         op.stride, op.pad, d.H, d.W, dst.data_ptr(),
+                                         B._stream()))
         else:
-            B.pool_i8(self.act[op.src], op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W,
-                      self.scale32(q_in, q_out), out=self.act[op.dst], out_c_off=op.dst_c_off)
+            B.pool_i8(src, op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W,
+                      self.scale32(q_in, q_out), out=dst, out_c_off=op.dst_c_off)
+
+    def conv_desc(self, op, n):
+        """Descriptor of ``op`` over ``n`` images (the whole batch or one part of it)."""
+        if n == self.N:
+            return self.desc[op.name]
+        key = (op.name, n)
+        if key not in self.part_desc:
+            self.part_desc[key] = self._desc(op, n)
+        return self.part_desc[key]
+
+    def run_conv(self, op, lo=0, n=None, acc_dump=None):
+        n = self.N if n is None else n
+        packed, bias = self.wq[op.name]
+        res = self.act[op.res][lo:lo + n] if op.res else None
+        q_res = self.q[op.res] if op.res else 0.0
+        B.conv_int8(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed, bias,
+                    self.q[op.src], self.qw[op.name], self.q[op.dst], res, q_res,
+                    out=self.act[op.dst][lo:lo + n], acc_dump=acc_dump)
+
+    def run_ops(self, ops, lo, n):
+        for op in ops:
+            if op.kind == "pool":
+                self.run_pool(op, lo, n)
+            else:
+                self.run_conv(op, lo, n)
 
     @staticmethod
     def scale32(q_in, q_out):
         """q_in / q_out rounded once to fp32 (both factors are fp32 values)."""
         return float(np.float32(q_in) / np.float32(q_out))
 
-    def run_layers(self, acc_dump=None):
-        for op in self.net.ops:
-            d = self.net.tensors[op.dst]
-            if op.kind == "pool":
-                self.run_pool(op)
-                continue
-            packed, bias = self.wq[op.name]
-            res = self.act[op.res] if op.res else None
-            q_res = self.q[op.res] if op.res else 0.0
-            dump = acc_dump.get(op.name) if acc_dump else None
-            B.conv_int8(self.desc[op.name], self.act[op.src], packed, bias, self.q[op.src],
-                        self.qw[op.name], self.q[op.dst], res, q_res, out=self.act[op.dst],
-                        acc_dump=dump)
+    def run_layers(self, acc_dump=None, serial=False):
+        """``serial``: the same launches (one per part) all on the caller's stream."""
+        ops = self.net.ops
+        if acc_dump or self.n_streams == 1:
+            for op in ops:
+                if op.kind == "pool":
+                    self.run_pool(op)
+                else:
+                    self.run_conv(op, acc_dump=acc_dump.get(op.name) if acc_dump else None)
+            return
+        self.run_ops(ops[:self.n_unsplit], 0, self.N)
+        if serial:
+            for lo, n in self.parts:
+                self.run_ops(ops[self.n_unsplit:], lo, n)
+            return
+        main = torch.cuda.current_stream()
+        self.side.wait_stream(main)
+        with torch.cuda.stream(self.side):
+            self.run_ops(ops[self.n_unsplit:], *self.parts[1])
+        self.run_ops(ops[self.n_unsplit:], *self.parts[0])
+        main.wait_stream(self.side)
 
     def forward(self, x):
         """x: fp32 NHWC device tensor of the network input.  Returns the int8 outputs."""

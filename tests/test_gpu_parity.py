@@ -359,7 +359,7 @@ def test_config2_bottleneck_block(B):
             assert np.array_equal(host(eng.act[o]), acts[o])
 
 
-def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch):
+def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -374,7 +374,7 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch):
     z_in = orc.Q(x[picks], q[net.input], 7)
     acts = onet.forward_i8(net, qparams, q, z_in)
 
-    eng = Engine(net, batch)
+    eng = Engine(net, batch, n_streams=n_streams)
     eng.load_params(params)
     eng.fold()
     eng.set_factors(q)
@@ -393,17 +393,22 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch):
         r = host(B.dequantize(out, float(q[o])))[picks]
         want = orc.D(acts[o], q[o])
         assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want)), o
-    # replay through a HIP graph: same bits
+    # replays of the captured HIP graph, with eager work between them: same bits each time
     eng.capture(xd)
-    for o in net.outputs:
-        eng.act[o].fill_(3)
-    eng.graph.replay()
-    for o in net.outputs:
-        assert np.array_equal(host(eng.act[o])[picks], acts[o]), o
+    for rep in range(3):
+        for o in net.outputs:
+            eng.act[o].fill_(3 + rep)
+        torch.cuda.synchronize()
+        eng.graph.replay()
+        for o in net.outputs:
+            assert np.array_equal(host(eng.act[o])[picks], acts[o]), (o, rep)
 
 
-def test_config3_resnet50_batch64_sampled_images(B):
-    _sampled_images_check(B, 3, 64, [0, 32, 63], n_cal=8, cal_batch=8)
+@pytest.mark.parametrize("n_streams", [2, 1])
+def test_config3_resnet50_batch64_sampled_images(B, n_streams):
+    # n_streams = 2 is the launch configuration the benchmark times (two half-batch
+    # pipelines); images 31 and 32 sit on either side of the split
+    _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=8, cal_batch=8, n_streams=n_streams)
 
 
 def test_config4_inception_v3_batch64_sampled_images(B):
