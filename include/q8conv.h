@@ -81,6 +81,16 @@ int q8_quantize(const float *r_dev, size_t n, float q, int p, int8_t *z_dev,
 int q8_quantize_pad_channels(const float *r_dev, size_t npix, int C, int C_pad,
                              float q, int p, int8_t *z_dev, void *stream);
 
+/* Eq. Q on an image of C <= 4 channels, stored as 4 int8 channels (zeros in the added
+ * ones) inside a larger zero frame: pixel (n, h, w) of the [N][H][W][C] fp32 tensor goes
+ * to pixel (n, top + h, left + w) of the [N][Hs][Ws][4] int8 tensor z_dev.  Only the
+ * H x W interior is written: the caller zeroes z_dev once and the frame stays zero.  With
+ * the padding of the first convolution stored in the frame, that layer runs without
+ * padding (the zeros Eq. A' reads outside the image are then real bytes).
+ * Q8_EINVAL if the interior does not fit the frame; N*H <= 65535.                       */
+int q8_quantize_image(const float *r_dev, int N, int H, int W, int C, float q, int p,
+                      int8_t *z_dev, int Hs, int Ws, int top, int left, void *stream);
+
 /* Eq. Q with p = 31 for the bias of Eq. A': z_b = clamp(Round(b / (q_x q_w))), the
  * factor being that of the accumulator (Eq. x).  Evaluated in fp64.               */
 int q8_quantize_bias(const float *b_dev, size_t n, float q_x, float q_w,

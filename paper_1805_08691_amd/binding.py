@@ -22,7 +22,7 @@ lib = C.CDLL(LIB_PATH)
 
 EXPORTS = [
     "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
-    "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_bias", "q8_dequantize",
+    "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_image", "q8_quantize_bias", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_variant", "q8_conv_force_variant",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
@@ -69,6 +69,7 @@ lib.q8_qfactor.restype = _f
 lib.q8_qfactor.argtypes = [_f, _i]
 lib.q8_quantize.argtypes = [_vp, _sz, _f, _i, _vp, _vp]
 lib.q8_quantize_pad_channels.argtypes = [_vp, _sz, _i, _i, _f, _i, _vp, _vp]
+lib.q8_quantize_image.argtypes = [_vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _i, _i, _vp]
 lib.q8_quantize_bias.argtypes = [_vp, _sz, _f, _f, _vp, _vp]
 lib.q8_dequantize.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_fold_bn.argtypes = [_vp] * 6 + [_f, _i, _i, _vp, _vp, _vp]
@@ -132,6 +133,15 @@ def quantize_pad_channels(r, c_pad, q, p, out=None):
     _check(lib.q8_quantize_pad_channels(_ptr(r, torch.float32), npix, Cc, c_pad, q, p,
                                         _ptr(z, torch.int8), _stream()))
     return z
+
+
+def quantize_image(r, q, p, out, top, left):
+    """r: [N,H,W,C<=4] fp32; out: zero-framed [N,Hs,Ws,4] int8, interior written at (top, left)."""
+    N, H, W, Cc = r.shape
+    assert out.shape[0] == N and out.shape[3] == 4
+    _check(lib.q8_quantize_image(_ptr(r, torch.float32), N, H, W, Cc, q, p, _ptr(out, torch.int8),
+                                 out.shape[1], out.shape[2], top, left, _stream()))
+    return out
 
 
 def quantize_bias(b, q_x, q_w, out=None):

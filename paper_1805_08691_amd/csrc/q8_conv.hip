@@ -74,8 +74,20 @@ int conv_mode(const q8_conv_desc* d) {
 constexpr int kRegBase = 100;
 int g_variant_override = -1;   // tests / tuning: force a stream variant where it is applicable
 
+// A 4-channel image without padding: the S4 16-byte chunks (4 pixels each) of a filter row
+// are contiguous bytes, i.e. the layer is an R x 1 convolution over 16*S4 "channels" whose
+// pixels overlap, and the streaming kernel takes it as such (4-byte aligned loads, nothing
+// needs a mask).  The pixels a row's last chunk reads beyond the last tap (next row, next
+// image, or past the tensor, where the buffer range check returns zeros) meet the zero
+// filter bytes that pad S to 4*S4 taps, so they add nothing.
+bool image_rows_contiguous(const q8_conv_desc* d) {
+  if (conv_mode(d) != 1 || d->pad_h || d->pad_w || d->dil_h != 1 || d->dil_w != 1) return false;
+  if (d->in_c_stride != 0 && d->in_c_stride != 4) return false;
+  return d->K > 32 && d->R <= 32 && d->H >= d->R && d->W >= d->S;
+}
+
 bool stream_capable(const q8_conv_desc* d) {
-  return conv_mode(d) == 0 && d->K > 32 && d->R * d->S <= 32;
+  return (conv_mode(d) == 0 && d->K > 32 && d->R * d->S <= 32) || image_rows_contiguous(d);
 }
 
 int pick_variant(const q8_conv_desc* d) {
@@ -83,6 +95,7 @@ int pick_variant(const q8_conv_desc* d) {
   const int tile = d->K > 64 ? 0 : d->K > 32 ? 1 : 2;      // 128x128, 256x64, 256x32
   if (!stream_capable(d)) return kRegBase + 3 * mode + tile;
   if (g_variant_override >= 0) return g_variant_override;
+  if (mode == 1) return d->K <= 64 ? 8 : 4;   // short reduction: small tiles, many per CU
   const int red = d->R * d->S * d->C;
   const int nk = (red + 63) / 64;     // reduction steps of 64 bytes
   const long M = (long)d->N * out_extent(d->H, d->pad_h, d->dil_h, d->R, d->stride_h) *
@@ -180,6 +193,10 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
     Q8_REQUIRE(d->dil_w == 1 && d->dil_h == 1, Q8_EUNSUPPORTED);
     p.S4 = (d->S + 3) / 4;
     p.red_len = d->R * p.S4 * 16;
+    if (image_rows_contiguous(d)) {     // R x 1 taps over 16*S4 overlapping "channels"
+      p.C = 16 * p.S4;
+      p.S = 1;
+    }
   }
   Q8_REQUIRE(bias_i32 == nullptr || q8_aligned(bias_i32, 16), Q8_EALIGN);
   Q8_REQUIRE(acc_dump == nullptr || q8_aligned(acc_dump, 16), Q8_EALIGN);

@@ -116,6 +116,45 @@ __global__ __launch_bounds__(kThreads) void quantize_pad4_kernel(const float* __
   }
 }
 
+// Image with a zero border: pixel (n, h, w) of an [N][H][W][C] fp32 tensor (C <= 4) goes to
+// pixel (n, top + h, left + w) of an [N][Hs][Ws][4] int8 tensor.  blockIdx.y = n * H + h;
+// a thread takes GROUP consecutive pixels of the row.  GROUP = 4 is the 3-channel case:
+// three 16-byte loads (12 floats) and one 16-byte store, both only 4-byte aligned (the
+// frame shifts the row start); the border is never written.
+typedef float f4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef unsigned u4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+
+template <int GROUP>
+__global__ __launch_bounds__(kThreads) void quantize_image_kernel(const float* __restrict__ r,
+                                                                  int H, int W, int C, int Hs,
+                                                                  int Ws, int top, int left,
+                                                                  float q, float lo, float hi,
+                                                                  unsigned* __restrict__ z) {
+  const int row = blockIdx.y;                 // n * H + h
+  const int n = row / H, h = row - n * H;
+  const int w = (blockIdx.x * blockDim.x + threadIdx.x) * GROUP;
+  if (w >= W) return;
+  const float* src = r + ((size_t)row * W + w) * C;
+  unsigned* dst = z + ((size_t)n * Hs + top + h) * Ws + left + w;
+  if (GROUP == 4 && w + 4 <= W) {             // C == 3
+    const f4_a4 a = *reinterpret_cast<const f4_a4*>(src);
+    const f4_a4 b = *reinterpret_cast<const f4_a4*>(src + 4);
+    const f4_a4 c = *reinterpret_cast<const f4_a4*>(src + 8);
+    u4_a4 o;
+    o[0] = pack4(quant1(a[0], q, lo, hi), quant1(a[1], q, lo, hi), quant1(a[2], q, lo, hi), 0);
+    o[1] = pack4(quant1(a[3], q, lo, hi), quant1(b[0], q, lo, hi), quant1(b[1], q, lo, hi), 0);
+    o[2] = pack4(quant1(b[2], q, lo, hi), quant1(b[3], q, lo, hi), quant1(c[0], q, lo, hi), 0);
+    o[3] = pack4(quant1(c[1], q, lo, hi), quant1(c[2], q, lo, hi), quant1(c[3], q, lo, hi), 0);
+    *reinterpret_cast<u4_a4*>(dst) = o;
+    return;
+  }
+  for (int g = 0; g < GROUP && w + g < W; ++g) {
+    int v[4] = {0, 0, 0, 0};
+    for (int c = 0; c < C; ++c) v[c] = quant1(src[g * C + c], q, lo, hi);
+    dst[g] = pack4(v[0], v[1], v[2], v[3]);
+  }
+}
+
 // The 3-channel image case: four pixels per thread = three aligned 16-byte loads (12
 // floats) and one 16-byte store.  r 16-byte aligned, z 16-byte aligned, npix4 = npix / 4.
 __global__ __launch_bounds__(kThreads) void quantize_rgb_pad4_kernel(const float4* __restrict__ r,
@@ -301,6 +340,25 @@ int q8_quantize_pad_channels(const float* r_dev, size_t npix, int C, int C_pad, 
     hipLaunchKernelGGL(quantize_padc_kernel, dim3(blocks_for(npix * (size_t)C_pad)), dim3(kThreads),
                        0, (hipStream_t)stream, r_dev, npix, C, C_pad, q, lo, hi, z_dev);
   }
+  return q8_launch_status();
+}
+
+int q8_quantize_image(const float* r_dev, int N, int H, int W, int C, float q, int p,
+                      int8_t* z_dev, int Hs, int Ws, int top, int left, void* stream) {
+  Q8_REQUIRE(p >= 1 && p <= 7 && q8_finite_pos(q), Q8_EINVAL);
+  Q8_REQUIRE(N >= 0 && H >= 1 && W >= 1 && C >= 1 && C <= 4, Q8_EINVAL);
+  Q8_REQUIRE(top >= 0 && left >= 0 && Hs >= top + H && Ws >= left + W, Q8_EINVAL);
+  Q8_REQUIRE((long)N * H <= 65535L, Q8_EUNSUPPORTED);          // grid rows
+  if (N == 0) return Q8_OK;
+  Q8_REQUIRE(r_dev != nullptr && z_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(r_dev, 4) && q8_aligned(z_dev, 4), Q8_EALIGN);
+  const float hi = (float)((1 << p) - 1), lo = -(float)(1 << p);
+  if (C == 3)
+    hipLaunchKernelGGL(quantize_image_kernel<4>, dim3((W + 255) / 256, N * H), dim3(64), 0, (hipStream_t)stream, r_dev, H, W, C, Hs, Ws, top, left, q,
+                       lo, hi, reinterpret_cast<unsigned*>(z_dev));
+  else
+    hipLaunchKernelGGL(quantize_image_kernel<1>, dim3((W + 63) / 64, N * H), dim3(64), 0, (hipStream_t)stream, r_dev, H, W, C, Hs, Ws, top, left, q,
+                       lo, hi, reinterpret_cast<unsigned*>(z_dev));
   return q8_launch_status();
 }
 

@@ -42,6 +42,14 @@ class Engine:
         first_pool = next((i for i, o in enumerate(net.ops) if o.kind == "pool"), -1)
         self.n_unsplit = first_pool + 1 if self.n_streams == 2 else len(net.ops)
         self.part_desc = {}   # (conv name, images) -> ConvDesc
+        # An image of fewer than 4 channels read by one convolution is stored inside a zero
+        # frame that holds that layer's padding, and the layer runs without padding.
+        self.in_frame = None
+        t_in = net.tensors[net.input]
+        readers = [o for o in net.convs() if o.src == net.input]
+        if _pad_c(t_in.C) != t_in.C and len(readers) == 1 and readers[0].dil == 1:
+            o = readers[0]
+            self.in_frame = (o.pad_h, o.pad_w, t_in.H + 2 * o.pad_h, t_in.W + 2 * o.pad_w)
         self.params = {}      # conv name -> dict of fp32 device tensors
         self.folded = {}      # conv name -> (W', b')
         self.q = {}           # tensor name -> activation factor (host float)
@@ -55,12 +63,18 @@ class Engine:
                 self.desc[op.name] = self._desc(op, batch)
 
     # ------------------------------------------------------------------ descriptors
-    def _desc(self, op, N):
+    def _desc(self, op, N, framed=True):
         s, d = self.net.tensors[op.src], self.net.tensors[op.dst]
         res_cs = _pad_c(self.net.tensors[op.res].C) if op.res else 0
-        return B.ConvDesc(N, s.H, s.W, op.C, op.K, op.R, op.S, op.stride, op.stride, op.pad_h,
-                          op.pad_w, op.dil, op.dil, relu=op.relu, in_c_stride=_pad_c(s.C),
+        H, W, pad_h, pad_w = s.H, s.W, op.pad_h, op.pad_w
+        if framed and op.src == self.net.input and self.in_frame:
+            _, _, H, W = self.in_frame
+            pad_h = pad_w = 0
+        desc = B.ConvDesc(N, H, W, op.C, op.K, op.R, op.S, op.stride, op.stride, pad_h, pad_w,
+                          op.dil, op.dil, relu=op.relu, in_c_stride=_pad_c(s.C),
                           out_c_stride=_pad_c(d.C), out_c_off=op.dst_c_off, res_c_stride=res_cs)
+        assert (desc.Ho, desc.Wo) == (d.H, d.W), (op.name, desc.Ho, desc.Wo, d)
+        return desc
 
     # ------------------------------------------------------------------ offline steps
     def load_params(self, params):
@@ -92,7 +106,7 @@ class Engine:
                                out=t[op.dst], out_c_off=op.dst_c_off)
             else:
                 Wf, bf = self.folded[op.name]
-                desc = self._desc(op, N)
+                desc = self._desc(op, N, framed=False)
                 desc.in_c_stride = desc.out_c_stride = desc.res_c_stride = 0
                 if op.res is not None and observe:
                     desc.relu = 0                  # the branch's own output, before the sum
@@ -167,12 +181,27 @@ class Engine:
     # ------------------------------------------------------------------ online step
     def allocate(self):
         for name, t in self.net.tensors.items():
-            self.act[name] = torch.zeros((self.N, t.H, t.W, _pad_c(t.C)), dtype=torch.int8,
+            H, W = t.H, t.W
+            if name == self.net.input and self.in_frame:
+                H, W = self.in_frame[2:]
+            self.act[name] = torch.zeros((self.N, H, W, _pad_c(t.C)), dtype=torch.int8,
                                          device=self.dev)
+
+    def input_codes(self):
+        """The int8 codes of the network input without the frame: [N, H, W, C_stored]."""
+        a = self.act[self.net.input]
+        if not self.in_frame:
+            return a
+        t = self.net.tensors[self.net.input]
+        top, left = self.in_frame[:2]
+        return a[:, top:top + t.H, left:left + t.W]
 
     def quantize_input(self, x):
         t = self.net.tensors[self.net.input]
-        if _pad_c(t.C) != t.C:
+        if self.in_frame:
+            B.quantize_image(x, self.q[self.net.input], P_ACT, self.act[self.net.input],
+                             self.in_frame[0], self.in_frame[1])
+        elif _pad_c(t.C) != t.C:
             B.quantize_pad_channels(x, _pad_c(t.C), self.q[self.net.input], P_ACT,
                                     out=self.act[self.net.input])
         else:

@@ -42,6 +42,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.q8_calibrate_maxabs(C.c_void_p(0x1002), 10, fake, None) == -3
     assert L.q8_calibrate_maxabs(None, 0, fake, None) == 0            # empty tensor: no-op
     assert L.q8_quantize(fake, 10, 0.0, 7, fake, None) == -1          # q <= 0
+    assert L.q8_quantize_image(fake, 1, 8, 8, 3, 0.5, 7, fake, 8, 9, 1, 0, None) == -1   # frame too low
+    assert L.q8_quantize_image(fake, 1, 8, 8, 5, 0.5, 7, fake, 8, 8, 0, 0, None) == -1   # C > 4
+    assert L.q8_quantize_image(fake, 1, 8, 8, 3, 0.5, 7, C.c_void_p(0x1002), 8, 8, 0, 0, None) == -3
+    assert L.q8_quantize_image(fake, 0, 8, 8, 3, 0.5, 7, fake, 8, 8, 0, 0, None) == 0    # empty batch
     assert L.q8_quantize(fake, 10, float("nan"), 7, fake, None) == -1
     assert L.q8_quantize(fake, 10, float("inf"), 7, fake, None) == -1
     assert L.q8_quantize(fake, 10, 1.0, 8, fake, None) == -1          # p outside 1..7

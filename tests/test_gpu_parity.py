@@ -190,6 +190,7 @@ VARIANT_CASES = [
     dict(N=1, H=17, W=17, C=48, K=272, R=1, S=7, pad_w=3),               # per-lane taps, tails
     dict(N=3, H=28, W=28, C=128, K=64, R=1, S=1, stride_h=2, stride_w=2),
     dict(N=1, H=33, W=31, C=256, K=384, R=1, S=1),                       # complete + ragged tiles
+    dict(N=2, H=43, W=47, C=3, K=96, R=7, S=7, stride_h=2, stride_w=2),  # unpadded 4-channel image
 ]
 
 
@@ -208,6 +209,46 @@ def test_conv_every_kernel_variant(B):
                                with_bias=True, seed=100 * v + k)
     finally:
         B.conv_force_variant(-1)
+
+
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=37, W=41, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
+    dict(N=1, H=39, W=39, C=3, K=64, R=3, S=3, stride_h=2, stride_w=2),
+    dict(N=2, H=30, W=31, C=3, K=64, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=1, H=24, W=20, C=1, K=40, R=5, S=5, pad_h=2, pad_w=2),
+    dict(N=1, H=12, W=12, C=4, K=48, R=3, S=9, pad_h=1, pad_w=4),
+])
+def test_conv_image_in_zero_frame(B, geom):
+    """A C <= 4 image quantised into a zero frame that holds the layer's padding, the layer
+    then run without padding, equals the oracle's padded convolution of the bare image."""
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(g.H * 100 + g.W)
+    r = rng.standard_normal((g.N, g.H, g.W, g.C)).astype(np.float32)
+    q_x = orc.qfactor(orc.maxabs(r), 7)
+    z_x = orc.Q(r, q_x, 7)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-2000, 2000, g.K).astype(np.int32)
+    q_w = np.float32(0.004)
+    q_out = np.float32(q_x * q_w * 74 * 40 * np.sqrt(g.R * g.S * g.C) / 40.0)
+    acc_o = orc.conv_i8(g, z_x, w, b)
+    want = orc.requant(acc_o, orc.requant_scale(q_x, q_w, q_out), True)
+
+    Hs, Ws = g.H + 2 * g.pad_h, g.W + 2 * g.pad_w
+    frame = torch.zeros((g.N, Hs, Ws, 4), dtype=torch.int8, device="cuda")
+    B.quantize_image(dev(r), float(q_x), 7, frame, g.pad_h, g.pad_w)
+    f = host(frame)
+    assert np.array_equal(f[:, g.pad_h:g.pad_h + g.H, g.pad_w:g.pad_w + g.W, :g.C], z_x)
+    f[:, g.pad_h:g.pad_h + g.H, g.pad_w:g.pad_w + g.W, :g.C] = 0
+    assert not f.any()
+    d = B.ConvDesc(g.N, Hs, Ws, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, 0, 0, 1, 1,
+                   relu=1, in_c_stride=4)
+    assert (d.Ho, d.Wo) == (g.Ho, g.Wo)
+    assert "ring" in B.conv_variant(d)
+    dump = torch.zeros((g.N, g.Ho, g.Wo, g.K), dtype=torch.int32, device="cuda")
+    got = B.conv_int8(d, frame, B.pack_weights(d, dev(w)), dev(b), float(q_x), float(q_w),
+                      float(q_out), acc_dump=dump)
+    assert np.array_equal(host(dump), acc_o)
+    assert np.array_equal(host(got), want)
 
 
 @pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
@@ -384,8 +425,13 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         assert np.array_equal(host(eng.wq[name][1]), qp["z_b"]), name
     xd = dev(x)
     outs = eng.forward(xd)
-    zi = host(eng.act[net.input])
+    zi = host(eng.input_codes())
     assert np.array_equal(zi[picks][..., :3], z_in) and np.all(zi[..., 3] == 0)
+    if eng.in_frame:                     # the frame around the image holds zeros
+        top, left = eng.in_frame[:2]
+        full = host(eng.act[net.input])
+        assert not full[:, :top].any() and not full[:, top + z_in.shape[1]:].any()
+        assert not full[:, :, :left].any() and not full[:, :, left + z_in.shape[2]:].any()
     for op in net.ops:
         got = host(eng.act[op.dst])[picks]
         assert np.array_equal(got, acts[op.dst]), op.name
