@@ -106,14 +106,15 @@ int pick_variant(const q8_conv_desc* d) {
   //  - few output channels: 128 pixels x 64 channels, more workgroups per CU;
   //  - very few tiles (the chip is not filled anyway, a workgroup's own chain of steps is
   //    what takes the time): smaller tiles with a deep ring, 64 x 64 at the smallest sizes;
-  //  - short reductions (bound by memory latency and epilogue work per workgroup):
-  //    64 pixels x 128 channels, ring of 2, three or more workgroups per CU;
+  //  - short reductions (bound by memory latency and epilogue work per workgroup): ring of
+  //    2, three or more workgroups per CU, 128 pixels x 64 channels on the large maps,
+  //    64 pixels x 128 channels otherwise;
   //  - otherwise 128 x 128 with a ring of 3; when at most one workgroup per CU exists,
   //    eight wavefronts share the tile (more waves to hide LDS latency) with a ring of 4.
   if (d->K <= 64) return 8;
   if (tiles128 <= 64) return 7;
   if (tiles128 <= 128) return d->R * d->S == 1 ? 5 : 9;
-  if (nk <= 4) return 4;
+  if (nk <= 4) return tiles128 >= 512 ? 8 : 4;
   return tiles128 <= 256 ? 11 : 1;    // 11: eight wavefronts on a 128 x 128 tile, ring of 4
 }
 
