@@ -86,6 +86,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
     a_off[j] = ch < p.K ? ch * p.red_len + lchunk * 16 : kOobOffset;
   }
+  const bool pointwise = p.R * p.S == 1 && p.stride_h * p.stride_w == 1 && (p.pad_h | p.pad_w) == 0;
   int b_off[B_LOADS];                  // offset of tap (0,0), channel 0 (+ chunk if UNIFORM)
   unsigned b_mask[B_LOADS];            // bit t: tap t of this pixel lies inside the image
 #pragma unroll
@@ -93,7 +94,10 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     const int pix = pix0 + (wave + NW * j) * RPW + lrow;
     unsigned mask = 0;
     int off = 0;
-    if (pix < p.M) {
+    if (pix < p.M && pointwise) {
+      off = pix * p.in_cs + (UNIFORM ? lchunk * 16 : 0);     // output pixel = input pixel
+      mask = 1u;
+    } else if (pix < p.M) {
       const int n = fast_div(pix, p.div_img_m, p.div_img_s);
       const int rem = pix - n * (p.Ho * p.Wo);
       const int ho = fast_div(rem, p.div_row_m, p.div_row_s);
@@ -231,20 +235,21 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   // last sub-step of step kt-1 run after the barrier of step kt, so LDS latency, the
   // barrier and the issue of the global loads all overlap matrix work.
   v4i af[2][TC], bf[2][TP];
-  int a_foff[NH][TC], b_foff[NH][TP];        // LDS offsets inside a stage, per sub-step
+  // LDS offsets inside a stage, per sub-step.  The swizzle term only looks at row bits below
+  // 32, and sub-step h uses chunk 2h + half = (chunk of sub-step 0) ^ 2h: one offset is
+  // computed in full, the others differ by a tile's row distance and one XOR.
+  int a_foff[NH][TC], b_foff[NH][TP];
+  const int foff0 = frag_row * BK + swz<CHUNKS>(frag_row, frag_half) * 16;
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
-    const int chunk = 2 * h + frag_half;
 #pragma unroll
     for (int i = 0; i < TC; ++i) {
-      const int row = (wave_c * TC + i) * 32 + frag_row;
-      a_foff[h][i] = row * BK + swz<CHUNKS>(row, chunk) * 16;
+      a_foff[h][i] = (foff0 ^ (h * 32)) + (wave_c * TC + i) * 32 * BK;
       asm volatile("" : "+v"(a_foff[h][i]));     // keep in a register, do not recompute
     }
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
-      const int row = (wave_p * TP + j) * 32 + frag_row;
-      b_foff[h][j] = A_BYTES + row * BK + swz<CHUNKS>(row, chunk) * 16;
+      b_foff[h][j] = (foff0 ^ (h * 32)) + A_BYTES + (wave_p * TP + j) * 32 * BK;
       asm volatile("" : "+v"(b_foff[h][j]));
     }
   }
