@@ -70,6 +70,9 @@ def main():
                     help="2: the layers behind the first pooling op run as two concurrent "
                          "half-batch pipelines")
     ap.add_argument("--layers-out", default="", help="write the per-layer table (JSON) here")
+    ap.add_argument("--sparsity-removal", action="store_true",
+                    help="config 3 only: run the graph after the paper's sparsity-removal "
+                         "transformation (reported as its own workload, not the headline)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="one eager pass plus one plain 256 MiB device copy, then exit: the "
                          "program to run under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the copy "
@@ -91,6 +94,9 @@ def main():
     torch.cuda.set_device(0)
     cfg = wl.CONFIGS[args.config]
     net = cfg["make"]()
+    if args.sparsity_removal:
+        assert args.config == 3, "--sparsity-removal applies to config 3"
+        net = wl.resnet50(sparsity_removal=True)       # same filters (seeded by config 3)
     N = args.batch or cfg["batch"]
     convs = net.convs()
     log(f"workload: {net.name} batch {N}: {len(convs)} convs, "
@@ -222,6 +228,34 @@ def main():
         f"each launch interval: sum {med.sum():.1f} us vs one-stream step {serial_us:.1f} us "
         f"(timed step, {eng.n_streams} stream(s): {ms_per_step * 1e3:.1f} us)")
 
+    # ---------------- HBM-bound passes: max-abs (calibration), quantise, dequantise ---------
+    def timed_us(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+    big = torch.randn(64 * 112 * 112 * 64, dtype=torch.float32, device="cuda")   # 205 MB
+    slot = torch.zeros(1, dtype=torch.float32, device="cuda")
+    t_maxabs = timed_us(lambda: B.calibrate_maxabs(big, slot))
+    del big
+    n_in = x.numel()
+    n_out = out_f32.numel()
+    passes = {
+        "maxabs": dict(bytes=4 * 64 * 112 * 112 * 64, us=round(t_maxabs, 2)),
+        "quantize_input": dict(bytes=5 * n_in + n_in // 3, us=round(float(med[0]), 2)),
+        "dequantize_output": dict(bytes=5 * n_out, us=round(float(med[-1]), 2)),
+    }
+    for k, v in passes.items():
+        v["gbs"] = round(v["bytes"] / v["us"] / 1e3, 1)
+        v["frac_of_hbm_peak"] = round(v["gbs"] / PEAK_HBM_GBS, 3)
+        log(f"pass {k}: {v['bytes'] / 1e6:.1f} MB in {v['us']:.2f} us = {v['gbs']:.0f} GB/s "
+            f"({100 * v['frac_of_hbm_peak']:.0f}% of HBM peak)")
+
     layers = []
     by_variant = {}
     tot_ops = tot_us = tot_bytes = 0.0
@@ -302,7 +336,7 @@ def main():
                    matches_gpu=same)
 
     result = {
-        "metric": "ResNet-50 int8 images/sec at batch 64" if args.config == 3
+        "metric": "ResNet-50 int8 images/sec at batch 64" if args.config == 3 and not args.sparsity_removal
                   else f"{net.name} int8 images/sec at batch {N}",
         "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
@@ -311,8 +345,13 @@ def main():
                                f"{len(convs)} fused convs", "batch": N,
                    "launch": "eager" if graph is None else "hip_graph",
                    "streams": eng.n_streams},
-        "int8_conv_tops": round(agg_tops, 1),
-        "pct_of_mfma_int8_peak": round(100 * agg_tops / PEAK_INT8_TOPS, 2),
+        # every convolution's algorithmic ops over the timed step (which also holds the
+        # quantise, pooling and dequantise launches), and over the convolutions' own
+        # back-to-back launch durations on one stream
+        "int8_conv_tops": round(tot_ops / (ms_per_step * 1e-3) / 1e12, 1),
+        "pct_of_mfma_int8_peak": round(100 * tot_ops / (ms_per_step * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
+        "int8_conv_tops_one_stream": round(agg_tops, 1),
+        "hbm_passes": passes,
         "conv_kernel_us_per_step": round(tot_us, 1),
         "one_stream_step_us": round(serial_us, 1),
         "conv_roofline_us_per_step": round(roof_us, 1),

@@ -153,24 +153,39 @@ def bottleneck_block(H=56, C=256, mid=64):
     return net
 
 
-def resnet50(image=224):
-    """Config 3: the 53 convolutions of ResNet-50 (stride 2 on the first 1x1 of a stage)."""
-    net = Network("resnet50", "image")
+def resnet50(image=224, sparsity_removal=False):
+    """Config 3: the 53 convolutions of ResNet-50 (stride 2 on the first 1x1 of a stage).
+
+    ``sparsity_removal`` applies the paper's graph transformation ("Model Optimization",
+    the sparsity figure): the two stride-2 1x1 convolutions that open a stage read only
+    every other pixel of their input, so the layer producing that input (the previous
+    block's last 1x1) is given the stride 2 instead and produces only the pixels that are
+    read, a 1x1 stride-2 pooling on the skip branch subsamples its residual to match, and the
+    two consumers become stride 1.  Same values at the kept positions, less work."""
+    net = Network("resnet50_sparse" if sparsity_removal else "resnet50", "image")
     net.tensor("image", image, image, 3)
     t = _conv(net, "conv1", "image", 64, 7, 7, stride=2, pad_h=3, pad_w=3)
     t = _maxpool(net, "pool1", t, 3, 2, 1)
     stages = [(2, 3, 64, 256), (3, 4, 128, 512), (4, 6, 256, 1024), (5, 3, 512, 2048)]
-    for stage, blocks, mid, out in stages:
+    pre_strided = False          # t already holds only the pixels a stride-2 consumer reads
+    for si, (stage, blocks, mid, out) in enumerate(stages):
         for blk in range(blocks):
             tag = f"res{stage}{chr(ord('a') + blk)}"
-            stride = 2 if (blk == 0 and stage > 2) else 1
+            stride = 2 if (blk == 0 and stage > 2 and not pre_strided) else 1
+            pre_strided = False
             if blk == 0:
                 short = _conv(net, tag + "_branch1", t, out, 1, 1, stride=stride, relu=False)
             else:
                 short = t
             a = _conv(net, tag + "_branch2a", t, mid, 1, 1, stride=stride)
             b = _conv(net, tag + "_branch2b", a, mid, 3, 3)
-            t = _conv(net, tag + "_branch2c", b, out, 1, 1, relu=True, res=short)
+            last = blk == blocks - 1 and si + 1 < len(stages)
+            if sparsity_removal and last:
+                short = _pool(net, tag + "_skip_pool", short, 1, 2, 0)
+                t = _conv(net, tag + "_branch2c", b, out, 1, 1, stride=2, relu=True, res=short)
+                pre_strided = True
+            else:
+                t = _conv(net, tag + "_branch2c", b, out, 1, 1, relu=True, res=short)
     net.outputs = [t]
     return net
 
@@ -323,4 +338,6 @@ CONFIGS = {
     3: dict(make=resnet50, batch=64, relu_input=False),
     4: dict(make=inception_v3, batch=64, relu_input=False),
     5: dict(make=ssd300_vgg16, batch=64, relu_input=False),
+    # config 3 after the paper's sparsity-removal graph transformation (not a BASELINE config)
+    6: dict(make=lambda: resnet50(sparsity_removal=True), batch=64, relu_input=False),
 }

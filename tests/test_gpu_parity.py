@@ -457,6 +457,12 @@ def test_config3_resnet50_batch64_sampled_images(B, n_streams):
     _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=8, cal_batch=8, n_streams=n_streams)
 
 
+def test_resnet50_after_sparsity_removal(B):
+    # the paper's graph transformation of the stride-2 stage entries (config 6): strided
+    # 1x1 layers with a residual that a 1x1 stride-2 pooling subsampled
+    _sampled_images_check(B, 6, 16, [0, 7, 8, 15], n_cal=2, cal_batch=8)
+
+
 def test_config4_inception_v3_batch64_sampled_images(B):
     # odd extents (299 -> 149 -> 147 -> 73 -> 71 -> 35 -> 17 -> 8), 1x7 / 7x1 filters,
     # pooled branches, channel-slice writes into concatenations

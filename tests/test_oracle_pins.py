@@ -517,3 +517,36 @@ def test_pool_i8_against_library_and_slices():
     big = np.full((1, 3, 3, 1), 127, np.int8)
     assert orc.pool_i8(big, "max", 3, 3, 1, 0, 1, 1, 2.0)[0, 0, 0, 0] == 127
     assert orc.pool_i8(-big - 1, "avg", 3, 3, 1, 0, 1, 1, 2.0)[0, 0, 0, 0] == -128
+
+
+def test_sparsity_removal_keeps_the_values_that_are_read():
+    """The paper's ResNet graph transformation (the producer of a stride-2 1x1 layer's input
+    computes only the pixels that are read, the skip branch is subsampled by a 1x1 stride-2
+    pooling): with one factor table both graphs give the same codes wherever the
+    transformed graph has a value, and the same network output."""
+    from oracle import net as onet
+    from paper_1805_08691_amd import workloads as wl
+    plain, sparse = wl.resnet50(image=64), wl.resnet50(image=64, sparsity_removal=True)
+    assert [o.name for o in plain.convs()] == [o.name for o in sparse.convs()]
+    assert sparse.macs_per_image() < plain.macs_per_image()
+    params = {op.name: wl.conv_params(3, i, op) for i, op in enumerate(plain.convs())}
+    folded = onet.fold_all(plain, params)
+    q = onet.calibrate(plain, folded, [wl.input_batch(3, plain, 2, 100)])
+    for op in sparse.ops:                         # tensors only the transformed graph has
+        if op.kind == "pool" and op.dst not in q:
+            q[op.dst] = q[op.src]
+    qparams = onet.quantize_params(plain, folded, q)
+    z_in = orc.Q(wl.input_batch(3, plain, 1, 0), q[plain.input], 7)
+    a = onet.forward_i8(plain, qparams, q, z_in)
+    b = onet.forward_i8(sparse, qparams, q, z_in)
+    assert np.array_equal(a[plain.outputs[0]], b[sparse.outputs[0]])
+    halved = 0
+    for name, t in b.items():
+        if name not in a:
+            continue
+        if t.shape == a[name].shape:
+            assert np.array_equal(t, a[name]), name
+        else:
+            assert np.array_equal(t, a[name][:, ::2, ::2]), name
+            halved += 1
+    assert halved == 3
