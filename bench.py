@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--sparsity-removal", action="store_true",
                     help="config 3 only: run the graph after the paper's sparsity-removal "
                          "transformation (reported as its own workload, not the headline)")
+    ap.add_argument("--unsigned-activations", action="store_true",
+                    help="unsigned p = 8 codes on the outputs of ReLU layers (the paper's "
+                         "precision for non-negative tensors); reported as its own workload")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="one eager pass plus one plain 256 MiB device copy, then exit: the "
                          "program to run under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the copy "
@@ -104,7 +107,7 @@ def main():
 
     # ---------------- offline: parameters, fold, calibrate, quantise weights ---------------
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
-    eng = Engine(net, N, n_streams=args.streams)
+    eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -136,7 +139,7 @@ def main():
     def step():
         eng.quantize_input(x)
         eng.run_layers()
-        B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
+        eng.dequantize(out_name, out=out_f32)
 
     step()
     torch.cuda.synchronize()
@@ -175,7 +178,7 @@ def main():
         def serial_step():
             eng.quantize_input(x)
             eng.run_layers(serial=True)
-            B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
+            eng.dequantize(out_name, out=out_f32)
         g1 = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g1):
             serial_step()
@@ -214,7 +217,7 @@ def main():
             for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
                 eng.run_ops([op], lo, n)
             ev[i + 2].record()
-        B.dequantize(eng.act[out_name], eng.q[out_name], out=out_f32)
+        eng.dequantize(out_name, out=out_f32)
         ev[-1].record()
         torch.cuda.synchronize()
         for i in range(len(ops_list) + 2):
@@ -323,12 +326,16 @@ def main():
         folded = onet.fold_all(net, params)
         q = {k: np.float32(v) for k, v in eng.q.items()}
         qparams = onet.quantize_params(net, folded, q)
+        U = onet.unsigned_tensors(net) if args.unsigned_activations else set()
         t0 = time.perf_counter()
         z_in = orc.Q(xs, q[net.input], 7)
-        acts = onet.forward_i8(net, qparams, q, z_in)
-        orc.D(acts[out_name], q[out_name])
+        acts = onet.forward_i8(net, qparams, q, z_in, unsigned=U)
+        (orc.D_u8 if out_name in U else orc.D)(acts[out_name], q[out_name])
         t_cpu = time.perf_counter() - t0
-        same = bool(np.array_equal(acts[out_name], eng.act[out_name][:sample].cpu().numpy()))
+        gpu_out = eng.act[out_name][:sample].cpu().numpy()
+        if out_name in U:
+            gpu_out = (gpu_out.astype(np.int16) + 128).astype(np.uint8)
+        same = bool(np.array_equal(acts[out_name], gpu_out))
         log(f"oracle: {sample} image(s) in {t_cpu:.2f} s on {orc.num_threads()} threads; "
             f"output equals the GPU's: {same}")
         cpu = dict(value=round(sample / t_cpu, 3), unit="images/s", cores=orc.num_threads(),
@@ -336,13 +343,17 @@ def main():
                    matches_gpu=same)
 
     result = {
-        "metric": "ResNet-50 int8 images/sec at batch 64" if args.config == 3 and not args.sparsity_removal
-                  else f"{net.name} int8 images/sec at batch {N}",
+        "metric": "ResNet-50 int8 images/sec at batch 64"
+                  if args.config == 3 and not args.sparsity_removal and not args.unsigned_activations
+                  else f"{net.name}{' (unsigned activations)' if args.unsigned_activations else ''} "
+                       f"int8 images/sec at batch {N}",
         "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{net.name} conv stack, batch {N}, NHWC int8, "
-                               f"{len(convs)} fused convs", "batch": N,
+                               f"{len(convs)} fused convs"
+                               + (", unsigned p=8 ReLU outputs" if args.unsigned_activations else ""),
+                   "batch": N,
                    "launch": "eager" if graph is None else "hip_graph",
                    "streams": eng.n_streams},
         # every convolution's algorithmic ops over the timed step (which also holds the

@@ -136,12 +136,45 @@ int q8_conv_int8(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packe
                  const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
                  void *stream);
 
+/* ---- unsigned activations: the calibration paragraph's p = 8 for non-negative tensors --
+ * An unsigned tensor (the output of a ReLU layer) holds codes 0..255 with q = max/255, one
+ * more bit than the signed p = 7 form.  The matrix instruction multiplies signed bytes, so
+ * a code is STORED as code - 128 (= code XOR 0x80) in an int8 byte; everything below
+ * reads and writes that form.
+ *
+ * q8_quantize_u8 / q8_dequantize_u8: Eq. Q with p = 8 clamped to [0, 255] (the tensor is
+ * non-negative) and Eq. D, on the stored form.
+ *
+ * q8_u8_prepare: for a layer that READS an unsigned tensor, from the dense KRSC int8
+ * filters and the int32 bias (or NULL): tap_sums, int32 [(R+1)*(S+1)][K], the 2-D prefix
+ * sums tap_sums[(r*(S+1)+s)*K + k] = sum_{r'<r, s'<s, c} z_w[k][r'][s'][c], and
+ * bias_eff[k] = bias[k] + 128 * (sum of filter k).  Since sum z_x z_w = sum (z_x - 128) z_w
+ * + 128 * sum z_w, the signed contraction of the stored bytes started at bias_eff equals
+ * Eq. A' on the codes wherever every tap reads inside the image; near the border the
+ * kernel replaces the whole-filter sum by the sum over the taps inside the image (a
+ * rectangle of the filter: four look-ups in tap_sums).  tap_sums 16-byte aligned.
+ *
+ * q8_conv_u8: q8_conv_int8 where the input, the output and the residual may each be an
+ * unsigned tensor (flags).  in_unsigned: pass bias_eff as the bias, and tap_sums if the
+ * layer has padding (else it may be NULL).  out_unsigned needs d->relu; the output is
+ * clamped to [0, 255].  acc_dump receives the accumulators of Eq. A' on the codes.
+ * Main-kernel geometries only (C % 16 == 0, K > 32, R*S <= 32): Q8_EUNSUPPORTED otherwise. */
+int q8_quantize_u8(const float *r_dev, size_t n, float q, int8_t *z_dev, void *stream);
+int q8_dequantize_u8(const int8_t *z_dev, size_t n, float q, float *r_dev, void *stream);
+int q8_u8_prepare(const q8_conv_desc *d, const int8_t *z_w_krsc_dev, const int32_t *bias_i32,
+                  int32_t *tap_sums_dev, int32_t *bias_eff_dev, void *stream);
+int q8_conv_u8(const q8_conv_desc *d, int in_unsigned, int out_unsigned, int res_unsigned,
+               const int8_t *z_x, const void *z_w_packed, const int32_t *bias_eff,
+               const int32_t *tap_sums, float q_x, float q_w, float q_out,
+               const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
+               void *stream);
+
 /* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
  * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.
  * For measurement code that groups launches by kernel.                              */
 const char *q8_conv_variant(const q8_conv_desc *d);
 
-/* Tests and tuning only: force tile/ring variant `index` (0 .. 8, in the order of the
+/* Tests and tuning only: force tile/ring variant `index` (0 .. n-1, in the order of the
  * library's variant table) for every later q8_conv_int8 call whose geometry the main
  * kernel can take (C % 16 == 0, K > 32, R*S <= 32); -1 restores automatic selection.
  * Process-wide, not thread-safe; results are identical for every variant.             */

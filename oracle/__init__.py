@@ -82,6 +82,15 @@ _lib.orc_out_h.restype = C.c_int
 _lib.orc_out_w.restype = C.c_int
 _lib.orc_conv_i8.restype = C.c_int
 _lib.orc_conv_i8.argtypes = [C.POINTER(_Geom), _i8p, _i8p, C.c_void_p, _i32p]
+_u8p = np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")
+_lib.orc_conv_u8.restype = C.c_int
+_lib.orc_conv_u8.argtypes = [C.POINTER(_Geom), _u8p, _i8p, C.c_void_p, _i32p]
+_lib.orc_requant_mixed.restype = None
+_lib.orc_requant_mixed.argtypes = [_i32p, C.c_size_t, C.c_int, C.c_float, C.c_void_p, C.c_int,
+                                   C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_int,
+                                   C.c_int, C.c_int]
+_lib.orc_dequantize_u8.restype = None
+_lib.orc_dequantize_u8.argtypes = [_u8p, C.c_size_t, C.c_float, _f32p]
 _lib.orc_requant_scale.restype = C.c_float
 _lib.orc_requant_scale.argtypes = [C.c_float] * 3
 _lib.orc_residual_scale.restype = C.c_float
@@ -126,6 +135,21 @@ def Q(r, q, p):
     z = np.empty(r.shape, np.int32)
     _lib.orc_quantize(r.ravel(), r.size, np.float32(q), int(p), z.reshape(-1))
     return z.astype(np.int8) if p <= 7 else z
+
+
+def Q_u8(r, q):
+    """Eq. Q with p = 8 on a non-negative tensor, as uint8 codes (negative values, which the
+    clamp would map below zero, are not representable: the caller guarantees r >= 0)."""
+    z = Q(r, q, 8)
+    assert z.min(initial=0) >= 0
+    return z.astype(np.uint8)
+
+
+def D_u8(z, q):
+    z = np.ascontiguousarray(z, dtype=np.uint8)
+    r = np.empty(z.shape, np.float32)
+    _lib.orc_dequantize_u8(z.ravel(), z.size, np.float32(q), r.reshape(-1))
+    return r
 
 
 def Q31_bias(b, q_x, q_w):
@@ -181,6 +205,45 @@ def conv_i8(g, z_x, z_w, z_b=None):
     if rc != 0:
         raise OverflowError("accumulator left the int32 range")
     return acc
+
+
+def conv_u8(g, z_x, z_w, z_b=None):
+    """conv_i8 with unsigned 8-bit activation codes (uint8 array)."""
+    assert z_x.dtype == np.uint8
+    z_x = np.ascontiguousarray(z_x)
+    z_w = np.ascontiguousarray(z_w, dtype=np.int8)
+    ics = g.in_c_stride or g.C
+    assert z_x.size == g.N * g.H * g.W * ics and z_w.size == g.K * g.R * g.S * g.C
+    zb = None if z_b is None else np.ascontiguousarray(z_b, dtype=np.int32)
+    acc = np.empty((g.N, g.Ho, g.Wo, g.K), np.int32)
+    gc = g._c()
+    if _lib.orc_conv_u8(C.byref(gc), z_x.ravel(), z_w.ravel(), _ptr(zb), acc.reshape(-1)) != 0:
+        raise OverflowError("accumulator left the int32 range")
+    return acc
+
+
+def requant_mixed(acc, m, relu, z_res=None, m_r=0.0, out_unsigned=False, out=None,
+                  out_c_off=0):
+    """requant where the residual (by its dtype: uint8 = unsigned codes) and the output
+    (``out_unsigned``) may be unsigned p = 8 codes.  ``out``: [..., C_total] of the matching
+    dtype, written at channels [out_c_off, out_c_off + K)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    K = acc.shape[-1]
+    npix = acc.size // K if K else 0
+    dt = np.uint8 if out_unsigned else np.int8
+    if out is None:
+        out = np.empty(acc.shape, dt)
+    assert out.dtype == dt and out.flags.c_contiguous and out_c_off + K <= out.shape[-1]
+    zr, res_u, rcs = None, 0, 0
+    if z_res is not None:
+        assert z_res.dtype in (np.uint8, np.int8)
+        zr = np.ascontiguousarray(z_res)
+        res_u, rcs = int(zr.dtype == np.uint8), zr.shape[-1]
+        assert zr.size == npix * rcs and rcs >= K
+    _lib.orc_requant_mixed(acc.reshape(-1), npix, K, np.float32(m), _ptr(zr), res_u, rcs, 0,
+                           np.float32(m_r), int(bool(relu)), _ptr(out), int(out_unsigned),
+                           out.shape[-1], out_c_off)
+    return out
 
 
 def requant_scale(q_x, q_w, q_out):

@@ -11,8 +11,8 @@ the factor of the branch's own pre-sum output.
 import numpy as np
 import torch
 
-from . import (ConvGeom, Q, Q31_bias, conv_f32, conv_i8, fold_bn, maxabs, pool_i8, qfactor,
-               requant, requant_scale, residual_scale)
+from . import (ConvGeom, Q, Q31_bias, conv_f32, conv_i8, conv_u8, fold_bn, maxabs, pool_i8,
+               qfactor, requant, requant_mixed, requant_scale, residual_scale)
 
 P_ACT = 7
 P_W = 7
@@ -91,9 +91,31 @@ def forward_f32(net, folded, x, use_library=True):
     return t, pre
 
 
-def calibrate(net, folded, batches, use_library=True):
+def unsigned_tensors(net):
+    """Tensors that hold unsigned p = 8 codes when the calibration paragraph's rule for
+    non-negative activations is applied: outputs of ReLU layers (a fused sum included) and
+    max-poolings of such tensors.  Everything else (the image, outputs without ReLU) stays
+    signed p = 7 (reading: instead of the paper's FP32 fallback)."""
+    u = set()
+    for op in net.ops:
+        if op.kind == "conv":
+            assert net.tensors[op.dst].C == op.K, "unsigned mode: no concatenations"
+            if op.relu:
+                u.add(op.dst)
+        else:
+            assert op.mode == "max" and net.tensors[op.dst].C == net.tensors[op.src].C
+            if op.src in u:
+                u.add(op.dst)
+    return u
+
+
+def calibrate(net, folded, batches, use_library=True, unsigned=None):
     """Running max-abs over ``batches`` (iterable of fp32 NHWC inputs) -> factor table
-    {tensor name: q} plus {conv name + ':branch': q1} for fused sums."""
+    {tensor name: q} plus {conv name + ':branch': q1} for fused sums.
+
+    ``unsigned`` (a set of tensor names): those tensors get q = max / (2^8 - 1); and the
+    output of a fused sum then keeps its OWN calibrated factor (the max(q1, q2) rule of
+    Eq. + presumes equal precisions, which a signed branch and an unsigned output are not)."""
     mx = {}
 
     def upd(key, arr):
@@ -108,10 +130,11 @@ def calibrate(net, folded, batches, use_library=True):
             upd(name, arr)
         for name, arr in pre.items():
             upd(name + ":branch", arr)
-    q = {k: qfactor(v, P_ACT) for k, v in mx.items()}
+    unsigned = unsigned or set()
+    q = {k: qfactor(v, 8 if k in unsigned else P_ACT) for k, v in mx.items()}
     # + rule: a fused sum is re-quantised at max(q1, q2)
     for op in net.ops:
-        if op.kind == "conv" and op.res is not None:
+        if op.kind == "conv" and op.res is not None and not unsigned:
             q[op.dst] = max(q[op.name + ":branch"], q[op.res])
         if op.kind == "pool" and net.tensors[op.dst].C == net.tensors[op.src].C:
             q[op.dst] = q[op.src]          # a stand-alone pool keeps its input's factor
@@ -130,12 +153,41 @@ def quantize_params(net, folded, q):
     return out
 
 
-def forward_i8(net, qparams, q, z_in, keep_acc=False):
-    """int8 forward (Eq. A' per conv).  Returns {tensor: int8 array} (and accumulators)."""
+def _maxpool_u8(x, op, Ho, Wo):
+    """max-pooling of unsigned codes with the library routine (exact on small integers)."""
+    xt = torch.from_numpy(x.astype(np.float32)).permute(0, 3, 1, 2)
+    ceil = Ho != (x.shape[1] + 2 * op.pad - op.R) // op.stride + 1
+    y = torch.nn.functional.max_pool2d(xt, (op.R, op.S), op.stride, op.pad, ceil_mode=ceil)
+    y = y.permute(0, 2, 3, 1).numpy()
+    assert y.shape[1:3] == (Ho, Wo)
+    return np.ascontiguousarray(y.astype(np.uint8))
+
+
+def forward_i8(net, qparams, q, z_in, keep_acc=False, unsigned=None):
+    """int8 forward (Eq. A' per conv).  Returns {tensor: int8 array} (and accumulators).
+    Tensors named in ``unsigned`` are uint8 arrays of p = 8 codes."""
+    unsigned = unsigned or set()
     t = {net.input: z_in}
     accs = {}
     N = z_in.shape[0]
     for op in net.ops:
+        if op.kind == "pool" and op.src in unsigned:
+            d = net.tensors[op.dst]
+            t[op.dst] = _maxpool_u8(t[op.src], op, d.H, d.W)
+            continue
+        if op.kind == "conv" and unsigned:
+            qp = qparams[op.name]
+            g = geom(op, net.tensors, N)
+            conv = conv_u8 if op.src in unsigned else conv_i8
+            acc = conv(g, t[op.src], qp["z_w"], qp["z_b"])
+            if keep_acc:
+                accs[op.name] = acc
+            res, m_r = None, 0.0
+            if op.res is not None:
+                res, m_r = t[op.res], residual_scale(q[op.res], q[op.dst])
+            t[op.dst] = requant_mixed(acc, requant_scale(q[op.src], qp["q_w"], q[op.dst]),
+                                      op.relu, res, m_r, out_unsigned=op.dst in unsigned)
+            continue
         if op.kind == "pool":
             d = net.tensors[op.dst]
             if op.dst not in t:

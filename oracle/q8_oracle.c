@@ -176,6 +176,38 @@ int orc_conv_i8(const orc_conv_geom *g, const int8_t *z_x, const int8_t *z_w,
   return overflow ? -1 : 0;
 }
 
+/* The same contraction with UNSIGNED 8-bit activations (the paper's p = 8 codes of a
+ * non-negative tensor, calibration paragraph): z_x holds the codes 0..255 themselves.  */
+int orc_conv_u8(const orc_conv_geom *g, const uint8_t *z_x, const int8_t *z_w,
+                const int32_t *z_b, int32_t *acc) {
+  const int Ho = orc_out_h(g), Wo = orc_out_w(g);
+  int overflow = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : overflow)
+  for (int n = 0; n < g->N; ++n)
+    for (int ho = 0; ho < Ho; ++ho)
+      for (int wo = 0; wo < Wo; ++wo)
+        for (int k = 0; k < g->K; ++k) {
+          int64_t a = z_b ? (int64_t)z_b[k] : 0;
+          for (int r = 0; r < g->R; ++r) {
+            int hi = ho * g->stride_h - g->pad_h + r * g->dil_h;
+            if (hi < 0 || hi >= g->H) continue;
+            for (int s = 0; s < g->S; ++s) {
+              int wi = wo * g->stride_w - g->pad_w + s * g->dil_w;
+              if (wi < 0 || wi >= g->W) continue;
+              const uint8_t *px =
+                  z_x + (((size_t)n * g->H + hi) * g->W + wi) * g->in_c_stride;
+              const int8_t *pw =
+                  z_w + (((size_t)k * g->R + r) * g->S + s) * g->C;
+              for (int c = 0; c < g->C; ++c)
+                a += (int64_t)((int)px[c] * (int)pw[c]);
+            }
+          }
+          if (a > INT32_MAX || a < INT32_MIN) overflow = 1;
+          acc[(((size_t)n * Ho + ho) * Wo + wo) * g->K + k] = (int32_t)a;
+        }
+  return overflow ? -1 : 0;
+}
+
 /* Scale factors of the epilogue below, formed once per layer in fp32:
  * the accumulator carries q_x*q_w (x rule) and is re-expressed at q_out.   */
 float orc_requant_scale(float q_x, float q_w, float q_out) {
@@ -213,6 +245,42 @@ void orc_requant(const int32_t *acc, size_t npix, int K, float m,
       t = rintf(t);
       z_y[p * out_c_stride + out_c_off + k] = (int8_t)t;
     }
+}
+
+/* The same tail where the residual and / or the output are unsigned p = 8 codes (0..255,
+ * one byte each): an unsigned output is clamped to [0, 2^8 - 1] (Eq. Q with p = 8 on a
+ * value that the ReLU made non-negative); an unsigned residual enters as its code.    */
+void orc_requant_mixed(const int32_t *acc, size_t npix, int K, float m,
+                       const void *z_res, int res_unsigned, int res_c_stride,
+                       int res_c_off, float m_r, int relu, void *z_y,
+                       int out_unsigned, int out_c_stride, int out_c_off) {
+#pragma omp parallel for schedule(static)
+  for (size_t p = 0; p < npix; ++p)
+    for (int k = 0; k < K; ++k) {
+      float t = (float)acc[p * K + k];
+      t = t * m;
+      if (z_res) {
+        size_t i = p * res_c_stride + res_c_off + k;
+        float u = res_unsigned ? (float)((const uint8_t *)z_res)[i]
+                               : (float)((const int8_t *)z_res)[i];
+        u = u * m_r;
+        t = t + u;
+      }
+      if (relu) t = t > 0.0f ? t : 0.0f;
+      const float hi = out_unsigned ? 255.0f : 127.0f;
+      const float lo = out_unsigned ? 0.0f : -128.0f;
+      if (t > hi) t = hi;
+      if (t < lo) t = lo;
+      t = rintf(t);
+      size_t o = p * out_c_stride + out_c_off + k;
+      if (out_unsigned) ((uint8_t *)z_y)[o] = (uint8_t)t;
+      else ((int8_t *)z_y)[o] = (int8_t)t;
+    }
+}
+
+/* Eq. D on unsigned codes. */
+void orc_dequantize_u8(const uint8_t *z, size_t n, float q, float *r) {
+  for (size_t i = 0; i < n; ++i) r[i] = (float)z[i] * q;
 }
 
 /* fp32 view of the same layer before quantisation, used only to calibrate

@@ -22,7 +22,8 @@ lib = C.CDLL(LIB_PATH)
 
 EXPORTS = [
     "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
-    "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_image", "q8_quantize_bias", "q8_dequantize",
+    "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_image", "q8_quantize_bias", "q8_quantize_u8", "q8_dequantize_u8",
+    "q8_u8_prepare", "q8_conv_u8", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_variant", "q8_conv_force_variant",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
@@ -77,6 +78,10 @@ lib.q8_packed_weight_bytes.restype = _sz
 lib.q8_packed_weight_bytes.argtypes = [_dp]
 lib.q8_pack_weights.argtypes = [_dp, _vp, _vp, _vp]
 lib.q8_conv_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
+lib.q8_conv_u8.argtypes = [_dp, _i, _i, _i, _vp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
+lib.q8_u8_prepare.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
+lib.q8_quantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
+lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
 lib.q8_conv_variant.argtypes = [_dp]
 lib.q8_conv_force_variant.argtypes = [_i]
@@ -192,6 +197,44 @@ def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q
                             _ptr(bias_i32, torch.int32), q_x, q_w, q_out,
                             _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
                             _ptr(acc_dump, torch.int32), _stream()))
+    return out
+
+
+def quantize_u8(r, q, out=None):
+    """Eq. Q, p = 8, on a non-negative tensor; codes stored as code - 128."""
+    z = torch.empty(r.shape, dtype=torch.int8, device=r.device) if out is None else out
+    _check(lib.q8_quantize_u8(_ptr(r, torch.float32), r.numel(), q, _ptr(z, torch.int8), _stream()))
+    return z
+
+
+def dequantize_u8(z, q, out=None):
+    r = torch.empty(z.shape, dtype=torch.float32, device=z.device) if out is None else out
+    _check(lib.q8_dequantize_u8(_ptr(z, torch.int8), z.numel(), q, _ptr(r, torch.float32),
+                                _stream()))
+    return r
+
+
+def u8_prepare(desc, z_w, bias_i32=None):
+    """-> (tap_sums int32 [(R+1)*(S+1), K] prefix sums, bias_eff int32 [K]) for a layer
+    reading unsigned codes."""
+    taps = torch.empty(((desc.R + 1) * (desc.S + 1), desc.K), dtype=torch.int32,
+                       device=z_w.device)
+    beff = torch.empty(desc.K, dtype=torch.int32, device=z_w.device)
+    _check(lib.q8_u8_prepare(C.byref(desc), _ptr(z_w, torch.int8), _ptr(bias_i32, torch.int32),
+                             _ptr(taps, torch.int32), _ptr(beff, torch.int32), _stream()))
+    return taps, beff
+
+
+def conv_u8(desc, in_u8, out_u8, res_u8, z_x, z_w_packed, bias, tap_sums, q_x, q_w, q_out,
+            residual=None, q_res=0.0, out=None, acc_dump=None):
+    if out is None:
+        ocs = desc.out_c_stride or desc.K
+        out = torch.empty((desc.N, desc.Ho, desc.Wo, ocs), dtype=torch.int8, device=z_x.device)
+    _check(lib.q8_conv_u8(C.byref(desc), int(in_u8), int(out_u8), int(res_u8),
+                          _ptr(z_x, torch.int8), _ptr(z_w_packed, torch.int8),
+                          _ptr(bias, torch.int32), _ptr(tap_sums, torch.int32), q_x, q_w, q_out,
+                          _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
+                          _ptr(acc_dump, torch.int32), _stream()))
     return out
 
 

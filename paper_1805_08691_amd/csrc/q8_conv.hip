@@ -157,10 +157,19 @@ int q8_pack_weights(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, void* pac
   return q8_launch_status();
 }
 
-int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
-                 const int32_t* bias_i32, float q_x, float q_w, float q_out,
-                 const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
-                 void* stream) {
+}  // extern "C"
+
+namespace {
+
+struct U8Flags {
+  int in_u8, out_u8, res_u8;
+  const int32_t* tap_sums;
+};
+
+int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
+                const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+                void* stream) {
   Q8_REQUIRE(desc_sane(d), Q8_EINVAL);
   Q8_REQUIRE(q8_finite_pos(q_x) && q8_finite_pos(q_w) && q8_finite_pos(q_out), Q8_EINVAL);
   Q8_REQUIRE(residual == nullptr || q8_finite_pos(q_res), Q8_EINVAL);
@@ -213,6 +222,21 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
   p.x = z_x; p.w = (const int8_t*)z_w_packed; p.bias = bias_i32; p.res = residual; p.y = z_y;
   p.acc_dump = acc_dump;
   p.M = (int)M;
+  p.in_u8 = u.in_u8; p.out_u8 = u.out_u8; p.res_u8 = u.res_u8;
+  p.tap_sums = u.tap_sums;
+  if (u.in_u8 || u.out_u8 || u.res_u8) {
+    // unsigned codes: the streaming kernel only; an unsigned input whose taps can fall into
+    // the padding needs the per-tap filter sums; an unsigned output is a ReLU output
+    Q8_REQUIRE(stream_capable(d) && (mode == 0 || !u.in_u8), Q8_EUNSUPPORTED);
+    Q8_REQUIRE(!u.out_u8 || d->relu, Q8_EINVAL);
+    Q8_REQUIRE(!u.res_u8 || residual, Q8_EINVAL);
+    if (u.in_u8 && (d->pad_h || d->pad_w)) {
+      Q8_REQUIRE(u.tap_sums != nullptr, Q8_EINVAL);
+      Q8_REQUIRE(q8_aligned(u.tap_sums, 16), Q8_EALIGN);
+    } else {
+      p.tap_sums = nullptr;          // every tap reads inside the image
+    }
+  }
   {
     const q8::FastDiv img = q8::make_fast_div((unsigned)(p.Ho * p.Wo));
     const q8::FastDiv row = q8::make_fast_div((unsigned)p.Wo);
@@ -237,6 +261,62 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
   const int variant = pick_variant(d);
   if (variant >= kRegBase) return q8::launch_reg_variant(variant - kRegBase, p, s);
   return q8::launch_stream_variant(variant, p, s);
+}
+
+// tap_sums[(r*(S+1) + s)*K + k] = sum over r' < r, s' < s and c of z_w[k][r'][s'][c] (2-D
+// prefix sums of the per-tap filter sums); bias_eff[k] = bias[k] + 128 * (sum of the filter)
+__global__ void u8_prepare_kernel(const int8_t* __restrict__ w, const int32_t* __restrict__ bias,
+                                  int K, int R, int S, int C, int32_t* __restrict__ tap_sums,
+                                  int32_t* __restrict__ bias_eff) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= K) return;
+  const int w1 = S + 1;
+  for (int s = 0; s <= S; ++s) tap_sums[(size_t)s * K + k] = 0;
+  for (int r = 1; r <= R; ++r) {
+    tap_sums[(size_t)(r * w1) * K + k] = 0;
+    int row = 0;                                   // sum of filter row r-1 up to column s
+    for (int s = 1; s <= S; ++s) {
+      const int8_t* tap = w + (((size_t)k * R + (r - 1)) * S + (s - 1)) * C;
+      int sum = 0;
+      for (int c = 0; c < C; ++c) sum += tap[c];
+      row += sum;
+      tap_sums[(size_t)(r * w1 + s) * K + k] = tap_sums[(size_t)((r - 1) * w1 + s) * K + k] + row;
+    }
+  }
+  bias_eff[k] = (bias ? bias[k] : 0) + 128 * tap_sums[(size_t)(R * w1 + S) * K + k];
+}
+
+}  // namespace
+
+extern "C" {
+
+int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                 const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                 const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+                 void* stream) {
+  return conv_launch(d, U8Flags{0, 0, 0, nullptr}, z_x, z_w_packed, bias_i32, q_x, q_w, q_out,
+                     residual, q_res, z_y, acc_dump, stream);
+}
+
+int q8_conv_u8(const q8_conv_desc* d, int in_unsigned, int out_unsigned, int res_unsigned,
+               const int8_t* z_x, const void* z_w_packed, const int32_t* bias_eff,
+               const int32_t* tap_sums, float q_x, float q_w, float q_out,
+               const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+               void* stream) {
+  Q8_REQUIRE(!in_unsigned || bias_eff != nullptr, Q8_EINVAL);
+  return conv_launch(d, U8Flags{in_unsigned ? 1 : 0, out_unsigned ? 1 : 0, res_unsigned ? 1 : 0,
+                                tap_sums},
+                     z_x, z_w_packed, bias_eff, q_x, q_w, q_out, residual, q_res, z_y, acc_dump,
+                     stream);
+}
+
+int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32_t* bias_i32,
+                  int32_t* tap_sums_dev, int32_t* bias_eff_dev, void* stream) {
+  Q8_REQUIRE(desc_sane(d) && z_w_krsc_dev && tap_sums_dev && bias_eff_dev, Q8_EINVAL);
+  Q8_REQUIRE(conv_mode(d) == 0, Q8_EUNSUPPORTED);
+  hipLaunchKernelGGL(u8_prepare_kernel, dim3((d->K + 63) / 64), dim3(64), 0, (hipStream_t)stream,
+                     z_w_krsc_dev, bias_i32, d->K, d->R, d->S, d->C, tap_sums_dev, bias_eff_dev);
+  return q8_launch_status();
 }
 
 int q8_conv_force_variant(int index) {

@@ -33,6 +33,11 @@ struct ConvParams {
   int x_bytes, w_bytes;   // sizes of the activation and filter tensors (buffer descriptors)
   unsigned div_img_m, div_img_s;   // division of a pixel index by Ho*Wo (see fast_div)
   unsigned div_row_m, div_row_s;   // division by Wo
+  // unsigned p = 8 activation codes (0..255), stored as code - 128 (= code ^ 0x80) so that
+  // the signed MFMA can take them: the input offset is undone through the bias (+128 times
+  // the filter sum, folded by the host) and, for taps outside the image, through tap_sums
+  const int32_t* __restrict__ tap_sums;   // [(R+1)*(S+1)][K] prefix sums of the filter, or null
+  int in_u8, out_u8, res_u8;
   float m, m_r;
   int relu;
   int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
@@ -66,6 +71,66 @@ __device__ __forceinline__ unsigned bits_below(int k) {
 // so the epilogue needs one 16-byte residual load and one 16-byte store per lane.
 __device__ __forceinline__ int row_to_channel(int row) {
   return (((row >> 2) & 1) << 4) | ((row >> 3) << 2) | (row & 3);
+}
+
+// Unsigned input codes are stored minus 128 and the host has added 128 * (sum of the whole
+// filter) to the bias, which is right where every tap reads inside the image.  A tap in
+// the padding contributes nothing to Eq. A' (the stored zero the kernel reads there stands
+// for code 128, not 0), so for a pixel near the border the sum over the taps INSIDE the
+// image has to replace the sum over all taps.  The taps inside form a rectangle
+// [r_lo, r_hi) x [s_lo, s_hi) of the filter, so that sum is four look-ups in a table of
+// 2-D prefix sums: tap_sums[(r*(S+1) + s)*K + k] = sum_{r' < r, s' < s, c} z_w[k][r'][s'][c].
+constexpr int kNoBorderFix = -1;
+
+// The rectangle of taps inside the image for output pixel `pix`, packed as
+// r_lo | r_hi << 8 | s_lo << 16 | s_hi << 24, or kNoBorderFix if it is the whole filter.
+__device__ __forceinline__ int u8_border_rect(const ConvParams& p, int pix) {
+  if (pix >= p.M) return kNoBorderFix;
+  const int n = fast_div(pix, p.div_img_m, p.div_img_s);
+  const int rem = pix - n * (p.Ho * p.Wo);
+  const int ho = fast_div(rem, p.div_row_m, p.div_row_s);
+  const int wo = rem - ho * p.Wo;
+  const int hi0 = ho * p.stride_h - p.pad_h;
+  const int wi0 = wo * p.stride_w - p.pad_w;
+  int r_lo = p.R, r_hi = 0, s_lo = p.S, s_hi = 0;
+  for (int r = 0; r < p.R; ++r)
+    if ((unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H) { r_lo = min(r_lo, r); r_hi = r + 1; }
+  for (int s2 = 0; s2 < p.S; ++s2)
+    if ((unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) { s_lo = min(s_lo, s2); s_hi = s2 + 1; }
+  if (r_hi <= r_lo || s_hi <= s_lo) r_lo = r_hi = s_lo = s_hi = 0;     // nothing inside
+  if (r_lo == 0 && r_hi == p.R && s_lo == 0 && s_hi == p.S) return kNoBorderFix;
+  return r_lo | (r_hi << 8) | (s_lo << 16) | (s_hi << 24);
+}
+
+// v += 128 * (sum over the rectangle - sum over the whole filter) for channels [ch, ch+16).
+// FULL: all 16 channels exist and K % 4 == 0 (16-byte loads).
+template <bool FULL>
+__device__ __forceinline__ void u8_border_apply(const ConvParams& p, int rect, int ch,
+                                                int (&v)[16]) {
+  const int nvalid = p.K - ch;
+  const int r_lo = rect & 0xff, r_hi = (rect >> 8) & 0xff, s_lo = (rect >> 16) & 0xff,
+            s_hi = (rect >> 24) & 0xff;
+  const int w1 = p.S + 1;
+  const int32_t* t_hh = p.tap_sums + (size_t)(r_hi * w1 + s_hi) * p.K + ch;
+  const int32_t* t_lh = p.tap_sums + (size_t)(r_lo * w1 + s_hi) * p.K + ch;
+  const int32_t* t_hl = p.tap_sums + (size_t)(r_hi * w1 + s_lo) * p.K + ch;
+  const int32_t* t_ll = p.tap_sums + (size_t)(r_lo * w1 + s_lo) * p.K + ch;
+  const int32_t* t_all = p.tap_sums + (size_t)(p.R * w1 + p.S) * p.K + ch;
+  if (FULL) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const v4i hh = *reinterpret_cast<const v4i*>(t_hh + 4 * a);
+      const v4i lh = *reinterpret_cast<const v4i*>(t_lh + 4 * a);
+      const v4i hl = *reinterpret_cast<const v4i*>(t_hl + 4 * a);
+      const v4i ll = *reinterpret_cast<const v4i*>(t_ll + 4 * a);
+      const v4i al = *reinterpret_cast<const v4i*>(t_all + 4 * a);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[4 * a + k] += 128 * (hh[k] - lh[k] - hl[k] + ll[k] - al[k]);
+    }
+  } else {
+    for (int e = 0; e < 16; ++e)
+      if (e < nvalid) v[e] += 128 * (t_hh[e] - t_lh[e] - t_hl[e] + t_ll[e] - t_all[e]);
+  }
 }
 
 // ---- Epilogue pieces, all for 16 consecutive channels [ch, ch+16) of one pixel ------------
@@ -135,19 +200,23 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
 #pragma unroll
   for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * p.m;
   if (p.res) {
+    const int res_add = p.res_u8 ? 128 : 0;        // stored byte + 128 = unsigned code
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      float u = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) * p.m_r;
+      const int code = (int)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) + res_add;
+      float u = (float)code * p.m_r;
       t[e] = t[e] + u;
     }
   }
+  const float lo = p.out_u8 ? 0.0f : -128.0f, hi = p.out_u8 ? 255.0f : 127.0f;
+  const int out_sub = p.out_u8 ? 128 : 0;          // unsigned code - 128 = stored byte
   unsigned zw[4] = {0, 0, 0, 0};
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     float u = t[e];
     if (p.relu) u = fmaxf(u, 0.0f);
-    u = fminf(fmaxf(u, -128.0f), 127.0f);
-    zw[e >> 2] |= ((unsigned)((int)rintf(u)) & 0xffu) << (8 * (e & 3));
+    u = fminf(fmaxf(u, lo), hi);
+    zw[e >> 2] |= ((unsigned)((int)rintf(u) - out_sub) & 0xffu) << (8 * (e & 3));
   }
   int8_t* o = p.y + (size_t)pix * p.out_cs + p.out_off + ch;
   if (full && p.vec16) {
@@ -172,27 +241,37 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
 // ReLU + clamp, and Round by adding 1.5 * 2^23 -- for |t| <= 128 the fp32 sum is the
 // round-half-to-even integer and its low byte is the two's-complement int8 code -- then
 // byte permutes to pack four codes per word.  Bit-identical to finish16.
-template <bool HAS_RES>
+// U8: the output may be unsigned codes stored minus 128 (run-time flag: a different clamp
+// and one XOR per packed word); RES_U8: the residual holds such codes.
+template <bool HAS_RES, bool U8 = false, bool RES_U8 = false>
 __device__ __forceinline__ void finish16_fast(const ConvParams& p, int pix, int ch,
                                               const int (&v)[16], const int (&rw)[4]) {
-  const float lo = p.relu ? 0.0f : -128.0f;     // ReLU folded into the lower clamp bound
+  const bool out_u8 = U8 && p.out_u8;
+  const float lo = (p.relu || out_u8) ? 0.0f : -128.0f;   // ReLU folded into the lower bound
+  const float hi = out_u8 ? 255.0f : 127.0f;
   unsigned r[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     float t = (float)v[e] * p.m;
     if (HAS_RES) {
-      const float u = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff) * p.m_r;
+      float code;
+      if (RES_U8)      // stored byte ^ 0x80 = the unsigned code: one unsigned byte convert
+        code = (float)(uint8_t)((((unsigned)rw[e >> 2] ^ 0x80808080u) >> (8 * (e & 3))) & 0xffu);
+      else
+        code = (float)(int8_t)((rw[e >> 2] >> (8 * (e & 3))) & 0xff);
+      const float u = code * p.m_r;
       t = t + u;
     }
-    t = __builtin_amdgcn_fmed3f(t, lo, 127.0f);
-    r[e] = __float_as_uint(t + 12582912.0f);
+    t = __builtin_amdgcn_fmed3f(t, lo, hi);
+    r[e] = __float_as_uint(t + 12582912.0f);      // low byte = the code (0..255 or int8)
   }
+  const unsigned flip = out_u8 ? 0x80808080u : 0u;   // code - 128 = code ^ 0x80 in a byte
   v4i out;
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
     const unsigned w01 = __builtin_amdgcn_perm(r[4 * a + 1], r[4 * a], 0x0c0c0400u);
     const unsigned w23 = __builtin_amdgcn_perm(r[4 * a + 3], r[4 * a + 2], 0x0c0c0400u);
-    out[a] = (int)__builtin_amdgcn_perm(w23, w01, 0x05040100u);
+    out[a] = (int)(__builtin_amdgcn_perm(w23, w01, 0x05040100u) ^ flip);
   }
   *reinterpret_cast<v4i*>(p.y + (size_t)pix * p.out_cs + p.out_off + ch) = out;
 }

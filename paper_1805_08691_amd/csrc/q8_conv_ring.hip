@@ -28,7 +28,10 @@ namespace {
 
 constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
 
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
+// U8 = 1: the build of the kernel that also handles unsigned activation codes (border
+// correction, unsigned residual / output); kept apart so that the signed build's register
+// count, and with it the number of resident wavefronts, stays what it is.
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8>
 __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
                                       // descriptor types exist for the device target alone
@@ -201,14 +204,39 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   // These loads are issued before any stage load, so the in-order vmcnt bookkeeping of
   // the ring is unaffected, and their latency hides behind the first stages.
   v16i acc[TC][TP];
+  // Unsigned input codes (stored minus 128): a pixel whose taps partly fall into the padding
+  // starts from a corrected value (see u8_border_apply); the look-ups ride along with the
+  // bias loads, ahead of the first stage.
+  int rect[TP];
+  bool any_fix = false;
+  if constexpr (U8) {
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+      rect[j] = kNoBorderFix;
+      if (p.tap_sums) rect[j] = u8_border_rect(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31));
+      any_fix = any_fix || __any(rect[j] != kNoBorderFix);
+    }
+  }
+  const bool full_ctile = ch0 + BC <= p.K && (p.K & 3) == 0;
 #pragma unroll
   for (int i = 0; i < TC; ++i) {
     int b[16];
-    load_bias16(p, ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
+    const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+    load_bias16(p, ch, b);
 #pragma unroll
-    for (int j = 0; j < TP; ++j)
+    for (int j = 0; j < TP; ++j) {
+      int v[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = b[v];
+      for (int e = 0; e < 16; ++e) v[e] = b[e];
+      if constexpr (U8) {
+        if (any_fix && rect[j] != kNoBorderFix && ch < p.K) {
+          if (full_ctile) u8_border_apply<true>(p, rect[j], ch, v);
+          else u8_border_apply<false>(p, rect[j], ch, v);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = v[e];
+    }
   }
   const int nk = (p.red_len + BK - 1) / BK;
   const int frag_row = lane & 31;
@@ -364,7 +392,9 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
   const bool fast_tile = p.vec16 && !p.acc_dump && ch0 + BC <= p.K && pix0 + BP <= p.M;
   auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
-    constexpr int MODE = decltype(mode_c)::value;     // 0 general, 1 fast, 2 fast + residual
+    // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
+    // residual, signed residual, unsigned residual)
+    constexpr int MODE = decltype(mode_c)::value;
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
       const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
@@ -377,20 +407,22 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 #pragma unroll
         for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
         if constexpr (MODE == 0) finish16(p, pix, ch, v, res_w[i][j]);
-        else finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j]);
+        else if constexpr (MODE <= 2) finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j]);
+        else finish16_fast<MODE >= 4, true, MODE == 5>(p, pix, ch, v, res_w[i][j]);
       }
     }
   };
   if (!fast_tile) finish_all(std::integral_constant<int, 0>{});
-  else if (p.res) finish_all(std::integral_constant<int, 2>{});
-  else finish_all(std::integral_constant<int, 1>{});
+  else if (!p.res) finish_all(std::integral_constant<int, U8 ? 3 : 1>{});
+  else if (U8 && p.res_u8) finish_all(std::integral_constant<int, 5>{});
+  else finish_all(std::integral_constant<int, U8 ? 4 : 2>{});
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM>
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8>
 int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
   constexpr int kLdsBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
-  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM>;
+  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8>;
   if constexpr (kLdsBytes > 65536) {
     // more than 64 KB of LDS per workgroup has to be requested once per kernel
     static const hipError_t attr = hipFuncSetAttribute(
@@ -401,7 +433,7 @@ int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
   return q8_launch_status();
 }
 
-template <int WP, int WC, int TP, int TC, int BK, int STAGES>
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int U8>
 int launch_ring(ConvParams& p, hipStream_t stream) {
   constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
   p.n_ptiles = (p.M + BP - 1) / BP;
@@ -409,17 +441,21 @@ int launch_ring(ConvParams& p, hipStream_t stream) {
   long nblk = (long)p.n_ptiles * p.n_ctiles;
   if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
   if (p.C % BK == 0)
-    return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1>(p, dim3((unsigned)nblk), stream);
-  return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 0>(p, dim3((unsigned)nblk), stream);
+    return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1, U8>(p, dim3((unsigned)nblk), stream);
+  return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 0, U8>(p, dim3((unsigned)nblk), stream);
 }
 
 struct RingVariant {
   const char* name;
   int (*launch)(ConvParams&, hipStream_t);
+  int (*launch_u8)(ConvParams&, hipStream_t);    // null: no unsigned-code build of this one
 };
 #define Q8_RING_VARIANT(WP, WC, TP, TC, BK, ST) \
   { "conv_i8_ring_kernel<" #WP "," #WC "," #TP "," #TC "," #BK "," #ST ">", \
-    &launch_ring<WP, WC, TP, TC, BK, ST> }
+    &launch_ring<WP, WC, TP, TC, BK, ST, 0>, &launch_ring<WP, WC, TP, TC, BK, ST, 1> }
+#define Q8_RING_SIGNED(WP, WC, TP, TC, BK, ST) \
+  { "conv_i8_ring_kernel<" #WP "," #WC "," #TP "," #TC "," #BK "," #ST ">", \
+    &launch_ring<WP, WC, TP, TC, BK, ST, 0>, nullptr }
 // pixels x channels per tile = (WP*TP*32) x (WC*TC*32); BK bytes per step; ring depth
 const RingVariant kRingVariants[] = {
     Q8_RING_VARIANT(2, 2, 2, 2, 64, 2),    //  0: 128 x 128
@@ -434,13 +470,13 @@ const RingVariant kRingVariants[] = {
     Q8_RING_VARIANT(2, 2, 2, 1, 64, 4),    //  9
     Q8_RING_VARIANT(2, 4, 2, 1, 64, 3),    // 10: 128 x 128, eight wavefronts of 64 x 32
     Q8_RING_VARIANT(2, 4, 2, 1, 64, 4),    // 11
-    Q8_RING_VARIANT(4, 2, 1, 2, 64, 3),    // 12: 128 x 128, eight wavefronts of 32 x 64
-    Q8_RING_VARIANT(4, 2, 2, 2, 64, 3),    // 13: 256 x 128, eight wavefronts of 64 x 64
-    Q8_RING_VARIANT(2, 4, 2, 2, 64, 3),    // 14: 128 x 256, eight wavefronts of 64 x 64
-    Q8_RING_VARIANT(2, 2, 2, 2, 64, 6),    // 15: 128 x 128, deep rings for one workgroup per CU
-    Q8_RING_VARIANT(2, 2, 2, 2, 64, 8),    // 16
-    Q8_RING_VARIANT(2, 4, 2, 1, 64, 8),    // 17: the same with eight wavefronts
-    Q8_RING_VARIANT(2, 2, 2, 1, 64, 8),    // 18: 128 x 64, deep ring
+    Q8_RING_SIGNED (4, 2, 1, 2, 64, 3),    // 12: 128 x 128, eight wavefronts of 32 x 64
+    Q8_RING_SIGNED (4, 2, 2, 2, 64, 3),    // 13: 256 x 128, eight wavefronts of 64 x 64
+    Q8_RING_SIGNED (2, 4, 2, 2, 64, 3),    // 14: 128 x 256, eight wavefronts of 64 x 64
+    Q8_RING_SIGNED (2, 2, 2, 2, 64, 6),    // 15: 128 x 128, deep rings for one workgroup per CU
+    Q8_RING_SIGNED (2, 2, 2, 2, 64, 8),    // 16
+    Q8_RING_SIGNED (2, 4, 2, 1, 64, 8),    // 17: the same with eight wavefronts
+    Q8_RING_SIGNED (2, 2, 2, 1, 64, 8),    // 18: 128 x 64, deep ring
 };
 constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]);
 
@@ -449,6 +485,11 @@ constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]
 int num_stream_variants() { return kNumRingVariants; }
 int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
   if (variant < 0 || variant >= kNumRingVariants) return Q8_EINVAL;
+  if (p.in_u8 | p.out_u8 | p.res_u8) {
+    // variants without an unsigned-code build fall back to the 128 x 128 ring of 3
+    const RingVariant& v = kRingVariants[variant].launch_u8 ? kRingVariants[variant] : kRingVariants[1];
+    return v.launch_u8(p, stream);
+  }
   return kRingVariants[variant].launch(p, stream);
 }
 const char* stream_variant_name(int variant) {

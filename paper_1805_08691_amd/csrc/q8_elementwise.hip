@@ -222,6 +222,23 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const int8_t* __re
   }
 }
 
+// Unsigned p = 8 codes (0..255) are kept as code - 128 in an int8 byte.
+__global__ __launch_bounds__(kThreads) void quantize_u8_kernel(const float* __restrict__ r,
+                                                               size_t n, float q,
+                                                               int8_t* __restrict__ z) {
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += nthreads)
+    z[i] = (int8_t)(quant1(r[i], q, 0.0f, 255.0f) - 128);
+}
+
+__global__ __launch_bounds__(kThreads) void dequantize_u8_kernel(const int8_t* __restrict__ z,
+                                                                 size_t n, float q,
+                                                                 float* __restrict__ r) {
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += nthreads)
+    r[i] = __fmul_rn(q, (float)((int)z[i] + 128));
+}
+
 __global__ __launch_bounds__(kThreads) void dequantize_vec_kernel(const int8_t* __restrict__ z,
                                                                   size_t n4, float q,
                                                                   float4* __restrict__ r) {
@@ -394,6 +411,26 @@ int q8_dequantize(const int8_t* z_dev, size_t n, float q, float* r_dev, void* st
   if (head > n) head = n;
   hipLaunchKernelGGL(dequantize_kernel, dim3(blocks_for((n + 3) / 4)), dim3(kThreads), 0,
                      (hipStream_t)stream, z_dev, n, head, q, r_dev);
+  return q8_launch_status();
+}
+
+int q8_quantize_u8(const float* r_dev, size_t n, float q, int8_t* z_dev, void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q), Q8_EINVAL);
+  if (n == 0) return Q8_OK;
+  Q8_REQUIRE(r_dev != nullptr && z_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(r_dev, 4), Q8_EALIGN);
+  hipLaunchKernelGGL(quantize_u8_kernel, dim3(blocks_for(n)), dim3(kThreads), 0,
+                     (hipStream_t)stream, r_dev, n, q, z_dev);
+  return q8_launch_status();
+}
+
+int q8_dequantize_u8(const int8_t* z_dev, size_t n, float q, float* r_dev, void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q), Q8_EINVAL);
+  if (n == 0) return Q8_OK;
+  Q8_REQUIRE(z_dev != nullptr && r_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(r_dev, 4), Q8_EALIGN);
+  hipLaunchKernelGGL(dequantize_u8_kernel, dim3(blocks_for(n)), dim3(kThreads), 0,
+                     (hipStream_t)stream, z_dev, n, q, r_dev);
   return q8_launch_status();
 }
 

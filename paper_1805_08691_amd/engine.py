@@ -30,8 +30,23 @@ class Engine:
     again before forward() returns.  A layer's launch latency and its tail then overlap the
     other half's work.  Results are the same bits as with one stream."""
 
-    def __init__(self, net, batch, device="cuda", n_streams=1):
+    def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False):
         self.net = net
+        # Unsigned p = 8 codes for the outputs of ReLU layers (the calibration paragraph's
+        # rule for non-negative tensors) and for max-poolings of such tensors; stored as
+        # code - 128.  Everything else stays signed p = 7.
+        self.unsigned = set()
+        if unsigned_activations:
+            for o in net.ops:
+                if o.kind == "conv":
+                    assert net.tensors[o.dst].C == o.K, "unsigned mode: no concatenations"
+                    if o.relu:
+                        self.unsigned.add(o.dst)
+                else:
+                    assert o.mode == "max" and net.tensors[o.dst].C == net.tensors[o.src].C
+                    if o.src in self.unsigned:
+                        self.unsigned.add(o.dst)
+        self.taps = {}        # conv name -> per-tap filter sums (layers reading unsigned codes)
         self.N = batch
         self.dev = torch.device(device)
         assert n_streams in (1, 2)
@@ -147,9 +162,10 @@ class Engine:
             self.forward_f32(x, observe)
         keys = list(slots)
         vals = torch.cat([slots[k] for k in keys]).cpu().numpy()
-        q = {k: B.qfactor(float(v), P_ACT) for k, v in zip(keys, vals)}
+        q = {k: B.qfactor(float(v), 8 if k in self.unsigned else P_ACT)
+             for k, v in zip(keys, vals)}
         for op in self.net.ops:
-            if op.kind == "conv" and op.res is not None:
+            if op.kind == "conv" and op.res is not None and not self.unsigned:
                 q[op.dst] = max(q[op.name + ":branch"], q[op.res])   # the + rule
             if op.kind == "pool" and self.net.tensors[op.dst].C == self.net.tensors[op.src].C:
                 q[op.dst] = q[op.src]       # a stand-alone pool keeps its input's factor
@@ -175,8 +191,10 @@ class Engine:
             z_w = B.quantize(Wf, q_w, P_W)
             self.zw_dense[name] = z_w
             self.qw[name] = q_w
-            self.wq[name] = (B.pack_weights(self.desc[name], z_w),
-                             B.quantize_bias(bf, self.q[op.src], q_w))
+            bias = B.quantize_bias(bf, self.q[op.src], q_w)
+            if op.src in self.unsigned:
+                self.taps[name], bias = B.u8_prepare(self.desc[name], z_w, bias)
+            self.wq[name] = (B.pack_weights(self.desc[name], z_w), bias)
 
     # ------------------------------------------------------------------ online step
     def allocate(self):
@@ -235,6 +253,13 @@ class Engine:
         packed, bias = self.wq[op.name]
         res = self.act[op.res][lo:lo + n] if op.res else None
         q_res = self.q[op.res] if op.res else 0.0
+        U = self.unsigned
+        if op.src in U or op.dst in U or op.res in U:
+            B.conv_u8(self.conv_desc(op, n), op.src in U, op.dst in U, op.res in U,
+                      self.act[op.src][lo:lo + n], packed, bias, self.taps.get(op.name),
+                      self.q[op.src], self.qw[op.name], self.q[op.dst], res, q_res,
+                      out=self.act[op.dst][lo:lo + n], acc_dump=acc_dump)
+            return
         B.conv_int8(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed, bias,
                     self.q[op.src], self.qw[op.name], self.q[op.dst], res, q_res,
                     out=self.act[op.dst][lo:lo + n], acc_dump=acc_dump)
@@ -272,6 +297,11 @@ class Engine:
             self.run_ops(ops[self.n_unsplit:], *self.parts[1])
         self.run_ops(ops[self.n_unsplit:], *self.parts[0])
         main.wait_stream(self.side)
+
+    def dequantize(self, name, out=None):
+        """Eq. D on tensor ``name`` (signed or unsigned codes)."""
+        fn = B.dequantize_u8 if name in self.unsigned else B.dequantize
+        return fn(self.act[name], self.q[name], out=out)
 
     def forward(self, x):
         """x: fp32 NHWC device tensor of the network input.  Returns the int8 outputs."""

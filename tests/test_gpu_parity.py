@@ -251,6 +251,100 @@ def test_conv_image_in_zero_frame(B, geom):
     assert np.array_equal(host(got), want)
 
 
+# ------------------------------------------------------------------ unsigned activations
+def _stored(u8):
+    """unsigned codes -> the stored form (code - 128 in an int8 byte)."""
+    return (u8.astype(np.int16) - 128).astype(np.int8)
+
+
+def test_quantize_dequantize_u8(B):
+    rng = np.random.default_rng(81)
+    r = np.abs(rng.standard_normal(100_003)).astype(np.float32) * 3
+    r[:4] = [0.0, 1e-9, 1e9, 2.5]
+    q = orc.qfactor(np.float32(9.0), 8)              # some values saturate at 255
+    want = orc.Q_u8(r, q)
+    got = host(B.quantize_u8(dev(r), float(q)))
+    assert np.array_equal(got, _stored(want))
+    back = host(B.dequantize_u8(dev(got), float(q)))
+    assert np.array_equal(back, orc.D_u8(want, q))
+
+
+U8_CASES = [
+    # geometry, in_u8, out_u8, res ("u8", "s8" or None), relu
+    (dict(N=2, H=14, W=14, C=64, K=160, R=3, S=3, pad_h=1, pad_w=1), 1, 1, "u8", 1),
+    (dict(N=2, H=14, W=14, C=64, K=160, R=3, S=3, pad_h=1, pad_w=1), 1, 0, "s8", 0),
+    (dict(N=1, H=15, W=13, C=32, K=64, R=3, S=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2), 1, 1, None, 1),
+    (dict(N=3, H=9, W=9, C=128, K=256, R=1, S=1), 1, 1, "s8", 1),
+    (dict(N=3, H=9, W=9, C=128, K=256, R=1, S=1), 0, 1, "u8", 1),
+    (dict(N=1, H=17, W=17, C=48, K=96, R=1, S=7, pad_w=3), 1, 0, None, 1),
+    (dict(N=1, H=12, W=12, C=16, K=72, R=3, S=3, dil_h=2, dil_w=2, pad_h=2, pad_w=2), 1, 1, "u8", 1),
+    (dict(N=1, H=7, W=7, C=64, K=64, R=5, S=5, pad_h=2, pad_w=2), 1, 1, None, 1),   # mostly border
+    (dict(N=2, H=28, W=28, C=64, K=128, R=3, S=3, pad_h=1, pad_w=1), 1, 1, "u8", 1),  # complete tiles
+]
+
+
+@pytest.mark.parametrize("idx", range(len(U8_CASES)))
+def test_conv_unsigned_activations(B, idx):
+    """Eq. A' on unsigned p = 8 codes (the paper's form for non-negative tensors) through
+    the signed matrix instruction: accumulators and outputs equal the oracle's, which
+    works on the codes 0..255 themselves."""
+    geom, in_u8, out_u8, res_kind, relu = U8_CASES[idx]
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(500 + idx)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, g.K).astype(np.int32)
+    if in_u8:
+        x = rng.integers(0, 256, (g.N, g.H, g.W, g.C)).astype(np.uint8)
+        acc_o = orc.conv_u8(g, x, w, b)
+        x_st = _stored(x)
+    else:
+        x = rng.integers(-128, 128, (g.N, g.H, g.W, g.C)).astype(np.int8)
+        acc_o = orc.conv_i8(g, x, w, b)
+        x_st = x
+    Ho, Wo = g.Ho, g.Wo
+    q_x, q_w = np.float32(0.011), np.float32(0.0017)
+    fan = g.R * g.S * g.C
+    q_out = np.float32(q_x * q_w * 74.0 * (147.0 if in_u8 else 74.0) * np.sqrt(fan) / 60.0)
+    q_res = np.float32(0.4) * q_out
+    res = res_st = None
+    if res_kind == "u8":
+        res = rng.integers(0, 256, (g.N, Ho, Wo, g.K)).astype(np.uint8)
+        res_st = _stored(res)
+    elif res_kind == "s8":
+        res = res_st = rng.integers(-128, 128, (g.N, Ho, Wo, g.K)).astype(np.int8)
+    m = orc.requant_scale(q_x, q_w, q_out)
+    m_r = orc.residual_scale(q_res, q_out) if res is not None else 0.0
+    want = orc.requant_mixed(acc_o, m, relu, res, m_r, out_unsigned=bool(out_u8))
+
+    d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                   g.dil_h, g.dil_w, relu=relu)
+    packed = B.pack_weights(d, dev(w))
+    if in_u8:
+        taps, bias = B.u8_prepare(d, dev(w), dev(b))
+        tw = w.astype(np.int64).sum(axis=3)                               # [K, R, S]
+        pre = np.zeros((g.R + 1, g.S + 1, g.K), np.int64)                 # 2-D prefix sums
+        pre[1:, 1:] = tw.cumsum(axis=1).cumsum(axis=2).transpose(1, 2, 0)
+        assert np.array_equal(host(taps).reshape(g.R + 1, g.S + 1, g.K), pre)
+        assert np.array_equal(host(bias), b + 128 * tw.sum(axis=(1, 2)))
+    else:
+        taps, bias = None, dev(b)
+    dump = torch.zeros((g.N, Ho, Wo, g.K), dtype=torch.int32, device="cuda")
+    for use_dump in (True, False):             # general epilogue, then the fast one
+        got = B.conv_u8(d, in_u8, out_u8, res_kind == "u8", dev(x_st), packed, bias, taps,
+                        float(q_x), float(q_w), float(q_out),
+                        None if res_st is None else dev(res_st), float(q_res),
+                        acc_dump=dump if use_dump else None)
+        if use_dump:
+            assert np.array_equal(host(dump), acc_o), "int32 accumulators differ"
+        got = host(got)
+        if out_u8:
+            assert np.array_equal(got.astype(np.int16) + 128, want.astype(np.int16))
+        else:
+            assert np.array_equal(got, want)
+    sat = np.mean((want == (255 if out_u8 else 127)))
+    assert sat < 0.5
+
+
 @pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
 def test_conv_channel_slice_of_concat(B, out_pad, out_off):
     geom = dict(N=2, H=9, W=9, C=32, K=40, R=3, S=3, pad_h=1, pad_w=1)
@@ -400,7 +494,7 @@ def test_config2_bottleneck_block(B):
             assert np.array_equal(host(eng.act[o]), acts[o])
 
 
-def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2):
+def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -408,21 +502,29 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
     net = wl.CONFIGS[cfg_id]["make"]()
     params = {op.name: wl.conv_params(cfg_id, i, op) for i, op in enumerate(net.convs())}
     folded = onet.fold_all(net, params)
+    U = onet.unsigned_tensors(net) if unsigned else set()
     q = onet.calibrate(net, folded, (wl.input_batch(cfg_id, net, cal_batch, 100 + i)
-                                     for i in range(n_cal)))
+                                     for i in range(n_cal)), unsigned=U)
     qparams = onet.quantize_params(net, folded, q)
     x = wl.input_batch(cfg_id, net, batch, 0)
     z_in = orc.Q(x[picks], q[net.input], 7)
-    acts = onet.forward_i8(net, qparams, q, z_in)
+    acts = onet.forward_i8(net, qparams, q, z_in, unsigned=U)
 
-    eng = Engine(net, batch, n_streams=n_streams)
+    def codes(name, a):       # the GPU's bytes as the oracle's codes
+        return (a.astype(np.int16) + 128).astype(np.uint8) if name in U else a
+
+    eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned)
+    assert eng.unsigned == U
     eng.load_params(params)
     eng.fold()
     eng.set_factors(q)
     eng.quantize_weights()
     for name, qp in qparams.items():
         assert np.float32(eng.qw[name]) == qp["q_w"], name
-        assert np.array_equal(host(eng.wq[name][1]), qp["z_b"]), name
+        bias = host(eng.wq[name][1])
+        if name in eng.taps:       # reads unsigned codes: 128 * (filter sum) is folded in
+            bias = bias - 128 * qp["z_w"].astype(np.int64).reshape(bias.size, -1).sum(axis=1)
+        assert np.array_equal(bias, qp["z_b"]), name
     xd = dev(x)
     outs = eng.forward(xd)
     zi = host(eng.input_codes())
@@ -433,11 +535,11 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         assert not full[:, :top].any() and not full[:, top + z_in.shape[1]:].any()
         assert not full[:, :, :left].any() and not full[:, :, left + z_in.shape[2]:].any()
     for op in net.ops:
-        got = host(eng.act[op.dst])[picks]
-        assert np.array_equal(got, acts[op.dst]), op.name
+        got = codes(op.dst, host(eng.act[op.dst])[picks])
+        assert got.dtype == acts[op.dst].dtype and np.array_equal(got, acts[op.dst]), op.name
     for o, out in zip(net.outputs, outs):
-        r = host(B.dequantize(out, float(q[o])))[picks]
-        want = orc.D(acts[o], q[o])
+        r = host(eng.dequantize(o))[picks]
+        want = orc.D_u8(acts[o], q[o]) if o in U else orc.D(acts[o], q[o])
         assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want)), o
     # replays of the captured HIP graph, with eager work between them: same bits each time
     eng.capture(xd)
@@ -447,7 +549,7 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         torch.cuda.synchronize()
         eng.graph.replay()
         for o in net.outputs:
-            assert np.array_equal(host(eng.act[o])[picks], acts[o]), (o, rep)
+            assert np.array_equal(codes(o, host(eng.act[o])[picks]), acts[o]), (o, rep)
 
 
 @pytest.mark.parametrize("n_streams", [2, 1])
@@ -455,6 +557,12 @@ def test_config3_resnet50_batch64_sampled_images(B, n_streams):
     # n_streams = 2 is the launch configuration the benchmark times (two half-batch
     # pipelines); images 31 and 32 sit on either side of the split
     _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=8, cal_batch=8, n_streams=n_streams)
+
+
+def test_resnet50_unsigned_activations(B):
+    # ResNet-50 with unsigned p = 8 codes on every ReLU output (the paper's precision for
+    # non-negative activations), batch 64 in the benchmark's launch configuration
+    _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, unsigned=True)
 
 
 def test_resnet50_after_sparsity_removal(B):

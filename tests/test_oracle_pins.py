@@ -550,3 +550,78 @@ def test_sparsity_removal_keeps_the_values_that_are_read():
             assert np.array_equal(t, a[name][:, ::2, ::2]), name
             halved += 1
     assert halved == 3
+
+
+# ----------------------------------------------------------------------------------------
+# unsigned p = 8 activation codes (calibration paragraph: non-negative tensors)
+# ----------------------------------------------------------------------------------------
+def test_conv_u8_against_float64_library_convolution():
+    rng = np.random.default_rng(41)
+    for geom in (dict(N=2, H=9, W=8, C=5, K=7, R=3, S=3, pad_h=1, pad_w=1),
+                 dict(N=1, H=11, W=11, C=4, K=3, R=3, S=2, stride_h=2, stride_w=1, pad_h=1, pad_w=0,
+                      dil_h=2)):
+        g = orc.ConvGeom(**geom)
+        x = rng.integers(0, 256, (g.N, g.H, g.W, g.C)).astype(np.uint8)
+        w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+        b = rng.integers(-1000, 1000, g.K).astype(np.int32)
+        ref = torch.nn.functional.conv2d(
+            torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2),
+            torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2),
+            torch.from_numpy(b.astype(np.float64)), stride=(g.stride_h, g.stride_w),
+            padding=(g.pad_h, g.pad_w), dilation=(g.dil_h, g.dil_w)).permute(0, 2, 3, 1).numpy()
+        assert np.array_equal(orc.conv_u8(g, x, w, b), ref.astype(np.int64))
+    # the identity the GPU path relies on: codes = (codes - 128) + 128, so the signed
+    # contraction of the shifted bytes plus 128 * (sum of the taps that read inside the
+    # image) is the same accumulator
+    g = orc.ConvGeom(N=1, H=5, W=5, C=3, K=2, R=3, S=3, pad_h=1, pad_w=1)
+    x = rng.integers(0, 256, (1, 5, 5, 3)).astype(np.uint8)
+    w = rng.integers(-128, 128, (2, 3, 3, 3)).astype(np.int8)
+    shifted = orc.conv_i8(g, (x.astype(np.int16) - 128).astype(np.int8), w)
+    ones = orc.conv_i8(g, np.ones((1, 5, 5, 3), np.int8), w)      # sum of the inside taps
+    assert np.array_equal(orc.conv_u8(g, x, w), shifted + 128 * ones)
+
+
+def test_requant_mixed_against_exact_rational():
+    rng = np.random.default_rng(42)
+    acc = rng.integers(-60000, 60000, (1, 512)).astype(np.int32)
+    m, m_r = np.float32(0.00437), np.float32(0.613)
+    for res_dtype in (np.uint8, np.int8):
+        lo_r, hi_r = (0, 256) if res_dtype == np.uint8 else (-128, 128)
+        res = rng.integers(lo_r, hi_r, (1, 512)).astype(res_dtype)
+        for out_u in (True, False):
+            got = orc.requant_mixed(acc, m, True, res, m_r, out_unsigned=out_u)
+            lo, hi = (0, 255) if out_u else (-128, 127)
+            want = []
+            for a, r in zip(acc.ravel().tolist(), res.ravel().tolist()):
+                t = fl32(fl32(F(a)) * F(float(m)))
+                t = fl32(t + fl32(F(r) * F(float(m_r))))
+                t = max(t, F(0))
+                want.append(round_half_even(clamp(t, F(lo), F(hi))))
+            assert got.ravel().tolist() == want, (res_dtype, out_u)
+    # hand-worked: acc * 0.5 = 2.5 300 -4 255.5 -> ties to even, saturation at 255, ReLU
+    assert orc.requant_mixed(np.array([[5, 600, -8, 511]], np.int32), 0.5, True,
+                             out_unsigned=True).ravel().tolist() == [2, 255, 0, 255]
+
+
+def test_unsigned_network_reading_on_a_small_resnet():
+    """Unsigned codes halve the quantisation step of the ReLU outputs: the int8 network's
+    dequantised output is closer to the fp32 network's with them than without."""
+    from oracle import net as onet
+    from paper_1805_08691_amd import workloads as wl
+    net = wl.resnet50(image=64)
+    params = {op.name: wl.conv_params(3, i, op) for i, op in enumerate(net.convs())}
+    folded = onet.fold_all(net, params)
+    cal = [wl.input_batch(3, net, 2, 100)]
+    x = wl.input_batch(3, net, 1, 0)
+    ref = onet.forward_f32(net, folded, x)[0][net.outputs[0]]
+    err = {}
+    for mode in (False, True):
+        U = onet.unsigned_tensors(net) if mode else set()
+        q = onet.calibrate(net, folded, cal, unsigned=U)
+        qp = onet.quantize_params(net, folded, q)
+        acts = onet.forward_i8(net, qp, q, orc.Q(x, q[net.input], 7), unsigned=U)
+        o = net.outputs[0]
+        assert acts[o].dtype == (np.uint8 if mode else np.int8)
+        y = orc.D_u8(acts[o], q[o]) if mode else orc.D(acts[o], q[o])
+        err[mode] = float(np.sqrt(np.mean((y - ref) ** 2)))
+    assert err[True] < err[False]
