@@ -12,7 +12,11 @@
  *   - Q, D, the + rule, BN folding and the requantising epilogue are fp32;
  *   - the p = 31 bias quantiser is fp64 (2^31-1 is not an fp32 value);
  *   - the convolution is exact integer arithmetic (int64 accumulator, checked
- *     to fit int32).
+ *     to fit int32), on signed codes (orc_conv_i8) or, for the paper's p = 8
+ *     precision of non-negative tensors, on unsigned codes 0..255
+ *     (orc_conv_u8, orc_requant_mixed, orc_dequantize_u8);
+ *   - pooling helpers (max, average with the padding counted) follow the same
+ *     fp32 order as the epilogue.
  *
  * Each function names the passage of the paper it follows:
  *   Eq. Q  quantisation, Eq. D  dequantisation, Eq. +/x  arithmetic on

@@ -81,6 +81,23 @@ def test_bad_arguments_are_rejected_on_the_host():
     empty = B.ConvDesc(0, 8, 8, 16, 16, 3, 3)
     assert L.q8_conv_int8(C.byref(empty), None, None, None, 1.0, 1.0, 1.0, None, 0.0, None, None,
                           None) == 0                   # empty batch: nothing to do
+    # unsigned activation codes
+    wide = B.ConvDesc(1, 8, 8, 16, 64, 3, 3, pad_h=1, pad_w=1, relu=1)
+    u8 = (fake, fake, fake, fake, 1.0, 1.0, 1.0, None, 0.0, fake, None, None)
+    assert L.q8_conv_u8(C.byref(d), 1, 1, 0, *u8) == -2          # K <= 32: not the main kernel
+    norelu = B.ConvDesc(1, 8, 8, 16, 64, 3, 3, pad_h=1, pad_w=1, relu=0)
+    assert L.q8_conv_u8(C.byref(norelu), 1, 1, 0, *u8) == -1     # unsigned output without ReLU
+    assert L.q8_conv_u8(C.byref(wide), 1, 1, 1, *u8) == -1       # unsigned residual, none given
+    assert L.q8_conv_u8(C.byref(wide), 1, 1, 0, fake, fake, None, fake, 1.0, 1.0, 1.0, None, 0.0,
+                        fake, None, None) == -1                  # unsigned input needs bias_eff
+    assert L.q8_conv_u8(C.byref(wide), 1, 1, 0, fake, fake, fake, None, 1.0, 1.0, 1.0, None, 0.0,
+                        fake, None, None) == -1                  # padding needs the tap sums
+    assert L.q8_u8_prepare(C.byref(wide), None, None, fake, fake, None) == -1
+    assert L.q8_u8_prepare(C.byref(B.ConvDesc(1, 8, 8, 3, 64, 3, 3)), fake, None, fake, fake,
+                           None) == -2
+    assert L.q8_quantize_u8(fake, 4, 0.0, fake, None) == -1
+    assert L.q8_dequantize_u8(None, 4, 1.0, fake, None) == -1
+    assert L.q8_dequantize_u8(None, 0, 1.0, None, None) == 0
     assert B.packed_weight_bytes(d) == 16 * 3 * 3 * 16
     assert B.packed_weight_bytes(B.ConvDesc(1, 8, 8, 3, 64, 7, 7)) == 64 * 7 * 2 * 16
     assert L.q8_maxpool_i8(fake, 1, 8, 8, 4, 3, 3, 2, 3, 4, 4, fake, None) == -1   # pad >= window
