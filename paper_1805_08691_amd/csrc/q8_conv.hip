@@ -215,7 +215,9 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
 
   {
     const long xb = (long)d->N * d->H * d->W * p.in_cs, wb = (long)d->K * p.red_len;
-    Q8_REQUIRE(xb < 0x7fffffffL && wb < 0x7fffffffL, Q8_EUNSUPPORTED);   // 32-bit buffer offsets
+    // 32-bit buffer offsets; the activation descriptor also spans the first padding rows
+    const long lead = ((long)d->pad_h * d->W + d->pad_w) * p.in_cs;
+    Q8_REQUIRE(xb + lead < 0x7fffffffL && wb < 0x7fffffffL, Q8_EUNSUPPORTED);
     p.x_bytes = (int)xb;
     p.w_bytes = (int)wb;
   }

@@ -73,8 +73,14 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 
   const __amdgpu_buffer_rsrc_t rsrc_w =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, p.w_bytes, 0x00020000);
+  // The activation descriptor starts (pad_h rows + pad_w pixels) BEFORE the tensor: a lane's
+  // offset of tap (0,0) of its pixel is then never negative, also where that tap lies in
+  // the padding, and can stay in the vector offset while the tap's own (uniform,
+  // non-negative) offset goes into the scalar offset.  Nothing is read in front of the
+  // tensor: a tap in the padding gets an out-of-range vector offset.
+  const int x_shift = (p.pad_h * p.W + p.pad_w) * p.in_cs;
   const __amdgpu_buffer_rsrc_t rsrc_x =
-      __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, p.x_bytes, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc((void*)(p.x - x_shift), 0, p.x_bytes + x_shift, 0x00020000);
 
   // ---- loader state: lane l of wave w fills, in its j-th load, row (w + 4j)*RPW + l/CHUNKS,
   // physical slot l % CHUNKS.  The swizzle term only depends on row bits that do not change
@@ -98,7 +104,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     unsigned mask = 0;
     int off = 0;
     if (pix < p.M && pointwise) {
-      off = pix * p.in_cs + (UNIFORM ? lchunk * 16 : 0);     // output pixel = input pixel
+      off = pix * p.in_cs + (UNIFORM ? lchunk * 16 : 0);     // output pixel = input pixel (no padding)
       mask = 1u;
     } else if (pix < p.M) {
       const int n = fast_div(pix, p.div_img_m, p.div_img_s);
@@ -107,7 +113,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       const int wo = rem - ho * p.Wo;
       const int hi0 = ho * p.stride_h - p.pad_h;
       const int wi0 = wo * p.stride_w - p.pad_w;
-      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + (UNIFORM ? lchunk * 16 : 0);
+      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + x_shift + (UNIFORM ? lchunk * 16 : 0);
       if (p.dil_h == 1 && p.dil_w == 1) {
         // taps inside the image: rows [r_lo, r_hi), columns [s_lo, s_hi)
         const unsigned cols = bits_below(min(p.S, p.W - wi0)) & ~bits_below(-wi0);
@@ -142,6 +148,16 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     tap_delta = (r * p.dil_h * p.W + tap_s * p.dil_w) * p.in_cs;
   }
 
+  int b_voff[B_LOADS];                   // UNIFORM: what the B loads of the current tap use
+  int tap_changed = 0;
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) b_voff[j] = (b_mask[j] & 1u) ? b_off[j] : kOobOffset;
+  auto refresh_taps = [&]() {            // UNIFORM, after the tap moved on
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j)
+      b_voff[j] = ((b_mask[j] >> tap) & 1u) ? b_off[j] : kOobOffset;
+  };
+
   auto issue_stage = [&](int buf) {
     int8_t* stage = lds + buf * STAGE_BYTES;
     if constexpr (UNIFORM) {
@@ -150,15 +166,15 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
             a_off[j], step_base, 0, 0);
+      // per lane: the pixel's offset, or "out of range" if the current tap lies in the
+      // padding (refreshed only when the tap changes); uniform: the tap's own offset
       const int delta = tap_delta + tap_c;
 #pragma unroll
-      for (int j = 0; j < B_LOADS; ++j) {
-        const int voff = ((b_mask[j] >> tap) & 1u) ? b_off[j] + delta : kOobOffset;
+      for (int j = 0; j < B_LOADS; ++j)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rsrc_x,
             (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
-            voff, 0, 0, 0);
-      }
+            b_voff[j], delta, 0, 0);
       step_base += BK;
       // advance (branch-free, so the whole step stays one scheduling region)
       tap_c += BK;
@@ -170,6 +186,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       const int wrap_s = tap_s == p.S ? 1 : 0;
       tap_s = wrap_s ? 0 : tap_s;
       tap_delta += wrap_s ? dh_step : 0;
+      tap_changed = wrap_c;
     } else {
       const bool red_ok = step_base + lchunk * 16 < p.red_len;
 #pragma unroll
@@ -308,8 +325,11 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   // One reduction step.  LATER = steps issued after step kt that may still be in flight
   // when step kt must have landed; ISSUE = whether a further step is issued; LAST = whether
   // the residual codes are fetched (no stage load follows, so vmcnt bookkeeping is over).
-  auto step = [&](int kt, auto later_c, auto issue_c, auto last_c) {
+  // STAGE = ring buffer of step kt when the caller knows it at compile time (the LDS reads
+  // then need no address arithmetic: fixed per-lane offsets plus an immediate), else -1.
+  auto step = [&](int kt, auto later_c, auto issue_c, auto last_c, auto stage_c) {
     constexpr int LATER = decltype(later_c)::value;
+    constexpr int STAGE = decltype(stage_c)::value;
     wait_vmcnt<LATER * LOADS>();
     // Bare barrier (no fence: a fence would drain the loads of the later steps too).
     // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS
@@ -317,9 +337,10 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    const int8_t* stage = lds + (kt % STAGES) * STAGE_BYTES;
+    const int8_t* stage = lds + (STAGE >= 0 ? STAGE : kt % STAGES) * STAGE_BYTES;
     load_frags(stage, 0);
-    if constexpr (decltype(issue_c)::value) issue_stage((kt + STAGES - 1) % STAGES);
+    if constexpr (decltype(issue_c)::value)
+      issue_stage(STAGE >= 0 ? (STAGE + STAGES - 1) % STAGES : (kt + STAGES - 1) % STAGES);
     if constexpr (decltype(last_c)::value) {
       if (!early_residual) fetch_residual();
     }
@@ -353,28 +374,49 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (UNIFORM && decltype(issue_c)::value) {
+      if (tap_changed) refresh_taps();
+    }
   };
   using std::integral_constant;
+  constexpr integral_constant<int, -1> any_stage{};
 
   // prologue: up to STAGES-1 reduction steps in flight
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (s < nk) issue_stage(s);
+    if (s < nk) {
+      issue_stage(s);
+      if constexpr (UNIFORM) {
+        if (tap_changed) refresh_taps();
+      }
+    }
   // Scalar loads still outstanding here would make every LDS wait inside the loop a full
   // one (scalar and LDS results share a counter but return in no fixed order): settle them
   // now, so the loop waits for exactly the fragments it needs.
   __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0), other counters untouched
   // steady state: every step finds STAGES-2 later steps in flight and issues one more
   int kt = 0;
+  // rounds of STAGES steps whose ring buffers are known at compile time
+  for (; kt + 2 * STAGES - 2 < nk; kt += STAGES) {
+    auto round = [&](auto self, auto s_c) __attribute__((always_inline)) -> void {
+      constexpr int S = decltype(s_c)::value;
+      if constexpr (S < STAGES) {
+        step(kt + S, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
+             integral_constant<bool, false>{}, integral_constant<int, S>{});
+        self(self, integral_constant<int, S + 1>{});
+      }
+    };
+    round(round, integral_constant<int, 0>{});
+  }
   for (; kt + STAGES - 1 < nk; ++kt)
     step(kt, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
-         integral_constant<bool, false>{});
+         integral_constant<bool, false>{}, any_stage);
   // drain: the last min(STAGES-1, nk) steps, with fewer and fewer loads behind them
 #define Q8_DRAIN_STEP(L)                                                              \
   if constexpr (STAGES >= (L) + 2) {                                                  \
     if (nk - kt == (L) + 1) {                                                         \
       step(kt, integral_constant<int, (L)>{}, integral_constant<bool, false>{},       \
-           integral_constant<bool, false>{});                                         \
+           integral_constant<bool, false>{}, any_stage);                              \
       ++kt;                                                                           \
     }                                                                                 \
   }
@@ -386,7 +428,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   Q8_DRAIN_STEP(1)
 #undef Q8_DRAIN_STEP
   step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
-       integral_constant<bool, true>{});
+       integral_constant<bool, true>{}, any_stage);
   mma(NH - 1);
 
   // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
