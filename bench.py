@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--unsigned-activations", action="store_true",
                     help="unsigned p = 8 codes on the outputs of ReLU layers (the paper's "
                          "precision for non-negative tensors); reported as its own workload")
+    ap.add_argument("--per-channel-weights", action="store_true",
+                    help="one weight factor per output channel instead of one per tensor; "
+                         "reported as its own workload")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="one eager pass plus one plain 256 MiB device copy, then exit: the "
                          "program to run under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the copy "
@@ -107,7 +110,8 @@ def main():
 
     # ---------------- offline: parameters, fold, calibrate, quantise weights ---------------
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
-    eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations)
+    eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations,
+                 per_channel_weights=args.per_channel_weights)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -325,7 +329,7 @@ def main():
         xs = x[:sample].cpu().numpy()
         folded = onet.fold_all(net, params)
         q = {k: np.float32(v) for k, v in eng.q.items()}
-        qparams = onet.quantize_params(net, folded, q)
+        qparams = onet.quantize_params(net, folded, q, per_channel=args.per_channel_weights)
         U = onet.unsigned_tensors(net) if args.unsigned_activations else set()
         t0 = time.perf_counter()
         z_in = orc.Q(xs, q[net.input], 7)
@@ -344,15 +348,18 @@ def main():
 
     result = {
         "metric": "ResNet-50 int8 images/sec at batch 64"
-                  if args.config == 3 and not args.sparsity_removal and not args.unsigned_activations
-                  else f"{net.name}{' (unsigned activations)' if args.unsigned_activations else ''} "
+                  if args.config == 3 and not (args.sparsity_removal or args.unsigned_activations
+                                               or args.per_channel_weights)
+                  else f"{net.name}{' (unsigned activations)' if args.unsigned_activations else ''}"
+                       f"{' (per-channel weights)' if args.per_channel_weights else ''} "
                        f"int8 images/sec at batch {N}",
         "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{net.name} conv stack, batch {N}, NHWC int8, "
                                f"{len(convs)} fused convs"
-                               + (", unsigned p=8 ReLU outputs" if args.unsigned_activations else ""),
+                               + (", unsigned p=8 ReLU outputs" if args.unsigned_activations else "")
+                               + (", per-channel weight factors" if args.per_channel_weights else ""),
                    "batch": N,
                    "launch": "eager" if graph is None else "hip_graph",
                    "streams": eng.n_streams},

@@ -169,6 +169,29 @@ int q8_conv_u8(const q8_conv_desc *d, int in_unsigned, int out_unsigned, int res
                const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
                void *stream);
 
+/* ---- per-output-channel weight factors ------------------------------------------------
+ * A finer granularity than the calibration paragraph's one factor per tensor: filter k gets
+ * q_w[k] = max|w'[k]| / (2^p - 1).  By Eq. x the accumulator of channel k then carries
+ * q_x * q_w[k], the bias is Q_31(b[k], q_x q_w[k]) and the tail of Eq. A' uses the scale
+ * m[k] = (q_x * q_w[k]) / q_out (two fp32 operations, as for the single scale).
+ *
+ * q8_quantize_weights_per_channel: W fp32 [K][row_len] (KRSC) -> q_w_dev fp32 [K] and int8
+ *   codes of the same shape (Eq. Q per row; an all-zero row gets q = 1).
+ * q8_quantize_bias_per_channel: z_b[k] = Q_31(b[k], q_x * q_w[k]) in fp64.
+ * q8_requant_scales: m_dev[k] = (q_x * q_w[k]) / q_out.
+ * q8_conv_int8_per_channel: q8_conv_int8 with m_dev (fp32 [K], 16-byte aligned) in place of
+ *   q_x and q_w.  Main-kernel geometries only; not combined with unsigned activations.   */
+int q8_quantize_weights_per_channel(const float *w_dev, int K, size_t row_len, int p,
+                                    float *q_w_dev, int8_t *z_w_dev, void *stream);
+int q8_quantize_bias_per_channel(const float *b_dev, int K, float q_x, const float *q_w_dev,
+                                 int32_t *z_b_dev, void *stream);
+int q8_requant_scales(float q_x, const float *q_w_dev, int K, float q_out, float *m_dev,
+                      void *stream);
+int q8_conv_int8_per_channel(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
+                             const int32_t *bias_i32, const float *m_dev, float q_out,
+                             const int8_t *residual, float q_res, int8_t *z_y,
+                             int32_t *acc_dump, void *stream);
+
 /* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
  * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.
  * For measurement code that groups launches by kernel.                              */

@@ -91,6 +91,13 @@ _lib.orc_requant_mixed.argtypes = [_i32p, C.c_size_t, C.c_int, C.c_float, C.c_vo
                                    C.c_int, C.c_int]
 _lib.orc_dequantize_u8.restype = None
 _lib.orc_dequantize_u8.argtypes = [_u8p, C.c_size_t, C.c_float, _f32p]
+_lib.orc_requant_scales_pc.restype = None
+_lib.orc_requant_scales_pc.argtypes = [C.c_float, _f32p, C.c_int, C.c_float, _f32p]
+_lib.orc_requant_pc.restype = None
+_lib.orc_requant_pc.argtypes = [_i32p, C.c_size_t, C.c_int, _f32p, C.c_void_p, C.c_int, C.c_int,
+                                C.c_float, C.c_int, _i8p, C.c_int, C.c_int]
+_lib.orc_quantize_bias_pc.restype = None
+_lib.orc_quantize_bias_pc.argtypes = [_f32p, C.c_size_t, C.c_float, _f32p, _i32p]
 _lib.orc_requant_scale.restype = C.c_float
 _lib.orc_requant_scale.argtypes = [C.c_float] * 3
 _lib.orc_residual_scale.restype = C.c_float
@@ -243,6 +250,53 @@ def requant_mixed(acc, m, relu, z_res=None, m_r=0.0, out_unsigned=False, out=Non
     _lib.orc_requant_mixed(acc.reshape(-1), npix, K, np.float32(m), _ptr(zr), res_u, rcs, 0,
                            np.float32(m_r), int(bool(relu)), _ptr(out), int(out_unsigned),
                            out.shape[-1], out_c_off)
+    return out
+
+
+def quantize_weights_pc(W, p=7):
+    """Per-output-channel weight quantisation: (z_w int8 like W, q_w fp32 [K])."""
+    W = _f32(W)
+    K = W.shape[0]
+    q_w = np.array([qfactor(maxabs(W[k]), p) for k in range(K)], np.float32)
+    z_w = np.stack([Q(W[k], q_w[k], p) for k in range(K)])
+    return z_w, q_w
+
+
+def Q31_bias_pc(b, q_x, q_w):
+    b = _f32(b)
+    q_w = _f32(q_w)
+    assert b.shape == q_w.shape
+    z = np.empty(b.shape, np.int32)
+    _lib.orc_quantize_bias_pc(b, b.size, np.float32(q_x), q_w, z)
+    return z
+
+
+def requant_scales_pc(q_x, q_w, q_out):
+    q_w = _f32(q_w)
+    m = np.empty(q_w.shape, np.float32)
+    _lib.orc_requant_scales_pc(np.float32(q_x), q_w, q_w.size, np.float32(q_out), m)
+    return m
+
+
+def requant_pc(acc, m, relu, z_res=None, m_r=0.0, out=None, out_c_stride=0, out_c_off=0):
+    """requant with one scale per output channel (m: fp32 [K])."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    K = acc.shape[-1]
+    m = _f32(m)
+    assert m.shape == (K,)
+    npix = acc.size // K if K else 0
+    if out is None:
+        out = np.empty(acc.shape, np.int8)
+        out_c_stride, out_c_off = K, 0
+    assert out.dtype == np.int8 and out.flags.c_contiguous
+    assert out.size >= npix * out_c_stride and out_c_off + K <= out_c_stride
+    zr, rcs = None, 0
+    if z_res is not None:
+        zr = np.ascontiguousarray(z_res, dtype=np.int8)
+        rcs = K
+        assert zr.size == npix * K
+    _lib.orc_requant_pc(acc.reshape(-1), npix, K, m, _ptr(zr), rcs, 0, np.float32(m_r),
+                        int(bool(relu)), out.reshape(-1), out_c_stride, out_c_off)
     return out
 
 

@@ -11,8 +11,9 @@ the factor of the branch's own pre-sum output.
 import numpy as np
 import torch
 
-from . import (ConvGeom, Q, Q31_bias, conv_f32, conv_i8, conv_u8, fold_bn, maxabs, pool_i8,
-               qfactor, requant, requant_mixed, requant_scale, residual_scale)
+from . import (ConvGeom, Q, Q31_bias, Q31_bias_pc, conv_f32, conv_i8, conv_u8, fold_bn, maxabs,
+               pool_i8, qfactor, quantize_weights_pc, requant, requant_mixed, requant_pc,
+               requant_scale, requant_scales_pc, residual_scale)
 
 P_ACT = 7
 P_W = 7
@@ -141,13 +142,18 @@ def calibrate(net, folded, batches, use_library=True, unsigned=None):
     return q
 
 
-def quantize_params(net, folded, q):
-    """name -> dict(z_w int8 KRSC, q_w, z_b int32)."""
+def quantize_params(net, folded, q, per_channel=False):
+    """name -> dict(z_w int8 KRSC, q_w, z_b int32).  ``per_channel``: q_w is an fp32 vector
+    with one factor per output channel."""
     out = {}
     for op in net.ops:
         if op.kind != "conv":
             continue
         Wf, bf = folded[op.name]
+        if per_channel:
+            z_w, q_w = quantize_weights_pc(Wf, P_W)
+            out[op.name] = dict(z_w=z_w, q_w=q_w, z_b=Q31_bias_pc(bf, q[op.src], q_w))
+            continue
         q_w = qfactor(maxabs(Wf), P_W)
         out[op.name] = dict(z_w=Q(Wf, q_w, P_W), q_w=q_w, z_b=Q31_bias(bf, q[op.src], q_w))
     return out
@@ -202,13 +208,17 @@ def forward_i8(net, qparams, q, z_in, keep_acc=False, unsigned=None):
         if keep_acc:
             accs[op.name] = acc
         q_out = q[op.dst]
-        m = requant_scale(q[op.src], qp["q_w"], q_out)
         d = net.tensors[op.dst]
         if op.dst not in t:
             t[op.dst] = np.zeros((N, d.H, d.W, d.C), np.int8)
         res, m_r = None, 0.0
         if op.res is not None:
             res, m_r = t[op.res], residual_scale(q[op.res], q_out)
+        if np.ndim(qp["q_w"]) == 1:                     # one weight factor per channel
+            requant_pc(acc, requant_scales_pc(q[op.src], qp["q_w"], q_out), op.relu, res, m_r,
+                       out=t[op.dst], out_c_stride=d.C, out_c_off=op.dst_c_off)
+            continue
+        m = requant_scale(q[op.src], qp["q_w"], q_out)
         requant(acc, m, op.relu, res, m_r, out=t[op.dst], out_c_stride=d.C,
                 out_c_off=op.dst_c_off)
     return (t, accs) if keep_acc else t

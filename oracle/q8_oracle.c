@@ -282,6 +282,44 @@ void orc_requant_mixed(const int32_t *acc, size_t npix, int K, float m,
     }
 }
 
+/* Per-output-channel weight factors (a finer granularity than the calibration
+ * paragraph's per-tensor factor): filter k has its own q_w[k], so the accumulator of
+ * channel k carries q_x*q_w[k] (Eq. x) and is re-expressed at q_out with its own scale
+ * m[k] = (q_x * q_w[k]) / q_out.  Same fixed fp32 order as orc_requant.               */
+void orc_requant_scales_pc(float q_x, const float *q_w, int K, float q_out, float *m) {
+  for (int k = 0; k < K; ++k) {
+    float prod = q_x * q_w[k];
+    m[k] = prod / q_out;
+  }
+}
+
+void orc_requant_pc(const int32_t *acc, size_t npix, int K, const float *m,
+                    const int8_t *z_res, int res_c_stride, int res_c_off, float m_r,
+                    int relu, int8_t *z_y, int out_c_stride, int out_c_off) {
+#pragma omp parallel for schedule(static)
+  for (size_t p = 0; p < npix; ++p)
+    for (int k = 0; k < K; ++k) {
+      float t = (float)acc[p * K + k];
+      t = t * m[k];
+      if (z_res) {
+        float u = (float)z_res[p * res_c_stride + res_c_off + k];
+        u = u * m_r;
+        t = t + u;
+      }
+      if (relu) t = t > 0.0f ? t : 0.0f;
+      if (t > 127.0f) t = 127.0f;
+      if (t < -128.0f) t = -128.0f;
+      t = rintf(t);
+      z_y[p * out_c_stride + out_c_off + k] = (int8_t)t;
+    }
+}
+
+/* Q_31 of the bias with one factor per channel: z_b[k] = Q(b[k], q_x * q_w[k]) in fp64. */
+void orc_quantize_bias_pc(const float *b, size_t n, float q_x, const float *q_w,
+                          int32_t *z) {
+  for (size_t k = 0; k < n; ++k) orc_quantize_bias(b + k, 1, q_x, q_w[k], z + k);
+}
+
 /* Eq. D on unsigned codes. */
 void orc_dequantize_u8(const uint8_t *z, size_t n, float q, float *r) {
   for (size_t i = 0; i < n; ++i) r[i] = (float)z[i] * q;

@@ -23,7 +23,8 @@ lib = C.CDLL(LIB_PATH)
 EXPORTS = [
     "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
     "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_image", "q8_quantize_bias", "q8_quantize_u8", "q8_dequantize_u8",
-    "q8_u8_prepare", "q8_conv_u8", "q8_dequantize",
+    "q8_u8_prepare", "q8_conv_u8", "q8_quantize_weights_per_channel",
+    "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_variant", "q8_conv_force_variant",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
@@ -80,6 +81,10 @@ lib.q8_pack_weights.argtypes = [_dp, _vp, _vp, _vp]
 lib.q8_conv_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_conv_u8.argtypes = [_dp, _i, _i, _i, _vp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_u8_prepare.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
+lib.q8_quantize_weights_per_channel.argtypes = [_vp, _i, _sz, _i, _vp, _vp, _vp]
+lib.q8_quantize_bias_per_channel.argtypes = [_vp, _i, _f, _vp, _vp, _vp]
+lib.q8_requant_scales.argtypes = [_f, _vp, _i, _f, _vp, _vp]
+lib.q8_conv_int8_per_channel.argtypes = [_dp, _vp, _vp, _vp, _vp, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_quantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
@@ -235,6 +240,45 @@ def conv_u8(desc, in_u8, out_u8, res_u8, z_x, z_w_packed, bias, tap_sums, q_x, q
                           _ptr(bias, torch.int32), _ptr(tap_sums, torch.int32), q_x, q_w, q_out,
                           _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
                           _ptr(acc_dump, torch.int32), _stream()))
+    return out
+
+
+def quantize_weights_per_channel(W, p=7):
+    """W fp32 [K, ...] -> (q_w fp32 [K], z_w int8 like W), one factor per output channel."""
+    K = W.shape[0]
+    q_w = torch.empty(K, dtype=torch.float32, device=W.device)
+    z_w = torch.empty(W.shape, dtype=torch.int8, device=W.device)
+    _check(lib.q8_quantize_weights_per_channel(_ptr(W, torch.float32), K, W.numel() // max(K, 1),
+                                               p, _ptr(q_w, torch.float32), _ptr(z_w, torch.int8),
+                                               _stream()))
+    return q_w, z_w
+
+
+def quantize_bias_per_channel(b, q_x, q_w):
+    z = torch.empty(b.shape, dtype=torch.int32, device=b.device)
+    _check(lib.q8_quantize_bias_per_channel(_ptr(b, torch.float32), b.numel(), q_x,
+                                            _ptr(q_w, torch.float32), _ptr(z, torch.int32),
+                                            _stream()))
+    return z
+
+
+def requant_scales(q_x, q_w, q_out):
+    m = torch.empty(q_w.shape, dtype=torch.float32, device=q_w.device)
+    _check(lib.q8_requant_scales(q_x, _ptr(q_w, torch.float32), q_w.numel(), q_out,
+                                 _ptr(m, torch.float32), _stream()))
+    return m
+
+
+def conv_int8_per_channel(desc, z_x, z_w_packed, bias_i32, m, q_out, residual=None, q_res=0.0,
+                          out=None, acc_dump=None):
+    if out is None:
+        ocs = desc.out_c_stride or desc.K
+        out = torch.empty((desc.N, desc.Ho, desc.Wo, ocs), dtype=torch.int8, device=z_x.device)
+    _check(lib.q8_conv_int8_per_channel(C.byref(desc), _ptr(z_x, torch.int8),
+                                        _ptr(z_w_packed, torch.int8), _ptr(bias_i32, torch.int32),
+                                        _ptr(m, torch.float32), q_out, _ptr(residual, torch.int8),
+                                        q_res, _ptr(out, torch.int8), _ptr(acc_dump, torch.int32),
+                                        _stream()))
     return out
 
 

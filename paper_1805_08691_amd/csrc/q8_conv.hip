@@ -164,6 +164,7 @@ namespace {
 struct U8Flags {
   int in_u8, out_u8, res_u8;
   const int32_t* tap_sums;
+  const float* m_vec = nullptr;     // per-output-channel scales (replace q_x * q_w / q_out)
 };
 
 int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
@@ -226,6 +227,12 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   p.M = (int)M;
   p.in_u8 = u.in_u8; p.out_u8 = u.out_u8; p.res_u8 = u.res_u8;
   p.tap_sums = u.tap_sums;
+  p.m_vec = u.m_vec;
+  if (u.m_vec) {
+    Q8_REQUIRE(stream_capable(d), Q8_EUNSUPPORTED);
+    Q8_REQUIRE(!(u.in_u8 || u.out_u8 || u.res_u8), Q8_EUNSUPPORTED);
+    Q8_REQUIRE(q8_aligned(u.m_vec, 16), Q8_EALIGN);
+  }
   if (u.in_u8 || u.out_u8 || u.res_u8) {
     // unsigned codes: the streaming kernel only; an unsigned input whose taps can fall into
     // the padding needs the per-tap filter sums; an unsigned output is a ReLU output
@@ -310,6 +317,18 @@ int q8_conv_u8(const q8_conv_desc* d, int in_unsigned, int out_unsigned, int res
                                 tap_sums},
                      z_x, z_w_packed, bias_eff, q_x, q_w, q_out, residual, q_res, z_y, acc_dump,
                      stream);
+}
+
+int q8_conv_int8_per_channel(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                             const int32_t* bias_i32, const float* m_dev, float q_out,
+                             const int8_t* residual, float q_res, int8_t* z_y,
+                             int32_t* acc_dump, void* stream) {
+  Q8_REQUIRE(m_dev != nullptr, Q8_EINVAL);
+  U8Flags u{0, 0, 0, nullptr};
+  u.m_vec = m_dev;
+  // q_x and q_w only enter through m_dev here: pass neutral factors to the shared checks
+  return conv_launch(d, u, z_x, z_w_packed, bias_i32, 1.0f, 1.0f, q_out, residual, q_res, z_y,
+                     acc_dump, stream);
 }
 
 int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32_t* bias_i32,

@@ -38,6 +38,7 @@ struct ConvParams {
   // the filter sum, folded by the host) and, for taps outside the image, through tap_sums
   const int32_t* __restrict__ tap_sums;   // [(R+1)*(S+1)][K] prefix sums of the filter, or null
   int in_u8, out_u8, res_u8;
+  const float* __restrict__ m_vec;   // [K] per-output-channel scales replacing m, or null
   float m, m_r;
   int relu;
   int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
@@ -155,6 +156,25 @@ __device__ __forceinline__ void load_bias16(const ConvParams& p, int ch, int (&b
   }
 }
 
+// Per-channel scales of the 16 channels (1 where the channel is beyond K).
+__device__ __forceinline__ void load_scale16(const ConvParams& p, int ch, float (&mv)[16]) {
+  const int nvalid = p.K - ch;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) mv[e] = 1.0f;
+  if (nvalid >= 16 && (p.K & 3) == 0) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const v4i q = *reinterpret_cast<const v4i*>(p.m_vec + ch + 4 * a);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) mv[4 * a + k] = __int_as_float(q[k]);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      if (e < nvalid) mv[e] = p.m_vec[ch + e];
+  }
+}
+
 // The 16 residual codes, packed four to a word (zero where absent).
 __device__ __forceinline__ void load_res16(const ConvParams& p, int pix, int ch, int (&rw)[4]) {
   rw[0] = rw[1] = rw[2] = rw[3] = 0;
@@ -197,8 +217,15 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
     }
   }
   float t[16];
+  if (p.m_vec) {
+    float mv[16];
+    load_scale16(p, ch, mv);
 #pragma unroll
-  for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * p.m;
+    for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * mv[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t[e] = (float)v[e] * p.m;
+  }
   if (p.res) {
     const int res_add = p.res_u8 ? 128 : 0;        // stored byte + 128 = unsigned code
 #pragma unroll
@@ -243,16 +270,18 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
 // byte permutes to pack four codes per word.  Bit-identical to finish16.
 // U8: the output may be unsigned codes stored minus 128 (run-time flag: a different clamp
 // and one XOR per packed word); RES_U8: the residual holds such codes.
-template <bool HAS_RES, bool U8 = false, bool RES_U8 = false>
+// PC: one scale per output channel (mv) instead of p.m.
+template <bool HAS_RES, bool U8 = false, bool RES_U8 = false, bool PC = false>
 __device__ __forceinline__ void finish16_fast(const ConvParams& p, int pix, int ch,
-                                              const int (&v)[16], const int (&rw)[4]) {
+                                              const int (&v)[16], const int (&rw)[4],
+                                              const float (&mv)[16]) {
   const bool out_u8 = U8 && p.out_u8;
   const float lo = (p.relu || out_u8) ? 0.0f : -128.0f;   // ReLU folded into the lower bound
   const float hi = out_u8 ? 255.0f : 127.0f;
   unsigned r[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
-    float t = (float)v[e] * p.m;
+    float t = (float)v[e] * (PC ? mv[e] : p.m);
     if (HAS_RES) {
       float code;
       if (RES_U8)      // stored byte ^ 0x80 = the unsigned code: one unsigned byte convert

@@ -220,8 +220,9 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
         load_res16(p, pix, ch, rw);
 #pragma unroll
         for (int e = 0; e < 16; ++e) v[e] += b[e];
-        if (p.res) finish16_fast<true>(p, pix, ch, v, rw);
-        else finish16_fast<false>(p, pix, ch, v, rw);
+        const float no_scales[16] = {};
+        if (p.res) finish16_fast<true>(p, pix, ch, v, rw, no_scales);
+        else finish16_fast<false>(p, pix, ch, v, rw, no_scales);
       } else {
         epilogue16(p, pix, ch, v);
       }

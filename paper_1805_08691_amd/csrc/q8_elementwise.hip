@@ -222,6 +222,44 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const int8_t* __re
   }
 }
 
+// One filter per workgroup: max |w| over the row, q = max / (2^p - 1) (1 for an all-zero
+// row), then Eq. Q on the row with that factor.
+__global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const float* __restrict__ w,
+                                                                 size_t row_len, float hi, float lo,
+                                                                 float* __restrict__ q_out,
+                                                                 int8_t* __restrict__ z) {
+  const float* row = w + (size_t)blockIdx.x * row_len;
+  float m = 0.0f;
+  for (size_t i = threadIdx.x; i < row_len; i += kThreads) m = fmaxf(m, fabsf(row[i]));
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  __shared__ float wave_max[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+  const float q = m > 0.0f ? __fdiv_rn(m, hi) : 1.0f;
+  if (threadIdx.x == 0) q_out[blockIdx.x] = q;
+  int8_t* zr = z + (size_t)blockIdx.x * row_len;
+  for (size_t i = threadIdx.x; i < row_len; i += kThreads) zr[i] = (int8_t)quant1(row[i], q, lo, hi);
+}
+
+__global__ void quantize_bias_pc_kernel(const float* __restrict__ b, int K, double q_x,
+                                        const float* __restrict__ q_w, int32_t* __restrict__ z) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= K) return;
+  const double q = q_x * (double)q_w[k];
+  double t = rint(__ddiv_rn((double)b[k], q));
+  t = fmin(fmax(t, -2147483648.0), 2147483647.0);
+  z[k] = (int32_t)t;
+}
+
+__global__ void requant_scales_kernel(float q_x, const float* __restrict__ q_w, int K, float q_out,
+                                      float* __restrict__ m) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= K) return;
+  const float prod = __fmul_rn(q_x, q_w[k]);      // the x rule: factor of the accumulator
+  m[k] = __fdiv_rn(prod, q_out);
+}
+
 // Unsigned p = 8 codes (0..255) are kept as code - 128 in an int8 byte.
 __global__ __launch_bounds__(kThreads) void quantize_u8_kernel(const float* __restrict__ r,
                                                                size_t n, float q,
@@ -411,6 +449,37 @@ int q8_dequantize(const int8_t* z_dev, size_t n, float q, float* r_dev, void* st
   if (head > n) head = n;
   hipLaunchKernelGGL(dequantize_kernel, dim3(blocks_for((n + 3) / 4)), dim3(kThreads), 0,
                      (hipStream_t)stream, z_dev, n, head, q, r_dev);
+  return q8_launch_status();
+}
+
+int q8_quantize_weights_per_channel(const float* w_dev, int K, size_t row_len, int p,
+                                    float* q_w_dev, int8_t* z_w_dev, void* stream) {
+  Q8_REQUIRE(p >= 1 && p <= 7 && K >= 0, Q8_EINVAL);
+  if (K == 0 || row_len == 0) return Q8_OK;
+  Q8_REQUIRE(w_dev != nullptr && q_w_dev != nullptr && z_w_dev != nullptr, Q8_EINVAL);
+  Q8_REQUIRE(q8_aligned(w_dev, 4) && q8_aligned(q_w_dev, 4), Q8_EALIGN);
+  hipLaunchKernelGGL(quantize_rows_kernel, dim3(K), dim3(kThreads), 0, (hipStream_t)stream, w_dev,
+                     row_len, (float)((1 << p) - 1), -(float)(1 << p), q_w_dev, z_w_dev);
+  return q8_launch_status();
+}
+
+int q8_quantize_bias_per_channel(const float* b_dev, int K, float q_x, const float* q_w_dev,
+                                 int32_t* z_b_dev, void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q_x) && K >= 0, Q8_EINVAL);
+  if (K == 0) return Q8_OK;
+  Q8_REQUIRE(b_dev != nullptr && q_w_dev != nullptr && z_b_dev != nullptr, Q8_EINVAL);
+  hipLaunchKernelGGL(quantize_bias_pc_kernel, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                     (hipStream_t)stream, b_dev, K, (double)q_x, q_w_dev, z_b_dev);
+  return q8_launch_status();
+}
+
+int q8_requant_scales(float q_x, const float* q_w_dev, int K, float q_out, float* m_dev,
+                      void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q_x) && q8_finite_pos(q_out) && K >= 0, Q8_EINVAL);
+  if (K == 0) return Q8_OK;
+  Q8_REQUIRE(q_w_dev != nullptr && m_dev != nullptr, Q8_EINVAL);
+  hipLaunchKernelGGL(requant_scales_kernel, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                     (hipStream_t)stream, q_x, q_w_dev, K, q_out, m_dev);
   return q8_launch_status();
 }
 

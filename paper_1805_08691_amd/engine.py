@@ -30,8 +30,12 @@ class Engine:
     again before forward() returns.  A layer's launch latency and its tail then overlap the
     other half's work.  Results are the same bits as with one stream."""
 
-    def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False):
+    def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
+                 per_channel_weights=False):
         self.net = net
+        assert not (unsigned_activations and per_channel_weights)
+        self.per_channel = per_channel_weights
+        self.m_vec = {}       # conv name -> per-channel scales (per_channel_weights)
         # Unsigned p = 8 codes for the outputs of ReLU layers (the calibration paragraph's
         # rule for non-negative tensors) and for max-poolings of such tensors; stored as
         # code - 128.  Everything else stays signed p = 7.
@@ -175,7 +179,20 @@ class Engine:
     def set_factors(self, q):
         self.q = {k: float(v) for k, v in q.items()}
 
+    def quantize_weights_per_channel(self):
+        for op in self.net.convs():
+            Wf, bf = self.folded[op.name]
+            q_w, z_w = B.quantize_weights_per_channel(Wf, P_W)
+            self.zw_dense = getattr(self, "zw_dense", {})
+            self.zw_dense[op.name] = z_w
+            self.qw[op.name] = q_w
+            self.wq[op.name] = (B.pack_weights(self.desc[op.name], z_w),
+                                B.quantize_bias_per_channel(bf, self.q[op.src], q_w))
+            self.m_vec[op.name] = B.requant_scales(self.q[op.src], q_w, self.q[op.dst])
+
     def quantize_weights(self):
+        if self.per_channel:
+            return self.quantize_weights_per_channel()
         slots = {}
         for op in self.net.convs():
             Wf, _ = self.folded[op.name]
@@ -254,6 +271,11 @@ class Engine:
         res = self.act[op.res][lo:lo + n] if op.res else None
         q_res = self.q[op.res] if op.res else 0.0
         U = self.unsigned
+        if self.per_channel:
+            B.conv_int8_per_channel(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed,
+                                    bias, self.m_vec[op.name], self.q[op.dst], res, q_res,
+                                    out=self.act[op.dst][lo:lo + n], acc_dump=acc_dump)
+            return
         if op.src in U or op.dst in U or op.res in U:
             B.conv_u8(self.conv_desc(op, n), op.src in U, op.dst in U, op.res in U,
                       self.act[op.src][lo:lo + n], packed, bias, self.taps.get(op.name),

@@ -98,6 +98,18 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.q8_quantize_u8(fake, 4, 0.0, fake, None) == -1
     assert L.q8_dequantize_u8(None, 4, 1.0, fake, None) == -1
     assert L.q8_dequantize_u8(None, 0, 1.0, None, None) == 0
+    # per-channel weight factors
+    pc = (fake, fake, None, fake, 1.0, None, 0.0, fake, None, None)
+    assert L.q8_conv_int8_per_channel(C.byref(wide), fake, fake, None, None, 1.0, None, 0.0, fake,
+                                      None, None) == -1          # no scale vector
+    assert L.q8_conv_int8_per_channel(C.byref(d), *pc) == -2     # K <= 32: not the main kernel
+    assert L.q8_conv_int8_per_channel(C.byref(wide), fake, fake, None, C.c_void_p(0x1004), 1.0,
+                                      None, 0.0, fake, None, None) == -3
+    assert L.q8_quantize_weights_per_channel(fake, 4, 16, 9, fake, fake, None) == -1   # p
+    assert L.q8_quantize_weights_per_channel(None, 4, 16, 7, fake, fake, None) == -1
+    assert L.q8_quantize_weights_per_channel(None, 0, 16, 7, None, None, None) == 0
+    assert L.q8_quantize_bias_per_channel(fake, 4, 0.0, fake, fake, None) == -1
+    assert L.q8_requant_scales(1.0, fake, 4, 0.0, fake, None) == -1
     assert B.packed_weight_bytes(d) == 16 * 3 * 3 * 16
     assert B.packed_weight_bytes(B.ConvDesc(1, 8, 8, 3, 64, 7, 7)) == 64 * 7 * 2 * 16
     assert L.q8_maxpool_i8(fake, 1, 8, 8, 4, 3, 3, 2, 3, 4, 4, fake, None) == -1   # pad >= window

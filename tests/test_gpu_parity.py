@@ -347,6 +347,56 @@ def test_conv_unsigned_activations(B, idx):
     assert sat < 0.5
 
 
+# ------------------------------------------------------------------ per-channel weights
+def test_per_channel_weight_preparation(B):
+    rng = np.random.default_rng(91)
+    K = 70
+    W = (rng.standard_normal((K, 3, 3, 16)) * rng.uniform(0.01, 3.0, K)[:, None, None, None])
+    W = W.astype(np.float32)
+    W[5] = 0                                            # an all-zero filter
+    b = rng.standard_normal(K).astype(np.float32)
+    z_o, q_o = orc.quantize_weights_pc(W)
+    q_g, z_g = B.quantize_weights_per_channel(dev(W))
+    assert np.array_equal(host(q_g), q_o) and np.array_equal(host(z_g), z_o)
+    q_x, q_out = np.float32(0.0231), np.float32(0.177)
+    assert np.array_equal(host(B.quantize_bias_per_channel(dev(b), float(q_x), q_g)),
+                          orc.Q31_bias_pc(b, q_x, q_o))
+    assert np.array_equal(host(B.requant_scales(float(q_x), q_g, float(q_out))),
+                          orc.requant_scales_pc(q_x, q_o, q_out))
+
+
+@pytest.mark.parametrize("geom,with_res", [
+    (dict(N=2, H=14, W=14, C=64, K=160, R=3, S=3, pad_h=1, pad_w=1), True),
+    (dict(N=2, H=28, W=28, C=64, K=128, R=1, S=1), False),
+    (dict(N=1, H=17, W=17, C=48, K=72, R=1, S=7, pad_w=3), True),
+    (dict(N=2, H=30, W=30, C=3, K=64, R=3, S=3, in_c_stride=4), False),     # unpadded image
+])
+def test_conv_per_channel_scales(B, geom, with_res):
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(g.K + g.C)
+    Cs = g.in_c_stride or g.C
+    x = rng.integers(-128, 128, (g.N, g.H, g.W, Cs)).astype(np.int8)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, g.K).astype(np.int32)
+    acc_o = orc.conv_i8(g, x, w, b)
+    base = 40.0 / (5476.0 * np.sqrt(g.R * g.S * g.C))
+    m = (base * rng.uniform(0.3, 3.0, g.K)).astype(np.float32)
+    res = rng.integers(-128, 128, acc_o.shape).astype(np.int8) if with_res else None
+    m_r = np.float32(0.3)
+    want = orc.requant_pc(acc_o, m, True, res, m_r)
+    d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                   g.dil_h, g.dil_w, relu=1, in_c_stride=Cs)
+    packed = B.pack_weights(d, dev(w))
+    dump = torch.zeros(acc_o.shape, dtype=torch.int32, device="cuda")
+    for use_dump in (True, False):             # general epilogue, then the fast one
+        got = B.conv_int8_per_channel(d, dev(x), packed, dev(b), dev(m), 1.0,
+                                      None if res is None else dev(res), float(m_r),
+                                      acc_dump=dump if use_dump else None)
+        if use_dump:
+            assert np.array_equal(host(dump), acc_o)
+        assert np.array_equal(host(got), want)
+
+
 @pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
 def test_conv_channel_slice_of_concat(B, out_pad, out_off):
     geom = dict(N=2, H=9, W=9, C=32, K=40, R=3, S=3, pad_h=1, pad_w=1)
@@ -496,7 +546,8 @@ def test_config2_bottleneck_block(B):
             assert np.array_equal(host(eng.act[o]), acts[o])
 
 
-def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False):
+def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
+                          per_channel=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -507,7 +558,7 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
     U = onet.unsigned_tensors(net) if unsigned else set()
     q = onet.calibrate(net, folded, (wl.input_batch(cfg_id, net, cal_batch, 100 + i)
                                      for i in range(n_cal)), unsigned=U)
-    qparams = onet.quantize_params(net, folded, q)
+    qparams = onet.quantize_params(net, folded, q, per_channel=per_channel)
     x = wl.input_batch(cfg_id, net, batch, 0)
     z_in = orc.Q(x[picks], q[net.input], 7)
     acts = onet.forward_i8(net, qparams, q, z_in, unsigned=U)
@@ -515,14 +566,18 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
     def codes(name, a):       # the GPU's bytes as the oracle's codes
         return (a.astype(np.int16) + 128).astype(np.uint8) if name in U else a
 
-    eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned)
+    eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned,
+                 per_channel_weights=per_channel)
     assert eng.unsigned == U
     eng.load_params(params)
     eng.fold()
     eng.set_factors(q)
     eng.quantize_weights()
     for name, qp in qparams.items():
-        assert np.float32(eng.qw[name]) == qp["q_w"], name
+        if per_channel:
+            assert np.array_equal(host(eng.qw[name]), qp["q_w"]), name
+        else:
+            assert np.float32(eng.qw[name]) == qp["q_w"], name
         bias = host(eng.wq[name][1])
         if name in eng.taps:       # reads unsigned codes: 128 * (filter sum) is folded in
             bias = bias - 128 * qp["z_w"].astype(np.int64).reshape(bias.size, -1).sum(axis=1)
@@ -565,6 +620,10 @@ def test_resnet50_unsigned_activations(B):
     # ResNet-50 with unsigned p = 8 codes on every ReLU output (the paper's precision for
     # non-negative activations), batch 64 in the benchmark's launch configuration
     _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, unsigned=True)
+
+
+def test_resnet50_per_channel_weights(B):
+    _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, per_channel=True)
 
 
 def test_resnet50_after_sparsity_removal(B):

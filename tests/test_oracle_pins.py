@@ -625,3 +625,50 @@ def test_unsigned_network_reading_on_a_small_resnet():
         y = orc.D_u8(acts[o], q[o]) if mode else orc.D(acts[o], q[o])
         err[mode] = float(np.sqrt(np.mean((y - ref) ** 2)))
     assert err[True] < err[False]
+
+
+# ----------------------------------------------------------------------------------------
+# per-output-channel weight factors
+# ----------------------------------------------------------------------------------------
+def test_per_channel_weights_and_scales():
+    rng = np.random.default_rng(51)
+    W = (rng.standard_normal((6, 3, 3, 5)) * np.array([.01, .1, 1, 3, 0, 7])[:, None, None, None])
+    W = W.astype(np.float32)
+    z_w, q_w = orc.quantize_weights_pc(W)
+    for k in range(6):
+        mx = np.abs(W[k]).max()
+        if mx == 0:
+            assert q_w[k] == 1 and not z_w[k].any()           # all-zero filter: q = 1
+            continue
+        assert q_w[k] == np.float32(mx) / np.float32(127)
+        assert np.abs(z_w[k].astype(int)).max() == 127        # the row's extreme hits the last code
+        assert np.array_equal(z_w[k], orc.Q(W[k], q_w[k], 7))
+    b = rng.standard_normal(6).astype(np.float32)
+    q_x = np.float32(0.0173)
+    z_b = orc.Q31_bias_pc(b, q_x, q_w)
+    for k in range(6):
+        q = fl64(F(float(q_x)) * F(float(q_w[k])))
+        assert z_b[k] == clamp(round_half_even(fl64(F(float(b[k])) / q)), -2**31, 2**31 - 1)
+    m = orc.requant_scales_pc(q_x, q_w, np.float32(0.31))
+    for k in range(6):
+        want = fl32(fl32(F(float(q_x)) * F(float(q_w[k]))) / F(float(np.float32(0.31))))
+        assert F(float(m[k])) == want
+
+
+def test_requant_per_channel_against_exact_rational():
+    rng = np.random.default_rng(52)
+    K = 9
+    acc = rng.integers(-90000, 90000, (40, K)).astype(np.int32)
+    m = (rng.uniform(0.0005, 0.004, K)).astype(np.float32)
+    res = rng.integers(-128, 128, (40, K)).astype(np.int8)
+    m_r = np.float32(0.37)
+    got = orc.requant_pc(acc, m, True, res, m_r)
+    for p in range(40):
+        for k in range(K):
+            t = fl32(fl32(F(int(acc[p, k]))) * F(float(m[k])))
+            t = fl32(t + fl32(F(int(res[p, k])) * F(float(m_r))))
+            t = max(t, F(0))
+            assert got[p, k] == round_half_even(clamp(t, F(-128), F(127))), (p, k)
+    # equal factors: the per-tensor tail
+    same = np.full(K, np.float32(0.0021), np.float32)
+    assert np.array_equal(orc.requant_pc(acc, same, False), orc.requant(acc, same[0], False))
