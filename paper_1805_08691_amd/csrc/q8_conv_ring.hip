@@ -28,9 +28,9 @@ namespace {
 
 constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
 
-// U8 = 1: the build of the kernel that also handles unsigned activation codes (border
-// correction, unsigned residual / output); kept apart so that the signed build's register
-// count, and with it the number of resident wavefronts, stays what it is.
+// U8 = 1: the extended build of the kernel: unsigned activation codes (border correction,
+// unsigned residual / output) and per-output-channel scales; kept apart so that the plain
+// build's register count, and with it the number of resident wavefronts, stays what it is.
 template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8>
 __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
@@ -435,27 +435,35 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   const bool fast_tile = p.vec16 && !p.acc_dump && ch0 + BC <= p.K && pix0 + BP <= p.M;
   auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
     // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
-    // residual, signed residual, unsigned residual)
+    // residual, signed residual, unsigned residual); 6, 7: fast with per-channel scales
+    // (no residual, residual)
     constexpr int MODE = decltype(mode_c)::value;
 #pragma unroll
-    for (int j = 0; j < TP; ++j) {
-      const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
-      if (MODE == 0 && pix >= p.M) continue;
+    for (int i = 0; i < TC; ++i) {
+      const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+      if (MODE == 0 && ch >= p.K) continue;
+      float mv[16] = {};
+      if constexpr (MODE >= 6) load_scale16(p, ch, mv);
 #pragma unroll
-      for (int i = 0; i < TC; ++i) {
-        const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-        if (MODE == 0 && ch >= p.K) continue;
+      for (int j = 0; j < TP; ++j) {
+        const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
+        if (MODE == 0 && pix >= p.M) continue;
         int v[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
         if constexpr (MODE == 0) finish16(p, pix, ch, v, res_w[i][j]);
-        else if constexpr (MODE <= 2) finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j]);
-        else finish16_fast<MODE >= 4, true, MODE == 5>(p, pix, ch, v, res_w[i][j]);
+        else if constexpr (MODE <= 2) finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j], mv);
+        else if constexpr (MODE <= 5)
+          finish16_fast<MODE >= 4, true, MODE == 5>(p, pix, ch, v, res_w[i][j], mv);
+        else finish16_fast<MODE == 7, false, false, true>(p, pix, ch, v, res_w[i][j], mv);
       }
     }
   };
   if (!fast_tile) finish_all(std::integral_constant<int, 0>{});
-  else if (!p.res) finish_all(std::integral_constant<int, U8 ? 3 : 1>{});
+  else if (U8 && p.m_vec) {
+    if (p.res) finish_all(std::integral_constant<int, 7>{});
+    else finish_all(std::integral_constant<int, 6>{});
+  } else if (!p.res) finish_all(std::integral_constant<int, U8 ? 3 : 1>{});
   else if (U8 && p.res_u8) finish_all(std::integral_constant<int, 5>{});
   else finish_all(std::integral_constant<int, U8 ? 4 : 2>{});
 #endif  // __HIP_DEVICE_COMPILE__
@@ -527,8 +535,8 @@ constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]
 int num_stream_variants() { return kNumRingVariants; }
 int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
   if (variant < 0 || variant >= kNumRingVariants) return Q8_EINVAL;
-  if (p.in_u8 | p.out_u8 | p.res_u8) {
-    // variants without an unsigned-code build fall back to the 128 x 128 ring of 3
+  if (p.in_u8 | p.out_u8 | p.res_u8 | (p.m_vec != nullptr)) {
+    // variants without an extended build fall back to the 128 x 128 ring of 3
     const RingVariant& v = kRingVariants[variant].launch_u8 ? kRingVariants[variant] : kRingVariants[1];
     return v.launch_u8(p, stream);
   }
