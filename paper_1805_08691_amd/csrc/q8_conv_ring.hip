@@ -1,7 +1,8 @@
 // Main int8 implicit-GEMM convolution kernel (Eq. x / Eq. A' of arxiv 1805.08691) for
-// gfx950: C % 16 == 0, more than 32 output channels, at most 32 filter taps.
+// gfx950: C % 16 == 0 (or an unpadded 4-channel image), more than 32 output channels, at
+// most 32 filter taps.
 //
-// One workgroup (4 wavefronts) per output tile.  Chunks go from global memory straight into
+// One workgroup (4 or 8 wavefronts) per output tile.  Chunks go from global memory straight into
 // LDS (buffer_load_dwordx4 ... lds, no register staging) through a ring of STAGES buffers,
 // so several reduction steps of loads are in flight per workgroup while the MFMAs of the
 // current step run.  One bare s_barrier per reduction step.
@@ -11,9 +12,9 @@
 // lane l fills row l / CHUNKS, physical slot l % CHUNKS, and therefore fetches logical chunk
 // (l % CHUNKS) ^ swz(row) of that row (XOR swizzle: conflict-free ds_read_b128 operand reads).
 //
-// Addressing uses raw buffer descriptors: a per-lane 32-bit offset that is computed once,
-// plus a wave-uniform offset per reduction step, so a load costs a handful of VALU
-// instructions.  A chunk that must read as zero (padding, pixel or channel beyond the
+// Addressing uses raw buffer descriptors: a per-lane 32-bit offset that is computed once
+// (for activations: once per filter tap), plus a wave-uniform scalar offset per reduction
+// step, so the loads of the steady state need no vector arithmetic.  A chunk that must read as zero (padding, pixel or channel beyond the
 // tensor, reduction tail) gets an offset beyond the descriptor's size: the hardware's
 // range check then returns zeros.
 //
@@ -396,9 +397,9 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0), other counters untouched
   // steady state: every step finds STAGES-2 later steps in flight and issues one more
   int kt = 0;
-  // rounds of STAGES steps whose ring buffers are known at compile time
+  // passes over the ring: STAGES steps whose buffers are known at compile time
   for (; kt + 2 * STAGES - 2 < nk; kt += STAGES) {
-    auto round = [&](auto self, auto s_c) __attribute__((always_inline)) -> void {
+    auto ring_pass = [&](auto self, auto s_c) __attribute__((always_inline)) -> void {
       constexpr int S = decltype(s_c)::value;
       if constexpr (S < STAGES) {
         step(kt + S, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
         self(self, integral_constant<int, S + 1>{});
       }
     };
-    round(round, integral_constant<int, 0>{});
+    ring_pass(ring_pass, integral_constant<int, 0>{});
   }
   for (; kt + STAGES - 1 < nk; ++kt)
     step(kt, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
