@@ -18,8 +18,12 @@
 // tensor, reduction tail) gets an offset beyond the descriptor's size: the hardware's
 // range check then returns zeros.
 //
-// UNIFORM (C % BK == 0): every lane of the block is in the same filter tap during one
-// reduction step, so the tap offset is a scalar.  Otherwise each lane tracks its own tap.
+// UNIFORM = 1 (C % BK == 0): every lane of the block is in the same filter tap during one
+// reduction step, so the tap offset is a scalar.  UNIFORM = 2 (S == 1 and BK % C == 0: a
+// column filter over few channels, which is also how an unpadded 4-channel image arrives):
+// a step covers BK / C whole taps; which of them a lane reads is fixed, and all lanes move
+// on by BK / C taps per step, so a lane adds a constant to a scalar.  UNIFORM = 0: each
+// lane tracks its own tap.
 #include <type_traits>
 #include "q8_common.h"
 #include "q8_conv_common.h"
@@ -105,7 +109,8 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     unsigned mask = 0;
     int off = 0;
     if (pix < p.M && pointwise) {
-      off = pix * p.in_cs + (UNIFORM ? lchunk * 16 : 0);     // output pixel = input pixel (no padding)
+      // output pixel = input pixel, no padding
+      off = pix * p.in_cs + (UNIFORM == 1 ? lchunk * 16 : 0);
       mask = 1u;
     } else if (pix < p.M) {
       const int n = fast_div(pix, p.div_img_m, p.div_img_s);
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       const int wo = rem - ho * p.Wo;
       const int hi0 = ho * p.stride_h - p.pad_h;
       const int wi0 = wo * p.stride_w - p.pad_w;
-      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + x_shift + (UNIFORM ? lchunk * 16 : 0);
+      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + x_shift + (UNIFORM == 1 ? lchunk * 16 : 0);
       if (p.dil_h == 1 && p.dil_w == 1) {
         // taps inside the image: rows [r_lo, r_hi), columns [s_lo, s_hi)
         const unsigned cols = bits_below(min(p.S, p.W - wi0)) & ~bits_below(-wi0);
@@ -140,7 +145,18 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   // UNIFORM: scalars shared by the block.  Otherwise: this lane's own chunk.
   int step_base = 0;                     // reduction byte offset of the next step to issue
   int tap = 0, tap_s = 0, tap_c = 0, tap_delta = 0;
-  if (!UNIFORM) {
+  // UNIFORM == 2: the lane's tap inside a step and its channel offset inside that tap
+  const int row_step = p.dil_h * p.W * p.in_cs;
+  const int tap_l = UNIFORM == 2 ? (lchunk * 16) / p.C : 0;
+  const int lane_red = lchunk * 16;                    // the lane's reduction byte inside a step
+  int b_rowoff[B_LOADS];
+  unsigned b_mask_l[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    b_rowoff[j] = b_off[j] + tap_l * row_step + (lane_red - tap_l * p.C);
+    b_mask_l[j] = b_mask[j] >> tap_l;
+  }
+  if (UNIFORM == 0) {
     const int red = lchunk * 16;
     tap = red / p.C;
     tap_c = red - tap * p.C;
@@ -161,7 +177,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 
   auto issue_stage = [&](int buf) {
     int8_t* stage = lds + buf * STAGE_BYTES;
-    if constexpr (UNIFORM) {
+    if constexpr (UNIFORM == 1) {
 #pragma unroll
       for (int j = 0; j < A_LOADS; ++j)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -188,6 +204,28 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       tap_s = wrap_s ? 0 : tap_s;
       tap_delta += wrap_s ? dh_step : 0;
       tap_changed = wrap_c;
+    } else if constexpr (UNIFORM == 2) {
+      const bool red_ok = step_base + lane_red < p.red_len;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        const int voff = red_ok ? a_off[j] : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
+            voff, step_base, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < B_LOADS; ++j) {
+        const bool ok = red_ok && ((b_mask_l[j] >> tap) & 1u);
+        const int voff = ok ? b_rowoff[j] : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc_x,
+            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
+            voff, tap_delta, 0, 0);
+      }
+      step_base += BK;
+      const int taps_per_step = BK / p.C;
+      tap += taps_per_step;
+      tap_delta += taps_per_step * row_step;
     } else {
       const bool red_ok = step_base + lchunk * 16 < p.red_len;
 #pragma unroll
@@ -375,7 +413,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (UNIFORM && decltype(issue_c)::value) {
+    if constexpr (UNIFORM == 1 && decltype(issue_c)::value) {
       if (tap_changed) refresh_taps();
     }
   };
@@ -387,7 +425,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   for (int s = 0; s < STAGES - 1; ++s)
     if (s < nk) {
       issue_stage(s);
-      if constexpr (UNIFORM) {
+      if constexpr (UNIFORM == 1) {
         if (tap_changed) refresh_taps();
       }
     }
@@ -493,6 +531,11 @@ int launch_ring(ConvParams& p, hipStream_t stream) {
   if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
   if (p.C % BK == 0)
     return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1, U8>(p, dim3((unsigned)nblk), stream);
+  if constexpr (WP * TP * 32 == 128 && WC * TC * 32 == 64 && STAGES == 2 && !U8) {
+    // the tile the first (image) layers use also has the column-filter build
+    if (p.S == 1 && BK % p.C == 0)
+      return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 2, U8>(p, dim3((unsigned)nblk), stream);
+  }
   return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 0, U8>(p, dim3((unsigned)nblk), stream);
 }
 
