@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload: 1..5 (BASELINE configs)")
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the per-layer timing with caches flushed before every layer")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
                     help="2: the layers behind the first pooling op run as two concurrent "
@@ -235,7 +237,31 @@ def main():
         f"each launch interval: sum {med.sum():.1f} us vs one-stream step {serial_us:.1f} us "
         f"(timed step, {eng.n_streams} stream(s): {ms_per_step * 1e3:.1f} us)")
 
-    # ---------------- HBM-bound passes: max-abs (calibration), quantise, dequantise ---------
+    # ---------------- the same launches cold: caches flushed before every layer -------------
+    # A 1 GiB device copy (four times the 256 MB last-level cache) runs before each layer's
+    # launches, so activations, residual and filters come from HBM.
+    cold = np.zeros(len(ops_list))
+    if not args.no_cold:
+        flush_src = torch.ones(512 << 20, dtype=torch.int8, device="cuda")
+        flush_dst = torch.empty_like(flush_src)
+        cold_reps = 5
+        cdur = np.zeros((cold_reps, len(ops_list)))
+        for r in range(cold_reps):
+            e0 = [torch.cuda.Event(enable_timing=True) for _ in ops_list]
+            e1 = [torch.cuda.Event(enable_timing=True) for _ in ops_list]
+            for i, op in enumerate(ops_list):
+                flush_dst.copy_(flush_src)
+                e0[i].record()
+                for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
+                    eng.run_ops([op], lo, n)
+                e1[i].record()
+            torch.cuda.synchronize()
+            for i in range(len(ops_list)):
+                cdur[r, i] = e0[i].elapsed_time(e1[i]) * 1e3
+        cold = np.maximum(np.median(cdur, axis=0) - ev_take, 0.0)
+        del flush_src, flush_dst
+
+    # ---------------- measured ceilings: a plain device copy, a register-resident MFMA loop --
     def timed_us(fn, reps=20):
         fn()
         torch.cuda.synchronize()
@@ -246,6 +272,23 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps
+    cp_src = torch.ones(1 << 30, dtype=torch.int8, device="cuda")
+    cp_dst = torch.empty_like(cp_src)
+    t_copy = timed_us(lambda: cp_dst.copy_(cp_src), reps=10)
+    del cp_src, cp_dst
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    probe_ops = [0]
+    def mfma_probe():
+        probe_ops[0] = B.probe_mfma_i8(2 * n_cu, 20000, sink)
+    t_mfma = timed_us(mfma_probe, reps=3)
+    ceilings = {"device_copy_gbs": round(2 * (1 << 30) / t_copy / 1e3, 1),
+                "mfma_int8_loop_tops": round(probe_ops[0] / t_mfma / 1e6, 1),
+                "compute_units": n_cu}
+    log(f"measured ceilings: 1 GiB device copy {ceilings['device_copy_gbs']:.0f} GB/s (read + write), "
+        f"register-resident int8 MFMA loop {ceilings['mfma_int8_loop_tops']:.0f} TOP/s on {n_cu} CUs")
+
+    # ---------------- HBM-bound passes: max-abs (calibration), quantise, dequantise ---------
     big = torch.randn(64 * 112 * 112 * 64, dtype=torch.float32, device="cuda")   # 205 MB
     slot = torch.zeros(1, dtype=torch.float32, device="cuda")
     t_maxabs = timed_us(lambda: B.calibrate_maxabs(big, slot))
@@ -265,7 +308,7 @@ def main():
 
     layers = []
     by_variant = {}
-    tot_ops = tot_us = tot_bytes = 0.0
+    tot_ops = tot_us = tot_bytes = tot_cold = 0.0
     roof_us = 0.0
     for i, op in enumerate(ops_list):
         if op.kind != "conv":
@@ -275,11 +318,13 @@ def main():
         ops, byts = conv_work(net, op, N)
         ops, byts = ops / n_launch, byts / n_launch          # per launch
         us = float(med[i + 1]) / n_launch
+        us_cold = float(cold[i]) / n_launch
         variant = B.conv_variant(eng.conv_desc(op, n_img))
         bound = "mfma" if ops / byts > RIDGE else "hbm"
         t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)) * 1e6
         layers.append(dict(name=op.name, C=op.C, K=op.K, R=op.R, S=op.S, stride=op.stride,
                            H=net.tensors[op.src].H, variant=variant, us=round(us, 2),
+                           cold_us=round(us_cold, 2),
                            tops=round(ops / us / 1e6, 1), gbs=round(byts / us / 1e3, 1),
                            bound=bound, roof_us=round(t_roof, 2), frac=round(t_roof / us, 3)))
         v = by_variant.setdefault(variant, dict(ops=0.0, us=0.0, bytes=0.0, launches=0))
@@ -287,9 +332,10 @@ def main():
         v["launches"] += n_launch
         tot_ops += ops * n_launch; tot_us += us * n_launch; tot_bytes += byts * n_launch
         roof_us += t_roof * n_launch
+        tot_cold += us_cold * n_launch
     for L in layers:
         log("{name:22s} C={C:<4d} K={K:<4d} {R}x{S}/{stride} H={H:<3d} {variant:30s} {us:8.2f} us "
-            "{tops:7.1f} TOP/s {gbs:7.1f} GB/s  {bound:4s} roof {roof_us:6.2f} us frac {frac:.3f}"
+            "(cold {cold_us:7.2f}) {tops:7.1f} TOP/s {gbs:7.1f} GB/s  {bound:4s} roof {roof_us:6.2f} us frac {frac:.3f}"
             .format(**L))
     dom_name, dom = max(by_variant.items(), key=lambda kv: kv[1]["us"])
     for k, v in by_variant.items():
@@ -371,6 +417,8 @@ def main():
         "int8_conv_tops_one_stream": round(agg_tops, 1),
         "hbm_passes": passes,
         "conv_kernel_us_per_step": round(tot_us, 1),
+        "conv_kernel_us_per_step_cold": round(tot_cold, 1) if not args.no_cold else None,
+        "measured_ceilings": ceilings,
         "one_stream_step_us": round(serial_us, 1),
         "conv_roofline_us_per_step": round(roof_us, 1),
         "roofline": roofline,

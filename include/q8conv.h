@@ -232,6 +232,13 @@ int q8_pool_f32(const float *x_dev, int N, int H, int W, int C, int mode, int R,
                 int stride, int pad, int Ho, int Wo, float *y_dev, int out_c_stride,
                 int out_c_off, void *stream);
 
+/* Measurement only: `blocks` workgroups of four wavefronts each issue 4 * iters
+ * register-resident v_mfma_i32_32x32x32_i8 (65536 int8 ops each), no memory traffic:
+ * ops = blocks * 4 * 4 * iters * 65536.  The caller times the launch; the result is the
+ * int8 matrix-core rate the chip sustains, to set beside the published peak.  sink_dev:
+ * one int32 of device memory (practically never written).                             */
+int q8_probe_mfma_i8(int blocks, int iters, int32_t *sink_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = [
     "q8_u8_prepare", "q8_conv_u8", "q8_quantize_weights_per_channel",
     "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
-    "q8_conv_variant", "q8_conv_force_variant",
+    "q8_conv_variant", "q8_conv_force_variant", "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
 
@@ -90,6 +90,7 @@ lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
 lib.q8_conv_variant.argtypes = [_dp]
 lib.q8_conv_force_variant.argtypes = [_i]
+lib.q8_probe_mfma_i8.argtypes = [_i, _i, _vp, _vp]
 lib.q8_conv_f32_ref.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.q8_maxpool_i8.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
 lib.q8_maxpool_f32.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
@@ -288,6 +289,12 @@ def conv_variant(desc):
 
 def conv_force_variant(index):
     _check(lib.q8_conv_force_variant(int(index)))
+
+
+def probe_mfma_i8(blocks, iters, sink):
+    """Launch the register-resident int8 MFMA loop; returns the int8 ops it performs."""
+    _check(lib.q8_probe_mfma_i8(int(blocks), int(iters), _ptr(sink, torch.int32), _stream()))
+    return blocks * 4 * 4 * iters * 65536
 
 
 def conv_f32_ref(desc, x, w, b=None, res=None, out=None):

@@ -259,6 +259,24 @@ int maxpool_launch(const T* x, int N, int H, int W, int C, int R, int S, int str
   return q8_launch_status();
 }
 
+// Register-resident i8 MFMA loop: what the matrix cores sustain with no operand traffic
+// (four independent accumulator chains per wave, four waves per block).
+typedef int probe_v4i __attribute__((ext_vector_type(4)));
+typedef int probe_v16i __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_i8_probe_kernel(int iters, int32_t* sink) {
+  probe_v4i a = {(int)threadIdx.x, 1, 2, 3}, b = {4, 5, 6, (int)blockIdx.x};
+  probe_v16i c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int i = 0; i < iters; ++i) {
+    c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c3, 0, 0, 0);
+  }
+  int s = 0;
+  for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+  if (s == 0x12345678) sink[0] = s;      // keeps the loop alive; practically never taken
+}
+
 }  // namespace
 
 extern "C" {
@@ -329,6 +347,14 @@ int q8_pool_f32(const float* x_dev, int N, int H, int W, int C, int mode, int R,
 int q8_maxpool_f32(const float* x_dev, int N, int H, int W, int C, int R, int S, int stride, int pad,
                    int Ho, int Wo, float* y_dev, void* stream) {
   return maxpool_launch<float>(x_dev, N, H, W, C, R, S, stride, pad, Ho, Wo, y_dev, stream);
+}
+
+int q8_probe_mfma_i8(int blocks, int iters, int32_t* sink_dev, void* stream) {
+  Q8_REQUIRE(blocks >= 1 && blocks <= 65536 && iters >= 1 && iters <= (1 << 22) && sink_dev,
+             Q8_EINVAL);
+  hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                     (hipStream_t)stream, iters, sink_dev);
+  return q8_launch_status();
 }
 
 }  // extern "C"
