@@ -102,6 +102,9 @@ _lib.orc_requant_scale.restype = C.c_float
 _lib.orc_requant_scale.argtypes = [C.c_float] * 3
 _lib.orc_residual_scale.restype = C.c_float
 _lib.orc_residual_scale.argtypes = [C.c_float] * 2
+_lib.orc_real_output.restype = None
+_lib.orc_real_output.argtypes = [_i32p, C.c_size_t, C.c_int, C.c_float, C.c_float, C.c_void_p,
+                                 C.c_int, C.c_int, C.c_float, C.c_int, _f32p, C.c_int, C.c_int]
 _lib.orc_requant.restype = None
 _lib.orc_requant.argtypes = [_i32p, C.c_size_t, C.c_int, C.c_float, C.c_void_p, C.c_int,
                              C.c_int, C.c_float, C.c_int, _i8p, C.c_int, C.c_int]
@@ -328,6 +331,28 @@ def requant(acc, m, relu, z_res=None, m_r=0.0, res_c_stride=0, res_c_off=0,
     _lib.orc_requant(acc.reshape(-1), npix, K, np.float32(m), _ptr(zr), res_c_stride,
                      res_c_off, np.float32(m_r), int(bool(relu)), out.reshape(-1),
                      out_c_stride, out_c_off)
+    return out
+
+
+def real_output(acc, q_x, q_w, relu, z_res=None, q_res=0.0, res_c_stride=0, res_c_off=0,
+                out=None, out_c_stride=0, out_c_off=0):
+    """int32 accumulators [..., K] -> fp32 values (Eq. D at q_x*q_w, fused sum, ReLU; no Q)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    K = acc.shape[-1]
+    npix = acc.size // K if K else 0
+    if out is None:
+        out = np.empty(acc.shape, np.float32)
+        out_c_stride, out_c_off = K, 0
+    assert out.dtype == np.float32 and out.flags.c_contiguous
+    assert out.size >= npix * out_c_stride and out_c_off + K <= out_c_stride
+    zr = None
+    if z_res is not None:
+        zr = np.ascontiguousarray(z_res, dtype=np.int8)
+        res_c_stride = res_c_stride or K
+        assert zr.size >= npix * res_c_stride and res_c_off + K <= res_c_stride
+    _lib.orc_real_output(acc.reshape(-1), npix, K, np.float32(q_x), np.float32(q_w), _ptr(zr),
+                         res_c_stride, res_c_off, np.float32(q_res), int(bool(relu)),
+                         out.reshape(-1), out_c_stride, out_c_off)
     return out
 
 

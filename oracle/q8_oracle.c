@@ -320,6 +320,33 @@ void orc_quantize_bias_pc(const float *b, size_t n, float q_x, const float *q_w,
   for (size_t k = 0; k < n; ++k) orc_quantize_bias(b + k, 1, q_x, q_w[k], z + k);
 }
 
+/* A layer whose output leaves the quantised domain (the last layer before a
+ * floating-point consumer): the first half of Eq. A' only, y' = ReLU(D(acc) [+ D(z_res)])
+ * with D of Eq. D at the accumulator's factor q_x*q_w of Eq. x, no Q afterwards:
+ *   s = q_x * q_w                   (one fp32 product, formed here)
+ *   t = fp32(acc) * s
+ *   t = t + fp32(z_res) * q_res     (only if z_res; separate multiply and add)
+ *   t = max(t, 0)                   (only if relu)
+ * y is fp32, addressed as pixel * out_c_stride + out_c_off + k.                       */
+void orc_real_output(const int32_t *acc, size_t npix, int K, float q_x, float q_w,
+                     const int8_t *z_res, int res_c_stride, int res_c_off, float q_res,
+                     int relu, float *y, int out_c_stride, int out_c_off) {
+  const float s = q_x * q_w;
+#pragma omp parallel for schedule(static)
+  for (size_t p = 0; p < npix; ++p)
+    for (int k = 0; k < K; ++k) {
+      float t = (float)acc[p * K + k];
+      t = t * s;
+      if (z_res) {
+        float u = (float)z_res[p * res_c_stride + res_c_off + k];
+        u = u * q_res;
+        t = t + u;
+      }
+      if (relu) t = t > 0.0f ? t : 0.0f;
+      y[p * out_c_stride + out_c_off + k] = t;
+    }
+}
+
 /* Eq. D on unsigned codes. */
 void orc_dequantize_u8(const uint8_t *z, size_t n, float q, float *r) {
   for (size_t i = 0; i < n; ++i) r[i] = (float)z[i] * q;

@@ -672,3 +672,60 @@ def test_requant_per_channel_against_exact_rational():
     # equal factors: the per-tensor tail
     same = np.full(K, np.float32(0.0021), np.float32)
     assert np.array_equal(orc.requant_pc(acc, same, False), orc.requant(acc, same[0], False))
+
+
+# ----------------------------------------------------------------------------------------
+# a layer whose output leaves the quantised domain: Eq. D on the accumulator, no Q
+# ----------------------------------------------------------------------------------------
+def test_real_output_against_exact_rational():
+    rng = np.random.default_rng(61)
+    K = 7
+    acc = rng.integers(-3_000_000, 3_000_000, (30, K)).astype(np.int32)
+    acc[0, :3] = [16777217, -16777219, 0]                 # int32 -> fp32 rounds first
+    res = rng.integers(-128, 128, (30, K)).astype(np.int8)
+    q_x, q_w, q_res = np.float32(0.0213), np.float32(0.00071), np.float32(0.0456)
+    s = fl32(F(float(q_x)) * F(float(q_w)))
+    for relu in (False, True):
+        for with_res in (False, True):
+            got = orc.real_output(acc, q_x, q_w, relu, res if with_res else None, q_res)
+            assert got.dtype == np.float32
+            for p in range(30):
+                for k in range(K):
+                    t = fl32(fl32(F(int(acc[p, k]))) * s)
+                    if with_res:
+                        t = fl32(t + fl32(F(int(res[p, k])) * F(float(q_res))))
+                    if relu:
+                        t = max(t, F(0))
+                    assert F(float(got[p, k])) == t, (relu, with_res, p, k)
+
+
+def test_real_output_is_the_value_the_int8_tail_quantises():
+    # power-of-two factors: every fp32 step is exact, so Q(y', q_out) equals the int8 tail,
+    # and y' equals the real-valued layer on the dequantised operands computed in float64
+    rng = np.random.default_rng(62)
+    g = orc.ConvGeom(N=2, H=6, W=5, C=8, K=6, R=3, S=3, pad_h=1, pad_w=1)
+    z_x = rng.integers(-128, 128, (2, 6, 5, 8)).astype(np.int8)
+    z_w = rng.integers(-127, 128, (6, 3, 3, 8)).astype(np.int8)
+    z_b = rng.integers(-5000, 5000, 6).astype(np.int32)
+    z_r = rng.integers(-128, 128, (2, 6, 5, 6)).astype(np.int8)
+    q_x, q_w, q_res, q_out = (np.float32(2.0 ** e) for e in (-5, -9, -4, -3))
+    acc = orc.conv_i8(g, z_x, z_w, z_b)
+    y = orc.real_output(acc, q_x, q_w, True, z_r, q_res)
+    xt = torch.from_numpy(z_x.astype(np.float64) * float(q_x)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(z_w.astype(np.float64) * float(q_w)).permute(0, 3, 1, 2)
+    bt = torch.from_numpy(z_b.astype(np.float64) * float(q_x) * float(q_w))
+    want = torch.nn.functional.conv2d(xt, wt, bt, padding=1).permute(0, 2, 3, 1).numpy()
+    want = np.maximum(want + z_r.astype(np.float64) * float(q_res), 0.0)
+    assert np.array_equal(y.astype(np.float64), want)
+    m = orc.requant_scale(q_x, q_w, q_out)
+    z_y = orc.requant(acc, m, True, z_r, orc.residual_scale(q_res, q_out))
+    assert np.array_equal(orc.Q(y, q_out, 7), z_y)
+
+
+def test_real_output_channel_slice():
+    rng = np.random.default_rng(63)
+    acc = rng.integers(-1000, 1000, (5, 3)).astype(np.int32)
+    out = np.full((5, 8), np.float32(-7.0))
+    orc.real_output(acc, 0.5, 0.25, False, out=out, out_c_stride=8, out_c_off=2)
+    assert np.array_equal(out[:, 2:5], acc.astype(np.float32) * np.float32(0.125))
+    assert np.all(out[:, :2] == -7.0) and np.all(out[:, 5:] == -7.0)
