@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--per-channel-weights", action="store_true",
                     help="one weight factor per output channel instead of one per tensor; "
                          "reported as its own workload")
+    ap.add_argument("--real-output", action="store_true",
+                    help="the output convolution writes fp32 itself (no int8 code, no separate "
+                         "dequantise pass); reported as its own workload")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="one eager pass plus one plain 256 MiB device copy, then exit: the "
                          "program to run under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the copy "
@@ -113,7 +116,7 @@ def main():
     # ---------------- offline: parameters, fold, calibrate, quantise weights ---------------
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
     eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations,
-                 per_channel_weights=args.per_channel_weights)
+                 per_channel_weights=args.per_channel_weights, real_outputs=args.real_output)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -142,10 +145,17 @@ def main():
     out_name = net.outputs[0]
     out_f32 = torch.empty(eng.act[out_name].shape, dtype=torch.float32, device="cuda")
 
+    if args.real_output:
+        assert out_name in eng.real, "this network's output is not written whole by a convolution"
+
+    def finish_output():
+        if not args.real_output:              # else the last convolution wrote fp32 already
+            eng.dequantize(out_name, out=out_f32)
+
     def step():
         eng.quantize_input(x)
         eng.run_layers()
-        eng.dequantize(out_name, out=out_f32)
+        finish_output()
 
     step()
     torch.cuda.synchronize()
@@ -184,7 +194,7 @@ def main():
         def serial_step():
             eng.quantize_input(x)
             eng.run_layers(serial=True)
-            eng.dequantize(out_name, out=out_f32)
+            finish_output()
         g1 = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g1):
             serial_step()
@@ -223,7 +233,7 @@ def main():
             for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
                 eng.run_ops([op], lo, n)
             ev[i + 2].record()
-        eng.dequantize(out_name, out=out_f32)
+        finish_output()
         ev[-1].record()
         torch.cuda.synchronize()
         for i in range(len(ops_list) + 2):
@@ -300,6 +310,8 @@ def main():
         "quantize_input": dict(bytes=5 * n_in + n_in // 3, us=round(float(med[0]), 2)),
         "dequantize_output": dict(bytes=5 * n_out, us=round(float(med[-1]), 2)),
     }
+    if args.real_output:
+        del passes["dequantize_output"]
     for k, v in passes.items():
         v["gbs"] = round(v["bytes"] / v["us"] / 1e3, 1)
         v["frac_of_hbm_peak"] = round(v["gbs"] / PEAK_HBM_GBS, 3)
@@ -382,10 +394,14 @@ def main():
         acts = onet.forward_i8(net, qparams, q, z_in, unsigned=U)
         (orc.D_u8 if out_name in U else orc.D)(acts[out_name], q[out_name])
         t_cpu = time.perf_counter() - t0
-        gpu_out = eng.act[out_name][:sample].cpu().numpy()
-        if out_name in U:
+        # the tensor compared: the output's codes, or (fp32 output) the codes its conv reads
+        cmp_name = out_name
+        if args.real_output:
+            cmp_name = next(o.src for o in convs if o.dst == out_name)
+        gpu_out = eng.act[cmp_name][:sample].cpu().numpy()
+        if cmp_name in U:
             gpu_out = (gpu_out.astype(np.int16) + 128).astype(np.uint8)
-        same = bool(np.array_equal(acts[out_name], gpu_out))
+        same = bool(np.array_equal(acts[cmp_name], gpu_out))
         log(f"oracle: {sample} image(s) in {t_cpu:.2f} s on {orc.num_threads()} threads; "
             f"output equals the GPU's: {same}")
         cpu = dict(value=round(sample / t_cpu, 3), unit="images/s", cores=orc.num_threads(),
@@ -395,9 +411,10 @@ def main():
     result = {
         "metric": "ResNet-50 int8 images/sec at batch 64"
                   if args.config == 3 and not (args.sparsity_removal or args.unsigned_activations
-                                               or args.per_channel_weights)
+                                               or args.per_channel_weights or args.real_output)
                   else f"{net.name}{' (unsigned activations)' if args.unsigned_activations else ''}"
-                       f"{' (per-channel weights)' if args.per_channel_weights else ''} "
+                       f"{' (per-channel weights)' if args.per_channel_weights else ''}"
+                       f"{' (fp32 output from the last conv)' if args.real_output else ''} "
                        f"int8 images/sec at batch {N}",
         "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
@@ -405,7 +422,8 @@ def main():
         "config": {"workload": f"{net.name} conv stack, batch {N}, NHWC int8, "
                                f"{len(convs)} fused convs"
                                + (", unsigned p=8 ReLU outputs" if args.unsigned_activations else "")
-                               + (", per-channel weight factors" if args.per_channel_weights else ""),
+                               + (", per-channel weight factors" if args.per_channel_weights else "")
+                               + (", fp32 output written by the last conv" if args.real_output else ""),
                    "batch": N,
                    "launch": "eager" if graph is None else "hip_graph",
                    "streams": eng.n_streams},

@@ -192,6 +192,19 @@ int q8_conv_int8_per_channel(const q8_conv_desc *d, const int8_t *z_x, const voi
                              const int8_t *residual, float q_res, int8_t *z_y,
                              int32_t *acc_dump, void *stream);
 
+/* A layer whose output leaves the quantised domain (the last layer before a
+ * floating-point consumer, a detection head): the first half of Eq. A' only,
+ *   y' = ReLU(D(acc) [+ D(z_res)])   (Eq. D at the accumulator's factor q_x*q_w of Eq. x),
+ * written as fp32 with no Q afterwards, which saves the separate q8_dequantize pass and the
+ * rounding to 8 bits.  Fixed fp32 order: s = q_x*q_w; t = fp32(acc)*s; with a residual
+ * t = t + fp32(z_res)*q_res (separate multiply and add); ReLU if d->relu.
+ * y_dev: fp32 [N][Ho][Wo][out_c_stride] (0 = K), channels [out_c_off, out_c_off + K),
+ * 4-byte aligned (16-byte aligned with strides % 4 == 0 for vector stores).  Other
+ * arguments, layouts and error codes as q8_conv_int8.                                   */
+int q8_conv_int8_real_output(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
+                             const int32_t *bias_i32, float q_x, float q_w,
+                             const int8_t *residual, float q_res, float *y_dev, void *stream);
+
 /* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
  * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.
  * For measurement code that groups launches by kernel.                              */

@@ -24,7 +24,7 @@ EXPORTS = [
     "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
     "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_image", "q8_quantize_bias", "q8_quantize_u8", "q8_dequantize_u8",
     "q8_u8_prepare", "q8_conv_u8", "q8_quantize_weights_per_channel",
-    "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_dequantize",
+    "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_conv_int8_real_output", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_variant", "q8_conv_force_variant", "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
@@ -85,6 +85,7 @@ lib.q8_quantize_weights_per_channel.argtypes = [_vp, _i, _sz, _i, _vp, _vp, _vp]
 lib.q8_quantize_bias_per_channel.argtypes = [_vp, _i, _f, _vp, _vp, _vp]
 lib.q8_requant_scales.argtypes = [_f, _vp, _i, _f, _vp, _vp]
 lib.q8_conv_int8_per_channel.argtypes = [_dp, _vp, _vp, _vp, _vp, _f, _vp, _f, _vp, _vp, _vp]
+lib.q8_conv_int8_real_output.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _vp, _f, _vp, _vp]
 lib.q8_quantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
@@ -280,6 +281,18 @@ def conv_int8_per_channel(desc, z_x, z_w_packed, bias_i32, m, q_out, residual=No
                                         _ptr(m, torch.float32), q_out, _ptr(residual, torch.int8),
                                         q_res, _ptr(out, torch.int8), _ptr(acc_dump, torch.int32),
                                         _stream()))
+    return out
+
+
+def conv_int8_real_output(desc, z_x, w_packed, bias, q_x, q_w, residual=None, q_res=0.0, out=None):
+    """The layer's real-valued output (fp32), no requantisation."""
+    if out is None:
+        out = torch.empty((desc.N, desc.Ho, desc.Wo, desc.out_c_stride or desc.K),
+                          dtype=torch.float32, device=z_x.device)
+    _check(lib.q8_conv_int8_real_output(C.byref(desc), _ptr(z_x, torch.int8), _ptr(w_packed),
+                                        _ptr(bias, torch.int32), q_x, q_w,
+                                        _ptr(residual, torch.int8), q_res,
+                                        _ptr(out, torch.float32), _stream()))
     return out
 
 

@@ -165,6 +165,7 @@ struct U8Flags {
   int in_u8, out_u8, res_u8;
   const int32_t* tap_sums;
   const float* m_vec = nullptr;     // per-output-channel scales (replace q_x * q_w / q_out)
+  float* y_f32 = nullptr;           // real-valued output instead of int8 codes
 };
 
 int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
@@ -195,8 +196,13 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   if (M == 0) return Q8_OK;
   Q8_REQUIRE(M <= 0x7fffffffL, Q8_EUNSUPPORTED);
   Q8_REQUIRE((long)d->H * d->W * p.in_cs <= 0x7fffffffL, Q8_EUNSUPPORTED);
-  Q8_REQUIRE(z_x && z_w_packed && z_y, Q8_EINVAL);
+  Q8_REQUIRE(z_x && z_w_packed && (z_y || u.y_f32), Q8_EINVAL);
   Q8_REQUIRE(q8_aligned(z_w_packed, 16), Q8_EALIGN);
+  if (u.y_f32) {
+    Q8_REQUIRE(!(u.in_u8 || u.out_u8 || u.res_u8 || u.m_vec) && acc_dump == nullptr,
+               Q8_EUNSUPPORTED);
+    Q8_REQUIRE(q8_aligned(u.y_f32, 4), Q8_EALIGN);
+  }
   if (mode == 0) {
     Q8_REQUIRE(p.in_cs % 16 == 0 && q8_aligned(z_x, 16), Q8_EALIGN);
     p.red_len = d->R * d->S * d->C;
@@ -255,16 +261,25 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   p.relu = d->relu ? 1 : 0;
   {
     float prod = q_x * q_w;      // the x rule: factor of the accumulator
-    p.m = prod / q_out;
-    p.m_r = residual ? q_res / q_out : 0.0f;
+    if (u.y_f32) {               // Eq. D on the accumulator and on the residual, no Q
+      p.m = prod;
+      p.m_r = residual ? q_res : 0.0f;
+    } else {
+      p.m = prod / q_out;
+      p.m_r = residual ? q_res / q_out : 0.0f;
+    }
   }
   auto aligned_to = [&](int a) {
-    return p.out_cs % a == 0 && p.out_off % a == 0 && q8_aligned(z_y, a) &&
+    return (u.y_f32 != nullptr ||
+            (p.out_cs % a == 0 && p.out_off % a == 0 && q8_aligned(z_y, a))) &&
            (residual == nullptr ||
             (p.res_cs % a == 0 && p.res_off % a == 0 && q8_aligned(residual, a)));
   };
   p.vec4 = aligned_to(4) ? 1 : 0;
   p.vec16 = aligned_to(16) ? 1 : 0;
+  p.y_f32 = u.y_f32;
+  p.f32_vec4 =
+      (u.y_f32 && p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(u.y_f32, 16)) ? 1 : 0;
 
   hipStream_t s = (hipStream_t)stream;
   const int variant = pick_variant(d);
@@ -329,6 +344,15 @@ int q8_conv_int8_per_channel(const q8_conv_desc* d, const int8_t* z_x, const voi
   // q_x and q_w only enter through m_dev here: pass neutral factors to the shared checks
   return conv_launch(d, u, z_x, z_w_packed, bias_i32, 1.0f, 1.0f, q_out, residual, q_res, z_y,
                      acc_dump, stream);
+}
+
+int q8_conv_int8_real_output(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                             const int32_t* bias_i32, float q_x, float q_w,
+                             const int8_t* residual, float q_res, float* y_dev, void* stream) {
+  U8Flags u{0, 0, 0, nullptr};
+  u.y_f32 = y_dev;            // null: rejected by the shared checks unless the output is empty
+  return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, 1.0f, residual, q_res, nullptr,
+                     nullptr, stream);
 }
 
 int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32_t* bias_i32,

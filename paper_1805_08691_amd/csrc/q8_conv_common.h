@@ -22,6 +22,10 @@ struct ConvParams {
   const int8_t* __restrict__ res;
   int8_t* __restrict__ y;
   int32_t* __restrict__ acc_dump;
+  // real-valued output (a layer that leaves the quantised domain): fp32 [M][out_cs] written
+  // instead of y; then m is the accumulator's factor q_x*q_w and m_r the residual's q_res
+  float* __restrict__ y_f32;
+  int f32_vec4;   // 1: fp32 output addresses of 4-channel groups are 16-byte aligned
   int N, H, W, C, K, R, S;
   int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
   int Ho, Wo;
@@ -234,6 +238,24 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
       float u = (float)code * p.m_r;
       t[e] = t[e] + u;
     }
+  }
+  if (p.y_f32) {      // Eq. D only: no clamp, no Round
+    float* o = p.y_f32 + (size_t)pix * p.out_cs + p.out_off + ch;
+    if (p.relu) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) t[e] = fmaxf(t[e], 0.0f);
+    }
+    if (full && p.f32_vec4) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        *reinterpret_cast<float4*>(o + 4 * a) =
+            float4{t[4 * a], t[4 * a + 1], t[4 * a + 2], t[4 * a + 3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e < nvalid) o[e] = t[e];
+    }
+    return;
   }
   const float lo = p.out_u8 ? 0.0f : -128.0f, hi = p.out_u8 ? 255.0f : 127.0f;
   const int out_sub = p.out_u8 ? 128 : 0;          // unsigned code - 128 = stored byte

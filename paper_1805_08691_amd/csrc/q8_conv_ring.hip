@@ -471,7 +471,8 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   mma(NH - 1);
 
   // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
-  const bool fast_tile = p.vec16 && !p.acc_dump && ch0 + BC <= p.K && pix0 + BP <= p.M;
+  const bool fast_tile =
+      p.vec16 && !p.acc_dump && !p.y_f32 && ch0 + BC <= p.K && pix0 + BP <= p.M;
   auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
     // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
     // residual, signed residual, unsigned residual); 6, 7: fast with per-channel scales

@@ -31,9 +31,19 @@ class Engine:
     other half's work.  Results are the same bits as with one stream."""
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
-                 per_channel_weights=False):
+                 per_channel_weights=False, real_outputs=False):
         self.net = net
         assert not (unsigned_activations and per_channel_weights)
+        # real_outputs: a network output that a convolution writes whole and no layer reads
+        # is produced as fp32 by that convolution (no int8 code, no separate Eq. D pass)
+        self.real = set()
+        if real_outputs:
+            assert not (unsigned_activations or per_channel_weights)
+            read = {o.src for o in net.ops} | {o.res for o in net.ops if o.kind == "conv" and o.res}
+            for o in net.convs():
+                if o.dst in net.outputs and o.dst not in read and net.tensors[o.dst].C == o.K:
+                    self.real.add(o.dst)
+        self.act_f32 = {}     # tensor name -> fp32 device buffer (real_outputs)
         self.per_channel = per_channel_weights
         self.m_vec = {}       # conv name -> per-channel scales (per_channel_weights)
         # Unsigned p = 8 codes for the outputs of ReLU layers (the calibration paragraph's
@@ -221,6 +231,9 @@ class Engine:
                 H, W = self.in_frame[2:]
             self.act[name] = torch.zeros((self.N, H, W, _pad_c(t.C)), dtype=torch.int8,
                                          device=self.dev)
+            if name in self.real:
+                self.act_f32[name] = torch.zeros((self.N, H, W, _pad_c(t.C)),
+                                                 dtype=torch.float32, device=self.dev)
 
     def input_codes(self):
         """The int8 codes of the network input without the frame: [N, H, W, C_stored]."""
@@ -271,6 +284,11 @@ class Engine:
         res = self.act[op.res][lo:lo + n] if op.res else None
         q_res = self.q[op.res] if op.res else 0.0
         U = self.unsigned
+        if op.dst in self.real and acc_dump is None:
+            B.conv_int8_real_output(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed,
+                                    bias, self.q[op.src], self.qw[op.name], res, q_res,
+                                    out=self.act_f32[op.dst][lo:lo + n])
+            return
         if self.per_channel:
             B.conv_int8_per_channel(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed,
                                     bias, self.m_vec[op.name], self.q[op.dst], res, q_res,
@@ -321,7 +339,13 @@ class Engine:
         main.wait_stream(self.side)
 
     def dequantize(self, name, out=None):
-        """Eq. D on tensor ``name`` (signed or unsigned codes)."""
+        """Eq. D on tensor ``name`` (signed or unsigned codes); a real-valued output is
+        already there."""
+        if name in self.real:
+            if out is not None:
+                out.copy_(self.act_f32[name])
+                return out
+            return self.act_f32[name]
         fn = B.dequantize_u8 if name in self.unsigned else B.dequantize
         return fn(self.act[name], self.q[name], out=out)
 

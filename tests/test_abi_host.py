@@ -105,6 +105,18 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.q8_conv_int8_per_channel(C.byref(d), *pc) == -2     # K <= 32: not the main kernel
     assert L.q8_conv_int8_per_channel(C.byref(wide), fake, fake, None, C.c_void_p(0x1004), 1.0,
                                       None, 0.0, fake, None, None) == -3
+    # real-valued (fp32) output
+    ro = (fake, fake, None, 1.0, 1.0, None, 0.0)
+    assert L.q8_conv_int8_real_output(C.byref(d), *ro, None, None) == -1        # no output
+    assert L.q8_conv_int8_real_output(C.byref(d), *ro, C.c_void_p(0x1002), None) == -3
+    assert L.q8_conv_int8_real_output(C.byref(d), fake, fake, None, 1.0, 0.0, None, 0.0, fake,
+                                      None) == -1                              # q_w <= 0
+    assert L.q8_conv_int8_real_output(C.byref(d), fake, fake, None, 1.0, 1.0, fake, 0.0, fake,
+                                      None) == -1                              # residual, q_res <= 0
+    assert L.q8_conv_int8_real_output(C.byref(empty), None, None, None, 1.0, 1.0, None, 0.0, None,
+                                      None) == 0
+    assert L.q8_probe_mfma_i8(0, 10, fake, None) == -1
+    assert L.q8_probe_mfma_i8(4, 10, None, None) == -1
     assert L.q8_quantize_weights_per_channel(fake, 4, 16, 9, fake, fake, None) == -1   # p
     assert L.q8_quantize_weights_per_channel(None, 4, 16, 7, fake, fake, None) == -1
     assert L.q8_quantize_weights_per_channel(None, 0, 16, 7, None, None, None) == 0

@@ -397,6 +397,52 @@ def test_conv_per_channel_scales(B, geom, with_res):
         assert np.array_equal(host(got), want)
 
 
+REAL_OUTPUT_CASES = [
+    # geometry, residual, ReLU, extra channels of the output tensor, channel offset
+    (dict(N=2, H=14, W=14, C=64, K=160, R=3, S=3, pad_h=1, pad_w=1), True, True, 0, 0),
+    (dict(N=2, H=7, W=7, C=512, K=256, R=1, S=1), True, True, 0, 0),          # complete tiles
+    (dict(N=1, H=19, W=19, C=64, K=84, R=3, S=3, pad_h=1, pad_w=1), False, False, 0, 0),  # SSD head
+    (dict(N=1, H=17, W=17, C=48, K=72, R=1, S=7, pad_w=3), False, True, 12, 4),
+    (dict(N=2, H=9, W=9, C=16, K=17, R=3, S=3, pad_h=1, pad_w=1), True, False, 5, 3),  # K <= 32 kernel
+    (dict(N=64, H=1, W=1, C=2048, K=1000, R=1, S=1), False, False, 0, 0),     # classifier logits
+    (dict(N=0, H=5, W=5, C=16, K=16, R=1, S=1), False, False, 0, 0),
+]
+
+
+@pytest.mark.parametrize("geom,with_res,relu,out_pad,out_off", REAL_OUTPUT_CASES)
+def test_conv_real_valued_output(B, geom, with_res, relu, out_pad, out_off):
+    """A layer that leaves the quantised domain writes fp32 directly: the same bits as the
+    oracle's fixed fp32 sequence (well inside the 1e-5 relative bound)."""
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(g.K * 7 + g.C)
+    x = rng.integers(-128, 128, (g.N, g.H, g.W, g.C)).astype(np.int8)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, g.K).astype(np.int32)
+    q_x, q_w, q_res = np.float32(0.021), np.float32(0.0017), np.float32(0.083)
+    Ho, Wo = g.Ho, g.Wo
+    res = rng.integers(-128, 128, (g.N, Ho, Wo, g.K)).astype(np.int8) if with_res else None
+    out_cs = g.K + out_pad
+    want = np.full((g.N, Ho, Wo, out_cs), np.float32(-7.5))
+    if g.N:
+        acc_o = orc.conv_i8(g, x, w, b)
+        orc.real_output(acc_o, q_x, q_w, relu, res, q_res, out=want, out_c_stride=out_cs,
+                        out_c_off=out_off)
+    d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                   g.dil_h, g.dil_w, relu=int(relu), out_c_stride=out_cs, out_c_off=out_off)
+    out = torch.full((g.N, Ho, Wo, out_cs), -7.5, dtype=torch.float32, device="cuda")
+    B.conv_int8_real_output(d, dev(x), B.pack_weights(d, dev(w)), dev(b), float(q_x), float(q_w),
+                            None if res is None else dev(res), float(q_res), out=out)
+    got = host(out)
+    assert np.array_equal(got, want)
+    if g.N:
+        # and it is the value the int8 tail would have quantised: D(Q(y')) is within q/2 of it
+        q_out = np.float32(np.abs(want[..., out_off:out_off + g.K]).max() / 127)
+        z = orc.requant(acc_o, orc.requant_scale(q_x, q_w, q_out), relu, res,
+                        orc.residual_scale(q_res, q_out) if with_res else 0.0)
+        err = np.abs(orc.D(z, q_out) - want[..., out_off:out_off + g.K])
+        assert err.max() <= 0.5001 * q_out
+
+
 @pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
 def test_conv_channel_slice_of_concat(B, out_pad, out_off):
     geom = dict(N=2, H=9, W=9, C=32, K=40, R=3, S=3, pad_h=1, pad_w=1)
@@ -547,7 +593,7 @@ def test_config2_bottleneck_block(B):
 
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
-                          per_channel=False):
+                          per_channel=False, real_outputs=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -567,8 +613,20 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         return (a.astype(np.int16) + 128).astype(np.uint8) if name in U else a
 
     eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned,
-                 per_channel_weights=per_channel)
+                 per_channel_weights=per_channel, real_outputs=real_outputs)
     assert eng.unsigned == U
+    # outputs that leave the quantised domain as fp32 straight from their convolution
+    real_want = {}
+    if real_outputs:
+        assert eng.real, "this network has no output a convolution writes whole"
+        for op in net.convs():
+            if op.dst in eng.real:
+                qp = qparams[op.name]
+                acc = orc.conv_i8(onet.geom(op, net.tensors, len(picks)), acts[op.src], qp["z_w"],
+                                  qp["z_b"])
+                real_want[op.dst] = orc.real_output(
+                    acc, q[op.src], qp["q_w"], op.relu, acts[op.res] if op.res else None,
+                    q[op.res] if op.res else 0.0)
     eng.load_params(params)
     eng.fold()
     eng.set_factors(q)
@@ -592,10 +650,19 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         assert not full[:, :top].any() and not full[:, top + z_in.shape[1]:].any()
         assert not full[:, :, :left].any() and not full[:, :, left + z_in.shape[2]:].any()
     for op in net.ops:
+        if op.dst in eng.real:
+            continue
         got = codes(op.dst, host(eng.act[op.dst])[picks])
         assert got.dtype == acts[op.dst].dtype and np.array_equal(got, acts[op.dst]), op.name
     for o, out in zip(net.outputs, outs):
         r = host(eng.dequantize(o))[picks]
+        if o in eng.real:
+            assert np.array_equal(r, real_want[o]), o
+            # the int8 path's D(Q(.)) of the same value is within half a step of it
+            # (where the int8 range holds it)
+            inside = np.abs(r) <= 127 * q[o]
+            assert np.all(np.abs(orc.D(acts[o], q[o]) - r)[inside] <= 0.5001 * q[o]), o
+            continue
         want = orc.D_u8(acts[o], q[o]) if o in U else orc.D(acts[o], q[o])
         assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want)), o
     # replays of the captured HIP graph, with eager work between them: same bits each time
@@ -604,9 +671,14 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         for o in net.outputs:
             eng.act[o].fill_(3 + rep)
         torch.cuda.synchronize()
+        for o in eng.real:
+            eng.act_f32[o].fill_(3 + rep)
         eng.graph.replay()
         for o in net.outputs:
-            assert np.array_equal(codes(o, host(eng.act[o])[picks]), acts[o]), (o, rep)
+            if o in eng.real:
+                assert np.array_equal(host(eng.act_f32[o])[picks], real_want[o]), (o, rep)
+            else:
+                assert np.array_equal(codes(o, host(eng.act[o])[picks]), acts[o]), (o, rep)
 
 
 @pytest.mark.parametrize("n_streams", [2, 1])
@@ -643,6 +715,13 @@ def test_config5_ssd300_vgg16_sampled_images(B, batch, picks):
     # 3x3 stack at 300x300, ceil-mode pooling, dilation 6, head convolutions with
     # K in {16, 24, 84, 126}, twelve int8 outputs
     _sampled_images_check(B, 5, batch, picks, n_cal=2, cal_batch=4)
+
+
+def test_networks_with_real_valued_outputs(B):
+    # the last convolution (ResNet-50: fused sum + ReLU) and the twelve SSD head
+    # convolutions write fp32 directly instead of int8 codes plus a dequantise pass
+    _sampled_images_check(B, 3, 8, [0, 3, 4, 7], n_cal=2, cal_batch=8, real_outputs=True)
+    _sampled_images_check(B, 5, 1, [0], n_cal=2, cal_batch=4, real_outputs=True)
 
 
 def test_gpu_calibration_matches_oracle_closely(B):
