@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--per-channel-weights", action="store_true",
                     help="one weight factor per output channel instead of one per tensor; "
                          "reported as its own workload")
+    ap.add_argument("--own-sum-factor", action="store_true",
+                    help="a fused sum's output factor from its own max-abs instead of the "
+                         "max(q1, q2) rule; reported as its own workload")
     ap.add_argument("--real-output", action="store_true",
                     help="the output convolution writes fp32 itself (no int8 code, no separate "
                          "dequantise pass); reported as its own workload")
@@ -116,7 +119,8 @@ def main():
     # ---------------- offline: parameters, fold, calibrate, quantise weights ---------------
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
     eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations,
-                 per_channel_weights=args.per_channel_weights, real_outputs=args.real_output)
+                 per_channel_weights=args.per_channel_weights, real_outputs=args.real_output,
+                 own_sum_factor=args.own_sum_factor)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -411,10 +415,12 @@ def main():
     result = {
         "metric": "ResNet-50 int8 images/sec at batch 64"
                   if args.config == 3 and not (args.sparsity_removal or args.unsigned_activations
-                                               or args.per_channel_weights or args.real_output)
+                                               or args.per_channel_weights or args.real_output
+                                               or args.own_sum_factor)
                   else f"{net.name}{' (unsigned activations)' if args.unsigned_activations else ''}"
                        f"{' (per-channel weights)' if args.per_channel_weights else ''}"
-                       f"{' (fp32 output from the last conv)' if args.real_output else ''} "
+                       f"{' (fp32 output from the last conv)' if args.real_output else ''}"
+                       f"{' (sums at their own factor)' if args.own_sum_factor else ''} "
                        f"int8 images/sec at batch {N}",
         "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,

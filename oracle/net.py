@@ -110,13 +110,16 @@ def unsigned_tensors(net):
     return u
 
 
-def calibrate(net, folded, batches, use_library=True, unsigned=None):
+def calibrate(net, folded, batches, use_library=True, unsigned=None, own_sum_factor=False):
     """Running max-abs over ``batches`` (iterable of fp32 NHWC inputs) -> factor table
     {tensor name: q} plus {conv name + ':branch': q1} for fused sums.
 
     ``unsigned`` (a set of tensor names): those tensors get q = max / (2^8 - 1); and the
     output of a fused sum then keeps its OWN calibrated factor (the max(q1, q2) rule of
-    Eq. + presumes equal precisions, which a signed branch and an unsigned output are not)."""
+    Eq. + presumes equal precisions, which a signed branch and an unsigned output are not).
+    ``own_sum_factor``: the same choice with signed codes -- a variant, not the paper's rule:
+    max(q1, q2) lets the sum saturate where both branches are large, the sum's own max-abs
+    does not."""
     mx = {}
 
     def upd(key, arr):
@@ -135,7 +138,7 @@ def calibrate(net, folded, batches, use_library=True, unsigned=None):
     q = {k: qfactor(v, 8 if k in unsigned else P_ACT) for k, v in mx.items()}
     # + rule: a fused sum is re-quantised at max(q1, q2)
     for op in net.ops:
-        if op.kind == "conv" and op.res is not None and not unsigned:
+        if op.kind == "conv" and op.res is not None and not unsigned and not own_sum_factor:
             q[op.dst] = max(q[op.name + ":branch"], q[op.res])
         if op.kind == "pool" and net.tensors[op.dst].C == net.tensors[op.src].C:
             q[op.dst] = q[op.src]          # a stand-alone pool keeps its input's factor

@@ -21,8 +21,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # accumulators that are also read by ordinary vector code (the in-loop epilogue of the
-         # persistent kernel) stay in VGPRs: no per-step copies between VGPRs and AGPRs
+         # MFMA accumulators live in ordinary VGPRs (the epilogue reads them with vector
+         # instructions): no copies between VGPRs and AGPRs
          "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-function",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -31,8 +31,11 @@ class Engine:
     other half's work.  Results are the same bits as with one stream."""
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
-                 per_channel_weights=False, real_outputs=False):
+                 per_channel_weights=False, real_outputs=False, own_sum_factor=False):
         self.net = net
+        # own_sum_factor: a fused sum's output is calibrated by its own max-abs instead of
+        # the max(q1, q2) rule of Eq. + (a variant; implied by unsigned activations)
+        self.own_sum_factor = own_sum_factor
         assert not (unsigned_activations and per_channel_weights)
         # real_outputs: a network output that a convolution writes whole and no layer reads
         # is produced as fp32 by that convolution (no int8 code, no separate Eq. D pass)
@@ -179,7 +182,8 @@ class Engine:
         q = {k: B.qfactor(float(v), 8 if k in self.unsigned else P_ACT)
              for k, v in zip(keys, vals)}
         for op in self.net.ops:
-            if op.kind == "conv" and op.res is not None and not self.unsigned:
+            if (op.kind == "conv" and op.res is not None and not self.unsigned
+                    and not self.own_sum_factor):
                 q[op.dst] = max(q[op.name + ":branch"], q[op.res])   # the + rule
             if op.kind == "pool" and self.net.tensors[op.dst].C == self.net.tensors[op.src].C:
                 q[op.dst] = q[op.src]       # a stand-alone pool keeps its input's factor

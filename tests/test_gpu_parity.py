@@ -593,7 +593,7 @@ def test_config2_bottleneck_block(B):
 
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
-                          per_channel=False, real_outputs=False):
+                          per_channel=False, real_outputs=False, own_sum_factor=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -603,7 +603,8 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
     folded = onet.fold_all(net, params)
     U = onet.unsigned_tensors(net) if unsigned else set()
     q = onet.calibrate(net, folded, (wl.input_batch(cfg_id, net, cal_batch, 100 + i)
-                                     for i in range(n_cal)), unsigned=U)
+                                     for i in range(n_cal)), unsigned=U,
+                       own_sum_factor=own_sum_factor)
     qparams = onet.quantize_params(net, folded, q, per_channel=per_channel)
     x = wl.input_batch(cfg_id, net, batch, 0)
     z_in = orc.Q(x[picks], q[net.input], 7)
@@ -715,6 +716,11 @@ def test_config5_ssd300_vgg16_sampled_images(B, batch, picks):
     # 3x3 stack at 300x300, ceil-mode pooling, dilation 6, head convolutions with
     # K in {16, 24, 84, 126}, twelve int8 outputs
     _sampled_images_check(B, 5, batch, picks, n_cal=2, cal_batch=4)
+
+
+def test_resnet50_sums_at_their_own_calibrated_factor(B):
+    # the variant of the sum rule: q of a fused sum from its own max-abs, not max(q1, q2)
+    _sampled_images_check(B, 3, 8, [0, 3, 4, 7], n_cal=2, cal_batch=8, own_sum_factor=True)
 
 
 def test_networks_with_real_valued_outputs(B):

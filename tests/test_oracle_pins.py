@@ -627,6 +627,39 @@ def test_unsigned_network_reading_on_a_small_resnet():
     assert err[True] < err[False]
 
 
+def test_sum_factor_rule_and_its_variant_on_a_small_resnet():
+    """Eq. + gives a fused sum the factor max(q1, q2), under which the sum can exceed the
+    int8 range; calibrating the sum's own max-abs (the variant) never saturates on the
+    calibration data itself."""
+    from oracle import net as onet
+    from paper_1805_08691_amd import workloads as wl
+    net = wl.resnet50(image=64)
+    params = {op.name: wl.conv_params(3, i, op) for i, op in enumerate(net.convs())}
+    folded = onet.fold_all(net, params)
+    x = wl.input_batch(3, net, 2, 100)
+    sums = [op for op in net.convs() if op.res]
+    ref = onet.forward_f32(net, folded, x)[0]
+    q_rule = onet.calibrate(net, folded, [x])
+    q_own = onet.calibrate(net, folded, [x], own_sum_factor=True)
+    for op in sums:
+        assert q_rule[op.dst] == max(q_rule[op.name + ":branch"], q_rule[op.res])
+        assert q_own[op.dst] == orc.qfactor(orc.maxabs(ref[op.dst]), 7)
+    assert {k: v for k, v in q_rule.items() if k not in {o.dst for o in sums}} == \
+           {k: v for k, v in q_own.items() if k not in {o.dst for o in sums}}
+    # the first fused sum reads tensors whose codes do not depend on the choice: compare there
+    op = sums[0]
+    sat = {}
+    for tag, q in (("rule", q_rule), ("own", q_own)):
+        qp = onet.quantize_params(net, folded, q)
+        acts = onet.forward_i8(net, qp, q, orc.Q(x, q[net.input], 7))
+        sat[tag] = int(np.sum(acts[op.dst] == 127))
+        err = np.abs(orc.D(acts[op.dst], q[op.dst]) - ref[op.dst]).max()
+        if tag == "own":       # no clipping: the error stays a few steps (it is inherited)
+            assert err < 6 * q[op.dst]
+    # under its own factor only the calibrated maximum (and near ties) reach the last code
+    assert sat["own"] <= 4
+
+
 # ----------------------------------------------------------------------------------------
 # per-output-channel weight factors
 # ----------------------------------------------------------------------------------------
