@@ -205,6 +205,24 @@ int q8_conv_int8_real_output(const q8_conv_desc *d, const int8_t *z_x, const voi
                              const int32_t *bias_i32, float q_x, float q_w,
                              const int8_t *residual, float q_res, float *y_dev, void *stream);
 
+/* Two layers in one launch: a convolution (d1; ReLU per d1->relu, no residual) whose output
+ * is read by one 1x1 layer (d2: stride 1, no padding, C = d1->K) and by nothing else -- the
+ * 3x3 -> 1x1 tail of a bottleneck block.  Each layer is Eq. A' as in q8_conv_int8 (the
+ * second may carry the fused sum and ReLU of the "Model Optimization" section); the
+ * intermediate int8 codes at factor q_mid never leave the chip.  Results are bit-identical
+ * to two q8_conv_int8 calls with the same factors.
+ * Supported (q8_conv_pair_supported returns 1): d1 takes the main kernel with C % 64 == 0,
+ * d1->K is 64 or 128, d2->K % d1->K == 0, d2 spans exactly d1's output.  d1's out_* / res_*
+ * fields are ignored; d2's describe z_y and the residual.  w2_packed: [K2][K1] int8
+ * (q8_pack_weights of d2), bias2 at q_mid*q_w2.  Otherwise Q8_EUNSUPPORTED: call the two
+ * layers one after the other.                                                           */
+int q8_conv_pair_supported(const q8_conv_desc *d1, const q8_conv_desc *d2);
+int q8_conv_pair_int8(const q8_conv_desc *d1, const int8_t *z_x, const void *w1_packed,
+                      const int32_t *bias1, float q_x, float q_w1, float q_mid,
+                      const q8_conv_desc *d2, const void *w2_packed, const int32_t *bias2,
+                      float q_w2, float q_out, const int8_t *residual, float q_res,
+                      int8_t *z_y, void *stream);
+
 /* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
  * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.
  * For measurement code that groups launches by kernel.                              */

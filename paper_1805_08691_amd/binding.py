@@ -24,7 +24,7 @@ EXPORTS = [
     "q8_strerror", "q8_conv_out_h", "q8_conv_out_w", "q8_calibrate_maxabs", "q8_qfactor",
     "q8_quantize", "q8_quantize_pad_channels", "q8_quantize_image", "q8_quantize_bias", "q8_quantize_u8", "q8_dequantize_u8",
     "q8_u8_prepare", "q8_conv_u8", "q8_quantize_weights_per_channel",
-    "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_conv_int8_real_output", "q8_dequantize",
+    "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_conv_int8_real_output", "q8_conv_pair_supported", "q8_conv_pair_int8", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_variant", "q8_conv_force_variant", "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
@@ -86,6 +86,8 @@ lib.q8_quantize_bias_per_channel.argtypes = [_vp, _i, _f, _vp, _vp, _vp]
 lib.q8_requant_scales.argtypes = [_f, _vp, _i, _f, _vp, _vp]
 lib.q8_conv_int8_per_channel.argtypes = [_dp, _vp, _vp, _vp, _vp, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_conv_int8_real_output.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _vp, _f, _vp, _vp]
+lib.q8_conv_pair_supported.argtypes = [_dp, _dp]
+lib.q8_conv_pair_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _dp, _vp, _vp, _f, _f, _vp, _f, _vp, _vp]
 lib.q8_quantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
@@ -293,6 +295,24 @@ def conv_int8_real_output(desc, z_x, w_packed, bias, q_x, q_w, residual=None, q_
                                         _ptr(bias, torch.int32), q_x, q_w,
                                         _ptr(residual, torch.int8), q_res,
                                         _ptr(out, torch.float32), _stream()))
+    return out
+
+
+def conv_pair_supported(d1, d2):
+    return bool(lib.q8_conv_pair_supported(C.byref(d1), C.byref(d2)))
+
+
+def conv_pair_int8(d1, z_x, w1_packed, bias1, q_x, q_w1, q_mid, d2, w2_packed, bias2, q_w2, q_out,
+                   residual=None, q_res=0.0, out=None):
+    """A convolution and the 1x1 layer behind it in one launch (the intermediate stays on chip)."""
+    if out is None:
+        out = torch.empty((d2.N, d2.Ho, d2.Wo, d2.out_c_stride or d2.K), dtype=torch.int8,
+                          device=z_x.device)
+    _check(lib.q8_conv_pair_int8(C.byref(d1), _ptr(z_x, torch.int8), _ptr(w1_packed),
+                                 _ptr(bias1, torch.int32), q_x, q_w1, q_mid, C.byref(d2),
+                                 _ptr(w2_packed), _ptr(bias2, torch.int32), q_w2, q_out,
+                                 _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
+                                 _stream()))
     return out
 
 

@@ -161,11 +161,23 @@ int q8_pack_weights(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, void* pac
 
 namespace {
 
+// The 1x1 layer fused behind a convolution (see q8_conv_pair_int8).
+struct PairArgs {
+  const q8_conv_desc* d2;
+  const void* w2;
+  const int32_t* bias2;
+  float q_w2, q_out;
+  const int8_t* residual;
+  float q_res;
+  int8_t* z_y;
+};
+
 struct U8Flags {
   int in_u8, out_u8, res_u8;
   const int32_t* tap_sums;
   const float* m_vec = nullptr;     // per-output-channel scales (replace q_x * q_w / q_out)
   float* y_f32 = nullptr;           // real-valued output instead of int8 codes
+  const PairArgs* pair = nullptr;   // a second, 1x1 layer on the output while it is on chip
 };
 
 int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
@@ -196,7 +208,7 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   if (M == 0) return Q8_OK;
   Q8_REQUIRE(M <= 0x7fffffffL, Q8_EUNSUPPORTED);
   Q8_REQUIRE((long)d->H * d->W * p.in_cs <= 0x7fffffffL, Q8_EUNSUPPORTED);
-  Q8_REQUIRE(z_x && z_w_packed && (z_y || u.y_f32), Q8_EINVAL);
+  Q8_REQUIRE(z_x && z_w_packed && (z_y || u.y_f32 || u.pair), Q8_EINVAL);
   Q8_REQUIRE(q8_aligned(z_w_packed, 16), Q8_EALIGN);
   if (u.y_f32) {
     Q8_REQUIRE(!(u.in_u8 || u.out_u8 || u.res_u8 || u.m_vec) && acc_dump == nullptr,
@@ -282,6 +294,47 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
       (u.y_f32 && p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(u.y_f32, 16)) ? 1 : 0;
 
   hipStream_t s = (hipStream_t)stream;
+  if (u.pair) {
+    // q_out of this call is the intermediate tensor's factor; the second layer reads it
+    const PairArgs& a = *u.pair;
+    const q8_conv_desc* d2 = a.d2;
+    Q8_REQUIRE(!(u.in_u8 || u.out_u8 || u.res_u8 || u.m_vec || u.y_f32) && !acc_dump && !residual,
+               Q8_EUNSUPPORTED);
+    Q8_REQUIRE(desc_sane(d2) && a.w2 && a.z_y, Q8_EINVAL);
+    Q8_REQUIRE(q8_finite_pos(a.q_w2) && q8_finite_pos(a.q_out), Q8_EINVAL);
+    Q8_REQUIRE(a.residual == nullptr || q8_finite_pos(a.q_res), Q8_EINVAL);
+    // the second layer: 1x1, stride 1, no padding, over exactly the first layer's output
+    Q8_REQUIRE(d2->N == d->N && d2->H == p.Ho && d2->W == p.Wo && d2->C == d->K, Q8_EINVAL);
+    Q8_REQUIRE(d2->R == 1 && d2->S == 1 && d2->stride_h == 1 && d2->stride_w == 1 &&
+                   d2->pad_h == 0 && d2->pad_w == 0 &&
+                   (d2->in_c_stride == 0 || d2->in_c_stride == d->K), Q8_EUNSUPPORTED);
+    Q8_REQUIRE(mode == 0 && stream_capable(d) && d->C % 64 == 0 && (d->K == 64 || d->K == 128) &&
+                   d2->K % d->K == 0, Q8_EUNSUPPORTED);
+    Q8_REQUIRE(q8_aligned(a.w2, 16) && (a.bias2 == nullptr || q8_aligned(a.bias2, 16)), Q8_EALIGN);
+    p.w2 = (const int8_t*)a.w2; p.bias2 = a.bias2; p.res2 = a.residual; p.y2 = a.z_y;
+    p.K2 = d2->K;
+    p.w2_bytes = d2->K * d->K;
+    p.out_cs2 = d2->out_c_stride ? d2->out_c_stride : d2->K;
+    p.out_off2 = d2->out_c_off;
+    p.res_cs2 = d2->res_c_stride ? d2->res_c_stride : d2->K;
+    p.res_off2 = d2->res_c_off;
+    Q8_REQUIRE(p.out_off2 >= 0 && p.res_off2 >= 0 && p.out_cs2 >= p.out_off2 + d2->K, Q8_EINVAL);
+    Q8_REQUIRE(a.residual == nullptr || p.res_cs2 >= p.res_off2 + d2->K, Q8_EINVAL);
+    {
+      float prod = q_out * a.q_w2;      // the intermediate's factor times the filters'
+      p.m2 = prod / a.q_out;
+      p.m_r2 = a.residual ? a.q_res / a.q_out : 0.0f;
+    }
+    p.relu2 = d2->relu ? 1 : 0;
+    auto aligned2 = [&](int al) {
+      return p.out_cs2 % al == 0 && p.out_off2 % al == 0 && q8_aligned(a.z_y, al) &&
+             (a.residual == nullptr ||
+              (p.res_cs2 % al == 0 && p.res_off2 % al == 0 && q8_aligned(a.residual, al)));
+    };
+    p.vec4_2 = aligned2(4) ? 1 : 0;
+    p.vec16_2 = aligned2(16) ? 1 : 0;
+    return q8::launch_pair_variant(p, s);
+  }
   const int variant = pick_variant(d);
   if (variant >= kRegBase) return q8::launch_reg_variant(variant - kRegBase, p, s);
   return q8::launch_stream_variant(variant, p, s);
@@ -353,6 +406,29 @@ int q8_conv_int8_real_output(const q8_conv_desc* d, const int8_t* z_x, const voi
   u.y_f32 = y_dev;            // null: rejected by the shared checks unless the output is empty
   return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, 1.0f, residual, q_res, nullptr,
                      nullptr, stream);
+}
+
+int q8_conv_pair_int8(const q8_conv_desc* d1, const int8_t* z_x, const void* w1_packed,
+                      const int32_t* bias1, float q_x, float q_w1, float q_mid,
+                      const q8_conv_desc* d2, const void* w2_packed, const int32_t* bias2,
+                      float q_w2, float q_out, const int8_t* residual, float q_res, int8_t* z_y,
+                      void* stream) {
+  PairArgs a{d2, w2_packed, bias2, q_w2, q_out, residual, q_res, z_y};
+  U8Flags u{0, 0, 0, nullptr};
+  u.pair = &a;
+  return conv_launch(d1, u, z_x, w1_packed, bias1, q_x, q_w1, q_mid, nullptr, 0.0f, nullptr, nullptr,
+                     stream);
+}
+
+int q8_conv_pair_supported(const q8_conv_desc* d1, const q8_conv_desc* d2) {
+  if (!desc_sane(d1) || !desc_sane(d2) || conv_mode(d1) != 0 || !stream_capable(d1)) return 0;
+  if (d1->C % 64 != 0 || (d1->K != 64 && d1->K != 128) || d2->K % d1->K != 0) return 0;
+  if (d2->N != d1->N || d2->H != q8_conv_out_h(d1) || d2->W != q8_conv_out_w(d1) || d2->C != d1->K)
+    return 0;
+  if (d2->R != 1 || d2->S != 1 || d2->stride_h != 1 || d2->stride_w != 1 || d2->pad_h || d2->pad_w)
+    return 0;
+  if (d2->in_c_stride != 0 && d2->in_c_stride != d1->K) return 0;
+  return 1;
 }
 
 int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32_t* bias_i32,

@@ -47,6 +47,18 @@ struct ConvParams {
   int relu;
   int vec4;       // 1: out/res addresses of 4-channel groups are 4-byte aligned
   int vec16;      // 1: out/res addresses of 16-channel groups are 16-byte aligned
+  // A second, 1x1 layer run on the tile's own output while it is still in LDS (the pair
+  // build of the main kernel; K == the tile's channel count, so a workgroup holds every
+  // channel of its pixels).  The first layer's y / out_* / res* are then unused: its codes
+  // (scale m, ReLU relu) never leave the chip.
+  const int8_t* __restrict__ w2;       // [K2][K] filters of the second layer, null: no pair
+  const int32_t* __restrict__ bias2;
+  const int8_t* __restrict__ res2;
+  int8_t* __restrict__ y2;
+  int K2, w2_bytes;
+  int out_cs2, out_off2, res_cs2, res_off2;
+  float m2, m_r2;
+  int relu2, vec4_2, vec16_2;
 };
 
 // x / d for 0 <= x < 2^31 with host-made constants s = ceil(log2 d), m = ceil(2^(31+s) / d):
@@ -294,9 +306,8 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
 // and one XOR per packed word); RES_U8: the residual holds such codes.
 // PC: one scale per output channel (mv) instead of p.m.
 template <bool HAS_RES, bool U8 = false, bool RES_U8 = false, bool PC = false>
-__device__ __forceinline__ void finish16_fast(const ConvParams& p, int pix, int ch,
-                                              const int (&v)[16], const int (&rw)[4],
-                                              const float (&mv)[16]) {
+__device__ __forceinline__ v4i codes16_fast(const ConvParams& p, const int (&v)[16],
+                                            const int (&rw)[4], const float (&mv)[16]) {
   const bool out_u8 = U8 && p.out_u8;
   const float lo = (p.relu || out_u8) ? 0.0f : -128.0f;   // ReLU folded into the lower bound
   const float hi = out_u8 ? 255.0f : 127.0f;
@@ -324,7 +335,15 @@ __device__ __forceinline__ void finish16_fast(const ConvParams& p, int pix, int 
     const unsigned w23 = __builtin_amdgcn_perm(r[4 * a + 3], r[4 * a + 2], 0x0c0c0400u);
     out[a] = (int)(__builtin_amdgcn_perm(w23, w01, 0x05040100u) ^ flip);
   }
-  *reinterpret_cast<v4i*>(p.y + (size_t)pix * p.out_cs + p.out_off + ch) = out;
+  return out;
+}
+
+template <bool HAS_RES, bool U8 = false, bool RES_U8 = false, bool PC = false>
+__device__ __forceinline__ void finish16_fast(const ConvParams& p, int pix, int ch,
+                                              const int (&v)[16], const int (&rw)[4],
+                                              const float (&mv)[16]) {
+  *reinterpret_cast<v4i*>(p.y + (size_t)pix * p.out_cs + p.out_off + ch) =
+      codes16_fast<HAS_RES, U8, RES_U8, PC>(p, v, rw, mv);
 }
 
 // Whole epilogue in one go (register-staged kernel).
@@ -363,6 +382,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // Entry points of the kernel translation units (host side).
 int launch_reg_variant(int variant, ConvParams& p, hipStream_t stream);      // q8_conv_reg.hip
 int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream);   // q8_conv_ring.hip
+int launch_pair_variant(ConvParams& p, hipStream_t stream);   // 3x3 -> 1x1 pair, K = 64 or 128
 const char* stream_variant_name(int variant);
 const char* reg_variant_name(int variant);
 

@@ -36,7 +36,13 @@ constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors
 // U8 = 1: the extended build of the kernel: unsigned activation codes (border correction,
 // unsigned residual / output) and per-output-channel scales; kept apart so that the plain
 // build's register count, and with it the number of resident wavefronts, stays what it is.
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8>
+//
+// PAIR = 1: the layer is followed by a 1x1 layer that reads nothing else (a bottleneck's
+// 3x3 -> 1x1).  The tile spans all K channels, so the workgroup holds every channel of its
+// pixels: their int8 codes go to LDS instead of HBM and serve as the activation operand of
+// the second layer, whose filters stream through LDS one channel tile after the other.
+// The two layers' arithmetic is exactly that of two launches.
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
 __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
                                       // descriptor types exist for the device target alone
@@ -294,6 +300,32 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       for (int e = 0; e < 16; ++e) acc[i][j][e] = v[e];
     }
   }
+  // Pair build: bias and residual codes of the second layer's first channel tile, requested
+  // ahead of the ring like the first layer's bias; double-buffered over its channel tiles.
+  v16i bias2[2][TC];
+  int res2[2][TC][TP][4];
+  ConvParams p2 = p;
+  if constexpr (PAIR) {
+    p2.K = p.K2; p2.bias = p.bias2; p2.res = p.res2; p2.y = p.y2;
+    p2.out_cs = p.out_cs2; p2.out_off = p.out_off2; p2.res_cs = p.res_cs2; p2.res_off = p.res_off2;
+    p2.m = p.m2; p2.m_r = p.m_r2; p2.relu = p.relu2; p2.vec4 = p.vec4_2; p2.vec16 = p.vec16_2;
+    p2.acc_dump = nullptr; p2.y_f32 = nullptr; p2.m_vec = nullptr;
+  }
+  auto fetch_second = [&](int t, auto buf_c) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_c)::value;
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+      const int ch = t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+      int b[16];
+      load_bias16(p2, ch, b);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) bias2[BUF][i][e] = b[e];
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+        load_res16(p2, pix0 + (wave_p * TP + j) * 32 + (lane & 31), ch, res2[BUF][i][j]);
+    }
+  };
+  if constexpr (PAIR) fetch_second(0, std::integral_constant<int, 0>{});
   const int nk = (p.red_len + BK - 1) / BK;
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
@@ -470,6 +502,127 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
        integral_constant<bool, true>{}, any_stage);
   mma(NH - 1);
 
+  if constexpr (PAIR) {
+    static_assert(UNIFORM == 1 && !U8, "pair build: plain uniform-tap kernel only");
+    constexpr int KS2 = BC / BK;        // reduction steps of the second layer (C2 = BC)
+    static_assert(STAGES >= 2 * KS2, "two filter buffers of KS2 stages each");
+    // LDS use from here on: the pixel rows of stages 0 .. KS2-1 hold the first layer's codes
+    // (step s = channels 64s .. 64s+63), the filter rows of stages b*KS2 .. b*KS2+KS2-1 the
+    // second layer's filters of one channel tile, b alternating between tiles.
+    const __amdgpu_buffer_rsrc_t rsrc_w2 =
+        __builtin_amdgcn_make_buffer_rsrc((void*)p.w2, 0, p.w2_bytes, 0x00020000);
+    int a2_off[A_LOADS];
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) {
+      const int row = (wave + NW * j) * RPW + lrow;
+      a2_off[j] = ((row & ~31) + row_to_channel(row & 31)) * BC + lchunk * 16;
+    }
+    auto issue_filters = [&](int t, int buf0) {
+      const int base = t * BC * BC;          // first byte of channel tile t's filters
+#pragma unroll
+      for (int s2 = 0; s2 < KS2; ++s2)
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(
+              rsrc_w2,
+              (__attribute__((address_space(3))) void*)(lds + (buf0 + s2) * STAGE_BYTES +
+                                                         (wave + NW * j) * 1024),
+              16, a2_off[j], base + s2 * BK, 0, 0);
+    };
+    // every wave has read its last operands of the first layer out of LDS
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue_filters(0, 0);
+    {
+      const float no_scales[16] = {};
+      const int no_res[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j) {
+          int v[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+          const v4i codes = codes16_fast<false>(p, v, no_res, no_scales);
+          const int chl = (wave_c * TC + i) * 32 + 16 * (lane >> 5);   // channel inside the tile
+          const int row = (wave_p * TP + j) * 32 + (lane & 31);        // pixel inside the tile
+          const int s2 = chl / BK, c = (chl % BK) / 16;
+          *reinterpret_cast<v4i*>(lds + s2 * STAGE_BYTES + A_BYTES + row * BK +
+                                  swz<CHUNKS>(row, c) * 16) = codes;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);            // the code writes
+    wait_vmcnt<0>();                               // the first filters (and bias2 / res2)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    // the tile's activations stay in registers for every channel tile
+    v4i bfr[KS2][NH][TP];
+#pragma unroll
+    for (int s2 = 0; s2 < KS2; ++s2)
+#pragma unroll
+      for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+          bfr[s2][h][j] = *reinterpret_cast<const v4i*>(lds + s2 * STAGE_BYTES + b_foff[h][j]);
+
+    const int n_pass = p.K2 / BC;
+    const bool fast2 = p2.vec16 && pix0 + BP <= p.M;
+    auto pass = [&](int t, auto buf_c) __attribute__((always_inline)) {
+      constexpr int BUF = decltype(buf_c)::value;
+      if (t + 1 < n_pass) {                 // everything of the next channel tile
+        fetch_second(t + 1, std::integral_constant<int, BUF ^ 1>{});
+        issue_filters(t + 1, (BUF ^ 1) * KS2);
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < KS2; ++s2)
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+          v4i afr[TC];
+#pragma unroll
+          for (int i = 0; i < TC; ++i)
+            afr[i] = *reinterpret_cast<const v4i*>(lds + (BUF * KS2 + s2) * STAGE_BYTES +
+                                                   a_foff[h][i]);
+#pragma unroll
+          for (int i = 0; i < TC; ++i)
+#pragma unroll
+            for (int j = 0; j < TP; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                  afr[i], bfr[s2][h][j], (s2 == 0 && h == 0) ? bias2[BUF][i] : acc[i][j], 0, 0, 0);
+        }
+      const float no_scales[16] = {};
+#pragma unroll
+      for (int i = 0; i < TC; ++i) {
+        const int ch = t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TP; ++j) {
+          const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
+          int v[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+          if (fast2) {
+            if (p2.res) finish16_fast<true>(p2, pix, ch, v, res2[BUF][i][j], no_scales);
+            else finish16_fast<false>(p2, pix, ch, v, res2[BUF][i][j], no_scales);
+          } else if (pix < p.M) {
+            finish16(p2, pix, ch, v, res2[BUF][i][j]);
+          }
+        }
+      }
+      // the next tile's filters have landed for every wave, and every wave is done with
+      // this tile's before they are overwritten
+      wait_vmcnt<0>();
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    };
+    for (int t = 0; t < n_pass; t += 2) {
+      pass(t, std::integral_constant<int, 0>{});
+      if (t + 1 < n_pass) pass(t + 1, std::integral_constant<int, 1>{});
+    }
+    return;
+  }
+
   // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
   const bool fast_tile =
       p.vec16 && !p.acc_dump && !p.y_f32 && ch0 + BC <= p.K && pix0 + BP <= p.M;
@@ -509,10 +662,10 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8>
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
 int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
   constexpr int kLdsBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
-  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8>;
+  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>;
   if constexpr (kLdsBytes > 65536) {
     // more than 64 KB of LDS per workgroup has to be requested once per kernel
     static const hipError_t attr = hipFuncSetAttribute(
@@ -538,6 +691,16 @@ int launch_ring(ConvParams& p, hipStream_t stream) {
       return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 2, U8>(p, dim3((unsigned)nblk), stream);
   }
   return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 0, U8>(p, dim3((unsigned)nblk), stream);
+}
+
+// The pair build: tile of WP*TP*32 pixels x all K = WC*TC*32 channels of the first layer.
+template <int WP, int WC, int TP, int TC, int BK, int STAGES>
+int launch_pair(ConvParams& p, hipStream_t stream) {
+  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
+  if (p.K != BC || p.C % BK != 0 || p.K2 % BC != 0 || !p.w2) return Q8_EUNSUPPORTED;
+  p.n_ptiles = (p.M + BP - 1) / BP;
+  p.n_ctiles = 1;
+  return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1, 0, 1>(p, dim3((unsigned)p.n_ptiles), stream);
 }
 
 struct RingVariant {
@@ -586,6 +749,11 @@ int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
     return v.launch_u8(p, stream);
   }
   return kRingVariants[variant].launch(p, stream);
+}
+int launch_pair_variant(ConvParams& p, hipStream_t stream) {
+  if (p.K == 64) return launch_pair<2, 2, 2, 1, 64, 2>(p, stream);     // 128 pixels x 64
+  if (p.K == 128) return launch_pair<2, 4, 2, 1, 64, 4>(p, stream);    // 128 pixels x 128
+  return Q8_EUNSUPPORTED;
 }
 const char* stream_variant_name(int variant) {
   return variant >= 0 && variant < kNumRingVariants ? kRingVariants[variant].name : "unsupported";

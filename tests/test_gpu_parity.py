@@ -397,6 +397,55 @@ def test_conv_per_channel_scales(B, geom, with_res):
         assert np.array_equal(host(got), want)
 
 
+PAIR_CASES = [
+    # first layer, K2, residual, ReLU of the second layer
+    (dict(N=2, H=14, W=14, C=64, K=64, R=3, S=3, pad_h=1, pad_w=1), 256, True, True),
+    (dict(N=3, H=13, W=11, C=64, K=64, R=3, S=3, pad_h=1, pad_w=1), 128, False, True),   # ragged pixels
+    (dict(N=2, H=28, W=28, C=128, K=128, R=3, S=3, pad_h=1, pad_w=1), 512, True, True),
+    (dict(N=1, H=9, W=7, C=128, K=128, R=3, S=3, pad_h=1, pad_w=1), 128, True, False),
+    (dict(N=2, H=20, W=20, C=64, K=64, R=1, S=1), 64, False, False),                      # 1x1 -> 1x1
+    (dict(N=1, H=31, W=31, C=192, K=128, R=3, S=3, stride_h=2, stride_w=2), 384, False, True),
+]
+
+
+@pytest.mark.parametrize("geom,K2,with_res,relu2", PAIR_CASES)
+def test_conv_pair_equals_two_layers(B, geom, K2, with_res, relu2):
+    """The fused 3x3 -> 1x1 launch gives the bits of the oracle's two layers."""
+    g1 = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(g1.K + K2 + g1.H)
+    x = rng.integers(-128, 128, (g1.N, g1.H, g1.W, g1.C)).astype(np.int8)
+    w1 = rng.integers(-128, 128, (g1.K, g1.R, g1.S, g1.C)).astype(np.int8)
+    b1 = rng.integers(-20000, 20000, g1.K).astype(np.int32)
+    Ho, Wo = g1.Ho, g1.Wo
+    g2 = orc.ConvGeom(N=g1.N, H=Ho, W=Wo, C=g1.K, K=K2, R=1, S=1)
+    w2 = rng.integers(-128, 128, (K2, 1, 1, g1.K)).astype(np.int8)
+    b2 = rng.integers(-20000, 20000, K2).astype(np.int32)
+    q_x, q_w1, q_w2 = np.float32(0.021), np.float32(0.0017), np.float32(0.0023)
+    q_mid = np.float32(q_x * q_w1 * 5476.0 * np.sqrt(g1.R * g1.S * g1.C) / 40.0)
+    q_out = np.float32(q_mid * q_w2 * 3000.0 * np.sqrt(g1.K) / 40.0)
+    q_res = np.float32(0.4) * q_out
+    res = rng.integers(-128, 128, (g1.N, Ho, Wo, K2)).astype(np.int8) if with_res else None
+    mid = orc.requant(orc.conv_i8(g1, x, w1, b1), orc.requant_scale(q_x, q_w1, q_mid), True)
+    want = orc.requant(orc.conv_i8(g2, mid, w2, b2), orc.requant_scale(q_mid, q_w2, q_out), relu2,
+                       res, orc.residual_scale(q_res, q_out) if with_res else 0.0)
+    assert 0.02 < np.mean(mid != 0) and np.mean(np.abs(want.astype(int)) >= 127) < 0.5
+
+    d1 = B.ConvDesc(g1.N, g1.H, g1.W, g1.C, g1.K, g1.R, g1.S, g1.stride_h, g1.stride_w, g1.pad_h,
+                    g1.pad_w, relu=1)
+    d2 = B.ConvDesc(g1.N, Ho, Wo, g1.K, K2, 1, 1, relu=int(relu2))
+    assert B.conv_pair_supported(d1, d2)
+    got = B.conv_pair_int8(d1, dev(x), B.pack_weights(d1, dev(w1)), dev(b1), float(q_x), float(q_w1),
+                           float(q_mid), d2, B.pack_weights(d2, dev(w2)), dev(b2), float(q_w2),
+                           float(q_out), None if res is None else dev(res), float(q_res))
+    assert np.array_equal(host(got), want)
+    # and the two launches it replaces give the same
+    mid_g = B.conv_int8(d1, dev(x), B.pack_weights(d1, dev(w1)), dev(b1), float(q_x), float(q_w1),
+                        float(q_mid))
+    two = B.conv_int8(d2, mid_g, B.pack_weights(d2, dev(w2)), dev(b2), float(q_mid), float(q_w2),
+                      float(q_out), None if res is None else dev(res), float(q_res))
+    assert np.array_equal(host(two), want)
+
+
 REAL_OUTPUT_CASES = [
     # geometry, residual, ReLU, extra channels of the output tensor, channel offset
     (dict(N=2, H=14, W=14, C=64, K=160, R=3, S=3, pad_h=1, pad_w=1), True, True, 0, 0),
