@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--per-channel-weights", action="store_true",
                     help="one weight factor per output channel instead of one per tensor; "
                          "reported as its own workload")
+    ap.add_argument("--fuse-pairs", action="store_true",
+                    help="a convolution and the 1x1 layer that alone reads it run as one launch")
     ap.add_argument("--own-sum-factor", action="store_true",
                     help="a fused sum's output factor from its own max-abs instead of the "
                          "max(q1, q2) rule; reported as its own workload")
@@ -120,7 +122,7 @@ def main():
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
     eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations,
                  per_channel_weights=args.per_channel_weights, real_outputs=args.real_output,
-                 own_sum_factor=args.own_sum_factor)
+                 own_sum_factor=args.own_sum_factor, fuse_pairs=args.fuse_pairs)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -329,13 +331,19 @@ def main():
     for i, op in enumerate(ops_list):
         if op.kind != "conv":
             continue
+        if op.name in eng.paired:
+            continue                      # counted with the layer in front of it
         n_launch = len(eng.parts) if i >= eng.n_unsplit else 1
         n_img = eng.parts[0][1] if i >= eng.n_unsplit else N
         ops, byts = conv_work(net, op, N)
+        if op.name in eng.pairs:          # one launch for two layers: the tensor between
+            ops2, byts2 = conv_work(net, eng.pairs[op.name], N)     # them is not moved
+            mid = net.tensors[op.dst]
+            ops, byts = ops + ops2, byts + byts2 - 2 * N * mid.H * mid.W * mid.C
         ops, byts = ops / n_launch, byts / n_launch          # per launch
         us = float(med[i + 1]) / n_launch
         us_cold = float(cold[i]) / n_launch
-        variant = B.conv_variant(eng.conv_desc(op, n_img))
+        variant = B.conv_variant(eng.conv_desc(op, n_img)) + ("+pair" if op.name in eng.pairs else "")
         bound = "mfma" if ops / byts > RIDGE else "hbm"
         t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)) * 1e6
         layers.append(dict(name=op.name, C=op.C, K=op.K, R=op.R, S=op.S, stride=op.stride,
@@ -429,6 +437,7 @@ def main():
                                f"{len(convs)} fused convs"
                                + (", unsigned p=8 ReLU outputs" if args.unsigned_activations else "")
                                + (", per-channel weight factors" if args.per_channel_weights else "")
+                               + (f", {len(eng.pairs)} fused layer pairs" if eng.pairs else "")
                                + (", fp32 output written by the last conv" if args.real_output else ""),
                    "batch": N,
                    "launch": "eager" if graph is None else "hip_graph",

@@ -428,6 +428,9 @@ int q8_conv_pair_supported(const q8_conv_desc* d1, const q8_conv_desc* d2) {
   if (d2->R != 1 || d2->S != 1 || d2->stride_h != 1 || d2->stride_w != 1 || d2->pad_h || d2->pad_w)
     return 0;
   if (d2->in_c_stride != 0 && d2->in_c_stride != d1->K) return 0;
+  // the operand ring and every filter of the second layer share the 160 KB of LDS
+  const long ring = d1->K == 64 ? 2L * (128 + 64) * 64 : 4L * (128 + 128) * 64;
+  if (ring + (long)d2->K * d1->K > 160 * 1024) return 0;
   return 1;
 }
 

@@ -302,7 +302,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   }
   // Pair build: bias and residual codes of the second layer's first channel tile, requested
   // ahead of the ring like the first layer's bias; double-buffered over its channel tiles.
-  v16i bias2[2][TC];
+  v16i bias2[TC];
   int res2[2][TC][TP][4];
   ConvParams p2 = p;
   if constexpr (PAIR) {
@@ -311,21 +311,49 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     p2.m = p.m2; p2.m_r = p.m_r2; p2.relu = p.relu2; p2.vec4 = p.vec4_2; p2.vec16 = p.vec16_2;
     p2.acc_dump = nullptr; p2.y_f32 = nullptr; p2.m_vec = nullptr;
   }
+  auto fetch_bias2 = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+      int b[16];
+      load_bias16(p2, t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) bias2[i][e] = b[e];
+    }
+  };
   auto fetch_second = [&](int t, auto buf_c) __attribute__((always_inline)) {
     constexpr int BUF = decltype(buf_c)::value;
 #pragma unroll
     for (int i = 0; i < TC; ++i) {
       const int ch = t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-      int b[16];
-      load_bias16(p2, ch, b);
-#pragma unroll
-      for (int e = 0; e < 16; ++e) bias2[BUF][i][e] = b[e];
 #pragma unroll
       for (int j = 0; j < TP; ++j)
         load_res16(p2, pix0 + (wave_p * TP + j) * 32 + (lane & 31), ch, res2[BUF][i][j]);
     }
   };
-  if constexpr (PAIR) fetch_second(0, std::integral_constant<int, 0>{});
+  // ... and ALL its filters, into LDS behind the ring: [K2 / BC tiles][KS2 steps][BC rows][BK]
+  constexpr int KS2 = BC / BK;          // reduction steps of the second layer (C2 = BC)
+  const int n_pass = PAIR ? p.K2 / BC : 0;
+  const int8_t* w2_lds = lds + STAGES * STAGE_BYTES;
+  if constexpr (PAIR) {
+    fetch_bias2(0);
+    fetch_second(0, std::integral_constant<int, 0>{});
+    const __amdgpu_buffer_rsrc_t rsrc_w2 =
+        __builtin_amdgcn_make_buffer_rsrc((void*)p.w2, 0, p.w2_bytes, 0x00020000);
+    for (int t = 0; t < n_pass; ++t)
+#pragma unroll
+      for (int s2 = 0; s2 < KS2; ++s2)
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j) {
+          const int row = (wave + NW * j) * RPW + lrow;
+          const int off = ((row & ~31) + row_to_channel(row & 31)) * BC + lchunk * 16;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(
+              rsrc_w2,
+              (__attribute__((address_space(3))) void*)(lds + STAGES * STAGE_BYTES +
+                                                         (t * KS2 + s2) * A_BYTES +
+                                                         (wave + NW * j) * 1024),
+              16, off, t * BC * BC + s2 * BK, 0, 0);
+        }
+  }
   const int nk = (p.red_len + BK - 1) / BK;
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
@@ -504,36 +532,12 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 
   if constexpr (PAIR) {
     static_assert(UNIFORM == 1 && !U8, "pair build: plain uniform-tap kernel only");
-    constexpr int KS2 = BC / BK;        // reduction steps of the second layer (C2 = BC)
-    static_assert(STAGES >= 2 * KS2, "two filter buffers of KS2 stages each");
-    // LDS use from here on: the pixel rows of stages 0 .. KS2-1 hold the first layer's codes
-    // (step s = channels 64s .. 64s+63), the filter rows of stages b*KS2 .. b*KS2+KS2-1 the
-    // second layer's filters of one channel tile, b alternating between tiles.
-    const __amdgpu_buffer_rsrc_t rsrc_w2 =
-        __builtin_amdgcn_make_buffer_rsrc((void*)p.w2, 0, p.w2_bytes, 0x00020000);
-    int a2_off[A_LOADS];
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-      const int row = (wave + NW * j) * RPW + lrow;
-      a2_off[j] = ((row & ~31) + row_to_channel(row & 31)) * BC + lchunk * 16;
-    }
-    auto issue_filters = [&](int t, int buf0) {
-      const int base = t * BC * BC;          // first byte of channel tile t's filters
-#pragma unroll
-      for (int s2 = 0; s2 < KS2; ++s2)
-#pragma unroll
-        for (int j = 0; j < A_LOADS; ++j)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              rsrc_w2,
-              (__attribute__((address_space(3))) void*)(lds + (buf0 + s2) * STAGE_BYTES +
-                                                         (wave + NW * j) * 1024),
-              16, a2_off[j], base + s2 * BK, 0, 0);
-    };
     // every wave has read its last operands of the first layer out of LDS
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue_filters(0, 0);
+    // The first layer's codes become the second layer's activation operand: the pixel rows
+    // of stages 0 .. KS2-1 (step s = channels 64s .. 64s+63), in the loader's swizzle.
     {
       const float no_scales[16] = {};
       const int no_res[4] = {0, 0, 0, 0};
@@ -553,7 +557,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
         }
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);            // the code writes
-    wait_vmcnt<0>();                               // the first filters (and bias2 / res2)
+    wait_vmcnt<0>();                               // the second layer's filters (long landed)
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -567,14 +571,13 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
         for (int j = 0; j < TP; ++j)
           bfr[s2][h][j] = *reinterpret_cast<const v4i*>(lds + s2 * STAGE_BYTES + b_foff[h][j]);
 
-    const int n_pass = p.K2 / BC;
+    // No synchronisation from here on: filters and activations are in place, a wave walks
+    // the channel tiles on its own; bias and residual codes are requested one tile ahead.
     const bool fast2 = p2.vec16 && pix0 + BP <= p.M;
     auto pass = [&](int t, auto buf_c) __attribute__((always_inline)) {
       constexpr int BUF = decltype(buf_c)::value;
-      if (t + 1 < n_pass) {                 // everything of the next channel tile
-        fetch_second(t + 1, std::integral_constant<int, BUF ^ 1>{});
-        issue_filters(t + 1, (BUF ^ 1) * KS2);
-      }
+      if (t + 1 < n_pass) fetch_second(t + 1, std::integral_constant<int, BUF ^ 1>{});
+      const int8_t* wt = w2_lds + t * KS2 * A_BYTES;
 #pragma unroll
       for (int s2 = 0; s2 < KS2; ++s2)
 #pragma unroll
@@ -582,15 +585,15 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
           v4i afr[TC];
 #pragma unroll
           for (int i = 0; i < TC; ++i)
-            afr[i] = *reinterpret_cast<const v4i*>(lds + (BUF * KS2 + s2) * STAGE_BYTES +
-                                                   a_foff[h][i]);
+            afr[i] = *reinterpret_cast<const v4i*>(wt + s2 * A_BYTES + a_foff[h][i]);
 #pragma unroll
           for (int i = 0; i < TC; ++i)
 #pragma unroll
             for (int j = 0; j < TP; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                  afr[i], bfr[s2][h][j], (s2 == 0 && h == 0) ? bias2[BUF][i] : acc[i][j], 0, 0, 0);
+                  afr[i], bfr[s2][h][j], (s2 == 0 && h == 0) ? bias2[i] : acc[i][j], 0, 0, 0);
         }
+      if (t + 1 < n_pass) fetch_bias2(t + 1);      // the MFMAs above have consumed this tile's
       const float no_scales[16] = {};
 #pragma unroll
       for (int i = 0; i < TC; ++i) {
@@ -609,12 +612,6 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
           }
         }
       }
-      // the next tile's filters have landed for every wave, and every wave is done with
-      // this tile's before they are overwritten
-      wait_vmcnt<0>();
-      asm volatile("" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
     };
     for (int t = 0; t < n_pass; t += 2) {
       pass(t, std::integral_constant<int, 0>{});
@@ -664,8 +661,20 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 
 template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
 int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
-  constexpr int kLdsBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
+  constexpr int kRingBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
   auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>;
+  if constexpr (PAIR) {
+    // the ring plus every filter of the second layer
+    constexpr int kMaxLds = 160 * 1024;
+    const long bytes = kRingBytes + (long)p.K2 * (WC * TC * 32);
+    if (bytes > kMaxLds) return Q8_EUNSUPPORTED;
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+    if (attr != hipSuccess) return Q8_EHIP;
+    hipLaunchKernelGGL(kernel, grid, dim3(WP * WC * 64), (unsigned)bytes, stream, p);
+    return q8_launch_status();
+  }
+  constexpr int kLdsBytes = kRingBytes;
   if constexpr (kLdsBytes > 65536) {
     // more than 64 KB of LDS per workgroup has to be requested once per kernel
     static const hipError_t attr = hipFuncSetAttribute(

@@ -31,8 +31,15 @@ class Engine:
     other half's work.  Results are the same bits as with one stream."""
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
-                 per_channel_weights=False, real_outputs=False, own_sum_factor=False):
+                 per_channel_weights=False, real_outputs=False, own_sum_factor=False,
+                 fuse_pairs=False):
         self.net = net
+        # fuse_pairs: a convolution whose output only one 1x1 layer reads runs together with
+        # that layer in one launch where the library supports the pair (same results; the
+        # intermediate tensor is then never written)
+        self.fuse_pairs = fuse_pairs
+        self.pairs = {}       # first conv name -> second conv (launched together)
+        self.paired = set()   # names of the second convs
         # own_sum_factor: a fused sum's output is calibrated by its own max-abs instead of
         # the max(q1, q2) rule of Eq. + (a variant; implied by unsigned activations)
         self.own_sum_factor = own_sum_factor
@@ -93,6 +100,30 @@ class Engine:
         for op in net.ops:
             if op.kind == "conv":
                 self.desc[op.name] = self._desc(op, batch)
+        if fuse_pairs:
+            assert not (unsigned_activations or per_channel_weights)
+            self._find_pairs()
+
+    def _find_pairs(self):
+        net = self.net
+        ops = net.ops
+        for i, a in enumerate(ops):
+            if a.kind != "conv" or a.res or a.dst in net.outputs or a.dst in self.real:
+                continue
+            if net.tensors[a.dst].C != a.K or a.name in self.paired:
+                continue
+            readers = [o for o in ops if o.src == a.dst or (o.kind == "conv" and o.res == a.dst)]
+            if len(readers) != 1 or readers[0].kind != "conv" or readers[0].src != a.dst:
+                continue
+            b = readers[0]
+            if b.dst in self.real or ops.index(b) != i + 1:
+                continue
+            # both launches must lie on the same side of the half-batch split
+            if (i < self.n_unsplit) != (i + 1 < self.n_unsplit):
+                continue
+            if B.conv_pair_supported(self.desc[a.name], self.desc[b.name]):
+                self.pairs[a.name] = b
+                self.paired.add(b.name)
 
     # ------------------------------------------------------------------ descriptors
     def _desc(self, op, N, framed=True):
@@ -288,6 +319,18 @@ class Engine:
         res = self.act[op.res][lo:lo + n] if op.res else None
         q_res = self.q[op.res] if op.res else 0.0
         U = self.unsigned
+        if op.name in self.paired and acc_dump is None:
+            return                       # ran with the layer in front of it
+        if op.name in self.pairs and acc_dump is None:
+            b = self.pairs[op.name]
+            packed2, bias2 = self.wq[b.name]
+            res2 = self.act[b.res][lo:lo + n] if b.res else None
+            B.conv_pair_int8(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed, bias,
+                             self.q[op.src], self.qw[op.name], self.q[op.dst],
+                             self.conv_desc(b, n), packed2, bias2, self.qw[b.name], self.q[b.dst],
+                             res2, self.q[b.res] if b.res else 0.0,
+                             out=self.act[b.dst][lo:lo + n])
+            return
         if op.dst in self.real and acc_dump is None:
             B.conv_int8_real_output(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed,
                                     bias, self.q[op.src], self.qw[op.name], res, q_res,

@@ -642,7 +642,8 @@ def test_config2_bottleneck_block(B):
 
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
-                          per_channel=False, real_outputs=False, own_sum_factor=False):
+                          per_channel=False, real_outputs=False, own_sum_factor=False,
+                          fuse_pairs=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -663,8 +664,11 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         return (a.astype(np.int16) + 128).astype(np.uint8) if name in U else a
 
     eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned,
-                 per_channel_weights=per_channel, real_outputs=real_outputs)
+                 per_channel_weights=per_channel, real_outputs=real_outputs,
+                 fuse_pairs=fuse_pairs)
     assert eng.unsigned == U
+    assert bool(eng.pairs) == fuse_pairs
+    unwritten = {op.dst for op in net.convs() if op.name in eng.pairs}   # stay on chip
     # outputs that leave the quantised domain as fp32 straight from their convolution
     real_want = {}
     if real_outputs:
@@ -700,7 +704,7 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
         assert not full[:, :top].any() and not full[:, top + z_in.shape[1]:].any()
         assert not full[:, :, :left].any() and not full[:, :, left + z_in.shape[2]:].any()
     for op in net.ops:
-        if op.dst in eng.real:
+        if op.dst in eng.real or op.dst in unwritten:
             continue
         got = codes(op.dst, host(eng.act[op.dst])[picks])
         assert got.dtype == acts[op.dst].dtype and np.array_equal(got, acts[op.dst]), op.name
@@ -765,6 +769,12 @@ def test_config5_ssd300_vgg16_sampled_images(B, batch, picks):
     # 3x3 stack at 300x300, ceil-mode pooling, dilation 6, head convolutions with
     # K in {16, 24, 84, 126}, twelve int8 outputs
     _sampled_images_check(B, 5, batch, picks, n_cal=2, cal_batch=4)
+
+
+def test_resnet50_with_fused_layer_pairs(B):
+    # every bottleneck's 3x3 -> 1x1 whose 3x3 has 64 or 128 filters runs as one launch, in
+    # the benchmark's launch configuration
+    _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, fuse_pairs=True)
 
 
 def test_resnet50_sums_at_their_own_calibrated_factor(B):
