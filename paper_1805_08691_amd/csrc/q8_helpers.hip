@@ -132,16 +132,29 @@ __global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* 
                                                                   int stride, int pad, int Ho, int Wo,
                                                                   int8_t* __restrict__ y) {
   const size_t total = (size_t)N * Ho * Wo * C16;
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+  // Workgroups go to the 8 XCDs round robin: renumber them so that each XCD owns one
+  // contiguous run of outputs.  Neighbouring output rows share input rows; with this they
+  // find them in their own L2 instead of fetching them once per XCD.
+  unsigned bid = blockIdx.x;
+  {
+    const unsigned xcd = bid % 8, idx = bid / 8;
+    const unsigned base = gridDim.x / 8, rem = gridDim.x % 8;
+    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  for (size_t i = (size_t)bid * kThreads + threadIdx.x; i < total;
        i += (size_t)gridDim.x * kThreads) {
     int c = (int)(i % C16);
     size_t t = i / C16;
     int wo = (int)(t % Wo); t /= Wo;
     int ho = (int)(t % Ho);
     int n = (int)(t / Ho);
-    int best[16];
+    // A byte in the high half of a 16-bit lane (low half zero) orders like the int8 it
+    // is: odd bytes are masked in place, even bytes shifted up, and each set takes a packed
+    // 16-bit max per tap.
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    unsigned best_odd[4], best_even[4];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) best[e] = -128;
+    for (int q = 0; q < 4; ++q) best_odd[q] = best_even[q] = 0x80008000u;     // -128, -128
     for (int r = 0; r < R; ++r) {
       int hi = ho * stride - pad + r;
       if ((unsigned)hi >= (unsigned)H) continue;
@@ -150,15 +163,21 @@ __global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* 
         if ((unsigned)wi >= (unsigned)W) continue;
         v4i v = *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          int b = (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
-          best[e] = b > best[e] ? b : best[e];
+        for (int q = 0; q < 4; ++q) {
+          const unsigned odd = (unsigned)v[q] & 0xff00ff00u;
+          const unsigned even = ((unsigned)v[q] << 8) & 0xff00ff00u;
+          const v2s mo = __builtin_elementwise_max(__builtin_bit_cast(v2s, best_odd[q]),
+                                                   __builtin_bit_cast(v2s, odd));
+          const v2s me = __builtin_elementwise_max(__builtin_bit_cast(v2s, best_even[q]),
+                                                   __builtin_bit_cast(v2s, even));
+          best_odd[q] = __builtin_bit_cast(unsigned, mo);
+          best_even[q] = __builtin_bit_cast(unsigned, me);
         }
       }
     }
-    v4i o = {0, 0, 0, 0};
+    v4i o;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) o[e >> 2] |= (best[e] & 0xff) << (8 * (e & 3));
+    for (int q = 0; q < 4; ++q) o[q] = (int)(best_odd[q] | (best_even[q] >> 8));
     *reinterpret_cast<v4i*>(y + i * 16) = o;
   }
 }
