@@ -111,7 +111,10 @@ int pick_variant(const q8_conv_desc* d) {
   //    64 pixels x 128 channels otherwise;
   //  - otherwise 128 x 128 with a ring of 3; when at most one workgroup per CU exists,
   //    eight wavefronts share the tile (more waves to hide LDS latency) with a ring of 4.
-  if (d->K <= 64) return 8;
+  //  - very large maps (hundreds of tiles per CU; the VGG-style layers of a detector at
+  //    batch 64): 256 pixels per tile, which halves the filter reads per pixel.
+  if (d->K <= 64) return tiles128 >= 16384 ? 3 : 8;
+  if (d->K >= 256 && tiles128 >= 1024 && nk > 4) return 13;
   if (tiles128 <= 64) return 7;
   if (tiles128 <= 128) return d->R * d->S == 1 ? 5 : 9;
   if (nk <= 4) return tiles128 >= 512 ? 8 : 4;
