@@ -126,7 +126,9 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       const int hi0 = ho * p.stride_h - p.pad_h;
       const int wi0 = wo * p.stride_w - p.pad_w;
       off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + x_shift + (UNIFORM == 1 ? lchunk * 16 : 0);
-      if (p.dil_h == 1 && p.dil_w == 1) {
+      if ((p.pad_h | p.pad_w) == 0) {
+        mask = bits_below(p.R * p.S);      // no padding: every tap of an output pixel is inside
+      } else if (p.dil_h == 1 && p.dil_w == 1) {
         // taps inside the image: rows [r_lo, r_hi), columns [s_lo, s_hi)
         const unsigned cols = bits_below(min(p.S, p.W - wi0)) & ~bits_below(-wi0);
         const int r_lo = -hi0, r_hi = p.H - hi0;
