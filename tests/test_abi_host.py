@@ -81,6 +81,31 @@ def test_bad_arguments_are_rejected_on_the_host():
     empty = B.ConvDesc(0, 8, 8, 16, 16, 3, 3)
     assert L.q8_conv_int8(C.byref(empty), None, None, None, 1.0, 1.0, 1.0, None, 0.0, None, None,
                           None) == 0                   # empty batch: nothing to do
+    # sizes beyond the kernels' 32-bit offsets are refused on the host, nothing is launched
+    big_x = B.ConvDesc(4096, 512, 512, 64, 64, 3, 3, pad_h=1, pad_w=1)        # activations > 2 GiB
+    assert L.q8_conv_int8(C.byref(big_x), *ok) == -2
+    big_m = B.ConvDesc(40000, 256, 256, 16, 64, 1, 1)                          # N*Ho*Wo > 2^31
+    assert L.q8_conv_int8(C.byref(big_m), *ok) == -2
+    big_w = B.ConvDesc(1, 8, 8, 16384, 16384, 3, 3, pad_h=1, pad_w=1)          # filters > 2 GiB
+    assert L.q8_conv_int8(C.byref(big_w), *ok) == -2
+    # layer pairs: what the pair build cannot take is reported, not attempted
+    p1 = B.ConvDesc(2, 14, 14, 64, 128, 3, 3, pad_h=1, pad_w=1, relu=1)
+    p2_ok = B.ConvDesc(2, 14, 14, 128, 512, 1, 1)
+    assert L.q8_conv_pair_supported(C.byref(p1), C.byref(p2_ok)) == 1
+    for bad2 in (B.ConvDesc(2, 14, 14, 128, 4096, 1, 1),          # its filters do not fit in LDS
+                 B.ConvDesc(2, 14, 14, 128, 192, 1, 1),           # K2 not a multiple of K1
+                 B.ConvDesc(2, 14, 14, 128, 512, 3, 3, pad_h=1, pad_w=1),
+                 B.ConvDesc(2, 7, 7, 128, 512, 1, 1),             # not the first layer's output
+                 B.ConvDesc(2, 14, 14, 128, 512, 1, 1, stride_h=2, stride_w=2)):
+        assert L.q8_conv_pair_supported(C.byref(p1), C.byref(bad2)) == 0
+    assert L.q8_conv_pair_supported(C.byref(B.ConvDesc(2, 14, 14, 64, 96, 3, 3)), C.byref(p2_ok)) == 0
+    pair_args = (fake, fake, None, 1.0, 1.0, 1.0)
+    assert L.q8_conv_pair_int8(C.byref(p1), *pair_args, C.byref(B.ConvDesc(2, 14, 14, 128, 4096, 1, 1)),
+                               fake, None, 1.0, 1.0, None, 0.0, fake, None) == -2
+    assert L.q8_conv_pair_int8(C.byref(p1), *pair_args, C.byref(p2_ok), None, None, 1.0, 1.0, None, 0.0,
+                               fake, None) == -1                     # no second filters
+    assert L.q8_conv_pair_int8(C.byref(p1), *pair_args, C.byref(p2_ok), fake, None, 1.0, 0.0, None, 0.0,
+                               fake, None) == -1                     # q_out <= 0
     # unsigned activation codes
     wide = B.ConvDesc(1, 8, 8, 16, 64, 3, 3, pad_h=1, pad_w=1, relu=1)
     u8 = (fake, fake, fake, fake, 1.0, 1.0, 1.0, None, 0.0, fake, None, None)
