@@ -14,8 +14,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libq8conv.so")
-SOURCES = ["q8_elementwise.hip", "q8_conv.hip", "q8_conv_ring.hip", "q8_conv_reg.hip",
-           "q8_helpers.hip"]
+SOURCES = ["q8_conv_ring.hip", "q8_conv_ring_ext.hip", "q8_conv_ring_pair.hip", "q8_conv.hip",
+           "q8_conv_reg.hip", "q8_elementwise.hip", "q8_helpers.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -36,7 +36,7 @@ def _compile(src):
 
 def build(verbose=True):
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:

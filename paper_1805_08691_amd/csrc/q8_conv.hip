@@ -13,7 +13,7 @@
 // column (= pixel) in four consecutive registers of a lane, which is what the epilogue
 // wants: bias, scale, residual, ReLU, Round, clamp on four channels, one packed store.
 // This file: host side of the convolution (argument checks, kernel choice, launch) and the
-// filter pre-pack.  Kernels: q8_conv_ring.hip (main), q8_conv_reg.hip (special shapes).
+// filter pre-pack.  Kernels: q8_conv_ring_kernel.h (main), q8_conv_reg.hip (special shapes).
 #include "q8_common.h"
 #include "q8_conv_common.h"
 

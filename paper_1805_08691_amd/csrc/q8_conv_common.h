@@ -382,7 +382,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 // Entry points of the kernel translation units (host side).
 int launch_reg_variant(int variant, ConvParams& p, hipStream_t stream);      // q8_conv_reg.hip
 int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream);   // q8_conv_ring.hip
-int launch_pair_variant(ConvParams& p, hipStream_t stream);   // 3x3 -> 1x1 pair, K = 64 or 128
+int launch_ring_ext_variant(int variant, ConvParams& p, hipStream_t stream);   // q8_conv_ring_ext.hip
+int launch_pair_variant(ConvParams& p, hipStream_t stream);   // q8_conv_ring_pair.hip: K = 64 or 128
 const char* stream_variant_name(int variant);
 const char* reg_variant_name(int variant);
 

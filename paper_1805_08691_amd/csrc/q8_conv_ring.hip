@@ -1,752 +1,29 @@
-// Main int8 implicit-GEMM convolution kernel (Eq. x / Eq. A' of arxiv 1805.08691) for
-// gfx950: C % 16 == 0 (or an unpadded 4-channel image), more than 32 output channels, at
-// most 32 filter taps.
-//
-// One workgroup (4 or 8 wavefronts) per output tile.  Chunks go from global memory straight into
-// LDS (buffer_load_dwordx4 ... lds, no register staging) through a ring of STAGES buffers,
-// so several reduction steps of loads are in flight per workgroup while the MFMAs of the
-// current step run.  One bare s_barrier per reduction step.
-//
-// A wavefront-wide direct load writes 64 x 16 bytes to consecutive LDS addresses, i.e. RPW
-// rows of BK bytes.  Which global chunk lands in which slot is chosen on the global side:
-// lane l fills row l / CHUNKS, physical slot l % CHUNKS, and therefore fetches logical chunk
-// (l % CHUNKS) ^ swz(row) of that row (XOR swizzle: conflict-free ds_read_b128 operand reads).
-//
-// Addressing uses raw buffer descriptors: a per-lane 32-bit offset that is computed once
-// (for activations: once per filter tap), plus a wave-uniform scalar offset per reduction
-// step, so the loads of the steady state need no vector arithmetic.  A chunk that must read as zero (padding, pixel or channel beyond the
-// tensor, reduction tail) gets an offset beyond the descriptor's size: the hardware's
-// range check then returns zeros.
-//
-// UNIFORM = 1 (C % BK == 0): every lane of the block is in the same filter tap during one
-// reduction step, so the tap offset is a scalar.  UNIFORM = 2 (S == 1 and BK % C == 0: a
-// column filter over few channels, which is also how an unpadded 4-channel image arrives):
-// a step covers BK / C whole taps; which of them a lane reads is fixed, and all lanes move
-// on by BK / C taps per step, so a lane adds a constant to a scalar.  UNIFORM = 0: each
-// lane tracks its own tap.
-#include <type_traits>
-#include "q8_common.h"
-#include "q8_conv_common.h"
+// The plain builds of the main convolution kernel (see q8_conv_ring_kernel.h) and the table
+// of tile / ring variants.  The extended builds (unsigned codes, per-channel scales) and the
+// pair builds are compiled in files of their own, so the three compile side by side.
+#include "q8_conv_ring_kernel.h"
 
 namespace q8 {
 namespace {
 
-constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
-
-// U8 = 1: the extended build of the kernel: unsigned activation codes (border correction,
-// unsigned residual / output) and per-output-channel scales; kept apart so that the plain
-// build's register count, and with it the number of resident wavefronts, stays what it is.
-//
-// PAIR = 1: the layer is followed by a 1x1 layer that reads nothing else (a bottleneck's
-// 3x3 -> 1x1).  The tile spans all K channels, so the workgroup holds every channel of its
-// pixels: their int8 codes go to LDS instead of HBM and serve as the activation operand of
-// the second layer, whose filters stream through LDS one channel tile after the other.
-// The two layers' arithmetic is exactly that of two launches.
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
-__global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
-#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
-                                      // descriptor types exist for the device target alone
-  constexpr int CHUNKS = BK / 16;          // 16-byte chunks per LDS row
-  constexpr int RPW = 64 / CHUNKS;         // rows filled by one wavefront-wide load (1 KB)
-  constexpr int NH = BK / 32;              // MFMA sub-steps (32 reduction bytes) per step
-  constexpr int BP = WP * TP * 32;
-  constexpr int BC = WC * TC * 32;
-  constexpr int A_GROUPS = BC / RPW, B_GROUPS = BP / RPW;
-  constexpr int NW = WP * WC;              // wavefronts per workgroup (4 or 8)
-  constexpr int A_LOADS = A_GROUPS / NW, B_LOADS = B_GROUPS / NW;
-  constexpr int LOADS = A_LOADS + B_LOADS;                   // per lane per stage
-  constexpr int A_BYTES = BC * BK, STAGE_BYTES = (BC + BP) * BK;
-  static_assert(BK == 64 || BK == 128, "reduction bytes per step");
-  static_assert(NW == 4 || NW == 8, "four or eight wavefronts per block");
-  static_assert(A_GROUPS % NW == 0 && B_GROUPS % NW == 0, "every wave issues the same loads");
-  static_assert(STAGES >= 2 && STAGES <= 8, "ring depth");
-  static_assert((STAGES - 2) * LOADS < 64, "vmcnt is 6 bits");
-
-  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // STAGES * STAGE_BYTES
-
-  const int nblk = p.n_ptiles * p.n_ctiles;
-  int bid = blockIdx.x;
-  {
-    const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
-    const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
-    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
-  }
-  const int ctile = bid % p.n_ctiles;
-  const int ptile = bid / p.n_ctiles;
-  const int pix0 = ptile * BP;
-  const int ch0 = ctile * BC;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wave_p = wave % WP;
-  const int wave_c = wave / WP;
-
-  const __amdgpu_buffer_rsrc_t rsrc_w =
-      __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, p.w_bytes, 0x00020000);
-  // The activation descriptor starts (pad_h rows + pad_w pixels) BEFORE the tensor: a lane's
-  // offset of tap (0,0) of its pixel is then never negative, also where that tap lies in
-  // the padding, and can stay in the vector offset while the tap's own (uniform,
-  // non-negative) offset goes into the scalar offset.  Nothing is read in front of the
-  // tensor: a tap in the padding gets an out-of-range vector offset.
-  const int x_shift = (p.pad_h * p.W + p.pad_w) * p.in_cs;
-  const __amdgpu_buffer_rsrc_t rsrc_x =
-      __builtin_amdgcn_make_buffer_rsrc((void*)(p.x - x_shift), 0, p.x_bytes + x_shift, 0x00020000);
-
-  // ---- loader state: lane l of wave w fills, in its j-th load, row (w + 4j)*RPW + l/CHUNKS,
-  // physical slot l % CHUNKS.  The swizzle term only depends on row bits that do not change
-  // with j, so the logical chunk a lane fetches is fixed.
-  const int lrow = lane / CHUNKS;
-  const int lchunk = (lane % CHUNKS) ^ swz<CHUNKS>(wave * RPW + lrow, 0);
-
-  int a_off[A_LOADS];                  // filter row offset + chunk, or out of range
-#pragma unroll
-  for (int j = 0; j < A_LOADS; ++j) {
-    const int row = (wave + NW * j) * RPW + lrow;
-    const int ch = ch0 + (row & ~31) + row_to_channel(row & 31);
-    a_off[j] = ch < p.K ? ch * p.red_len + lchunk * 16 : kOobOffset;
-  }
-  const bool pointwise = p.R * p.S == 1 && p.stride_h * p.stride_w == 1 && (p.pad_h | p.pad_w) == 0;
-  int b_off[B_LOADS];                  // offset of tap (0,0), channel 0 (+ chunk if UNIFORM)
-  unsigned b_mask[B_LOADS];            // bit t: tap t of this pixel lies inside the image
-#pragma unroll
-  for (int j = 0; j < B_LOADS; ++j) {
-    const int pix = pix0 + (wave + NW * j) * RPW + lrow;
-    unsigned mask = 0;
-    int off = 0;
-    if (pix < p.M && pointwise) {
-      // output pixel = input pixel, no padding
-      off = pix * p.in_cs + (UNIFORM == 1 ? lchunk * 16 : 0);
-      mask = 1u;
-    } else if (pix < p.M) {
-      const int n = fast_div(pix, p.div_img_m, p.div_img_s);
-      const int rem = pix - n * (p.Ho * p.Wo);
-      const int ho = fast_div(rem, p.div_row_m, p.div_row_s);
-      const int wo = rem - ho * p.Wo;
-      const int hi0 = ho * p.stride_h - p.pad_h;
-      const int wi0 = wo * p.stride_w - p.pad_w;
-      off = ((n * p.H + hi0) * p.W + wi0) * p.in_cs + x_shift + (UNIFORM == 1 ? lchunk * 16 : 0);
-      if ((p.pad_h | p.pad_w) == 0) {
-        mask = bits_below(p.R * p.S);      // no padding: every tap of an output pixel is inside
-      } else if (p.dil_h == 1 && p.dil_w == 1) {
-        // taps inside the image: rows [r_lo, r_hi), columns [s_lo, s_hi)
-        const unsigned cols = bits_below(min(p.S, p.W - wi0)) & ~bits_below(-wi0);
-        const int r_lo = -hi0, r_hi = p.H - hi0;
-        for (int r = 0; r < p.R; ++r)
-          if (r >= r_lo && r < r_hi) mask |= cols << (r * p.S);
-      } else {
-        int t = 0;
-        for (int r = 0; r < p.R; ++r) {
-          const bool hok = (unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H;
-          for (int s2 = 0; s2 < p.S; ++s2, ++t)
-            if (hok && (unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) mask |= 1u << t;
-        }
-      }
-    }
-    b_off[j] = off;
-    b_mask[j] = mask;
-  }
-
-  // ---- position in the reduction
-  const int dw_step = p.dil_w * p.in_cs;                     // offset step of one tap along S
-  const int dh_step = p.dil_h * p.W * p.in_cs - p.S * dw_step;   // extra step when a row wraps
-  // UNIFORM: scalars shared by the block.  Otherwise: this lane's own chunk.
-  int step_base = 0;                     // reduction byte offset of the next step to issue
-  int tap = 0, tap_s = 0, tap_c = 0, tap_delta = 0;
-  // UNIFORM == 2: the lane's tap inside a step and its channel offset inside that tap
-  const int row_step = p.dil_h * p.W * p.in_cs;
-  const int tap_l = UNIFORM == 2 ? (lchunk * 16) / p.C : 0;
-  const int lane_red = lchunk * 16;                    // the lane's reduction byte inside a step
-  int b_rowoff[B_LOADS];
-  unsigned b_mask_l[B_LOADS];
-#pragma unroll
-  for (int j = 0; j < B_LOADS; ++j) {
-    b_rowoff[j] = b_off[j] + tap_l * row_step + (lane_red - tap_l * p.C);
-    b_mask_l[j] = b_mask[j] >> tap_l;
-  }
-  if (UNIFORM == 0) {
-    const int red = lchunk * 16;
-    tap = red / p.C;
-    tap_c = red - tap * p.C;
-    const int r = tap / p.S;
-    tap_s = tap - r * p.S;
-    tap_delta = (r * p.dil_h * p.W + tap_s * p.dil_w) * p.in_cs;
-  }
-
-  int b_voff[B_LOADS];                   // UNIFORM: what the B loads of the current tap use
-  int tap_changed = 0;
-#pragma unroll
-  for (int j = 0; j < B_LOADS; ++j) b_voff[j] = (b_mask[j] & 1u) ? b_off[j] : kOobOffset;
-  auto refresh_taps = [&]() {            // UNIFORM, after the tap moved on
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j)
-      b_voff[j] = ((b_mask[j] >> tap) & 1u) ? b_off[j] : kOobOffset;
-  };
-
-  auto issue_stage = [&](int buf) {
-    int8_t* stage = lds + buf * STAGE_BYTES;
-    if constexpr (UNIFORM == 1) {
-#pragma unroll
-      for (int j = 0; j < A_LOADS; ++j)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
-            a_off[j], step_base, 0, 0);
-      // per lane: the pixel's offset, or "out of range" if the current tap lies in the
-      // padding (refreshed only when the tap changes); uniform: the tap's own offset
-      const int delta = tap_delta + tap_c;
-#pragma unroll
-      for (int j = 0; j < B_LOADS; ++j)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_x,
-            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
-            b_voff[j], delta, 0, 0);
-      step_base += BK;
-      // advance (branch-free, so the whole step stays one scheduling region)
-      tap_c += BK;
-      const int wrap_c = tap_c >= p.C ? 1 : 0;
-      tap_c = wrap_c ? 0 : tap_c;
-      tap += wrap_c;
-      tap_s += wrap_c;
-      tap_delta += wrap_c ? dw_step : 0;
-      const int wrap_s = tap_s == p.S ? 1 : 0;
-      tap_s = wrap_s ? 0 : tap_s;
-      tap_delta += wrap_s ? dh_step : 0;
-      tap_changed = wrap_c;
-    } else if constexpr (UNIFORM == 2) {
-      const bool red_ok = step_base + lane_red < p.red_len;
-#pragma unroll
-      for (int j = 0; j < A_LOADS; ++j) {
-        const int voff = red_ok ? a_off[j] : kOobOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
-            voff, step_base, 0, 0);
-      }
-#pragma unroll
-      for (int j = 0; j < B_LOADS; ++j) {
-        const bool ok = red_ok && ((b_mask_l[j] >> tap) & 1u);
-        const int voff = ok ? b_rowoff[j] : kOobOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_x,
-            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
-            voff, tap_delta, 0, 0);
-      }
-      step_base += BK;
-      const int taps_per_step = BK / p.C;
-      tap += taps_per_step;
-      tap_delta += taps_per_step * row_step;
-    } else {
-      const bool red_ok = step_base + lchunk * 16 < p.red_len;
-#pragma unroll
-      for (int j = 0; j < A_LOADS; ++j) {
-        const int voff = red_ok ? a_off[j] : kOobOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_w, (__attribute__((address_space(3))) void*)(stage + (wave + NW * j) * 1024), 16,
-            voff, step_base, 0, 0);
-      }
-      const int delta = tap_delta + tap_c;
-#pragma unroll
-      for (int j = 0; j < B_LOADS; ++j) {
-        const bool ok = red_ok && ((b_mask[j] >> tap) & 1u);
-        const int voff = ok ? b_off[j] + delta : kOobOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrc_x,
-            (__attribute__((address_space(3))) void*)(stage + A_BYTES + (wave + NW * j) * 1024), 16,
-            voff, 0, 0, 0);
-      }
-      step_base += BK;
-      tap_c += BK;
-      while (tap_c >= p.C) {
-        tap_c -= p.C;
-        ++tap;
-        tap_delta += dw_step;
-        if (++tap_s == p.S) { tap_s = 0; tap_delta += dh_step; }
-      }
-    }
-  };
-
-  // Accumulators start at the bias (Eq. A': the int32 bias shares the accumulator's factor).
-  // These loads are issued before any stage load, so the in-order vmcnt bookkeeping of
-  // the ring is unaffected, and their latency hides behind the first stages.
-  v16i acc[TC][TP];
-  // Unsigned input codes (stored minus 128): a pixel whose taps partly fall into the padding
-  // starts from a corrected value (see u8_border_apply); the look-ups ride along with the
-  // bias loads, ahead of the first stage.
-  int rect[TP];
-  bool any_fix = false;
-  if constexpr (U8) {
-#pragma unroll
-    for (int j = 0; j < TP; ++j) {
-      rect[j] = kNoBorderFix;
-      if (p.tap_sums) rect[j] = u8_border_rect(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31));
-      any_fix = any_fix || __any(rect[j] != kNoBorderFix);
-    }
-  }
-  const bool full_ctile = ch0 + BC <= p.K && (p.K & 3) == 0;
-#pragma unroll
-  for (int i = 0; i < TC; ++i) {
-    int b[16];
-    const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-    load_bias16(p, ch, b);
-#pragma unroll
-    for (int j = 0; j < TP; ++j) {
-      int v[16];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) v[e] = b[e];
-      if constexpr (U8) {
-        if (any_fix && rect[j] != kNoBorderFix && ch < p.K) {
-          if (full_ctile) u8_border_apply<true>(p, rect[j], ch, v);
-          else u8_border_apply<false>(p, rect[j], ch, v);
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = v[e];
-    }
-  }
-  // Pair build: bias and residual codes of the second layer's first channel tile, requested
-  // ahead of the ring like the first layer's bias; double-buffered over its channel tiles.
-  v16i bias2[TC];
-  int res2[2][TC][TP][4];
-  ConvParams p2 = p;
-  if constexpr (PAIR) {
-    p2.K = p.K2; p2.bias = p.bias2; p2.res = p.res2; p2.y = p.y2;
-    p2.out_cs = p.out_cs2; p2.out_off = p.out_off2; p2.res_cs = p.res_cs2; p2.res_off = p.res_off2;
-    p2.m = p.m2; p2.m_r = p.m_r2; p2.relu = p.relu2; p2.vec4 = p.vec4_2; p2.vec16 = p.vec16_2;
-    p2.acc_dump = nullptr; p2.y_f32 = nullptr; p2.m_vec = nullptr;
-  }
-  auto fetch_bias2 = [&](int t) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < TC; ++i) {
-      int b[16];
-      load_bias16(p2, t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
-#pragma unroll
-      for (int e = 0; e < 16; ++e) bias2[i][e] = b[e];
-    }
-  };
-  auto fetch_second = [&](int t, auto buf_c) __attribute__((always_inline)) {
-    constexpr int BUF = decltype(buf_c)::value;
-#pragma unroll
-    for (int i = 0; i < TC; ++i) {
-      const int ch = t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-#pragma unroll
-      for (int j = 0; j < TP; ++j)
-        load_res16(p2, pix0 + (wave_p * TP + j) * 32 + (lane & 31), ch, res2[BUF][i][j]);
-    }
-  };
-  // ... and ALL its filters, into LDS behind the ring: [K2 / BC tiles][KS2 steps][BC rows][BK]
-  constexpr int KS2 = BC / BK;          // reduction steps of the second layer (C2 = BC)
-  const int n_pass = PAIR ? p.K2 / BC : 0;
-  const int8_t* w2_lds = lds + STAGES * STAGE_BYTES;
-  if constexpr (PAIR) {
-    fetch_bias2(0);
-    fetch_second(0, std::integral_constant<int, 0>{});
-    const __amdgpu_buffer_rsrc_t rsrc_w2 =
-        __builtin_amdgcn_make_buffer_rsrc((void*)p.w2, 0, p.w2_bytes, 0x00020000);
-    for (int t = 0; t < n_pass; ++t)
-#pragma unroll
-      for (int s2 = 0; s2 < KS2; ++s2)
-#pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) {
-          const int row = (wave + NW * j) * RPW + lrow;
-          const int off = ((row & ~31) + row_to_channel(row & 31)) * BC + lchunk * 16;
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              rsrc_w2,
-              (__attribute__((address_space(3))) void*)(lds + STAGES * STAGE_BYTES +
-                                                         (t * KS2 + s2) * A_BYTES +
-                                                         (wave + NW * j) * 1024),
-              16, off, t * BC * BC + s2 * BK, 0, 0);
-        }
-  }
-  const int nk = (p.red_len + BK - 1) / BK;
-  const int frag_row = lane & 31;
-  const int frag_half = lane >> 5;
-
-  // Residual codes (fused element-wise sum).  With a short reduction (every step fits in
-  // the prologue) they are requested first of all, so one memory latency covers bias,
-  // residual and operands; otherwise they are requested in the last step.
-  int res_w[TC][TP][4];
-  auto fetch_residual = [&]() {
-#pragma unroll
-    for (int i = 0; i < TC; ++i)
-#pragma unroll
-      for (int j = 0; j < TP; ++j)
-        load_res16(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31),
-                   ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), res_w[i][j]);
-  };
-  const bool early_residual = nk <= STAGES - 1;
-  if (early_residual) fetch_residual();
-
-  // Operand fragments of the 32-byte sub-steps of a reduction step, double-buffered in
-  // registers.  The loop is software-pipelined inside one wavefront: the LDS reads of a
-  // sub-step are issued one phase before the MFMAs that consume them, and the MFMAs of the
-  // last sub-step of step kt-1 run after the barrier of step kt, so LDS latency, the
-  // barrier and the issue of the global loads all overlap matrix work.
-  v4i af[2][TC], bf[2][TP];
-  // LDS offsets inside a stage, per sub-step.  The swizzle term only looks at row bits below
-  // 32, and sub-step h uses chunk 2h + half = (chunk of sub-step 0) ^ 2h: one offset is
-  // computed in full, the others differ by a tile's row distance and one XOR.
-  int a_foff[NH][TC], b_foff[NH][TP];
-  const int foff0 = frag_row * BK + swz<CHUNKS>(frag_row, frag_half) * 16;
-#pragma unroll
-  for (int h = 0; h < NH; ++h) {
-#pragma unroll
-    for (int i = 0; i < TC; ++i) {
-      a_foff[h][i] = (foff0 ^ (h * 32)) + (wave_c * TC + i) * 32 * BK;
-      asm volatile("" : "+v"(a_foff[h][i]));     // keep in a register, do not recompute
-    }
-#pragma unroll
-    for (int j = 0; j < TP; ++j) {
-      b_foff[h][j] = (foff0 ^ (h * 32)) + A_BYTES + (wave_p * TP + j) * 32 * BK;
-      asm volatile("" : "+v"(b_foff[h][j]));
-    }
-  }
-#pragma unroll
-  for (int b = 0; b < 2; ++b) {
-#pragma unroll
-    for (int i = 0; i < TC; ++i) af[b][i] = v4i{0, 0, 0, 0};
-#pragma unroll
-    for (int j = 0; j < TP; ++j) bf[b][j] = v4i{0, 0, 0, 0};
-  }
-  auto load_frags = [&](const int8_t* stage, int h) {
-#pragma unroll
-    for (int i = 0; i < TC; ++i)
-      af[h & 1][i] = *reinterpret_cast<const v4i*>(stage + a_foff[h][i]);
-#pragma unroll
-    for (int j = 0; j < TP; ++j)
-      bf[h & 1][j] = *reinterpret_cast<const v4i*>(stage + b_foff[h][j]);
-  };
-  auto mma = [&](int h) {
-#pragma unroll
-    for (int i = 0; i < TC; ++i)
-#pragma unroll
-      for (int j = 0; j < TP; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
-                                                          0, 0, 0);
-  };
-
-  // One reduction step.  LATER = steps issued after step kt that may still be in flight
-  // when step kt must have landed; ISSUE = whether a further step is issued; LAST = whether
-  // the residual codes are fetched (no stage load follows, so vmcnt bookkeeping is over).
-  // STAGE = ring buffer of step kt when the caller knows it at compile time (the LDS reads
-  // then need no address arithmetic: fixed per-lane offsets plus an immediate), else -1.
-  auto step = [&](int kt, auto later_c, auto issue_c, auto last_c, auto stage_c) {
-    constexpr int LATER = decltype(later_c)::value;
-    constexpr int STAGE = decltype(stage_c)::value;
-    wait_vmcnt<LATER * LOADS>();
-    // Bare barrier (no fence: a fence would drain the loads of the later steps too).
-    // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS
-    // (its last fragments are in registers already).
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    const int8_t* stage = lds + (STAGE >= 0 ? STAGE : kt % STAGES) * STAGE_BYTES;
-    load_frags(stage, 0);
-    if constexpr (decltype(issue_c)::value)
-      issue_stage(STAGE >= 0 ? (STAGE + STAGES - 1) % STAGES : (kt + STAGES - 1) % STAGES);
-    if constexpr (decltype(last_c)::value) {
-      if (!early_residual) fetch_residual();
-    }
-    mma(NH - 1);                        // last sub-step of step kt-1 (zeros on the first step)
-#pragma unroll
-    for (int h = 1; h < NH; ++h) {
-      load_frags(stage, h);
-      mma(h - 1);
-    }
-    // Instruction order inside the step (one scheduling region): the LDS reads of the
-    // first sub-step; then MFMAs with one global->LDS load after each (a wavefront issues
-    // in order: spreading the loads lets a load that waits for queue space hide behind a
-    // running MFMA); the LDS reads of sub-step h are spread between the MFMAs of h-1.
-    if constexpr (!decltype(last_c)::value) {
-      constexpr int kMma = TC * TP, kFrag = TC + TP;
-      constexpr int kVmem = decltype(issue_c)::value ? LOADS : 0;
-      __builtin_amdgcn_sched_group_barrier(0x100, kFrag, 0);              // DS reads, sub-step 0
-      int vmem_left = kVmem;
-#pragma unroll
-      for (int h = 0; h < NH; ++h) {
-#pragma unroll
-        for (int g = 0; g < kMma; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
-          if (vmem_left > 0) {
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);            // one VMEM read
-            --vmem_left;
-          }
-          if (h + 1 < NH && g < kFrag)
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // one DS read
-        }
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (UNIFORM == 1 && decltype(issue_c)::value) {
-      if (tap_changed) refresh_taps();
-    }
-  };
-  using std::integral_constant;
-  constexpr integral_constant<int, -1> any_stage{};
-
-  // prologue: up to STAGES-1 reduction steps in flight
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s)
-    if (s < nk) {
-      issue_stage(s);
-      if constexpr (UNIFORM == 1) {
-        if (tap_changed) refresh_taps();
-      }
-    }
-  // Scalar loads still outstanding here would make every LDS wait inside the loop a full
-  // one (scalar and LDS results share a counter but return in no fixed order): settle them
-  // now, so the loop waits for exactly the fragments it needs.
-  __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0), other counters untouched
-  // steady state: every step finds STAGES-2 later steps in flight and issues one more
-  int kt = 0;
-  // passes over the ring: STAGES steps whose buffers are known at compile time
-  for (; kt + 2 * STAGES - 2 < nk; kt += STAGES) {
-    auto ring_pass = [&](auto self, auto s_c) __attribute__((always_inline)) -> void {
-      constexpr int S = decltype(s_c)::value;
-      if constexpr (S < STAGES) {
-        step(kt + S, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
-             integral_constant<bool, false>{}, integral_constant<int, S>{});
-        self(self, integral_constant<int, S + 1>{});
-      }
-    };
-    ring_pass(ring_pass, integral_constant<int, 0>{});
-  }
-  for (; kt + STAGES - 1 < nk; ++kt)
-    step(kt, integral_constant<int, STAGES - 2>{}, integral_constant<bool, true>{},
-         integral_constant<bool, false>{}, any_stage);
-  // drain: the last min(STAGES-1, nk) steps, with fewer and fewer loads behind them
-#define Q8_DRAIN_STEP(L)                                                              \
-  if constexpr (STAGES >= (L) + 2) {                                                  \
-    if (nk - kt == (L) + 1) {                                                         \
-      step(kt, integral_constant<int, (L)>{}, integral_constant<bool, false>{},       \
-           integral_constant<bool, false>{}, any_stage);                              \
-      ++kt;                                                                           \
-    }                                                                                 \
-  }
-  Q8_DRAIN_STEP(6)
-  Q8_DRAIN_STEP(5)
-  Q8_DRAIN_STEP(4)
-  Q8_DRAIN_STEP(3)
-  Q8_DRAIN_STEP(2)
-  Q8_DRAIN_STEP(1)
-#undef Q8_DRAIN_STEP
-  step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
-       integral_constant<bool, true>{}, any_stage);
-  mma(NH - 1);
-
-  if constexpr (PAIR) {
-    static_assert(UNIFORM == 1 && !U8, "pair build: plain uniform-tap kernel only");
-    // every wave has read its last operands of the first layer out of LDS
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    // The first layer's codes become the second layer's activation operand: the pixel rows
-    // of stages 0 .. KS2-1 (step s = channels 64s .. 64s+63), in the loader's swizzle.
-    {
-      const float no_scales[16] = {};
-      const int no_res[4] = {0, 0, 0, 0};
-#pragma unroll
-      for (int i = 0; i < TC; ++i)
-#pragma unroll
-        for (int j = 0; j < TP; ++j) {
-          int v[16];
-#pragma unroll
-          for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
-          const v4i codes = codes16_fast<false>(p, v, no_res, no_scales);
-          const int chl = (wave_c * TC + i) * 32 + 16 * (lane >> 5);   // channel inside the tile
-          const int row = (wave_p * TP + j) * 32 + (lane & 31);        // pixel inside the tile
-          const int s2 = chl / BK, c = (chl % BK) / 16;
-          *reinterpret_cast<v4i*>(lds + s2 * STAGE_BYTES + A_BYTES + row * BK +
-                                  swz<CHUNKS>(row, c) * 16) = codes;
-        }
-    }
-    __builtin_amdgcn_s_waitcnt(0xc07f);            // the code writes
-    wait_vmcnt<0>();                               // the second layer's filters (long landed)
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    // the tile's activations stay in registers for every channel tile
-    v4i bfr[KS2][NH][TP];
-#pragma unroll
-    for (int s2 = 0; s2 < KS2; ++s2)
-#pragma unroll
-      for (int h = 0; h < NH; ++h)
-#pragma unroll
-        for (int j = 0; j < TP; ++j)
-          bfr[s2][h][j] = *reinterpret_cast<const v4i*>(lds + s2 * STAGE_BYTES + b_foff[h][j]);
-
-    // No synchronisation from here on: filters and activations are in place, a wave walks
-    // the channel tiles on its own; bias and residual codes are requested one tile ahead.
-    const bool fast2 = p2.vec16 && pix0 + BP <= p.M;
-    auto pass = [&](int t, auto buf_c) __attribute__((always_inline)) {
-      constexpr int BUF = decltype(buf_c)::value;
-      if (t + 1 < n_pass) fetch_second(t + 1, std::integral_constant<int, BUF ^ 1>{});
-      const int8_t* wt = w2_lds + t * KS2 * A_BYTES;
-#pragma unroll
-      for (int s2 = 0; s2 < KS2; ++s2)
-#pragma unroll
-        for (int h = 0; h < NH; ++h) {
-          v4i afr[TC];
-#pragma unroll
-          for (int i = 0; i < TC; ++i)
-            afr[i] = *reinterpret_cast<const v4i*>(wt + s2 * A_BYTES + a_foff[h][i]);
-#pragma unroll
-          for (int i = 0; i < TC; ++i)
-#pragma unroll
-            for (int j = 0; j < TP; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                  afr[i], bfr[s2][h][j], (s2 == 0 && h == 0) ? bias2[i] : acc[i][j], 0, 0, 0);
-        }
-      if (t + 1 < n_pass) fetch_bias2(t + 1);      // the MFMAs above have consumed this tile's
-      const float no_scales[16] = {};
-#pragma unroll
-      for (int i = 0; i < TC; ++i) {
-        const int ch = t * BC + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-#pragma unroll
-        for (int j = 0; j < TP; ++j) {
-          const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
-          int v[16];
-#pragma unroll
-          for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
-          if (fast2) {
-            if (p2.res) finish16_fast<true>(p2, pix, ch, v, res2[BUF][i][j], no_scales);
-            else finish16_fast<false>(p2, pix, ch, v, res2[BUF][i][j], no_scales);
-          } else if (pix < p.M) {
-            finish16(p2, pix, ch, v, res2[BUF][i][j]);
-          }
-        }
-      }
-    };
-    for (int t = 0; t < n_pass; t += 2) {
-      pass(t, std::integral_constant<int, 0>{});
-      if (t + 1 < n_pass) pass(t + 1, std::integral_constant<int, 1>{});
-    }
-    return;
-  }
-
-  // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
-  const bool fast_tile =
-      p.vec16 && !p.acc_dump && !p.y_f32 && ch0 + BC <= p.K && pix0 + BP <= p.M;
-  auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
-    // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
-    // residual, signed residual, unsigned residual); 6, 7: fast with per-channel scales
-    // (no residual, residual)
-    constexpr int MODE = decltype(mode_c)::value;
-#pragma unroll
-    for (int i = 0; i < TC; ++i) {
-      const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-      if (MODE == 0 && ch >= p.K) continue;
-      float mv[16] = {};
-      if constexpr (MODE >= 6) load_scale16(p, ch, mv);
-#pragma unroll
-      for (int j = 0; j < TP; ++j) {
-        const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
-        if (MODE == 0 && pix >= p.M) continue;
-        int v[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
-        if constexpr (MODE == 0) finish16(p, pix, ch, v, res_w[i][j]);
-        else if constexpr (MODE <= 2) finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j], mv);
-        else if constexpr (MODE <= 5)
-          finish16_fast<MODE >= 4, true, MODE == 5>(p, pix, ch, v, res_w[i][j], mv);
-        else finish16_fast<MODE == 7, false, false, true>(p, pix, ch, v, res_w[i][j], mv);
-      }
-    }
-  };
-  if (!fast_tile) finish_all(std::integral_constant<int, 0>{});
-  else if (U8 && p.m_vec) {
-    if (p.res) finish_all(std::integral_constant<int, 7>{});
-    else finish_all(std::integral_constant<int, 6>{});
-  } else if (!p.res) finish_all(std::integral_constant<int, U8 ? 3 : 1>{});
-  else if (U8 && p.res_u8) finish_all(std::integral_constant<int, 5>{});
-  else finish_all(std::integral_constant<int, U8 ? 4 : 2>{});
-#endif  // __HIP_DEVICE_COMPILE__
-}
-
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
-int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
-  constexpr int kRingBytes = STAGES * (WP * TP + WC * TC) * 32 * BK;
-  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>;
-  if constexpr (PAIR) {
-    // the ring plus every filter of the second layer
-    constexpr int kMaxLds = 160 * 1024;
-    const long bytes = kRingBytes + (long)p.K2 * (WC * TC * 32);
-    if (bytes > kMaxLds) return Q8_EUNSUPPORTED;
-    static const hipError_t attr = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
-    if (attr != hipSuccess) return Q8_EHIP;
-    hipLaunchKernelGGL(kernel, grid, dim3(WP * WC * 64), (unsigned)bytes, stream, p);
-    return q8_launch_status();
-  }
-  constexpr int kLdsBytes = kRingBytes;
-  if constexpr (kLdsBytes > 65536) {
-    // more than 64 KB of LDS per workgroup has to be requested once per kernel
-    static const hipError_t attr = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (attr != hipSuccess) return Q8_EHIP;
-  }
-  hipLaunchKernelGGL(kernel, grid, dim3(WP * WC * 64), kLdsBytes, stream, p);
-  return q8_launch_status();
-}
-
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int U8>
-int launch_ring(ConvParams& p, hipStream_t stream) {
-  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
-  p.n_ptiles = (p.M + BP - 1) / BP;
-  p.n_ctiles = (p.K + BC - 1) / BC;
-  long nblk = (long)p.n_ptiles * p.n_ctiles;
-  if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
-  if (p.C % BK == 0)
-    return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1, U8>(p, dim3((unsigned)nblk), stream);
-  if constexpr (WP * TP * 32 == 128 && WC * TC * 32 == 64 && STAGES == 2 && !U8) {
-    // the tile the first (image) layers use also has the column-filter build
-    if (p.S == 1 && BK % p.C == 0)
-      return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 2, U8>(p, dim3((unsigned)nblk), stream);
-  }
-  return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 0, U8>(p, dim3((unsigned)nblk), stream);
-}
-
-// The pair build: tile of WP*TP*32 pixels x all K = WC*TC*32 channels of the first layer.
-template <int WP, int WC, int TP, int TC, int BK, int STAGES>
-int launch_pair(ConvParams& p, hipStream_t stream) {
-  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
-  if (p.K != BC || p.C % BK != 0 || p.K2 % BC != 0 || !p.w2) return Q8_EUNSUPPORTED;
-  p.n_ptiles = (p.M + BP - 1) / BP;
-  p.n_ctiles = 1;
-  return launch_ring_grid<WP, WC, TP, TC, BK, STAGES, 1, 0, 1>(p, dim3((unsigned)p.n_ptiles), stream);
-}
-
 struct RingVariant {
   const char* name;
   int (*launch)(ConvParams&, hipStream_t);
-  int (*launch_u8)(ConvParams&, hipStream_t);    // null: no unsigned-code build of this one
 };
-#define Q8_RING_VARIANT(WP, WC, TP, TC, BK, ST) \
+#define Q8_RING_ROW(I, WP, WC, TP, TC, BK, ST) \
   { "conv_i8_ring_kernel<" #WP "," #WC "," #TP "," #TC "," #BK "," #ST ">", \
-    &launch_ring<WP, WC, TP, TC, BK, ST, 0>, &launch_ring<WP, WC, TP, TC, BK, ST, 1> }
-#define Q8_RING_SIGNED(WP, WC, TP, TC, BK, ST) \
-  { "conv_i8_ring_kernel<" #WP "," #WC "," #TP "," #TC "," #BK "," #ST ">", \
-    &launch_ring<WP, WC, TP, TC, BK, ST, 0>, nullptr }
-// pixels x channels per tile = (WP*TP*32) x (WC*TC*32); BK bytes per step; ring depth
+    &launch_ring<WP, WC, TP, TC, BK, ST, 0> },
 const RingVariant kRingVariants[] = {
-    Q8_RING_VARIANT(2, 2, 2, 2, 64, 2),    //  0: 128 x 128
-    Q8_RING_VARIANT(2, 2, 2, 2, 64, 3),    //  1
-    Q8_RING_VARIANT(2, 2, 2, 2, 64, 4),    //  2
-    Q8_RING_VARIANT(4, 1, 2, 2, 64, 3),    //  3: 256 x 64
-    Q8_RING_VARIANT(2, 2, 1, 2, 64, 2),    //  4:  64 x 128
-    Q8_RING_VARIANT(2, 2, 1, 2, 64, 4),    //  5
-    Q8_RING_VARIANT(2, 2, 1, 1, 64, 2),    //  6:  64 x 64
-    Q8_RING_VARIANT(2, 2, 1, 1, 64, 4),    //  7
-    Q8_RING_VARIANT(2, 2, 2, 1, 64, 2),    //  8: 128 x 64
-    Q8_RING_VARIANT(2, 2, 2, 1, 64, 4),    //  9
-    Q8_RING_VARIANT(2, 4, 2, 1, 64, 3),    // 10: 128 x 128, eight wavefronts of 64 x 32
-    Q8_RING_VARIANT(2, 4, 2, 1, 64, 4),    // 11
-    Q8_RING_SIGNED (4, 2, 1, 2, 64, 3),    // 12: 128 x 128, eight wavefronts of 32 x 64
-    Q8_RING_SIGNED (4, 2, 2, 2, 64, 3),    // 13: 256 x 128, eight wavefronts of 64 x 64
-    Q8_RING_SIGNED (2, 4, 2, 2, 64, 3),    // 14: 128 x 256, eight wavefronts of 64 x 64
-    Q8_RING_SIGNED (2, 2, 2, 2, 64, 6),    // 15: 128 x 128, deep rings for one workgroup per CU
-    Q8_RING_SIGNED (2, 2, 2, 2, 64, 8),    // 16
-    Q8_RING_SIGNED (2, 4, 2, 1, 64, 8),    // 17: the same with eight wavefronts
-    Q8_RING_SIGNED (2, 2, 2, 1, 64, 8),    // 18: 128 x 64, deep ring
+    Q8_RING_EXT_LIST(Q8_RING_ROW)          //  0 .. 11: also in the extended build
+    Q8_RING_ROW(12, 4, 2, 1, 2, 64, 3)     // 12: 128 x 128, eight wavefronts of 32 x 64
+    Q8_RING_ROW(13, 4, 2, 2, 2, 64, 3)     // 13: 256 x 128, eight wavefronts of 64 x 64
+    Q8_RING_ROW(14, 2, 4, 2, 2, 64, 3)     // 14: 128 x 256, eight wavefronts of 64 x 64
+    Q8_RING_ROW(15, 2, 2, 2, 2, 64, 6)     // 15: 128 x 128, deep rings for one workgroup per CU
+    Q8_RING_ROW(16, 2, 2, 2, 2, 64, 8)     // 16
+    Q8_RING_ROW(17, 2, 4, 2, 1, 64, 8)     // 17: the same with eight wavefronts
+    Q8_RING_ROW(18, 2, 2, 2, 1, 64, 8)     // 18: 128 x 64, deep ring
 };
+#undef Q8_RING_ROW
 constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]);
 
 }  // namespace
@@ -756,15 +33,9 @@ int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
   if (variant < 0 || variant >= kNumRingVariants) return Q8_EINVAL;
   if (p.in_u8 | p.out_u8 | p.res_u8 | (p.m_vec != nullptr)) {
     // variants without an extended build fall back to the 128 x 128 ring of 3
-    const RingVariant& v = kRingVariants[variant].launch_u8 ? kRingVariants[variant] : kRingVariants[1];
-    return v.launch_u8(p, stream);
+    return launch_ring_ext_variant(variant < kNumRingExtVariants ? variant : 1, p, stream);
   }
   return kRingVariants[variant].launch(p, stream);
-}
-int launch_pair_variant(ConvParams& p, hipStream_t stream) {
-  if (p.K == 64) return launch_pair<2, 2, 2, 1, 64, 2>(p, stream);     // 128 pixels x 64
-  if (p.K == 128) return launch_pair<2, 4, 2, 1, 64, 4>(p, stream);    // 128 pixels x 128
-  return Q8_EUNSUPPORTED;
 }
 const char* stream_variant_name(int variant) {
   return variant >= 0 && variant < kNumRingVariants ? kRingVariants[variant].name : "unsupported";
