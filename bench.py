@@ -328,8 +328,15 @@ def main():
     by_variant = {}
     tot_ops = tot_us = tot_bytes = tot_cold = 0.0
     roof_us = 0.0
+    helpers = []          # the pooling launches between convolutions (not the paper's method)
     for i, op in enumerate(ops_list):
         if op.kind != "conv":
+            n_launch = len(eng.parts) if i >= eng.n_unsplit else 1
+            s_t, d_t = net.tensors[op.src], net.tensors[op.dst]
+            byts = N * (s_t.H * s_t.W * s_t.C + d_t.H * d_t.W * s_t.C) / n_launch
+            us = float(med[i + 1]) / n_launch
+            helpers.append(dict(name=op.name, mode=op.mode, H=s_t.H, C=s_t.C, R=op.R, stride=op.stride,
+                                us=round(us, 2), gbs=round(byts / us / 1e3, 1), launches=n_launch))
             continue
         if op.name in eng.paired:
             continue                      # counted with the layer in front of it
@@ -357,6 +364,9 @@ def main():
         tot_ops += ops * n_launch; tot_us += us * n_launch; tot_bytes += byts * n_launch
         roof_us += t_roof * n_launch
         tot_cold += us_cold * n_launch
+    for Hh in helpers:
+        log("{name:22s} {mode}-pool {R}x{R}/{stride} H={H:<3d} C={C:<4d} {us:8.2f} us {gbs:7.1f} GB/s x{launches}"
+            .format(**Hh))
     for L in layers:
         log("{name:22s} C={C:<4d} K={K:<4d} {R}x{S}/{stride} H={H:<3d} {variant:30s} {us:8.2f} us "
             "(cold {cold_us:7.2f}) {tops:7.1f} TOP/s {gbs:7.1f} GB/s  {bound:4s} roof {roof_us:6.2f} us frac {frac:.3f}"
@@ -450,6 +460,7 @@ def main():
         "int8_conv_tops_one_stream": round(agg_tops, 1),
         "hbm_passes": passes,
         "conv_kernel_us_per_step": round(tot_us, 1),
+        "helper_kernel_us_per_step": round(sum(h["us"] * h["launches"] for h in helpers), 1),
         "conv_kernel_us_per_step_cold": round(tot_cold, 1) if not args.no_cold else None,
         "measured_ceilings": ceilings,
         "one_stream_step_us": round(serial_us, 1),
@@ -461,7 +472,8 @@ def main():
     }
     if args.layers_out:
         with open(args.layers_out, "w") as f:
-            json.dump(dict(result=result, layers=layers, variants=by_variant), f, indent=1)
+            json.dump(dict(result=result, layers=layers, helpers=helpers, variants=by_variant), f,
+                      indent=1)
     print(json.dumps(result), flush=True)
 
 

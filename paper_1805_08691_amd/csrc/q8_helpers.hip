@@ -217,6 +217,63 @@ __global__ __launch_bounds__(kThreads) void pool_i8_kernel(const int8_t* __restr
   }
 }
 
+// The same with 16 channels per lane (C, out_cs and out_off multiples of 16, 16-byte aligned
+// tensors): 16-byte loads and one 16-byte store; workgroups renumbered so that each XCD owns
+// a contiguous run of outputs (neighbouring outputs share input rows).
+__global__ __launch_bounds__(kThreads) void pool_i8_vec_kernel(const int8_t* __restrict__ x, int N,
+                                                               int H, int W, int C16, int mode, int R,
+                                                               int S, int stride, int pad, int Ho,
+                                                               int Wo, float m, float inv_count,
+                                                               int8_t* __restrict__ y, int out_cs,
+                                                               int out_off) {
+  const size_t total = (size_t)N * Ho * Wo * C16;
+  unsigned bid = blockIdx.x;
+  {
+    const unsigned xcd = bid % 8, idx = bid / 8;
+    const unsigned base = gridDim.x / 8, rem = gridDim.x % 8;
+    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  for (size_t i = (size_t)bid * kThreads + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * kThreads) {
+    int c = (int)(i % C16);
+    size_t t = i / C16;
+    int wo = (int)(t % Wo); t /= Wo;
+    int ho = (int)(t % Ho);
+    int n = (int)(t / Ho);
+    int best[16], sum[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { best[e] = -128; sum[e] = 0; }
+    for (int r = 0; r < R; ++r) {
+      int hi = ho * stride - pad + r;
+      if ((unsigned)hi >= (unsigned)H) continue;
+      for (int s2 = 0; s2 < S; ++s2) {
+        int wi = wo * stride - pad + s2;
+        if ((unsigned)wi >= (unsigned)W) continue;
+        v4i v = *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16);
+        if (mode == 0) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            int b = (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
+            best[e] = b > best[e] ? b : best[e];
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sum[e] += (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
+        }
+      }
+    }
+    v4i o = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float f = mode == 0 ? (float)best[e] : (float)sum[e] * inv_count;
+      f = f * m;
+      f = fminf(fmaxf(f, -128.0f), 127.0f);
+      o[e >> 2] |= ((int)rintf(f) & 0xff) << (8 * (e & 3));
+    }
+    *reinterpret_cast<v4i*>(y + (((size_t)n * Ho + ho) * Wo + wo) * out_cs + out_off + c * 16) = o;
+  }
+}
+
 // fp32 twin for the calibration forward (max, or mean with padding counted as zeros).
 __global__ __launch_bounds__(kThreads) void pool_f32_kernel(const float* __restrict__ x, int N, int H,
                                                             int W, int C, int mode, int R, int S,
@@ -335,9 +392,18 @@ int q8_pool_i8(const int8_t* x_dev, int N, int H, int W, int C, int mode, int R,
   size_t total = (size_t)N * Ho * Wo * C;
   if (total == 0) return Q8_OK;
   Q8_REQUIRE(x_dev && y_dev, Q8_EINVAL);
+  const float inv_count = 1.0f / (float)(R * S);
+  if (C % 16 == 0 && out_c_stride % 16 == 0 && out_c_off % 16 == 0 && q8_aligned(x_dev, 16) &&
+      q8_aligned(y_dev, 16)) {
+    size_t vb = (total / 16 + kThreads - 1) / kThreads;
+    if (vb > 65536) vb = 65536;
+    hipLaunchKernelGGL(pool_i8_vec_kernel, dim3((unsigned)vb), dim3(kThreads), 0, (hipStream_t)stream,
+                       x_dev, N, H, W, C / 16, mode, R, S, stride, pad, Ho, Wo, m, inv_count, y_dev,
+                       out_c_stride, out_c_off);
+    return q8_launch_status();
+  }
   size_t blocks = (total + kThreads - 1) / kThreads;
   if (blocks > 65536) blocks = 65536;
-  const float inv_count = 1.0f / (float)(R * S);
   hipLaunchKernelGGL(pool_i8_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
                      x_dev, N, H, W, C, mode, R, S, stride, pad, Ho, Wo, m, inv_count, y_dev,
                      out_c_stride, out_c_off);
