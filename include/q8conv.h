@@ -230,7 +230,7 @@ const char *q8_conv_variant(const q8_conv_desc *d);
 
 /* Tests and tuning only: force tile/ring variant `index` (0 .. n-1, in the order of the
  * library's variant table) for every later q8_conv_int8 call whose geometry the main
- * kernel can take (C % 16 == 0, K > 32, R*S <= 32); -1 restores automatic selection.
+ * kernel can take (C % 16 == 0, R*S <= 32); -1 restores automatic selection.
  * Process-wide, not thread-safe; results are identical for every variant.             */
 int q8_conv_force_variant(int index);
 

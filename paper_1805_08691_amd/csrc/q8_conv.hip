@@ -86,9 +86,14 @@ bool image_rows_contiguous(const q8_conv_desc* d) {
   return d->K > 32 && d->R <= 32 && d->H >= d->R && d->W >= d->S;
 }
 
+// The main kernel: 16-channel chunks and at most 32 taps (its in-image tap mask is 32 bits),
+// any K (a channel tile is at least 64 wide; filter rows beyond K read as zeros), or an
+// unpadded 4-channel image.
 bool stream_capable(const q8_conv_desc* d) {
-  return (conv_mode(d) == 0 && d->K > 32 && d->R * d->S <= 32) || image_rows_contiguous(d);
+  return (conv_mode(d) == 0 && d->R * d->S <= 32) || image_rows_contiguous(d);
 }
+// Its extended build (unsigned codes, per-channel scales) is kept to K > 32.
+bool ext_capable(const q8_conv_desc* d) { return stream_capable(d) && d->K > 32; }
 
 int pick_variant(const q8_conv_desc* d) {
   const int mode = conv_mode(d);
@@ -113,7 +118,13 @@ int pick_variant(const q8_conv_desc* d) {
   //    eight wavefronts share the tile (more waves to hide LDS latency) with a ring of 4.
   //  - very large maps (hundreds of tiles per CU; the VGG-style layers of a detector at
   //    batch 64): 256 pixels per tile, which halves the filter reads per pixel.
-  if (d->K <= 64) return tiles128 >= 16384 ? 3 : 8;
+  if (d->K <= 64) {
+    if (tiles128 >= 16384) return 3;
+    // a long reduction on a small map (a detector's box head): at most a workgroup or two
+    // per CU, so the ring has to cover the memory latency by itself
+    if (nk >= 16 && tiles128 <= 512) return tiles128 <= 128 ? 7 : 9;
+    return 8;
+  }
   if (d->K >= 256 && tiles128 >= 1024 && nk > 4) return 13;
   if (tiles128 <= 64) return 7;
   if (tiles128 <= 128) return d->R * d->S == 1 ? 5 : 9;
@@ -250,14 +261,14 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   p.tap_sums = u.tap_sums;
   p.m_vec = u.m_vec;
   if (u.m_vec) {
-    Q8_REQUIRE(stream_capable(d), Q8_EUNSUPPORTED);
+    Q8_REQUIRE(ext_capable(d), Q8_EUNSUPPORTED);
     Q8_REQUIRE(!(u.in_u8 || u.out_u8 || u.res_u8), Q8_EUNSUPPORTED);
     Q8_REQUIRE(q8_aligned(u.m_vec, 16), Q8_EALIGN);
   }
   if (u.in_u8 || u.out_u8 || u.res_u8) {
     // unsigned codes: the streaming kernel only; an unsigned input whose taps can fall into
     // the padding needs the per-tap filter sums; an unsigned output is a ReLU output
-    Q8_REQUIRE(stream_capable(d) && (mode == 0 || !u.in_u8), Q8_EUNSUPPORTED);
+    Q8_REQUIRE(ext_capable(d) && (mode == 0 || !u.in_u8), Q8_EUNSUPPORTED);
     Q8_REQUIRE(!u.out_u8 || d->relu, Q8_EINVAL);
     Q8_REQUIRE(!u.res_u8 || residual, Q8_EINVAL);
     if (u.in_u8 && (d->pad_h || d->pad_w)) {

@@ -109,7 +109,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     # unsigned activation codes
     wide = B.ConvDesc(1, 8, 8, 16, 64, 3, 3, pad_h=1, pad_w=1, relu=1)
     u8 = (fake, fake, fake, fake, 1.0, 1.0, 1.0, None, 0.0, fake, None, None)
-    assert L.q8_conv_u8(C.byref(d), 1, 1, 0, *u8) == -2          # K <= 32: not the main kernel
+    assert L.q8_conv_u8(C.byref(d), 1, 1, 0, *u8) == -2          # K <= 32: not in the extended build
     norelu = B.ConvDesc(1, 8, 8, 16, 64, 3, 3, pad_h=1, pad_w=1, relu=0)
     assert L.q8_conv_u8(C.byref(norelu), 1, 1, 0, *u8) == -1     # unsigned output without ReLU
     assert L.q8_conv_u8(C.byref(wide), 1, 1, 1, *u8) == -1       # unsigned residual, none given
@@ -127,7 +127,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     pc = (fake, fake, None, fake, 1.0, None, 0.0, fake, None, None)
     assert L.q8_conv_int8_per_channel(C.byref(wide), fake, fake, None, None, 1.0, None, 0.0, fake,
                                       None, None) == -1          # no scale vector
-    assert L.q8_conv_int8_per_channel(C.byref(d), *pc) == -2     # K <= 32: not the main kernel
+    assert L.q8_conv_int8_per_channel(C.byref(d), *pc) == -2     # K <= 32: not in the extended build
     assert L.q8_conv_int8_per_channel(C.byref(wide), fake, fake, None, C.c_void_p(0x1004), 1.0,
                                       None, 0.0, fake, None, None) == -3
     # real-valued (fp32) output

@@ -452,7 +452,7 @@ REAL_OUTPUT_CASES = [
     (dict(N=2, H=7, W=7, C=512, K=256, R=1, S=1), True, True, 0, 0),          # complete tiles
     (dict(N=1, H=19, W=19, C=64, K=84, R=3, S=3, pad_h=1, pad_w=1), False, False, 0, 0),  # SSD head
     (dict(N=1, H=17, W=17, C=48, K=72, R=1, S=7, pad_w=3), False, True, 12, 4),
-    (dict(N=2, H=9, W=9, C=16, K=17, R=3, S=3, pad_h=1, pad_w=1), True, False, 5, 3),  # K <= 32 kernel
+    (dict(N=2, H=9, W=9, C=16, K=17, R=3, S=3, pad_h=1, pad_w=1), True, False, 5, 3),  # K <= 32: a channel tile mostly beyond K
     (dict(N=64, H=1, W=1, C=2048, K=1000, R=1, S=1), False, False, 0, 0),     # classifier logits
     (dict(N=0, H=5, W=5, C=16, K=16, R=1, S=1), False, False, 0, 0),
 ]
