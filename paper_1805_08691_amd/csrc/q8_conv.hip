@@ -83,7 +83,7 @@ int g_variant_override = -1;   // tests / tuning: force a stream variant where i
 bool image_rows_contiguous(const q8_conv_desc* d) {
   if (conv_mode(d) != 1 || d->pad_h || d->pad_w || d->dil_h != 1 || d->dil_w != 1) return false;
   if (d->in_c_stride != 0 && d->in_c_stride != 4) return false;
-  return d->K > 32 && d->R <= 32 && d->H >= d->R && d->W >= d->S;
+  return d->R <= 32 && d->H >= d->R && d->W >= d->S;
 }
 
 // The main kernel: 16-channel chunks and at most 32 taps (its in-image tap mask is 32 bits),

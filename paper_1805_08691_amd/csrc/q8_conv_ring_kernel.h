@@ -624,8 +624,10 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   }
 
   // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
-  const bool fast_tile =
-      p.vec16 && !p.acc_dump && !p.y_f32 && ch0 + BC <= p.K && pix0 + BP <= p.M;
+  // (complete in pixels; in channels either complete or K a multiple of the 16-channel group
+  // a lane holds, the groups beyond K being skipped)
+  const bool fast_tile = p.vec16 && !p.acc_dump && !p.y_f32 && pix0 + BP <= p.M &&
+                         (ch0 + BC <= p.K || (p.K & 15) == 0);
   auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
     // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
     // residual, signed residual, unsigned residual); 6, 7: fast with per-channel scales
@@ -634,7 +636,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 #pragma unroll
     for (int i = 0; i < TC; ++i) {
       const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-      if (MODE == 0 && ch >= p.K) continue;
+      if (ch >= p.K) continue;
       float mv[16] = {};
       if constexpr (MODE >= 6) load_scale16(p, ch, mv);
 #pragma unroll
