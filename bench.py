@@ -154,14 +154,11 @@ def main():
     if args.real_output:
         assert out_name in eng.real, "this network's output is not written whole by a convolution"
 
-    def finish_output():
-        if not args.real_output:              # else the last convolution wrote fp32 already
-            eng.dequantize(out_name, out=out_f32)
+    # what leaves the int8 domain in a step (nothing when the last convolution writes fp32)
+    dequant = {} if args.real_output else {out_name: out_f32}
 
     def step():
-        eng.quantize_input(x)
-        eng.run_layers()
-        finish_output()
+        eng.run_step(x, dequant)
 
     step()
     torch.cuda.synchronize()
@@ -197,13 +194,9 @@ def main():
     # total the per-launch intervals below must add up to
     serial_us = ms_per_step * 1e3
     if graph is not None and eng.n_streams > 1:
-        def serial_step():
-            eng.quantize_input(x)
-            eng.run_layers(serial=True)
-            finish_output()
         g1 = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g1):
-            serial_step()
+            eng.run_step(x, dequant, serial=True)
         for _ in range(3):
             g1.replay()
         torch.cuda.synchronize()
@@ -239,7 +232,8 @@ def main():
             for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
                 eng.run_ops([op], lo, n)
             ev[i + 2].record()
-        finish_output()
+        for name, buf in dequant.items():
+            eng.dequantize(name, out=buf)
         ev[-1].record()
         torch.cuda.synchronize()
         for i in range(len(ops_list) + 2):

@@ -24,11 +24,12 @@ def _pad_c(c):
 
 
 class Engine:
-    """``n_streams`` = 2 runs the layers behind the first pooling op as two concurrent
-    half-batch pipelines (batch elements are independent once the factor table is frozen):
-    one on the caller's stream, one on a side stream of the same (default) priority, joined
-    again before forward() returns.  A layer's launch latency and its tail then overlap the
-    other half's work.  Results are the same bits as with one stream."""
+    """``n_streams`` = 2 runs every layer as two concurrent half-batch pipelines (batch elements
+    are independent once the factor table is frozen): one on the caller's stream, one on a
+    side stream of the same (default) priority, forked behind the quantisation of the input
+    and joined again before the outputs are dequantised.  A layer's
+    launch latency and its tail then overlap the other half's work.  Results are the same bits
+    as with one stream."""
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
                  per_channel_weights=False, real_outputs=False, own_sum_factor=False,
@@ -78,8 +79,9 @@ class Engine:
         self.side = torch.cuda.Stream(device=self.dev) if self.n_streams == 2 else None
         half = (batch + 1) // 2
         self.parts = [(0, half), (half, batch - half)] if self.n_streams == 2 else [(0, batch)]
-        first_pool = next((i for i, o in enumerate(net.ops) if o.kind == "pool"), -1)
-        self.n_unsplit = first_pool + 1 if self.n_streams == 2 else len(net.ops)
+        # number of leading layers that run on the whole batch before it is split (none: the
+        # pipelines start right behind the quantisation of the input)
+        self.n_unsplit = 0 if self.n_streams == 2 else len(net.ops)
         self.part_desc = {}   # (conv name, images) -> ConvDesc
         # An image of fewer than 4 channels read by one convolution is stored inside a zero
         # frame that holds that layer's padding, and the layer runs without padding.
@@ -279,16 +281,18 @@ class Engine:
         top, left = self.in_frame[:2]
         return a[:, top:top + t.H, left:left + t.W]
 
-    def quantize_input(self, x):
+    def quantize_input(self, x, lo=0, n=None):
+        """Eq. Q on images [lo, lo + n) of the fp32 batch ``x`` into the input's codes."""
+        n = self.N if n is None else n
         t = self.net.tensors[self.net.input]
+        x = x[lo:lo + n]
+        z = self.act[self.net.input][lo:lo + n]
         if self.in_frame:
-            B.quantize_image(x, self.q[self.net.input], P_ACT, self.act[self.net.input],
-                             self.in_frame[0], self.in_frame[1])
+            B.quantize_image(x, self.q[self.net.input], P_ACT, z, self.in_frame[0], self.in_frame[1])
         elif _pad_c(t.C) != t.C:
-            B.quantize_pad_channels(x, _pad_c(t.C), self.q[self.net.input], P_ACT,
-                                    out=self.act[self.net.input])
+            B.quantize_pad_channels(x, _pad_c(t.C), self.q[self.net.input], P_ACT, out=z)
         else:
-            B.quantize(x, self.q[self.net.input], P_ACT, out=self.act[self.net.input])
+            B.quantize(x, self.q[self.net.input], P_ACT, out=z)
 
     def run_pool(self, op, lo=0, n=None):
         n = self.N if n is None else n
@@ -363,45 +367,59 @@ class Engine:
         """q_in / q_out rounded once to fp32 (both factors are fp32 values)."""
         return float(np.float32(q_in) / np.float32(q_out))
 
+    def run_step(self, x=None, dequant=None, serial=False):
+        """One pass over the batch: Eq. Q on ``x`` (if given), every layer, Eq. D on the
+        tensors named in ``dequant`` ({name: fp32 output buffer}).  With two streams the
+        layers of each half batch form a pipeline of their own between the (whole-batch)
+        quantise and dequantise launches -- splitting those two as well was slower;
+        ``serial`` issues the same launches one pipeline after the other on the caller's
+        stream."""
+        if x is not None:
+            self.quantize_input(x)
+        if self.n_streams == 1 or serial:
+            for lo, n in self.parts:
+                self.run_ops(self.net.ops, lo, n)
+        else:
+            main = torch.cuda.current_stream()
+            self.side.wait_stream(main)
+            with torch.cuda.stream(self.side):
+                self.run_ops(self.net.ops, *self.parts[1])
+            self.run_ops(self.net.ops, *self.parts[0])
+            main.wait_stream(self.side)
+        for name, out in (dequant or {}).items():
+            self.dequantize(name, out=out)
+
     def run_layers(self, acc_dump=None, serial=False):
-        """``serial``: the same launches (one per part) all on the caller's stream."""
-        ops = self.net.ops
-        if acc_dump or self.n_streams == 1:
-            for op in ops:
+        """Every layer on the codes already in the input buffer.  ``acc_dump``
+        ({conv name: int32 buffer}): whole-batch launches that also store the accumulators."""
+        if acc_dump:
+            for op in self.net.ops:
                 if op.kind == "pool":
                     self.run_pool(op)
                 else:
-                    self.run_conv(op, acc_dump=acc_dump.get(op.name) if acc_dump else None)
+                    self.run_conv(op, acc_dump=acc_dump.get(op.name))
             return
-        self.run_ops(ops[:self.n_unsplit], 0, self.N)
-        if serial:
-            for lo, n in self.parts:
-                self.run_ops(ops[self.n_unsplit:], lo, n)
-            return
-        main = torch.cuda.current_stream()
-        self.side.wait_stream(main)
-        with torch.cuda.stream(self.side):
-            self.run_ops(ops[self.n_unsplit:], *self.parts[1])
-        self.run_ops(ops[self.n_unsplit:], *self.parts[0])
-        main.wait_stream(self.side)
+        self.run_step(serial=serial)
 
-    def dequantize(self, name, out=None):
-        """Eq. D on tensor ``name`` (signed or unsigned codes); a real-valued output is
-        already there."""
+    def dequantize(self, name, out=None, lo=0, n=None):
+        """Eq. D on images [lo, lo + n) of tensor ``name`` (signed or unsigned codes); a
+        real-valued output is already there."""
+        n = self.N if n is None else n
+        if out is not None:
+            out = out[lo:lo + n]
         if name in self.real:
             if out is not None:
-                out.copy_(self.act_f32[name])
+                out.copy_(self.act_f32[name][lo:lo + n])
                 return out
-            return self.act_f32[name]
+            return self.act_f32[name][lo:lo + n]
         fn = B.dequantize_u8 if name in self.unsigned else B.dequantize
-        return fn(self.act[name], self.q[name], out=out)
+        return fn(self.act[name][lo:lo + n], self.q[name], out=out)
 
     def forward(self, x):
         """x: fp32 NHWC device tensor of the network input.  Returns the int8 outputs."""
         if not self.act:
             self.allocate()
-        self.quantize_input(x)
-        self.run_layers()
+        self.run_step(x)
         return [self.act[o] for o in self.net.outputs]
 
     def capture(self, x):
