@@ -127,11 +127,14 @@ __global__ __launch_bounds__(kThreads) void maxpool_kernel(const T* __restrict__
 
 // int8 max-pool, 16 channels per thread (C % 16 == 0): 16-byte loads and stores.
 typedef int v4i __attribute__((ext_vector_type(4)));
+// WIN = 3: a 3 x 3 window, unrolled, all nine taps loaded at once from clamped addresses.
+template <int WIN>
 __global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* __restrict__ x, int N,
                                                                   int H, int W, int C16, int R, int S,
                                                                   int stride, int pad, int Ho, int Wo,
                                                                   int8_t* __restrict__ y) {
-  const size_t total = (size_t)N * Ho * Wo * C16;
+  // 32-bit index arithmetic: the host takes this kernel only below 2^31 items
+  const unsigned total = (unsigned)N * Ho * Wo * C16;
   // Workgroups go to the 8 XCDs round robin: renumber them so that each XCD owns one
   // contiguous run of outputs.  Neighbouring output rows share input rows; with this they
   // find them in their own L2 instead of fetching them once per XCD.
@@ -141,13 +144,12 @@ __global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* 
     const unsigned base = gridDim.x / 8, rem = gridDim.x % 8;
     bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  for (size_t i = (size_t)bid * kThreads + threadIdx.x; i < total;
-       i += (size_t)gridDim.x * kThreads) {
-    int c = (int)(i % C16);
-    size_t t = i / C16;
-    int wo = (int)(t % Wo); t /= Wo;
-    int ho = (int)(t % Ho);
-    int n = (int)(t / Ho);
+  for (unsigned i = bid * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
+    int c = (int)(i % (unsigned)C16);
+    unsigned t = i / (unsigned)C16;
+    int wo = (int)(t % (unsigned)Wo); t /= (unsigned)Wo;
+    int ho = (int)(t % (unsigned)Ho);
+    int n = (int)(t / (unsigned)Ho);
     // A byte in the high half of a 16-bit lane (low half zero) orders like the int8 it
     // is: odd bytes are masked in place, even bytes shifted up, and each set takes a packed
     // 16-bit max per tap.
@@ -155,30 +157,53 @@ __global__ __launch_bounds__(kThreads) void maxpool_i8_vec_kernel(const int8_t* 
     unsigned best_odd[4], best_even[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) best_odd[q] = best_even[q] = 0x80008000u;     // -128, -128
-    for (int r = 0; r < R; ++r) {
-      int hi = ho * stride - pad + r;
-      if ((unsigned)hi >= (unsigned)H) continue;
-      for (int s = 0; s < S; ++s) {
-        int wi = wo * stride - pad + s;
-        if ((unsigned)wi >= (unsigned)W) continue;
-        v4i v = *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16);
+    auto take = [&](const v4i& v, bool in) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const unsigned odd = (unsigned)v[q] & 0xff00ff00u;
-          const unsigned even = ((unsigned)v[q] << 8) & 0xff00ff00u;
-          const v2s mo = __builtin_elementwise_max(__builtin_bit_cast(v2s, best_odd[q]),
-                                                   __builtin_bit_cast(v2s, odd));
-          const v2s me = __builtin_elementwise_max(__builtin_bit_cast(v2s, best_even[q]),
-                                                   __builtin_bit_cast(v2s, even));
-          best_odd[q] = __builtin_bit_cast(unsigned, mo);
-          best_even[q] = __builtin_bit_cast(unsigned, me);
+      for (int q = 0; q < 4; ++q) {
+        const unsigned odd = in ? ((unsigned)v[q] & 0xff00ff00u) : 0x80008000u;
+        const unsigned even = in ? (((unsigned)v[q] << 8) & 0xff00ff00u) : 0x80008000u;
+        const v2s mo = __builtin_elementwise_max(__builtin_bit_cast(v2s, best_odd[q]),
+                                                 __builtin_bit_cast(v2s, odd));
+        const v2s me = __builtin_elementwise_max(__builtin_bit_cast(v2s, best_even[q]),
+                                                 __builtin_bit_cast(v2s, even));
+        best_odd[q] = __builtin_bit_cast(unsigned, mo);
+        best_even[q] = __builtin_bit_cast(unsigned, me);
+      }
+    };
+    if constexpr (WIN == 3) {
+      v4i taps[9];
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+          const int hi = ho * stride - pad + r, wi = wo * stride - pad + s;
+          const int hc = min(max(hi, 0), H - 1), wc = min(max(wi, 0), W - 1);
+          taps[3 * r + s] =
+              *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hc) * W + wc) * C16 + c) * 16);
+        }
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+          const int hi = ho * stride - pad + r, wi = wo * stride - pad + s;
+          take(taps[3 * r + s], (unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W);
+        }
+    } else {
+      for (int r = 0; r < R; ++r) {
+        int hi = ho * stride - pad + r;
+        if ((unsigned)hi >= (unsigned)H) continue;
+        for (int s = 0; s < S; ++s) {
+          int wi = wo * stride - pad + s;
+          if ((unsigned)wi >= (unsigned)W) continue;
+          take(*reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16),
+               true);
         }
       }
     }
     v4i o;
 #pragma unroll
     for (int q = 0; q < 4; ++q) o[q] = (int)(best_odd[q] | (best_even[q] >> 8));
-    *reinterpret_cast<v4i*>(y + i * 16) = o;
+    *reinterpret_cast<v4i*>(y + (size_t)i * 16) = o;
   }
 }
 
@@ -220,55 +245,106 @@ __global__ __launch_bounds__(kThreads) void pool_i8_kernel(const int8_t* __restr
 // The same with 16 channels per lane (C, out_cs and out_off multiples of 16, 16-byte aligned
 // tensors): 16-byte loads and one 16-byte store; workgroups renumbered so that each XCD owns
 // a contiguous run of outputs (neighbouring outputs share input rows).
+// WIN = 3: a 3 x 3 window, unrolled, every tap loaded unconditionally from a clamped address
+// (nine loads in flight per lane) and neutralised afterwards if it lies outside the image;
+// WIN = 0: any window, taps outside skipped.
+template <int WIN, int MODE>
 __global__ __launch_bounds__(kThreads) void pool_i8_vec_kernel(const int8_t* __restrict__ x, int N,
-                                                               int H, int W, int C16, int mode, int R,
+                                                               int H, int W, int C16, int, int R,
                                                                int S, int stride, int pad, int Ho,
                                                                int Wo, float m, float inv_count,
                                                                int8_t* __restrict__ y, int out_cs,
                                                                int out_off) {
-  const size_t total = (size_t)N * Ho * Wo * C16;
+  // 32-bit index arithmetic: the host takes this kernel only below 2^31 items
+  const unsigned total = (unsigned)N * Ho * Wo * C16;
   unsigned bid = blockIdx.x;
   {
     const unsigned xcd = bid % 8, idx = bid / 8;
     const unsigned base = gridDim.x / 8, rem = gridDim.x % 8;
     bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  for (size_t i = (size_t)bid * kThreads + threadIdx.x; i < total;
-       i += (size_t)gridDim.x * kThreads) {
-    int c = (int)(i % C16);
-    size_t t = i / C16;
-    int wo = (int)(t % Wo); t /= Wo;
-    int ho = (int)(t % Ho);
-    int n = (int)(t / Ho);
-    int best[16], sum[16];
+  for (unsigned i = bid * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
+    int c = (int)(i % (unsigned)C16);
+    unsigned t = i / (unsigned)C16;
+    int wo = (int)(t % (unsigned)Wo); t /= (unsigned)Wo;
+    int ho = (int)(t % (unsigned)Ho);
+    int n = (int)(t / (unsigned)Ho);
+    // Two bytes per 32-bit word at a time, as 16-bit lanes: the odd bytes and the even
+    // bytes of a word, each sign-extended by a packed arithmetic shift, take a packed max
+    // or a packed add per tap (a window of at most 128 taps cannot overflow 16 bits).
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    v2s acc_odd[4], acc_even[4];
+    const short init = MODE == 0 ? (short)-128 : (short)0;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { best[e] = -128; sum[e] = 0; }
-    for (int r = 0; r < R; ++r) {
-      int hi = ho * stride - pad + r;
-      if ((unsigned)hi >= (unsigned)H) continue;
-      for (int s2 = 0; s2 < S; ++s2) {
-        int wi = wo * stride - pad + s2;
-        if ((unsigned)wi >= (unsigned)W) continue;
-        v4i v = *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16);
-        if (mode == 0) {
+    for (int q = 0; q < 4; ++q) acc_odd[q] = acc_even[q] = v2s{init, init};
+    auto take = [&](const v4i& v) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            int b = (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
-            best[e] = b > best[e] ? b : best[e];
-          }
+      for (int q = 0; q < 4; ++q) {
+        const int w = v[q], w8 = w << 8;
+        const v2s odd = __builtin_bit_cast(v2s, w) >> 8;               // bytes 1 and 3
+        const v2s even = __builtin_bit_cast(v2s, w8) >> 8;             // bytes 0 and 2
+        if (MODE == 0) {
+          acc_odd[q] = __builtin_elementwise_max(acc_odd[q], odd);
+          acc_even[q] = __builtin_elementwise_max(acc_even[q], even);
         } else {
+          acc_odd[q] += odd;
+          acc_even[q] += even;
+        }
+      }
+    };
+    if constexpr (WIN == 3) {
+      // a tap outside the image reads as the neutral element: -128 in every byte for the
+      // maximum, 0 for the sum
+      const int neutral = MODE == 0 ? (int)0x80808080 : 0;
+      v4i taps[9];
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sum[e] += (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s2 = 0; s2 < 3; ++s2) {
+          const int hi = ho * stride - pad + r, wi = wo * stride - pad + s2;
+          const int hc = min(max(hi, 0), H - 1), wc = min(max(wi, 0), W - 1);
+          taps[3 * r + s2] =
+              *reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hc) * W + wc) * C16 + c) * 16);
+        }
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s2 = 0; s2 < 3; ++s2) {
+          const int hi = ho * stride - pad + r, wi = wo * stride - pad + s2;
+          const bool in = (unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W;
+          v4i v = taps[3 * r + s2];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = in ? v[q] : neutral;
+          take(v);
+        }
+    } else {
+      for (int r = 0; r < R; ++r) {
+        int hi = ho * stride - pad + r;
+        if ((unsigned)hi >= (unsigned)H) continue;
+        for (int s2 = 0; s2 < S; ++s2) {
+          int wi = wo * stride - pad + s2;
+          if ((unsigned)wi >= (unsigned)W) continue;
+          take(*reinterpret_cast<const v4i*>(x + ((((size_t)n * H + hi) * W + wi) * C16 + c) * 16));
         }
       }
     }
-    v4i o = {0, 0, 0, 0};
+    // scale, clamp, Round by adding 1.5 * 2^23 (for |t| <= 128 the fp32 sum is the
+    // round-half-to-even integer, its low byte the int8 code), byte permutes to pack
+    unsigned rr[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      float f = mode == 0 ? (float)best[e] : (float)sum[e] * inv_count;
+      const int val = (e & 1) ? acc_odd[e >> 2][(e >> 1) & 1] : acc_even[e >> 2][(e >> 1) & 1];
+      float f = MODE == 0 ? (float)val : (float)val * inv_count;
       f = f * m;
-      f = fminf(fmaxf(f, -128.0f), 127.0f);
-      o[e >> 2] |= ((int)rintf(f) & 0xff) << (8 * (e & 3));
+      f = __builtin_amdgcn_fmed3f(f, -128.0f, 127.0f);
+      rr[e] = __float_as_uint(f + 12582912.0f);
+    }
+    v4i o;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const unsigned w01 = __builtin_amdgcn_perm(rr[4 * a + 1], rr[4 * a], 0x0c0c0400u);
+      const unsigned w23 = __builtin_amdgcn_perm(rr[4 * a + 3], rr[4 * a + 2], 0x0c0c0400u);
+      o[a] = (int)__builtin_amdgcn_perm(w23, w01, 0x05040100u);
     }
     *reinterpret_cast<v4i*>(y + (((size_t)n * Ho + ho) * Wo + wo) * out_cs + out_off + c * 16) = o;
   }
@@ -318,13 +394,18 @@ int maxpool_launch(const T* x, int N, int H, int W, int C, int R, int S, int str
   if (total == 0) return Q8_OK;
   Q8_REQUIRE(x && y, Q8_EINVAL);
   if constexpr (sizeof(T) == 1) {
-    if (C % 16 == 0 && q8_aligned(x, 16) && q8_aligned(y, 16)) {
+    if (C % 16 == 0 && q8_aligned(x, 16) && q8_aligned(y, 16) && total / 16 < 0x7fffffffUL) {
       size_t items = total / 16;
       size_t vb = (items + kThreads - 1) / kThreads;
       if (vb > 65536) vb = 65536;
-      hipLaunchKernelGGL(maxpool_i8_vec_kernel, dim3((unsigned)vb), dim3(kThreads), 0,
-                         (hipStream_t)stream, (const int8_t*)x, N, H, W, C / 16, R, S, stride, pad, Ho,
-                         Wo, (int8_t*)y);
+      if (R == 3 && S == 3)
+        hipLaunchKernelGGL(maxpool_i8_vec_kernel<3>, dim3((unsigned)vb), dim3(kThreads), 0,
+                           (hipStream_t)stream, (const int8_t*)x, N, H, W, C / 16, R, S, stride, pad,
+                           Ho, Wo, (int8_t*)y);
+      else
+        hipLaunchKernelGGL(maxpool_i8_vec_kernel<0>, dim3((unsigned)vb), dim3(kThreads), 0,
+                           (hipStream_t)stream, (const int8_t*)x, N, H, W, C / 16, R, S, stride, pad,
+                           Ho, Wo, (int8_t*)y);
       return q8_launch_status();
     }
   }
@@ -394,12 +475,14 @@ int q8_pool_i8(const int8_t* x_dev, int N, int H, int W, int C, int mode, int R,
   Q8_REQUIRE(x_dev && y_dev, Q8_EINVAL);
   const float inv_count = 1.0f / (float)(R * S);
   if (C % 16 == 0 && out_c_stride % 16 == 0 && out_c_off % 16 == 0 && q8_aligned(x_dev, 16) &&
-      q8_aligned(y_dev, 16)) {
+      q8_aligned(y_dev, 16) && R * S <= 128 && total / 16 < 0x7fffffffUL) {
     size_t vb = (total / 16 + kThreads - 1) / kThreads;
     if (vb > 65536) vb = 65536;
-    hipLaunchKernelGGL(pool_i8_vec_kernel, dim3((unsigned)vb), dim3(kThreads), 0, (hipStream_t)stream,
-                       x_dev, N, H, W, C / 16, mode, R, S, stride, pad, Ho, Wo, m, inv_count, y_dev,
-                       out_c_stride, out_c_off);
+    auto kernel = R == 3 && S == 3 ? (mode == 0 ? pool_i8_vec_kernel<3, 0> : pool_i8_vec_kernel<3, 1>)
+                                   : (mode == 0 ? pool_i8_vec_kernel<0, 0> : pool_i8_vec_kernel<0, 1>);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)vb), dim3(kThreads), 0, (hipStream_t)stream, x_dev, N, H,
+                       W, C / 16, mode, R, S, stride, pad, Ho, Wo, m, inv_count, y_dev, out_c_stride,
+                       out_c_off);
     return q8_launch_status();
   }
   size_t blocks = (total + kThreads - 1) / kThreads;
