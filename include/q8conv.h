@@ -146,26 +146,28 @@ int q8_conv_int8(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packe
  * non-negative) and Eq. D, on the stored form.
  *
  * q8_u8_prepare: for a layer that READS an unsigned tensor, from the dense KRSC int8
- * filters and the int32 bias (or NULL): tap_sums, int32 [(R+1)*(S+1)][K], the 2-D prefix
- * sums tap_sums[(r*(S+1)+s)*K + k] = sum_{r'<r, s'<s, c} z_w[k][r'][s'][c], and
- * bias_eff[k] = bias[k] + 128 * (sum of filter k).  Since sum z_x z_w = sum (z_x - 128) z_w
- * + 128 * sum z_w, the signed contraction of the stored bytes started at bias_eff equals
- * Eq. A' on the codes wherever every tap reads inside the image; near the border the
- * kernel replaces the whole-filter sum by the sum over the taps inside the image (a
- * rectangle of the filter: four look-ups in tap_sums).  tap_sums 16-byte aligned.
+ * filters and the int32 bias (or NULL).  Since sum z_x z_w = sum (z_x - 128) z_w
+ * + 128 * sum z_w, the signed contraction of the stored bytes started at
+ * bias_eff[k] = bias[k] + 128 * (sum of filter k) equals Eq. A' on the codes wherever every
+ * tap reads inside the image.  Near the border the taps inside the image are a rectangle
+ * [r_lo, r_hi) x [s_lo, s_hi) of the filter, and the accumulator has to start at the bias
+ * plus 128 times the sum over that rectangle only: start_dev, int32
+ * [((R+1)*(S+1))^2][K], holds that value for every rectangle,
+ *   start[idx*K + k], idx = ((r_lo*(R+1) + r_hi)*(S+1) + s_lo)*(S+1) + s_hi,
+ * and the kernel loads a pixel's accumulators from its rectangle's row.  16-byte aligned.
  *
  * q8_conv_u8: q8_conv_int8 where the input, the output and the residual may each be an
- * unsigned tensor (flags).  in_unsigned: pass bias_eff as the bias, and tap_sums if the
- * layer has padding (else it may be NULL).  out_unsigned needs d->relu; the output is
+ * unsigned tensor (flags).  in_unsigned: pass bias_eff as the bias, and the start table if
+ * the layer has padding (else it may be NULL).  out_unsigned needs d->relu; the output is
  * clamped to [0, 255].  acc_dump receives the accumulators of Eq. A' on the codes.
  * Main-kernel geometries only (C % 16 == 0, K > 32, R*S <= 32): Q8_EUNSUPPORTED otherwise. */
 int q8_quantize_u8(const float *r_dev, size_t n, float q, int8_t *z_dev, void *stream);
 int q8_dequantize_u8(const int8_t *z_dev, size_t n, float q, float *r_dev, void *stream);
 int q8_u8_prepare(const q8_conv_desc *d, const int8_t *z_w_krsc_dev, const int32_t *bias_i32,
-                  int32_t *tap_sums_dev, int32_t *bias_eff_dev, void *stream);
+                  int32_t *start_dev, int32_t *bias_eff_dev, void *stream);
 int q8_conv_u8(const q8_conv_desc *d, int in_unsigned, int out_unsigned, int res_unsigned,
                const int8_t *z_x, const void *z_w_packed, const int32_t *bias_eff,
-               const int32_t *tap_sums, float q_x, float q_w, float q_out,
+               const int32_t *start_table, float q_x, float q_w, float q_out,
                const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
                void *stream);
 

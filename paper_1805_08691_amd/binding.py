@@ -224,9 +224,9 @@ def dequantize_u8(z, q, out=None):
 
 
 def u8_prepare(desc, z_w, bias_i32=None):
-    """-> (tap_sums int32 [(R+1)*(S+1), K] prefix sums, bias_eff int32 [K]) for a layer
-    reading unsigned codes."""
-    taps = torch.empty(((desc.R + 1) * (desc.S + 1), desc.K), dtype=torch.int32,
+    """-> (start values int32 [((R+1)*(S+1))**2, K], one row per rectangle of taps inside the
+    image, bias_eff int32 [K]) for a layer reading unsigned codes."""
+    taps = torch.empty((((desc.R + 1) * (desc.S + 1)) ** 2, desc.K), dtype=torch.int32,
                        device=z_w.device)
     beff = torch.empty(desc.K, dtype=torch.int32, device=z_w.device)
     _check(lib.q8_u8_prepare(C.byref(desc), _ptr(z_w, torch.int8), _ptr(bias_i32, torch.int32),

@@ -354,27 +354,42 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   return q8::launch_stream_variant(variant, p, s);
 }
 
-// tap_sums[(r*(S+1) + s)*K + k] = sum over r' < r, s' < s and c of z_w[k][r'][s'][c] (2-D
-// prefix sums of the per-tap filter sums); bias_eff[k] = bias[k] + 128 * (sum of the filter)
+// start[idx*K + k] = bias[k] + 128 * (sum of filter k over the taps of rectangle idx), for
+// every rectangle [r_lo, r_hi) x [s_lo, s_hi) of the filter (see u8_start_index; an empty or
+// inverted rectangle gets the bare bias); bias_eff[k] = the whole filter's row.
+constexpr int kMaxPrefix = 128;      // (R+1)*(S+1) with R*S <= 32 is at most 66
 __global__ void u8_prepare_kernel(const int8_t* __restrict__ w, const int32_t* __restrict__ bias,
-                                  int K, int R, int S, int C, int32_t* __restrict__ tap_sums,
+                                  int K, int R, int S, int C, int32_t* __restrict__ start,
                                   int32_t* __restrict__ bias_eff) {
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= K) return;
   const int w1 = S + 1;
-  for (int s = 0; s <= S; ++s) tap_sums[(size_t)s * K + k] = 0;
+  int pre[kMaxPrefix];               // 2-D prefix sums of the per-tap filter sums
+  for (int s = 0; s <= S; ++s) pre[s] = 0;
   for (int r = 1; r <= R; ++r) {
-    tap_sums[(size_t)(r * w1) * K + k] = 0;
+    pre[r * w1] = 0;
     int row = 0;                                   // sum of filter row r-1 up to column s
     for (int s = 1; s <= S; ++s) {
       const int8_t* tap = w + (((size_t)k * R + (r - 1)) * S + (s - 1)) * C;
       int sum = 0;
       for (int c = 0; c < C; ++c) sum += tap[c];
       row += sum;
-      tap_sums[(size_t)(r * w1 + s) * K + k] = tap_sums[(size_t)((r - 1) * w1 + s) * K + k] + row;
+      pre[r * w1 + s] = pre[(r - 1) * w1 + s] + row;
     }
   }
-  bias_eff[k] = (bias ? bias[k] : 0) + 128 * tap_sums[(size_t)(R * w1 + S) * K + k];
+  const int b = bias ? bias[k] : 0;
+  for (int r_lo = 0; r_lo <= R; ++r_lo)
+    for (int r_hi = 0; r_hi <= R; ++r_hi)
+      for (int s_lo = 0; s_lo <= S; ++s_lo)
+        for (int s_hi = 0; s_hi <= S; ++s_hi) {
+          int sum = 0;
+          if (r_hi > r_lo && s_hi > s_lo)
+            sum = pre[r_hi * w1 + s_hi] - pre[r_lo * w1 + s_hi] - pre[r_hi * w1 + s_lo] +
+                  pre[r_lo * w1 + s_lo];
+          const size_t idx = ((size_t)(r_lo * (R + 1) + r_hi) * w1 + s_lo) * w1 + s_hi;
+          start[idx * K + k] = b + 128 * sum;
+        }
+  bias_eff[k] = b + 128 * pre[R * w1 + S];
 }
 
 }  // namespace
@@ -451,7 +466,7 @@ int q8_conv_pair_supported(const q8_conv_desc* d1, const q8_conv_desc* d2) {
 int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32_t* bias_i32,
                   int32_t* tap_sums_dev, int32_t* bias_eff_dev, void* stream) {
   Q8_REQUIRE(desc_sane(d) && z_w_krsc_dev && tap_sums_dev && bias_eff_dev, Q8_EINVAL);
-  Q8_REQUIRE(conv_mode(d) == 0, Q8_EUNSUPPORTED);
+  Q8_REQUIRE(conv_mode(d) == 0 && (d->R + 1) * (d->S + 1) <= kMaxPrefix, Q8_EUNSUPPORTED);
   hipLaunchKernelGGL(u8_prepare_kernel, dim3((d->K + 63) / 64), dim3(64), 0, (hipStream_t)stream,
                      z_w_krsc_dev, bias_i32, d->K, d->R, d->S, d->C, tap_sums_dev, bias_eff_dev);
   return q8_launch_status();

@@ -39,8 +39,9 @@ struct ConvParams {
   unsigned div_row_m, div_row_s;   // division by Wo
   // unsigned p = 8 activation codes (0..255), stored as code - 128 (= code ^ 0x80) so that
   // the signed MFMA can take them: the input offset is undone through the bias (+128 times
-  // the filter sum, folded by the host) and, for taps outside the image, through tap_sums
-  const int32_t* __restrict__ tap_sums;   // [(R+1)*(S+1)][K] prefix sums of the filter, or null
+  // the filter sum, folded by the host) or, in a layer with padding, through the table of
+  // start values per rectangle of taps inside the image (see u8_start_index)
+  const int32_t* __restrict__ tap_sums;   // [((R+1)*(S+1))^2][K] start values, or null
   int in_u8, out_u8, res_u8;
   const float* __restrict__ m_vec;   // [K] per-output-channel scales replacing m, or null
   float m, m_r;
@@ -90,63 +91,52 @@ __device__ __forceinline__ int row_to_channel(int row) {
   return (((row >> 2) & 1) << 4) | ((row >> 3) << 2) | (row & 3);
 }
 
-// Unsigned input codes are stored minus 128 and the host has added 128 * (sum of the whole
-// filter) to the bias, which is right where every tap reads inside the image.  A tap in
-// the padding contributes nothing to Eq. A' (the stored zero the kernel reads there stands
-// for code 128, not 0), so for a pixel near the border the sum over the taps INSIDE the
-// image has to replace the sum over all taps.  The taps inside form a rectangle
-// [r_lo, r_hi) x [s_lo, s_hi) of the filter, so that sum is four look-ups in a table of
-// 2-D prefix sums: tap_sums[(r*(S+1) + s)*K + k] = sum_{r' < r, s' < s, c} z_w[k][r'][s'][c].
-constexpr int kNoBorderFix = -1;
-
-// The rectangle of taps inside the image for output pixel `pix`, packed as
-// r_lo | r_hi << 8 | s_lo << 16 | s_hi << 24, or kNoBorderFix if it is the whole filter.
-__device__ __forceinline__ int u8_border_rect(const ConvParams& p, int pix) {
-  if (pix >= p.M) return kNoBorderFix;
-  const int n = fast_div(pix, p.div_img_m, p.div_img_s);
-  const int rem = pix - n * (p.Ho * p.Wo);
-  const int ho = fast_div(rem, p.div_row_m, p.div_row_s);
-  const int wo = rem - ho * p.Wo;
-  const int hi0 = ho * p.stride_h - p.pad_h;
-  const int wi0 = wo * p.stride_w - p.pad_w;
-  int r_lo = p.R, r_hi = 0, s_lo = p.S, s_hi = 0;
-  for (int r = 0; r < p.R; ++r)
-    if ((unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H) { r_lo = min(r_lo, r); r_hi = r + 1; }
-  for (int s2 = 0; s2 < p.S; ++s2)
-    if ((unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) { s_lo = min(s_lo, s2); s_hi = s2 + 1; }
-  if (r_hi <= r_lo || s_hi <= s_lo) r_lo = r_hi = s_lo = s_hi = 0;     // nothing inside
-  if (r_lo == 0 && r_hi == p.R && s_lo == 0 && s_hi == p.S) return kNoBorderFix;
-  return r_lo | (r_hi << 8) | (s_lo << 16) | (s_hi << 24);
+// Unsigned input codes are stored minus 128, and sum z w = sum (z - 128) w + 128 * sum w: the
+// signed contraction of the stored bytes has to start at bias + 128 * (sum of the filter
+// taps the pixel really reads).  A tap in the padding contributes nothing to Eq. A' (the
+// stored zero the kernel reads there stands for code 128, not 0), and the taps inside the
+// image form a rectangle [r_lo, r_hi) x [s_lo, s_hi) of the filter, so the host tabulates
+// the start value of every rectangle:
+//   u8_start[idx * K + k] = bias[k] + 128 * sum_{r_lo <= r < r_hi, s_lo <= s < s_hi, c} z_w[k][r][s][c],
+//   idx = ((r_lo * (R+1) + r_hi) * (S+1) + s_lo) * (S+1) + s_hi,
+// and a pixel's accumulators are loaded from its rectangle's row instead of from the bias.
+__device__ __forceinline__ int u8_start_index(const ConvParams& p, int pix) {
+  int r_lo = 0, r_hi = p.R, s_lo = 0, s_hi = p.S;          // beyond M: any valid row
+  if (pix < p.M) {
+    const int n = fast_div(pix, p.div_img_m, p.div_img_s);
+    const int rem = pix - n * (p.Ho * p.Wo);
+    const int ho = fast_div(rem, p.div_row_m, p.div_row_s);
+    const int wo = rem - ho * p.Wo;
+    const int hi0 = ho * p.stride_h - p.pad_h;
+    const int wi0 = wo * p.stride_w - p.pad_w;
+    r_lo = p.R; r_hi = 0; s_lo = p.S; s_hi = 0;
+    for (int r = 0; r < p.R; ++r)
+      if ((unsigned)(hi0 + r * p.dil_h) < (unsigned)p.H) { r_lo = min(r_lo, r); r_hi = r + 1; }
+    for (int s2 = 0; s2 < p.S; ++s2)
+      if ((unsigned)(wi0 + s2 * p.dil_w) < (unsigned)p.W) { s_lo = min(s_lo, s2); s_hi = s2 + 1; }
+    if (r_hi <= r_lo || s_hi <= s_lo) r_lo = r_hi = s_lo = s_hi = 0;     // nothing inside
+  }
+  return ((r_lo * (p.R + 1) + r_hi) * (p.S + 1) + s_lo) * (p.S + 1) + s_hi;
 }
 
-// v += 128 * (sum over the rectangle - sum over the whole filter) for channels [ch, ch+16).
-// FULL: all 16 channels exist and K % 4 == 0 (16-byte loads).
-template <bool FULL>
-__device__ __forceinline__ void u8_border_apply(const ConvParams& p, int rect, int ch,
-                                                int (&v)[16]) {
+// The 16 start values of channels [ch, ch+16) from table row `idx` (zero beyond K).
+__device__ __forceinline__ void load_start16(const ConvParams& p, int idx, int ch, int (&b)[16]) {
   const int nvalid = p.K - ch;
-  const int r_lo = rect & 0xff, r_hi = (rect >> 8) & 0xff, s_lo = (rect >> 16) & 0xff,
-            s_hi = (rect >> 24) & 0xff;
-  const int w1 = p.S + 1;
-  const int32_t* t_hh = p.tap_sums + (size_t)(r_hi * w1 + s_hi) * p.K + ch;
-  const int32_t* t_lh = p.tap_sums + (size_t)(r_lo * w1 + s_hi) * p.K + ch;
-  const int32_t* t_hl = p.tap_sums + (size_t)(r_hi * w1 + s_lo) * p.K + ch;
-  const int32_t* t_ll = p.tap_sums + (size_t)(r_lo * w1 + s_lo) * p.K + ch;
-  const int32_t* t_all = p.tap_sums + (size_t)(p.R * w1 + p.S) * p.K + ch;
-  if (FULL) {
+#pragma unroll
+  for (int e = 0; e < 16; ++e) b[e] = 0;
+  if (nvalid <= 0) return;
+  const int32_t* row = p.tap_sums + (size_t)idx * p.K + ch;
+  if (nvalid >= 16 && (p.K & 3) == 0) {
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-      const v4i hh = *reinterpret_cast<const v4i*>(t_hh + 4 * a);
-      const v4i lh = *reinterpret_cast<const v4i*>(t_lh + 4 * a);
-      const v4i hl = *reinterpret_cast<const v4i*>(t_hl + 4 * a);
-      const v4i ll = *reinterpret_cast<const v4i*>(t_ll + 4 * a);
-      const v4i al = *reinterpret_cast<const v4i*>(t_all + 4 * a);
+      const v4i q = *reinterpret_cast<const v4i*>(row + 4 * a);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) v[4 * a + k] += 128 * (hh[k] - lh[k] - hl[k] + ll[k] - al[k]);
+      for (int k = 0; k < 4; ++k) b[4 * a + k] = q[k];
     }
   } else {
+#pragma unroll
     for (int e = 0; e < 16; ++e)
-      if (e < nvalid) v[e] += 128 * (t_hh[e] - t_lh[e] - t_hl[e] + t_ll[e] - t_all[e]);
+      if (e < nvalid) b[e] = row[e];
   }
 }
 

@@ -269,38 +269,30 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   // These loads are issued before any stage load, so the in-order vmcnt bookkeeping of
   // the ring is unaffected, and their latency hides behind the first stages.
   v16i acc[TC][TP];
-  // Unsigned input codes (stored minus 128): a pixel whose taps partly fall into the padding
-  // starts from a corrected value (see u8_border_apply); the look-ups ride along with the
-  // bias loads, ahead of the first stage.
-  int rect[TP];
-  bool any_fix = false;
-  if constexpr (U8) {
+  // Unsigned input codes (stored minus 128) in a layer with padding: a pixel's accumulators
+  // start at the table row of the rectangle of taps it reads inside the image (see
+  // u8_start_index) instead of at the bias.
+  if (U8 && p.tap_sums) {
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
-      rect[j] = kNoBorderFix;
-      if (p.tap_sums) rect[j] = u8_border_rect(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31));
-      any_fix = any_fix || __any(rect[j] != kNoBorderFix);
-    }
-  }
-  const bool full_ctile = ch0 + BC <= p.K && (p.K & 3) == 0;
+      const int idx = u8_start_index(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31));
 #pragma unroll
-  for (int i = 0; i < TC; ++i) {
-    int b[16];
-    const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-    load_bias16(p, ch, b);
+      for (int i = 0; i < TC; ++i) {
+        int b[16];
+        load_start16(p, idx, ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
 #pragma unroll
-    for (int j = 0; j < TP; ++j) {
-      int v[16];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) v[e] = b[e];
-      if constexpr (U8) {
-        if (any_fix && rect[j] != kNoBorderFix && ch < p.K) {
-          if (full_ctile) u8_border_apply<true>(p, rect[j], ch, v);
-          else u8_border_apply<false>(p, rect[j], ch, v);
-        }
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = b[e];
       }
+    }
+  } else {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = v[e];
+    for (int i = 0; i < TC; ++i) {
+      int b[16];
+      load_bias16(p, ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), b);
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = b[e];
     }
   }
   // Pair build: bias and residual codes of the second layer's first channel tile, requested

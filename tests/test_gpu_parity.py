@@ -324,9 +324,12 @@ def test_conv_unsigned_activations(B, idx):
     if in_u8:
         taps, bias = B.u8_prepare(d, dev(w), dev(b))
         tw = w.astype(np.int64).sum(axis=3)                               # [K, R, S]
-        pre = np.zeros((g.R + 1, g.S + 1, g.K), np.int64)                 # 2-D prefix sums
-        pre[1:, 1:] = tw.cumsum(axis=1).cumsum(axis=2).transpose(1, 2, 0)
-        assert np.array_equal(host(taps).reshape(g.R + 1, g.S + 1, g.K), pre)
+        # one row per rectangle [r_lo, r_hi) x [s_lo, s_hi) of taps inside the image
+        tab = host(taps).reshape(g.R + 1, g.R + 1, g.S + 1, g.S + 1, g.K)
+        for r_lo, r_hi, s_lo, s_hi in [(0, g.R, 0, g.S), (1, g.R, 0, g.S), (0, g.R - 1, 0, g.S - 1),
+                                       (0, 1, 0, 1), (g.R, 0, 0, g.S), (0, 0, 0, 0)]:
+            inside = tw[:, r_lo:r_hi, s_lo:s_hi].sum(axis=(1, 2)) if r_hi > r_lo and s_hi > s_lo else 0
+            assert np.array_equal(tab[r_lo, r_hi, s_lo, s_hi], b + 128 * inside)
         assert np.array_equal(host(bias), b + 128 * tw.sum(axis=(1, 2)))
     else:
         taps, bias = None, dev(b)
