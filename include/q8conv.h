@@ -87,7 +87,7 @@ int q8_quantize_pad_channels(const float *r_dev, size_t npix, int C, int C_pad,
  * H x W interior is written: the caller zeroes z_dev once and the frame stays zero.  With
  * the padding of the first convolution stored in the frame, that layer runs without
  * padding (the zeros Eq. A' reads outside the image are then real bytes).
- * Q8_EINVAL if the interior does not fit the frame; N*H <= 65535.                       */
+ * Q8_EINVAL if the interior does not fit the frame.                                      */
 int q8_quantize_image(const float *r_dev, int N, int H, int W, int C, float q, int p,
                       int8_t *z_dev, int Hs, int Ws, int top, int left, void *stream);
 

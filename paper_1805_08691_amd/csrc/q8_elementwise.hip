@@ -126,14 +126,18 @@ typedef unsigned u4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 template <int GROUP>
 __global__ __launch_bounds__(kThreads) void quantize_image_kernel(const float* __restrict__ r,
-                                                                  int H, int W, int C, int Hs,
+                                                                  int n_rows, int H, int W, int C, int Hs,
                                                                   int Ws, int top, int left,
                                                                   float q, float lo, float hi,
                                                                   unsigned* __restrict__ z) {
-  const int row = blockIdx.y;                 // n * H + h
-  const int n = row / H, h = row - n * H;
-  const int w = (blockIdx.x * blockDim.x + threadIdx.x) * GROUP;
-  if (w >= W) return;
+  // one item = GROUP consecutive pixels of one image row; items are numbered through the
+  // whole batch so that every wave is full whatever the row length
+  const unsigned per_row = (unsigned)(W + GROUP - 1) / GROUP;
+  const unsigned item = blockIdx.x * blockDim.x + threadIdx.x;
+  const unsigned row = item / per_row;        // n * H + h
+  if (row >= (unsigned)n_rows) return;
+  const int w = (int)(item - row * per_row) * GROUP;
+  const int n = (int)(row / (unsigned)H), h = (int)row - n * H;
   const float* src = r + ((size_t)row * W + w) * C;
   unsigned* dst = z + ((size_t)n * Hs + top + h) * Ws + left + w;
   if (GROUP == 4 && w + 4 <= W) {             // C == 3
@@ -403,17 +407,22 @@ int q8_quantize_image(const float* r_dev, int N, int H, int W, int C, float q, i
   Q8_REQUIRE(p >= 1 && p <= 7 && q8_finite_pos(q), Q8_EINVAL);
   Q8_REQUIRE(N >= 0 && H >= 1 && W >= 1 && C >= 1 && C <= 4, Q8_EINVAL);
   Q8_REQUIRE(top >= 0 && left >= 0 && Hs >= top + H && Ws >= left + W, Q8_EINVAL);
-  Q8_REQUIRE((long)N * H <= 65535L, Q8_EUNSUPPORTED);          // grid rows
   if (N == 0) return Q8_OK;
   Q8_REQUIRE(r_dev != nullptr && z_dev != nullptr, Q8_EINVAL);
   Q8_REQUIRE(q8_aligned(r_dev, 4) && q8_aligned(z_dev, 4), Q8_EALIGN);
   const float hi = (float)((1 << p) - 1), lo = -(float)(1 << p);
+  const int group = C == 3 ? 4 : 1;
+  const long items = (long)N * H * ((W + group - 1) / group);
+  Q8_REQUIRE(items < 0x7fffffffL, Q8_EUNSUPPORTED);             // 32-bit item numbers
+  const dim3 grid((unsigned)((items + kThreads - 1) / kThreads));
   if (C == 3)
-    hipLaunchKernelGGL(quantize_image_kernel<4>, dim3((W + 255) / 256, N * H), dim3(64), 0, (hipStream_t)stream, r_dev, H, W, C, Hs, Ws, top, left, q,
-                       lo, hi, reinterpret_cast<unsigned*>(z_dev));
+    hipLaunchKernelGGL(quantize_image_kernel<4>, grid, dim3(kThreads), 0, (hipStream_t)stream, r_dev,
+                       N * H, H, W, C, Hs, Ws, top, left, q, lo, hi,
+                       reinterpret_cast<unsigned*>(z_dev));
   else
-    hipLaunchKernelGGL(quantize_image_kernel<1>, dim3((W + 63) / 64, N * H), dim3(64), 0, (hipStream_t)stream, r_dev, H, W, C, Hs, Ws, top, left, q,
-                       lo, hi, reinterpret_cast<unsigned*>(z_dev));
+    hipLaunchKernelGGL(quantize_image_kernel<1>, grid, dim3(kThreads), 0, (hipStream_t)stream, r_dev,
+                       N * H, H, W, C, Hs, Ws, top, left, q, lo, hi,
+                       reinterpret_cast<unsigned*>(z_dev));
   return q8_launch_status();
 }
 
