@@ -7,7 +7,8 @@ Offline steps (in the paper's flow, Fig. "steps to generate the optimized model"
   calibrate(batches)   fp32 forward of the folded net + running max-abs per tensor
   quantize_weights()   per-tensor q_w, int8 filters (packed), int32 bias at q_x * q_w
 Online step:
-  forward(x)           Q on the input image, then one fused conv launch per layer (Eq. A').
+  run_step(x, dequant) Q on the input image, one fused conv launch per layer (Eq. A'), D on the
+                       outputs that leave the int8 domain; forward(x) is run_step without D.
 """
 import numpy as np
 import torch
@@ -27,9 +28,8 @@ class Engine:
     """``n_streams`` = 2 runs every layer as two concurrent half-batch pipelines (batch elements
     are independent once the factor table is frozen): one on the caller's stream, one on a
     side stream of the same (default) priority, forked behind the quantisation of the input
-    and joined again before the outputs are dequantised.  A layer's
-    launch latency and its tail then overlap the other half's work.  Results are the same bits
-    as with one stream."""
+    and joined again before the outputs are dequantised.  A layer's launch latency and its
+    tail then overlap the other half's work.  Results are the same bits as with one stream."""
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
                  per_channel_weights=False, real_outputs=False, own_sum_factor=False,
@@ -71,7 +71,8 @@ class Engine:
                     assert o.mode == "max" and net.tensors[o.dst].C == net.tensors[o.src].C
                     if o.src in self.unsigned:
                         self.unsigned.add(o.dst)
-        self.taps = {}        # conv name -> per-tap filter sums (layers reading unsigned codes)
+        self.taps = {}        # conv name -> table of accumulator start values (padded layers
+                              # reading unsigned codes)
         self.N = batch
         self.dev = torch.device(device)
         assert n_streams in (1, 2)
