@@ -426,7 +426,7 @@ def main():
 
     result = {
         "metric": "ResNet-50 int8 images/sec at batch 64"
-                  if args.config == 3 and not (args.sparsity_removal or args.unsigned_activations
+                  if args.config == 3 and N == 64 and not (args.sparsity_removal or args.unsigned_activations
                                                or args.per_channel_weights or args.real_output
                                                or args.own_sum_factor)
                   else f"{net.name}{' (unsigned activations)' if args.unsigned_activations else ''}"
