@@ -644,6 +644,32 @@ def test_config2_bottleneck_block(B):
             assert np.array_equal(host(eng.act[o]), acts[o])
 
 
+def test_run_step_one_and_two_pipelines_and_serial(B):
+    """The step the benchmark times (quantise, layers, dequantise) gives the oracle's values
+    whether the batch runs whole, as two concurrent half-batch pipelines, or as the same
+    launches one pipeline after the other; an odd batch splits unevenly."""
+    from paper_1805_08691_amd.engine import Engine
+    cfg_id, batch = 2, 7
+    net, params, x, folded, q, qparams, z_in, acts, accs = _oracle_pipeline(cfg_id, batch, True)
+    o = net.outputs[0]
+    want = orc.D(acts[o], q[o])
+    for n_streams, serial in ((1, False), (2, False), (2, True)):
+        eng = Engine(net, batch, n_streams=n_streams)
+        eng.load_params(params)
+        eng.fold()
+        eng.set_factors(q)
+        eng.quantize_weights()
+        eng.allocate()
+        if n_streams == 2:
+            assert eng.parts == [(0, 4), (4, 3)]
+        out = torch.full(eng.act[o].shape, -1.0, dtype=torch.float32, device="cuda")
+        eng.run_step(dev(x), {o: out}, serial=serial)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(eng.act[o]), acts[o]), (n_streams, serial)
+        got = host(out)
+        assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want)), (n_streams, serial)
+
+
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
                           per_channel=False, real_outputs=False, own_sum_factor=False,
                           fuse_pairs=False):
