@@ -68,9 +68,9 @@ def main():
     ap.add_argument("--no-cold", action="store_true",
                     help="skip the per-layer timing with caches flushed before every layer")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2: the layers behind the first pooling op run as two concurrent "
-                         "half-batch pipelines")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2, 3, 4),
+                    help="number of concurrent part-batch pipelines the layers run as (2: two "
+                         "half-batch pipelines, the default and the headline configuration)")
     ap.add_argument("--layers-out", default="", help="write the per-layer table (JSON) here")
     ap.add_argument("--sparsity-removal", action="store_true",
                     help="config 3 only: run the graph after the paper's sparsity-removal "

@@ -25,10 +25,10 @@ def _pad_c(c):
 
 
 class Engine:
-    """``n_streams`` = 2 runs every layer as two concurrent half-batch pipelines (batch elements
-    are independent once the factor table is frozen): one on the caller's stream, one on a
-    side stream of the same (default) priority, forked behind the quantisation of the input
-    and joined again before the outputs are dequantised.  A layer's launch latency and its
+    """``n_streams`` = 2 (up to 4) runs every layer as that many concurrent part-batch pipelines
+    (batch elements are independent once the factor table is frozen): one on the caller's
+    stream, the others on side streams of the same (default) priority, forked behind the
+    quantisation of the input and joined again before the outputs are dequantised.  A layer's launch latency and its
     tail then overlap the other half's work.  Results are the same bits as with one stream."""
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
@@ -75,14 +75,18 @@ class Engine:
                               # reading unsigned codes)
         self.N = batch
         self.dev = torch.device(device)
-        assert n_streams in (1, 2)
-        self.n_streams = n_streams if batch >= 2 else 1
-        self.side = torch.cuda.Stream(device=self.dev) if self.n_streams == 2 else None
-        half = (batch + 1) // 2
-        self.parts = [(0, half), (half, batch - half)] if self.n_streams == 2 else [(0, batch)]
+        assert 1 <= n_streams <= 4
+        self.n_streams = min(n_streams, max(batch, 1))
+        self.side = [torch.cuda.Stream(device=self.dev) for _ in range(self.n_streams - 1)]
+        # the batch in n_streams nearly equal parts (the first ones one image larger)
+        self.parts, lo = [], 0
+        for i in range(self.n_streams):
+            n = batch // self.n_streams + (1 if i < batch % self.n_streams else 0)
+            self.parts.append((lo, n))
+            lo += n
         # number of leading layers that run on the whole batch before it is split (none: the
         # pipelines start right behind the quantisation of the input)
-        self.n_unsplit = 0 if self.n_streams == 2 else len(net.ops)
+        self.n_unsplit = 0 if self.n_streams > 1 else len(net.ops)
         self.part_desc = {}   # (conv name, images) -> ConvDesc
         # An image of fewer than 4 channels read by one convolution is stored inside a zero
         # frame that holds that layer's padding, and the layer runs without padding.
@@ -382,11 +386,13 @@ class Engine:
                 self.run_ops(self.net.ops, lo, n)
         else:
             main = torch.cuda.current_stream()
-            self.side.wait_stream(main)
-            with torch.cuda.stream(self.side):
-                self.run_ops(self.net.ops, *self.parts[1])
+            for side, part in zip(self.side, self.parts[1:]):
+                side.wait_stream(main)
+                with torch.cuda.stream(side):
+                    self.run_ops(self.net.ops, *part)
             self.run_ops(self.net.ops, *self.parts[0])
-            main.wait_stream(self.side)
+            for side in self.side:
+                main.wait_stream(side)
         for name, out in (dequant or {}).items():
             self.dequantize(name, out=out)
 

@@ -653,7 +653,7 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
     net, params, x, folded, q, qparams, z_in, acts, accs = _oracle_pipeline(cfg_id, batch, True)
     o = net.outputs[0]
     want = orc.D(acts[o], q[o])
-    for n_streams, serial in ((1, False), (2, False), (2, True)):
+    for n_streams, serial in ((1, False), (2, False), (2, True), (3, False)):
         eng = Engine(net, batch, n_streams=n_streams)
         eng.load_params(params)
         eng.fold()
@@ -662,6 +662,8 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
         eng.allocate()
         if n_streams == 2:
             assert eng.parts == [(0, 4), (4, 3)]
+        if n_streams == 3:
+            assert eng.parts == [(0, 3), (3, 2), (5, 2)]
         out = torch.full(eng.act[o].shape, -1.0, dtype=torch.float32, device="cuda")
         eng.run_step(dev(x), {o: out}, serial=serial)
         torch.cuda.synchronize()
