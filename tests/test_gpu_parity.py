@@ -400,6 +400,61 @@ def test_conv_per_channel_scales(B, geom, with_res):
         assert np.array_equal(host(got), want)
 
 
+def _random_geometries(seed, count):
+    """Seeded small geometries with everything unequal: strides, pads, dilations, odd extents,
+    K and C off the tile sizes."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        g = dict(N=int(rng.integers(1, 4)), H=int(rng.integers(5, 24)), W=int(rng.integers(5, 24)),
+                 C=16 * int(rng.integers(1, 7)), K=int(rng.integers(1, 200)), R=R, S=S,
+                 stride_h=int(rng.integers(1, 4)), stride_w=int(rng.integers(1, 4)),
+                 pad_h=int(rng.integers(0, R)), pad_w=int(rng.integers(0, S)),
+                 dil_h=int(rng.integers(1, 3)), dil_w=int(rng.integers(1, 3)))
+        geom = orc.ConvGeom(**g)
+        if geom.Ho >= 1 and geom.Wo >= 1:
+            out.append(g)
+    return out
+
+
+@pytest.mark.parametrize("geom", _random_geometries(1805, 24))
+def test_conv_random_geometries(B, geom):
+    """int32 accumulators and int8 outputs for seeded random geometries, signed and (where
+    the extended build takes the shape) with unsigned input codes."""
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(g.K * 31 + g.C + g.H)
+    x = rng.integers(-128, 128, (g.N, g.H, g.W, g.C)).astype(np.int8)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, g.K).astype(np.int32)
+    res = rng.integers(-128, 128, (g.N, g.Ho, g.Wo, g.K)).astype(np.int8)
+    q_x, q_w = np.float32(0.021), np.float32(0.0017)
+    q_out = np.float32(q_x * q_w * 5476.0 * np.sqrt(g.R * g.S * g.C) / 40.0)
+    q_res = np.float32(0.3) * q_out
+    d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                   g.dil_h, g.dil_w, relu=1)
+    packed = B.pack_weights(d, dev(w))
+    m, m_r = orc.requant_scale(q_x, q_w, q_out), orc.residual_scale(q_res, q_out)
+    acc_o = orc.conv_i8(g, x, w, b)
+    want = orc.requant(acc_o, m, True, res, m_r)
+    dump = torch.zeros((g.N, g.Ho, g.Wo, g.K), dtype=torch.int32, device="cuda")
+    for use_dump in (True, False):
+        got = B.conv_int8(d, dev(x), packed, dev(b), float(q_x), float(q_w), float(q_out), dev(res),
+                          float(q_res), acc_dump=dump if use_dump else None)
+        if use_dump:
+            assert np.array_equal(host(dump), acc_o)
+        assert np.array_equal(host(got), want)
+    if g.K > 32 and g.R * g.S <= 32:          # unsigned input codes, border start table
+        xu = rng.integers(0, 256, (g.N, g.H, g.W, g.C)).astype(np.uint8)
+        acc_u = orc.conv_u8(g, xu, w, b)
+        want_u = orc.requant_mixed(acc_u, m, True, res, m_r, out_unsigned=True)
+        taps, bias = B.u8_prepare(d, dev(w), dev(b))
+        got = B.conv_u8(d, 1, 1, 0, dev(_stored(xu)), packed, bias, taps, float(q_x), float(q_w),
+                        float(q_out), dev(res), float(q_res), acc_dump=dump)
+        assert np.array_equal(host(dump), acc_u)
+        assert np.array_equal(host(got).astype(np.int16) + 128, want_u.astype(np.int16))
+
+
 PAIR_CASES = [
     # first layer, K2, residual, ReLU of the second layer
     (dict(N=2, H=14, W=14, C=64, K=64, R=3, S=3, pad_h=1, pad_w=1), 256, True, True),
