@@ -135,6 +135,9 @@ CONV_CASES = [
     dict(N=1, H=20, W=20, C=3, K=32, R=3, S=3, stride_h=2, stride_w=2),
     dict(N=1, H=16, W=16, C=4, K=8, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=1, H=7, W=7, C=512, K=2048 // 8, R=1, S=1),
+    # more than 32 taps over 16-channel chunks: the register-staged kernel
+    dict(N=1, H=15, W=15, C=16, K=40, R=7, S=7, pad_h=3, pad_w=3),
+    dict(N=2, H=13, W=9, C=32, K=72, R=6, S=6, stride_h=2, stride_w=1, pad_h=2, pad_w=3),
     # a fully connected layer (Eq. A covers it): 1x1 convolution on a 1x1 map, M = batch
     dict(N=64, H=1, W=1, C=2048, K=1000, R=1, S=1),
 ]
