@@ -88,6 +88,30 @@ def test_dequantize(B, n, offset):
     assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want))
 
 
+def test_elementwise_passes_beyond_2_31_elements(B):
+    """Max-abs, Eq. Q and Eq. D on a tensor of more than 2^31 elements (64-bit indexing): a
+    constant with a few planted values, checked on those and on sums over the whole tensor."""
+    n = 2**31 + 1029
+    x = torch.full((n,), 0.25, dtype=torch.float32, device="cuda")
+    planted = {0: 3.0, 12345: -0.75, 2**31 - 1: 1.25, 2**31: -1.75, 2**31 + 3: 12.75, n - 1: -77.5}
+    for i, v in planted.items():
+        x[i] = v
+    slot = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.calibrate_maxabs(x, slot)
+    assert float(host(slot)[0]) == 77.5                     # the extreme is the very last element
+    q = np.float32(0.5)
+    z = B.quantize(x, float(q), 7)
+    idx = sorted(planted)
+    want = orc.Q(np.array([planted[i] for i in idx], np.float32), q, 7)
+    assert [int(z[i]) for i in idx] == want.tolist()        # incl. the tie 25.5 -> 26, clamp at -128
+    assert int(orc.Q(np.array([0.25], np.float32), q, 7)[0]) == 0
+    assert int(z.sum(dtype=torch.int64)) == int(want.astype(np.int64).sum())   # every other code is 0
+    del x
+    r = B.dequantize(z, float(q))
+    assert [float(r[i]) for i in idx] == orc.D(want, q).tolist()
+    assert int(torch.count_nonzero(r)) == int(np.count_nonzero(want))
+
+
 def test_quantize_bias(B):
     rng = np.random.default_rng(9)
     b = (rng.standard_normal(1000) * 0.1).astype(np.float32)
