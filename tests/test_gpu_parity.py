@@ -577,6 +577,40 @@ def test_conv_real_valued_output(B, geom, with_res, relu, out_pad, out_off):
         assert err.max() <= 0.5001 * q_out
 
 
+def test_conv_near_the_32_bit_offset_limit(B):
+    """An activation tensor of just under 2 GiB (the kernels' 32-bit offsets end there): a
+    3x3 layer over it, checked on sampled output pixels (first, last, image borders, random)
+    whose 3x3 neighbourhoods the oracle convolves one by one."""
+    N, H, W, C, K = 8, 2044, 2044, 64, 64
+    assert 2**31 - 2**24 < N * H * W * C < 2**31
+    gen = torch.Generator(device="cuda").manual_seed(1805)
+    x = torch.randint(-128, 128, (N, H, W, C), dtype=torch.int8, device="cuda", generator=gen)
+    rng = np.random.default_rng(8691)
+    w = rng.integers(-128, 128, (K, 3, 3, C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, K).astype(np.int32)
+    q_x, q_w = np.float32(0.021), np.float32(0.0017)
+    q_out = np.float32(q_x * q_w * 5476.0 * np.sqrt(9 * C) / 40.0)
+    d = B.ConvDesc(N, H, W, C, K, 3, 3, pad_h=1, pad_w=1, relu=1)
+    y = B.conv_int8(d, x, B.pack_weights(d, dev(w)), dev(b), float(q_x), float(q_w), float(q_out))
+    picks = [(0, 0, 0), (N - 1, H - 1, W - 1), (N - 1, H - 1, 0), (N - 1, 0, W - 1), (3, 1000, 0),
+             (7, 2043, 1022)]
+    picks += [tuple(int(v) for v in (rng.integers(0, N), rng.integers(0, H), rng.integers(0, W)))
+              for _ in range(58)]
+    # the 3x3 neighbourhood of each picked pixel, zeros outside the image
+    nb = np.zeros((len(picks), 3, 3, C), np.int8)
+    for i, (n, h, ww) in enumerate(picks):
+        for r in range(3):
+            for s2 in range(3):
+                hi, wi = h - 1 + r, ww - 1 + s2
+                if 0 <= hi < H and 0 <= wi < W:
+                    nb[i, r, s2] = host(x[n, hi, wi])
+    g1 = orc.ConvGeom(N=len(picks), H=3, W=3, C=C, K=K, R=3, S=3)
+    want = orc.requant(orc.conv_i8(g1, nb, w, b), orc.requant_scale(q_x, q_w, q_out), True)
+    got = np.stack([host(y[n, h, ww]) for n, h, ww in picks])
+    assert np.array_equal(got, want.reshape(len(picks), K))
+    assert len(np.unique(want)) > 32
+
+
 @pytest.mark.parametrize("out_pad,out_off", [(16, 0), (16, 16), (36, 4), (7, 3)])
 def test_conv_channel_slice_of_concat(B, out_pad, out_off):
     geom = dict(N=2, H=9, W=9, C=32, K=40, R=3, S=3, pad_h=1, pad_w=1)
