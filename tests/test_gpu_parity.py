@@ -577,6 +577,32 @@ def test_conv_real_valued_output(B, geom, with_res, relu, out_pad, out_off):
         assert err.max() <= 0.5001 * q_out
 
 
+@pytest.mark.parametrize("xv,wv", [(-128, -128), (127, -128), (-128, 127), (0, 0)])
+def test_conv_extreme_and_degenerate_values(B, xv, wv):
+    """Constant tensors at the ends of the int8 range with the longest reduction of the
+    benchmark networks (R*S*C = 4608): accumulators of +-7.5e7, beyond 2^24, so the int32 ->
+    fp32 conversion of the epilogue rounds; and all-zero operands (the output is the bias)."""
+    g = orc.ConvGeom(N=1, H=9, W=9, C=512, K=80, R=3, S=3, pad_h=1, pad_w=1)
+    x = np.full((1, 9, 9, 512), xv, np.int8)
+    w = np.full((80, 3, 3, 512), wv, np.int8)
+    b = (np.arange(80, dtype=np.int32) - 40) * 1001
+    acc_o = orc.conv_i8(g, x, w, b)
+    if xv and wv:
+        assert np.abs(acc_o).max() > 2**24
+    q_x, q_w = np.float32(0.013), np.float32(0.0021)
+    q_out = np.float32(float(q_x) * float(q_w) * max(float(np.abs(acc_o).max()), 1.0) / 100.0)
+    want = orc.requant(acc_o, orc.requant_scale(q_x, q_w, q_out), False)
+    d = B.ConvDesc(1, 9, 9, 512, 80, 3, 3, pad_h=1, pad_w=1)
+    dump = torch.zeros(acc_o.shape, dtype=torch.int32, device="cuda")
+    got = B.conv_int8(d, dev(x), B.pack_weights(d, dev(w)), dev(b), float(q_x), float(q_w),
+                      float(q_out), acc_dump=dump)
+    assert np.array_equal(host(dump), acc_o)
+    assert np.array_equal(host(got), want)
+    got = B.conv_int8(d, dev(x), B.pack_weights(d, dev(w)), dev(b), float(q_x), float(q_w),
+                      float(q_out))                      # the fast epilogue
+    assert np.array_equal(host(got), want)
+
+
 def test_conv_near_the_32_bit_offset_limit(B):
     """An activation tensor of just under 2 GiB (the kernels' 32-bit offsets end there): a
     3x3 layer over it, checked on sampled output pixels (first, last, image borders, random)
