@@ -393,6 +393,20 @@ def main():
                     tops=round(dom_tops, 2), pct_of_mfma_int8_peak=round(100 * dom_tops / PEAK_INT8_TOPS, 2),
                     hbm_gbs=round(dom_gbs, 1))
 
+    # the same figures for every kernel variant of the step, largest share first
+    def variant_roofline(name, v):
+        tops, gbs = v["ops"] / v["us"] / 1e6, v["bytes"] / v["us"] / 1e3
+        mfma = v["ops"] / v["bytes"] > RIDGE
+        return dict(kernel=name, launches_per_step=v["launches"],
+                    avg_launch_us=round(v["us"] / v["launches"], 3),
+                    share_of_conv_time=round(v["us"] / tot_us, 3), bound="mfma" if mfma else "hbm",
+                    achieved=round(tops, 2) if mfma else round(gbs, 1),
+                    peak=PEAK_INT8_TOPS if mfma else PEAK_HBM_GBS, unit="TOP/s" if mfma else "GB/s",
+                    frac=round(tops / PEAK_INT8_TOPS if mfma else gbs / PEAK_HBM_GBS, 4),
+                    traffic=measured_traffic(name, net.name, N))
+    kernels = [variant_roofline(k, v)
+               for k, v in sorted(by_variant.items(), key=lambda kv: -kv[1]["us"])]
+
     # ---------------- the oracle on the host cores, bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -460,6 +474,7 @@ def main():
         "one_stream_step_us": round(serial_us, 1),
         "conv_roofline_us_per_step": round(roof_us, 1),
         "roofline": roofline,
+        "kernels": kernels,
         "cpu_baseline": cpu,
         "offline": {"fold_bn_ms": round(t_fold * 1e3, 2), "calibrate_ms": round(t_cal * 1e3, 2),
                     "quantize_weights_ms": round(t_qw * 1e3, 2)},
