@@ -42,7 +42,8 @@ enum {
   Q8_EINVAL = -1,       /* null pointer, negative size, q <= 0 or not finite, bad p   */
   Q8_EUNSUPPORTED = -2, /* a shape the kernels cannot take (see q8_conv_int8)         */
   Q8_EALIGN = -3,       /* pointer or channel-stride alignment (see each call)        */
-  Q8_EHIP = -4          /* the HIP runtime refused a launch                            */
+  Q8_EHIP = -4,         /* the HIP runtime refused a launch                            */
+  Q8_EWORKSPACE = -5    /* the workspace passed in is smaller than the call needs      */
 };
 
 const char *q8_strerror(int code);
@@ -224,6 +225,56 @@ int q8_conv_pair_int8(const q8_conv_desc *d1, const int8_t *z_x, const void *w1_
                       const q8_conv_desc *d2, const void *w2_packed, const int32_t *bias2,
                       float q_w2, float q_out, const int8_t *residual, float q_res,
                       int8_t *z_y, void *stream);
+
+/* ---- a list of layers in one launch (cross-layer fusion, "Model Optimization" section) --
+ * q8_conv_chain_int8 runs a list of convolution layers, each one Eq. A' exactly as
+ * q8_conv_int8 computes it (bias, scale, fused residual sum of Eq. +, ReLU, Round, clamp, one
+ * int8 store), as ONE persistent launch instead of one launch per layer; the results are
+ * bit-identical to calling q8_conv_int8 layer by layer.  The batch is split into eight groups
+ * of images, one per XCD of the chip; output tiles are queued per XCD in layer order and a
+ * tile starts as soon as the tiles producing the pixels it reads have finished, so there is
+ * no launch boundary and no chip-wide barrier between layers.
+ *
+ * q8_chain_layer (HOST memory): the arguments of q8_conv_int8 for one layer, plus
+ *   src_layer / res_layer   index (smaller than the layer's own) of the layer of this list
+ *                           whose z_y is this layer's z_x / residual, or -1 if that tensor
+ *                           was written before the call;
+ *   variant                 -1, or a tile variant 0..3 (128x128, 128x64, 64x128, 64x64
+ *                           pixels x channels) to force for this layer (tests, tuning).
+ * Supported layers (q8_conv_chain_supported): C % 64 == 0, K > 32, R*S <= 32, dense tensors
+ * (no channel strides or offsets); every z_y of the list is a distinct tensor that no layer
+ * reads from outside the list; all layers share N.  Otherwise Q8_EUNSUPPORTED / Q8_EINVAL.
+ *
+ * Use: plan_host = malloc(q8_conv_chain_plan_bytes(...)); q8_conv_chain_plan fills it (host
+ * work only; it holds the device pointers and factors of the list, so it is rebuilt when
+ * those change); the caller copies the same bytes to DEVICE memory (plan_dev, 256-byte
+ * aligned) and provides q8_conv_chain_workspace_bytes(plan_host) bytes of device workspace
+ * (16-byte aligned; completion counters and queue heads, cleared by the call itself).
+ * q8_conv_chain_int8 then enqueues the clear and the launch on `stream`; it may be called any
+ * number of times with the same plan (also inside a stream capture).  Two calls that share
+ * a workspace must not overlap in time.
+ * After the stream has drained, word 0 of the workspace (int32) is 0 if every tile found its
+ * inputs; 1 means a tile gave up waiting (the outputs are then invalid; cannot happen
+ * unless the launch was starved of its workgroups for about a second); 2 means the chip
+ * reported an XCD number above 7.                                                      */
+typedef struct q8_chain_layer {
+  q8_conv_desc d;
+  const int8_t *z_x;
+  const void *z_w_packed;
+  const int32_t *bias_i32;
+  float q_x, q_w, q_out;
+  const int8_t *residual;
+  float q_res;
+  int8_t *z_y;
+  int32_t src_layer, res_layer, variant;
+} q8_chain_layer;
+int q8_conv_chain_supported(const q8_conv_desc *d);
+size_t q8_conv_chain_plan_bytes(const q8_chain_layer *layers, int n_layers);
+int q8_conv_chain_plan(const q8_chain_layer *layers, int n_layers, void *plan_host,
+                       size_t plan_bytes);
+size_t q8_conv_chain_workspace_bytes(const void *plan_host);
+int q8_conv_chain_int8(const void *plan_host, const void *plan_dev, void *workspace_dev,
+                       size_t workspace_bytes, void *stream);
 
 /* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
  * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.

@@ -26,6 +26,8 @@ EXPORTS = [
     "q8_u8_prepare", "q8_conv_u8", "q8_quantize_weights_per_channel",
     "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_conv_int8_real_output", "q8_conv_pair_supported", "q8_conv_pair_int8", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
+    "q8_conv_chain_supported", "q8_conv_chain_plan_bytes", "q8_conv_chain_plan",
+    "q8_conv_chain_workspace_bytes", "q8_conv_chain_int8",
     "q8_conv_variant", "q8_conv_force_variant", "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
@@ -60,8 +62,24 @@ class ConvDesc(C.Structure):
         return lib.q8_conv_out_w(C.byref(self))
 
 
+class ChainLayer(C.Structure):
+    """Mirror of ``q8_chain_layer``: one layer of a q8_conv_chain_int8 list."""
+    _fields_ = [("d", ConvDesc), ("z_x", C.c_void_p), ("z_w_packed", C.c_void_p),
+                ("bias_i32", C.c_void_p), ("q_x", C.c_float), ("q_w", C.c_float),
+                ("q_out", C.c_float), ("residual", C.c_void_p), ("q_res", C.c_float),
+                ("z_y", C.c_void_p), ("src_layer", C.c_int32), ("res_layer", C.c_int32),
+                ("variant", C.c_int32)]
+
+
 _vp, _sz, _f, _i = C.c_void_p, C.c_size_t, C.c_float, C.c_int
 _dp = C.POINTER(ConvDesc)
+lib.q8_conv_chain_supported.argtypes = [_dp]
+lib.q8_conv_chain_plan_bytes.restype = C.c_size_t
+lib.q8_conv_chain_plan_bytes.argtypes = [C.POINTER(ChainLayer), _i]
+lib.q8_conv_chain_plan.argtypes = [C.POINTER(ChainLayer), _i, _vp, _sz]
+lib.q8_conv_chain_workspace_bytes.restype = C.c_size_t
+lib.q8_conv_chain_workspace_bytes.argtypes = [_vp]
+lib.q8_conv_chain_int8.argtypes = [_vp, _vp, _vp, _sz, _vp]
 lib.q8_strerror.restype = C.c_char_p
 lib.q8_strerror.argtypes = [_i]
 lib.q8_conv_out_h.argtypes = [_dp]
@@ -314,6 +332,52 @@ def conv_pair_int8(d1, z_x, w1_packed, bias1, q_x, q_w1, q_mid, d2, w2_packed, b
                                  _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
                                  _stream()))
     return out
+
+
+def conv_chain_supported(desc):
+    return bool(lib.q8_conv_chain_supported(C.byref(desc)))
+
+
+class ConvChain:
+    """A planned q8_conv_chain_int8 launch.  ``layers``: list of dicts with the arguments of
+    conv_int8 (desc, z_x, w, bias, q_x, q_w, q_out, residual, q_res, out) plus src_layer,
+    res_layer (index in the list, or -1) and optionally variant.  Holds the host plan, its
+    device copy and the workspace; the tensors named in the plan must stay alive."""
+
+    def __init__(self, layers, device):
+        n = len(layers)
+        arr = (ChainLayer * n)()
+        self.keep = []
+        for i, L in enumerate(layers):
+            a = arr[i]
+            a.d = L["desc"]
+            a.z_x = _ptr(L["z_x"], torch.int8)
+            a.z_w_packed = _ptr(L["w"], torch.int8)
+            a.bias_i32 = _ptr(L["bias"], torch.int32)
+            a.q_x, a.q_w, a.q_out = L["q_x"], L["q_w"], L["q_out"]
+            a.residual = _ptr(L.get("residual"), torch.int8)
+            a.q_res = L.get("q_res", 0.0)
+            a.z_y = _ptr(L["out"], torch.int8)
+            a.src_layer, a.res_layer = L["src_layer"], L["res_layer"]
+            a.variant = L.get("variant", -1)
+            self.keep.append((L["z_x"], L["w"], L["bias"], L.get("residual"), L["out"]))
+        nbytes = lib.q8_conv_chain_plan_bytes(arr, n)
+        if nbytes == 0:
+            raise Q8Error(-2)
+        self.plan_host = C.create_string_buffer(nbytes)
+        _check(lib.q8_conv_chain_plan(arr, n, self.plan_host, nbytes))
+        host = torch.frombuffer(self.plan_host, dtype=torch.uint8, count=nbytes)
+        self.plan_dev = host.to(device)
+        ws_bytes = lib.q8_conv_chain_workspace_bytes(self.plan_host)
+        self.ws = torch.zeros(ws_bytes // 4, dtype=torch.int32, device=device)
+
+    def run(self):
+        _check(lib.q8_conv_chain_int8(self.plan_host, self.plan_dev.data_ptr(),
+                                      self.ws.data_ptr(), self.ws.numel() * 4, _stream()))
+
+    def status(self):
+        """Word 0 of the workspace after a synchronisation: 0 = every tile found its inputs."""
+        return int(self.ws[0].item())
 
 
 def conv_variant(desc):

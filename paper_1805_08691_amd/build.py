@@ -12,12 +12,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libq8conv.so")
-SOURCES = ["q8_conv_ring.hip", "q8_conv_ring_ext.hip", "q8_conv_ring_pair.hip", "q8_conv.hip",
-           "q8_conv_reg.hip", "q8_elementwise.hip", "q8_helpers.hip"]
+OBJ = os.environ.get("Q8_OBJ_DIR") or os.path.join(HERE, "_build")
+LIB = os.environ.get("Q8_LIB_OUT") or os.path.join(HERE, "libq8conv.so")
+SOURCES = ["q8_conv_ring.hip", "q8_conv_ring_ext.hip", "q8_conv_ring_pair.hip", "q8_conv_chain.hip",
+           "q8_conv.hip", "q8_conv_reg.hip", "q8_elementwise.hip", "q8_helpers.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+EXTRA = os.environ.get("Q8_EXTRA_FLAGS", "").split()
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -30,13 +31,13 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 
 def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    subprocess.check_call([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+    subprocess.check_call([HIPCC, *FLAGS, *EXTRA, "-c", os.path.join(CSRC, src), "-o", obj])
     return obj
 
 
 def build(verbose=True):
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:

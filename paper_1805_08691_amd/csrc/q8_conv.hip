@@ -194,17 +194,20 @@ struct U8Flags {
   const PairArgs* pair = nullptr;   // a second, 1x1 layer on the output while it is on chip
 };
 
-int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
-                const int32_t* bias_i32, float q_x, float q_w, float q_out,
-                const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
-                void* stream) {
+// Checks the arguments of one layer and fills the kernels' parameter block.  *empty: the
+// layer has no output pixel (nothing to launch).
+int conv_fill(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
+              const int32_t* bias_i32, float q_x, float q_w, float q_out,
+              const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+              ConvParams& p, bool* empty) {
+  *empty = false;
   Q8_REQUIRE(desc_sane(d), Q8_EINVAL);
   Q8_REQUIRE(q8_finite_pos(q_x) && q8_finite_pos(q_w) && q8_finite_pos(q_out), Q8_EINVAL);
   Q8_REQUIRE(residual == nullptr || q8_finite_pos(q_res), Q8_EINVAL);
   const int mode = conv_mode(d);
   Q8_REQUIRE(mode >= 0, Q8_EUNSUPPORTED);
 
-  ConvParams p{};
+  p = ConvParams{};
   p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C; p.K = d->K; p.R = d->R; p.S = d->S;
   p.stride_h = d->stride_h; p.stride_w = d->stride_w; p.pad_h = d->pad_h; p.pad_w = d->pad_w;
   p.dil_h = d->dil_h; p.dil_w = d->dil_w;
@@ -219,7 +222,10 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   Q8_REQUIRE(residual == nullptr || p.res_cs >= p.res_off + d->K, Q8_EINVAL);
 
   const long M = (long)d->N * p.Ho * p.Wo;
-  if (M == 0) return Q8_OK;
+  if (M == 0) {
+    *empty = true;
+    return Q8_OK;
+  }
   Q8_REQUIRE(M <= 0x7fffffffL, Q8_EUNSUPPORTED);
   Q8_REQUIRE((long)d->H * d->W * p.in_cs <= 0x7fffffffL, Q8_EUNSUPPORTED);
   Q8_REQUIRE(z_x && z_w_packed && (z_y || u.y_f32 || u.pair), Q8_EINVAL);
@@ -307,6 +313,19 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   p.f32_vec4 =
       (u.y_f32 && p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(u.y_f32, 16)) ? 1 : 0;
 
+  return Q8_OK;
+}
+
+int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
+                const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+                void* stream) {
+  ConvParams p;
+  bool empty = false;
+  const int rc = conv_fill(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual, q_res, z_y,
+                           acc_dump, p, &empty);
+  if (rc != Q8_OK || empty) return rc;
+  const int mode = conv_mode(d);
   hipStream_t s = (hipStream_t)stream;
   if (u.pair) {
     // q_out of this call is the intermediate tensor's factor; the second layer reads it
@@ -353,6 +372,19 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
   if (variant >= kRegBase) return q8::launch_reg_variant(variant - kRegBase, p, s);
   return q8::launch_stream_variant(variant, p, s);
 }
+
+}  // namespace
+
+namespace q8 {
+int conv_fill_plain(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                    const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                    const int8_t* residual, float q_res, int8_t* z_y, ConvParams& p, bool* empty) {
+  return conv_fill(d, U8Flags{0, 0, 0, nullptr}, z_x, z_w_packed, bias_i32, q_x, q_w, q_out,
+                   residual, q_res, z_y, nullptr, p, empty);
+}
+}  // namespace q8
+
+namespace {
 
 // start[idx*K + k] = bias[k] + 128 * (sum of filter k over the taps of rectangle idx), for
 // every rectangle [r_lo, r_hi) x [s_lo, s_hi) of the filter (see u8_start_index; an empty or

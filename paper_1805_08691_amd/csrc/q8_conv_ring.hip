@@ -22,6 +22,12 @@ const RingVariant kRingVariants[] = {
     Q8_RING_ROW(16, 2, 2, 2, 2, 64, 8)     // 16
     Q8_RING_ROW(17, 2, 4, 2, 1, 64, 8)     // 17: the same with eight wavefronts
     Q8_RING_ROW(18, 2, 2, 2, 1, 64, 8)     // 18: 128 x 64, deep ring
+    Q8_RING_ROW(19, 2, 2, 1, 1, 64, 8)     // 19: 64 x 64, deep ring (small maps, long reductions)
+    Q8_RING_ROW(20, 2, 2, 1, 2, 64, 8)     // 20: 64 x 128, deep ring
+    Q8_RING_ROW(21, 2, 2, 1, 1, 128, 4)    // 21: 64 x 64, 128 reduction bytes per step
+    Q8_RING_ROW(22, 2, 2, 1, 2, 128, 4)    // 22: 64 x 128, 128 reduction bytes per step
+    Q8_RING_ROW(23, 2, 2, 2, 1, 128, 4)    // 23: 128 x 64, 128 reduction bytes per step
+    Q8_RING_ROW(24, 2, 2, 1, 1, 128, 8)    // 24: 64 x 64, 128 bytes per step, deep ring (128 KB)
 };
 #undef Q8_RING_ROW
 constexpr int kNumRingVariants = sizeof(kRingVariants) / sizeof(kRingVariants[0]);

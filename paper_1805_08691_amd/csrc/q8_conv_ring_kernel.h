@@ -43,8 +43,15 @@ constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors
 // pixels: their int8 codes go to LDS instead of HBM and serve as the activation operand of
 // the second layer, all of whose filters wait in LDS behind the ring (requested at kernel
 // start).  The two layers' arithmetic is exactly that of two launches.
+//
+// conv_tile_ring computes ONE output tile (pixel tile `ptile`, channel tile `ctile`) with the
+// workgroup's WP*WC wavefronts, using `lds` (STAGES * (BP + BC) * BK bytes, 1 KB aligned) as
+// the operand ring.  No vector-memory operation of the workgroup may be outstanding on entry
+// (the ring counts its own loads); the caller synchronises the workgroup before `lds` is
+// used again.
 template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
-__global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int ptile,
+                                               const int ctile, int8_t* const lds) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
                                       // descriptor types exist for the device target alone
   constexpr int CHUNKS = BK / 16;          // 16-byte chunks per LDS row
@@ -63,17 +70,6 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   static_assert(STAGES >= 2 && STAGES <= 8, "ring depth");
   static_assert((STAGES - 2) * LOADS < 64, "vmcnt is 6 bits");
 
-  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // STAGES * STAGE_BYTES
-
-  const int nblk = p.n_ptiles * p.n_ctiles;
-  int bid = blockIdx.x;
-  {
-    const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
-    const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
-    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
-  }
-  const int ctile = bid % p.n_ctiles;
-  const int ptile = bid / p.n_ctiles;
   const int pix0 = ptile * BP;
   const int ch0 = ctile * BC;
 
@@ -184,6 +180,9 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       b_voff[j] = ((b_mask[j] >> tap) & 1u) ? b_off[j] : kOobOffset;
   };
 
+  // What the reduction loop reads of `p`, in registers: when `p` lives in global memory (a
+  // layer list) the compiler barriers of the loop would otherwise force a reload per step.
+  const int p_C = p.C, p_S = p.S, p_red_len = p.red_len;
   auto issue_stage = [&](int buf) {
     int8_t* stage = lds + buf * STAGE_BYTES;
     if constexpr (UNIFORM == 1) {
@@ -204,17 +203,17 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       step_base += BK;
       // advance (branch-free, so the whole step stays one scheduling region)
       tap_c += BK;
-      const int wrap_c = tap_c >= p.C ? 1 : 0;
+      const int wrap_c = tap_c >= p_C ? 1 : 0;
       tap_c = wrap_c ? 0 : tap_c;
       tap += wrap_c;
       tap_s += wrap_c;
       tap_delta += wrap_c ? dw_step : 0;
-      const int wrap_s = tap_s == p.S ? 1 : 0;
+      const int wrap_s = tap_s == p_S ? 1 : 0;
       tap_s = wrap_s ? 0 : tap_s;
       tap_delta += wrap_s ? dh_step : 0;
       tap_changed = wrap_c;
     } else if constexpr (UNIFORM == 2) {
-      const bool red_ok = step_base + lane_red < p.red_len;
+      const bool red_ok = step_base + lane_red < p_red_len;
 #pragma unroll
       for (int j = 0; j < A_LOADS; ++j) {
         const int voff = red_ok ? a_off[j] : kOobOffset;
@@ -232,11 +231,11 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
             voff, tap_delta, 0, 0);
       }
       step_base += BK;
-      const int taps_per_step = BK / p.C;
+      const int taps_per_step = BK / p_C;
       tap += taps_per_step;
       tap_delta += taps_per_step * row_step;
     } else {
-      const bool red_ok = step_base + lchunk * 16 < p.red_len;
+      const bool red_ok = step_base + lchunk * 16 < p_red_len;
 #pragma unroll
       for (int j = 0; j < A_LOADS; ++j) {
         const int voff = red_ok ? a_off[j] : kOobOffset;
@@ -256,11 +255,11 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
       }
       step_base += BK;
       tap_c += BK;
-      while (tap_c >= p.C) {
-        tap_c -= p.C;
+      while (tap_c >= p_C) {
+        tap_c -= p_C;
         ++tap;
         tap_delta += dw_step;
-        if (++tap_s == p.S) { tap_s = 0; tap_delta += dh_step; }
+        if (++tap_s == p_S) { tap_s = 0; tap_delta += dh_step; }
       }
     }
   };
@@ -425,9 +424,13 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     constexpr int LATER = decltype(later_c)::value;
     constexpr int STAGE = decltype(stage_c)::value;
     wait_vmcnt<LATER * LOADS>();
+    // Every LDS read this wave has issued (the last fragments of step kt-1) has returned:
+    // behind the barrier the other waves request step kt+STAGES-1 into the buffer of step
+    // kt-1, and a read still queued in the LDS could otherwise be overtaken by that data
+    // (seen with several workgroups per CU and operands that come from a warm L2).
+    __builtin_amdgcn_s_waitcnt(0xc07f);
     // Bare barrier (no fence: a fence would drain the loads of the later steps too).
-    // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS
-    // (its last fragments are in registers already).
+    // Step kt is now visible to all waves, and everyone has read step kt-1 out of LDS.
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -654,6 +657,25 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
   else if (U8 && p.res_u8) finish_all(std::integral_constant<int, 5>{});
   else finish_all(std::integral_constant<int, U8 ? 4 : 2>{});
 #endif  // __HIP_DEVICE_COMPILE__
+}
+
+// One workgroup per output tile.  Workgroup id -> tile: each XCD (workgroups are dealt to
+// the XCDs round-robin) gets a contiguous run of tiles, channel tile fastest, so tiles that
+// share activations share an L2.
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
+__global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // the operand ring
+  const int nblk = p.n_ptiles * p.n_ctiles;
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
+    const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
+    bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(p, bid / p.n_ctiles,
+                                                                bid % p.n_ctiles, lds);
+#endif
 }
 
 template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>

@@ -330,6 +330,7 @@ const char* q8_strerror(int code) {
     case Q8_EUNSUPPORTED: return "shape not supported by the kernels";
     case Q8_EALIGN: return "pointer or channel stride not aligned as the call requires";
     case Q8_EHIP: return "HIP launch failed";
+    case Q8_EWORKSPACE: return "workspace too small for this call";
     default: return "unknown q8conv error code";
   }
 }

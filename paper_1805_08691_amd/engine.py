@@ -33,8 +33,15 @@ class Engine:
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
                  per_channel_weights=False, real_outputs=False, own_sum_factor=False,
-                 fuse_pairs=False):
+                 fuse_pairs=False, chain=False):
         self.net = net
+        # chain: every run of consecutive convolutions the library can take as a list runs as
+        # ONE persistent launch (q8_conv_chain_int8: the batch split over the XCDs, tiles
+        # started by the completion of the tiles they read) instead of one launch per layer
+        self.chain = chain
+        self.chains = None    # [(first op index, one past the last, binding.ConvChain)]
+        assert not (chain and (n_streams > 1 or unsigned_activations or per_channel_weights
+                               or real_outputs or fuse_pairs))
         # fuse_pairs: a convolution whose output only one 1x1 layer reads runs together with
         # that layer in one launch where the library supports the pair (same results; the
         # intermediate tensor is then never written)
@@ -367,6 +374,61 @@ class Engine:
             else:
                 self.run_conv(op, lo, n)
 
+    # ------------------------------------------------------------------ layer lists
+    def _chainable(self, op):
+        if op.kind != "conv" or op.dst_c_off != 0:
+            return False
+        s, d = self.net.tensors[op.src], self.net.tensors[op.dst]
+        if d.C != op.K or s.C != op.C or (op.res and self.net.tensors[op.res].C != op.K):
+            return False
+        return B.conv_chain_supported(self.desc[op.name])
+
+    def build_chains(self, variants=None):
+        """Plan one q8_conv_chain_int8 launch per run of two or more chainable convolutions.
+        ``variants`` ({conv name: tile variant}) forces tile shapes (tests, tuning)."""
+        ops = self.net.ops
+        self.chains = []
+        i = 0
+        while i < len(ops):
+            j = i
+            while j < len(ops) and self._chainable(ops[j]):
+                j += 1
+            if j - i >= 2:
+                writer = {}
+                layers = []
+                for k, op in enumerate(ops[i:j]):
+                    packed, bias = self.wq[op.name]
+                    layers.append(dict(
+                        desc=self.desc[op.name], z_x=self.act[op.src], w=packed, bias=bias,
+                        q_x=self.q[op.src], q_w=self.qw[op.name], q_out=self.q[op.dst],
+                        residual=self.act[op.res] if op.res else None,
+                        q_res=self.q[op.res] if op.res else 0.0, out=self.act[op.dst],
+                        src_layer=writer.get(op.src, -1),
+                        res_layer=writer.get(op.res, -1) if op.res else -1,
+                        variant=(variants or {}).get(op.name, -1)))
+                    writer[op.dst] = k
+                self.chains.append((i, j, B.ConvChain(layers, self.dev)))
+                i = j
+            else:
+                i = max(j, i + 1)
+        return self.chains
+
+    def run_chained(self):
+        """Every op on the whole batch: planned runs as one launch each, the rest one by one."""
+        if self.chains is None:
+            self.build_chains()
+        ops = self.net.ops
+        starts = {a: (b, c) for a, b, c in self.chains}
+        i = 0
+        while i < len(ops):
+            if i in starts:
+                end, ch = starts[i]
+                ch.run()
+                i = end
+            else:
+                self.run_ops([ops[i]], 0, self.N)
+                i += 1
+
     @staticmethod
     def scale32(q_in, q_out):
         """q_in / q_out rounded once to fp32 (both factors are fp32 values)."""
@@ -381,7 +443,9 @@ class Engine:
         stream."""
         if x is not None:
             self.quantize_input(x)
-        if self.n_streams == 1 or serial:
+        if self.chain:
+            self.run_chained()
+        elif self.n_streams == 1 or serial:
             for lo, n in self.parts:
                 self.run_ops(self.net.ops, lo, n)
         else:
