@@ -816,7 +816,7 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
                           per_channel=False, real_outputs=False, own_sum_factor=False,
-                          fuse_pairs=False):
+                          fuse_pairs=False, chain=False, chain_variants=None):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -838,7 +838,7 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
 
     eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned,
                  per_channel_weights=per_channel, real_outputs=real_outputs,
-                 fuse_pairs=fuse_pairs)
+                 fuse_pairs=fuse_pairs, chain=chain)
     assert eng.unsigned == U
     assert bool(eng.pairs) == fuse_pairs
     unwritten = {op.dst for op in net.convs() if op.name in eng.pairs}   # stay on chip
@@ -868,9 +868,19 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
             bias = bias - 128 * qp["z_w"].astype(np.int64).reshape(bias.size, -1).sum(axis=1)
         assert np.array_equal(bias, qp["z_b"]), name
     xd = dev(x)
+    if chain:
+        eng.allocate()
+        chains = eng.build_chains(chain_variants)
+        assert chains, "no run of chainable layers in this network"
     outs = eng.forward(xd)
+    if chain:
+        torch.cuda.synchronize()
+        assert [c.status() for _, _, c in eng.chains] == [0] * len(eng.chains)
     zi = host(eng.input_codes())
-    assert np.array_equal(zi[picks][..., :3], z_in) and np.all(zi[..., 3] == 0)
+    if z_in.shape[-1] == 3:              # an image: stored with a zero fourth channel
+        assert np.array_equal(zi[picks][..., :3], z_in) and np.all(zi[..., 3] == 0)
+    else:
+        assert np.array_equal(zi[picks], z_in)
     if eng.in_frame:                     # the frame around the image holds zeros
         top, left = eng.in_frame[:2]
         full = host(eng.act[net.input])
@@ -948,6 +958,30 @@ def test_resnet50_with_fused_layer_pairs(B):
     # every bottleneck's 3x3 -> 1x1 whose 3x3 has 64 or 128 filters runs as one launch, in
     # the benchmark's launch configuration
     _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, fuse_pairs=True)
+
+
+def test_resnet50_as_one_chained_launch(B):
+    # the 52 convolutions behind the first pooling as ONE persistent launch (the batch split
+    # over the eight XCDs, tiles started by completion counters); images on both sides of
+    # every boundary between two XCDs' shares are among the picks
+    _sampled_images_check(B, 3, 64, [0, 7, 8, 31, 32, 55, 56, 63], n_cal=4, cal_batch=8,
+                          n_streams=1, chain=True)
+
+
+@pytest.mark.parametrize("batch", [13, 3])
+def test_chained_launch_with_uneven_and_empty_shares(B, batch):
+    # 13 images: shares of 2 and 1; 3 images: five XCDs have no work at all
+    _sampled_images_check(B, 3, batch, list(range(batch)), n_cal=2, cal_batch=8, n_streams=1,
+                          chain=True)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+def test_chained_launch_with_every_tile_variant(B, variant):
+    # the bottleneck block of config 2 with one tile shape forced on all three layers:
+    # ragged pixel tiles (25 images: shares of 4 and 3) and the residual dependency
+    net = wl.CONFIGS[2]["make"]()
+    _sampled_images_check(B, 2, 25, [0, 3, 4, 12, 24], n_cal=1, cal_batch=4, n_streams=1,
+                          chain=True, chain_variants={op.name: variant for op in net.convs()})
 
 
 def test_resnet50_sums_at_their_own_calibrated_factor(B):
