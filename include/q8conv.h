@@ -276,6 +276,20 @@ size_t q8_conv_chain_workspace_bytes(const void *plan_host);
 int q8_conv_chain_int8(const void *plan_host, const void *plan_dev, void *workspace_dev,
                        size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory for the workspace (code under HIP graph
+ * capture that has nothing preallocated, tight serving loops, harnesses that forbid
+ * hipMalloc): q8_conv_chain_int8 with the workspace taken from a fixed array inside the
+ * library's own device image, q8_conv_chain_static_workspace_limit() bytes (1 MiB) per GPU,
+ * held from the moment the library is loaded until the process ends.  The call allocates and
+ * frees nothing; a plan whose workspace is larger is refused with Q8_EWORKSPACE (use
+ * q8_conv_chain_int8).  Same results as q8_conv_chain_int8.  Every call on one GPU shares
+ * that GPU's array (the call clears what it uses first): two such calls must not overlap in
+ * time on one GPU, whatever their streams.  q8_conv_chain_static_status copies the status
+ * word (see above) of the current device's array to host memory; it synchronises.       */
+size_t q8_conv_chain_static_workspace_limit(void);
+int q8_conv_chain_int8_static(const void *plan_host, const void *plan_dev, void *stream);
+int q8_conv_chain_static_status(int32_t *status_host);
+
 /* Name of the kernel variant (tile shape) q8_conv_int8 picks for this geometry, as it
  * appears in a profiler's kernel trace; "unsupported" if the call would be rejected.
  * For measurement code that groups launches by kernel.                              */

@@ -28,6 +28,8 @@ EXPORTS = [
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
     "q8_conv_chain_supported", "q8_conv_chain_plan_bytes", "q8_conv_chain_plan",
     "q8_conv_chain_workspace_bytes", "q8_conv_chain_int8",
+    "q8_conv_chain_static_workspace_limit", "q8_conv_chain_int8_static",
+    "q8_conv_chain_static_status",
     "q8_conv_variant", "q8_conv_force_variant", "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
@@ -80,6 +82,10 @@ lib.q8_conv_chain_plan.argtypes = [C.POINTER(ChainLayer), _i, _vp, _sz]
 lib.q8_conv_chain_workspace_bytes.restype = C.c_size_t
 lib.q8_conv_chain_workspace_bytes.argtypes = [_vp]
 lib.q8_conv_chain_int8.argtypes = [_vp, _vp, _vp, _sz, _vp]
+lib.q8_conv_chain_static_workspace_limit.restype = C.c_size_t
+lib.q8_conv_chain_static_workspace_limit.argtypes = []
+lib.q8_conv_chain_int8_static.argtypes = [_vp, _vp, _vp]
+lib.q8_conv_chain_static_status.argtypes = [C.POINTER(C.c_int32)]
 lib.q8_strerror.restype = C.c_char_p
 lib.q8_strerror.argtypes = [_i]
 lib.q8_conv_out_h.argtypes = [_dp]
@@ -378,6 +384,16 @@ class ConvChain:
     def status(self):
         """Word 0 of the workspace after a synchronisation: 0 = every tile found its inputs."""
         return int(self.ws[0].item())
+
+    def run_static(self):
+        """The same launch on the library's own fixed workspace (allocates nothing)."""
+        _check(lib.q8_conv_chain_int8_static(self.plan_host, self.plan_dev.data_ptr(), _stream()))
+
+    @staticmethod
+    def static_status():
+        v = C.c_int32(-1)
+        _check(lib.q8_conv_chain_static_status(C.byref(v)))
+        return v.value
 
 
 def conv_variant(desc):

@@ -26,6 +26,7 @@
 
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include <vector>
 
 namespace q8 {
@@ -47,7 +48,7 @@ constexpr int kSpinLimit = 1 << 19;               // polls (about 0.4 s) before 
 // Workspace layout (int32 words): word 0 = status (0 ok; 1 a wait gave up; 2 unexpected
 // XCC_ID); from word 32 on one region per XCD, 32-word aligned so that no two XCDs ever
 // touch the same 128-byte line: the queue head, then that XCD's completion counters.
-constexpr int kWsStatus = 0;      // (device code)
+constexpr int kWsStatus = 0;
 constexpr int kWsRegions = 32;
 constexpr int kRegionHead = 0;                    // first word of a region: next queue entry
 constexpr int kRegionDone = 32;                   // completion counters from here on
@@ -373,6 +374,41 @@ int chain_layout(const q8_chain_layer* layers, int n, std::vector<ChainLayerDev>
   return Q8_OK;
 }
 
+int chain_launch(const ChainHeader* hd, const void* plan_dev, int* ws, hipStream_t s) {
+  static const hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(conv_chain_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kChainLds + 64);
+  if (attr != hipSuccess) return Q8_EHIP;
+  const int words = hd->ws_words;
+  // (a fill kernel, not a memset: the call may be recorded into a HIP graph)
+  hipLaunchKernelGGL(chain_clear_kernel, dim3((words + 1023) / 1024), dim3(256), 0, s, ws, words);
+  hipLaunchKernelGGL(conv_chain_kernel, dim3(hd->grid), dim3(kChainThreads), kChainLds + 64, s,
+                     (const unsigned char*)plan_dev, ws, 0);
+  return q8_launch_status();
+}
+
+// The workspace of q8_conv_chain_int8_static: device memory that belongs to the library's
+// code object, one copy per GPU, never allocated or freed by a call.  In host code the
+// array's name only stands for the symbol; its device address is looked up once per device.
+constexpr size_t kStaticWsBytes = 1u << 20;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) int g_chain_scratch[kStaticWsBytes / 4];
+
+int static_scratch(int** ws) {
+  static std::mutex mu;
+  static int* addr[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Q8_EHIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_chain_scratch)) != hipSuccess || !p) return Q8_EHIP;
+    addr[dev] = (int*)p;
+  }
+  *ws = addr[dev];
+  return Q8_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -457,17 +493,29 @@ int q8_conv_chain_int8(const void* plan_host, const void* plan_dev, void* worksp
   Q8_REQUIRE(hd && hd->magic == kPlanMagic && plan_dev && workspace_dev, Q8_EINVAL);
   Q8_REQUIRE(workspace_bytes >= (size_t)hd->ws_words * 4, Q8_EWORKSPACE);
   Q8_REQUIRE(q8_aligned(plan_dev, 256) && q8_aligned(workspace_dev, 16), Q8_EALIGN);
-  static const hipError_t attr =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(conv_chain_kernel),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kChainLds + 64);
-  if (attr != hipSuccess) return Q8_EHIP;
-  hipStream_t s = (hipStream_t)stream;
-  const int words = hd->ws_words;
-  hipLaunchKernelGGL(chain_clear_kernel, dim3((words + 1023) / 1024), dim3(256), 0, s,
-                     (int*)workspace_dev, words);
-  hipLaunchKernelGGL(conv_chain_kernel, dim3(hd->grid), dim3(kChainThreads), kChainLds + 64, s,
-                     (const unsigned char*)plan_dev, (int*)workspace_dev, 0);
-  return q8_launch_status();
+  return chain_launch(hd, plan_dev, (int*)workspace_dev, (hipStream_t)stream);
+}
+
+size_t q8_conv_chain_static_workspace_limit(void) { return kStaticWsBytes; }
+
+int q8_conv_chain_int8_static(const void* plan_host, const void* plan_dev, void* stream) {
+  const ChainHeader* hd = (const ChainHeader*)plan_host;
+  Q8_REQUIRE(hd && hd->magic == kPlanMagic && plan_dev, Q8_EINVAL);
+  Q8_REQUIRE((size_t)hd->ws_words * 4 <= kStaticWsBytes, Q8_EWORKSPACE);
+  Q8_REQUIRE(q8_aligned(plan_dev, 256), Q8_EALIGN);
+  int* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != Q8_OK) return rc;
+  return chain_launch(hd, plan_dev, ws, (hipStream_t)stream);
+}
+
+int q8_conv_chain_static_status(int32_t* status_host) {
+  Q8_REQUIRE(status_host, Q8_EINVAL);
+  int* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != Q8_OK) return rc;
+  return hipMemcpy(status_host, ws + kWsStatus, 4, hipMemcpyDeviceToHost) == hipSuccess
+             ? Q8_OK : Q8_EHIP;
 }
 
 int q8_conv_chain_supported(const q8_conv_desc* d) { return d && chain_capable(*d) ? 1 : 0; }

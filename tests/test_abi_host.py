@@ -150,3 +150,86 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert B.packed_weight_bytes(d) == 16 * 3 * 3 * 16
     assert B.packed_weight_bytes(B.ConvDesc(1, 8, 8, 3, 64, 7, 7)) == 64 * 7 * 2 * 16
     assert L.q8_maxpool_i8(fake, 1, 8, 8, 4, 3, 3, 2, 3, 4, 4, fake, None) == -1   # pad >= window
+
+
+# ------------------------------------------------------------------ layer lists (host side)
+def _chain_layers(n_img=16, bad=None):
+    """A bottleneck block (1x1 256->64, 3x3 64->64, 1x1 64->256 + residual) as a layer list on
+    made-up, distinct, aligned device addresses (nothing is dereferenced on the host)."""
+    base = 0x7F0000000000
+    t = {"x": base, "a": base + (1 << 28), "b": base + (2 << 28), "y": base + (3 << 28)}
+    geo = [(256, 64, 1, "x", "a", None), (64, 64, 3, "a", "b", None), (64, 256, 1, "b", "y", "x")]
+    arr = (B.ChainLayer * 3)()
+    for i, (Cc, K, R, src, dst, res) in enumerate(geo):
+        a = arr[i]
+        a.d = B.ConvDesc(n_img, 28, 28, Cc, K, R, R, 1, 1, R // 2, R // 2, relu=1)
+        a.z_x, a.z_y = t[src], t[dst]
+        a.z_w_packed, a.bias_i32 = 0x100000 + i * 0x100000, 0x10000 + i * 0x1000
+        a.q_x = a.q_w = a.q_out = a.q_res = 0.5
+        a.residual = t[res] if res else None
+        a.src_layer = i - 1 if i else -1
+        a.res_layer = -1
+        a.variant = -1
+    if bad:
+        bad(arr)
+    return arr
+
+
+def test_chain_plan_accepts_a_block_and_sizes_its_workspace():
+    arr = _chain_layers()
+    n = B.lib.q8_conv_chain_plan_bytes(arr, 3)
+    assert n > 0 and n % 256 == 0
+    buf = C.create_string_buffer(n)
+    assert B.lib.q8_conv_chain_plan(arr, 3, buf, n) == 0
+    assert B.lib.q8_conv_chain_plan(arr, 3, buf, n - 1) == -1          # plan buffer too small
+    ws = B.lib.q8_conv_chain_workspace_bytes(buf)
+    # status line + per XCD a queue head line and one counter per pixel tile of every layer
+    assert ws >= 4 * (32 + 8 * 32) and ws % 128 == 0
+    fake = C.c_void_p(0x7F1000000000)
+    assert B.lib.q8_conv_chain_int8(buf, fake, fake, ws - 4, None) == -5    # workspace too small
+    assert B.lib.q8_conv_chain_int8(buf, C.c_void_p(0x7F1000000010), fake, ws, None) == -3
+    assert B.lib.q8_conv_chain_int8(buf, None, fake, ws, None) == -1
+    assert B.lib.q8_conv_chain_workspace_bytes(C.create_string_buffer(256)) == 0   # not a plan
+    assert B.lib.q8_conv_chain_int8(C.create_string_buffer(256), fake, fake, 1 << 20, None) == -1
+    assert B.lib.q8_conv_chain_int8_static(C.create_string_buffer(256), fake, None) == -1
+    assert B.lib.q8_conv_chain_static_workspace_limit() == 1 << 20
+    assert B.lib.q8_strerror(-5) != B.lib.q8_strerror(-99)
+
+
+def test_chain_plan_rejects_inconsistent_lists():
+    def plan_rc(bad):
+        arr = _chain_layers(bad=bad)
+        return B.lib.q8_conv_chain_plan_bytes(arr, 3)
+
+    def forward_ref(arr): arr[1].src_layer = 2                     # reads a later layer
+    def wrong_src(arr): arr[2].src_layer = 0                       # z_x is not that layer's z_y
+    def alias(arr): arr[1].z_y = arr[0].z_y                        # a tensor written twice
+    def clobber_input(arr): arr[2].z_y = arr[0].z_x                # writes what the list reads
+    def odd_c(arr): arr[0].d.C = 48                                # not a chain geometry
+    def sliced(arr): arr[2].d.out_c_off = 16
+    def batches(arr): arr[1].d.N = 3
+    def res_without_tensor(arr): arr[1].res_layer = 0
+    for bad in (forward_ref, wrong_src, alias, clobber_input, odd_c, sliced, batches,
+                res_without_tensor):
+        assert plan_rc(bad) == 0, bad.__name__
+    assert B.lib.q8_conv_chain_plan_bytes(None, 3) == 0
+    assert B.lib.q8_conv_chain_plan_bytes(_chain_layers(), 0) == 0
+    assert B.lib.q8_conv_chain_supported(C.byref(B.ConvDesc(8, 14, 14, 256, 256, 3, 3, 1, 1, 1, 1))) == 1
+    assert B.lib.q8_conv_chain_supported(C.byref(B.ConvDesc(8, 14, 14, 48, 256, 3, 3, 1, 1, 1, 1))) == 0
+    assert B.lib.q8_conv_chain_supported(C.byref(B.ConvDesc(8, 14, 14, 64, 16, 1, 1))) == 0
+
+
+def test_chain_plan_splits_the_batch_over_eight_queues():
+    import struct
+    for n_img, want in ((16, [2] * 8), (13, [2, 2, 2, 2, 2, 1, 1, 1]), (3, [1, 1, 1, 0, 0, 0, 0, 0])):
+        arr = _chain_layers(n_img)
+        n = B.lib.q8_conv_chain_plan_bytes(arr, 3)
+        buf = C.create_string_buffer(n)
+        assert B.lib.q8_conv_chain_plan(arr, 3, buf, n) == 0
+        hd = struct.unpack_from("<I7i8i", bytes(buf), 0)
+        assert hd[1] == 3
+        n_items = hd[8:16]
+        # queue entries of an XCD are proportional to its images (28x28 = 784 pixels each)
+        per_image = [i // w if w else 0 for i, w in zip(n_items, want)]
+        assert [bool(i) for i in n_items] == [bool(w) for w in want]
+        assert len({p for p, w in zip(per_image, want) if w == want[0]}) == 1
