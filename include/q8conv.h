@@ -15,7 +15,8 @@
  *   - Every pointer named *_dev, z_*, residual, acc_dump, packed is DEVICE memory
  *     owned by the caller.  The library never allocates, frees or keeps pointers,
  *     and holds no state between calls, so calls on different streams are
- *     independent.
+ *     independent.  (One exception, stated where it is declared: the fixed workspace
+ *     of q8_conv_chain_int8_static.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work on that stream and return at once.
  *   - Descriptors (q8_conv_desc) are HOST memory and are read before return.
@@ -72,6 +73,11 @@ int q8_calibrate_maxabs(const float *x_dev, size_t n, float *maxabs_dev, void *s
 
 /* Host helper: q = maxabs / (2^p - 1) in fp32; an all-zero tensor gets q = 1.      */
 float q8_qfactor(float maxabs, int p);
+
+/* Host helper, Eq. +: the factor of the sum of two quantised tensors, max(q1, q2).
+ * For a sum fused into a convolution q1 is the factor of the branch's own output
+ * before the sum and q2 that of the residual; the result is the layer's q_out.    */
+float q8_sum_factor(float q1, float q2);
 
 /* Eq. Q for 1 <= p <= 7: n fp32 values -> n int8 codes.  True fp32 division.       */
 int q8_quantize(const float *r_dev, size_t n, float q, int p, int8_t *z_dev,
@@ -295,11 +301,16 @@ int q8_conv_chain_static_status(int32_t *status_host);
  * For measurement code that groups launches by kernel.                              */
 const char *q8_conv_variant(const q8_conv_desc *d);
 
-/* Tests and tuning only: force tile/ring variant `index` (0 .. n-1, in the order of the
- * library's variant table) for every later q8_conv_int8 call whose geometry the main
- * kernel can take (C % 16 == 0, R*S <= 32); -1 restores automatic selection.
- * Process-wide, not thread-safe; results are identical for every variant.             */
-int q8_conv_force_variant(int index);
+/* Tests and tuning only: q8_conv_int8 with the tile / ring variant of the main kernel given
+ * by the caller (0 .. q8_conv_num_variants() - 1, in the order of the library's variant
+ * table; -1 = automatic choice, i.e. q8_conv_int8 itself).  The variant is used wherever the
+ * main kernel can take the geometry (C % 16 == 0, R*S <= 32) and ignored otherwise.  The
+ * results are identical for every variant.                                              */
+int q8_conv_num_variants(void);
+int q8_conv_int8_variant(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
+                         const int32_t *bias_i32, float q_x, float q_w, float q_out,
+                         const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
+                         int variant, void *stream);
 
 /* ---- helpers that only chain layers; not part of the paper's method ------------ */
 
@@ -320,17 +331,18 @@ int q8_maxpool_f32(const float *x_dev, int N, int H, int W, int C, int R, int S,
  * stride out_c_stride, with a change of quantisation factor.  mode 0: v = max over the taps
  * inside the image, t = fp32(v).  mode 1: v = sum over the taps inside the image,
  * t = fp32(v) * (1 / fp32(R*S)) (padding counts as zeros).  Then t = t * m with
- * m = q_in / q_out (formed by the caller in fp32), z = int8(Round(clamp(t, -128, 127))).
- * With m = 1 max-pooling is exact.  x is dense [N][H][W][C].                           */
+ * m = q_in / q_out (one fp32 division, formed here as q8_conv_int8 forms its scales: the
+ * tail of Eq. A' between the input's factor and the output's), z = int8(Round(clamp(t,
+ * -128, 127))).  With q_in == q_out max-pooling is exact.  x is dense [N][H][W][C].     */
 int q8_pool_i8(const int8_t *x_dev, int N, int H, int W, int C, int mode, int R, int S,
-               int stride, int pad, int Ho, int Wo, float m, int8_t *y_dev,
+               int stride, int pad, int Ho, int Wo, float q_in, float q_out, int8_t *y_dev,
                int out_c_stride, int out_c_off, void *stream);
 /* fp32 twin for the calibration forward: max, or mean with padding counted as zeros.   */
 int q8_pool_f32(const float *x_dev, int N, int H, int W, int C, int mode, int R, int S,
                 int stride, int pad, int Ho, int Wo, float *y_dev, int out_c_stride,
                 int out_c_off, void *stream);
 
-/* Measurement only: `blocks` workgroups of four wavefronts each issue 4 * iters
+/* Measurement only, not part of the method (no parity claim rests on it): `blocks` workgroups of four wavefronts each issue 4 * iters
  * register-resident v_mfma_i32_32x32x32_i8 (65536 int8 ops each), no memory traffic:
  * ops = blocks * 4 * 4 * iters * 65536.  The caller times the launch; the result is the
  * int8 matrix-core rate the chip sustains, to set beside the published peak.  sink_dev:

@@ -30,7 +30,8 @@ EXPORTS = [
     "q8_conv_chain_workspace_bytes", "q8_conv_chain_int8",
     "q8_conv_chain_static_workspace_limit", "q8_conv_chain_int8_static",
     "q8_conv_chain_static_status",
-    "q8_conv_variant", "q8_conv_force_variant", "q8_probe_mfma_i8",
+    "q8_conv_variant", "q8_conv_num_variants", "q8_conv_int8_variant", "q8_sum_factor",
+    "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
 
@@ -116,14 +117,17 @@ lib.q8_quantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
 lib.q8_conv_variant.argtypes = [_dp]
-lib.q8_conv_force_variant.argtypes = [_i]
+lib.q8_conv_num_variants.argtypes = []
+lib.q8_conv_int8_variant.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _i, _vp]
+lib.q8_sum_factor.restype = _f
+lib.q8_sum_factor.argtypes = [_f, _f]
 lib.q8_probe_mfma_i8.argtypes = [_i, _i, _vp, _vp]
 lib.q8_conv_f32_ref.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.q8_maxpool_i8.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
 lib.q8_maxpool_f32.argtypes = [_vp] + [_i] * 10 + [_vp, _vp]
 
 
-lib.q8_pool_i8.argtypes = [_vp] + [_i] * 11 + [_f, _vp, _i, _i, _vp]
+lib.q8_pool_i8.argtypes = [_vp] + [_i] * 11 + [_f, _f, _vp, _i, _i, _vp]
 lib.q8_pool_f32.argtypes = [_vp] + [_i] * 11 + [_vp, _i, _i, _vp]
 
 
@@ -222,14 +226,18 @@ def pack_weights(desc, z_w):
 
 
 def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q_res=0.0,
-              out=None, acc_dump=None):
+              out=None, acc_dump=None, variant=-1):
+    """``variant`` >= 0 (tests, tuning): that tile variant of the main kernel."""
     if out is None:
         ocs = desc.out_c_stride or desc.K
         out = torch.empty((desc.N, desc.Ho, desc.Wo, ocs), dtype=torch.int8, device=z_x.device)
-    _check(lib.q8_conv_int8(C.byref(desc), _ptr(z_x, torch.int8), _ptr(z_w_packed, torch.int8),
-                            _ptr(bias_i32, torch.int32), q_x, q_w, q_out,
-                            _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
-                            _ptr(acc_dump, torch.int32), _stream()))
+    args = (C.byref(desc), _ptr(z_x, torch.int8), _ptr(z_w_packed, torch.int8),
+            _ptr(bias_i32, torch.int32), q_x, q_w, q_out, _ptr(residual, torch.int8), q_res,
+            _ptr(out, torch.int8), _ptr(acc_dump, torch.int32))
+    if variant >= 0:
+        _check(lib.q8_conv_int8_variant(*args, int(variant), _stream()))
+    else:
+        _check(lib.q8_conv_int8(*args, _stream()))
     return out
 
 
@@ -400,8 +408,13 @@ def conv_variant(desc):
     return lib.q8_conv_variant(C.byref(desc)).decode()
 
 
-def conv_force_variant(index):
-    _check(lib.q8_conv_force_variant(int(index)))
+def conv_num_variants():
+    return lib.q8_conv_num_variants()
+
+
+def sum_factor(q1, q2):
+    """Eq. +: the factor of a sum of two quantised tensors."""
+    return lib.q8_sum_factor(float(q1), float(q2))
 
 
 def probe_mfma_i8(blocks, iters, sink):
@@ -435,13 +448,14 @@ def maxpool_f32(x, R, S, stride, pad, Ho, Wo):
     return _pool(lib.q8_maxpool_f32, torch.float32, x, R, S, stride, pad, Ho, Wo)
 
 
-def pool_i8(x, mode, R, S, stride, pad, Ho, Wo, m=1.0, out=None, out_c_off=0):
-    """mode 'max' or 'avg'; writes channels [out_c_off, out_c_off + C) of ``out``."""
+def pool_i8(x, mode, R, S, stride, pad, Ho, Wo, q_in=1.0, q_out=1.0, out=None, out_c_off=0):
+    """mode 'max' or 'avg'; writes channels [out_c_off, out_c_off + C) of ``out``, rescaled from
+    factor ``q_in`` to ``q_out``."""
     N, H, W, Cc = x.shape
     if out is None:
         out = torch.zeros((N, Ho, Wo, Cc), dtype=torch.int8, device=x.device)
     _check(lib.q8_pool_i8(_ptr(x, torch.int8), N, H, W, Cc, 0 if mode == "max" else 1, R, S, stride,
-                          pad, Ho, Wo, m, _ptr(out, torch.int8), out.shape[3], out_c_off,
+                          pad, Ho, Wo, q_in, q_out, _ptr(out, torch.int8), out.shape[3], out_c_off,
                           _stream()))
     return out
 

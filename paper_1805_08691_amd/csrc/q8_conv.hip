@@ -72,7 +72,6 @@ int conv_mode(const q8_conv_desc* d) {
 // Kernel choice.  Stream variants (q8_conv_ring.hip) are numbered 0..; the register-staged
 // kernel's variants (q8_conv_reg.hip) are offset by kRegBase.
 constexpr int kRegBase = 100;
-int g_variant_override = -1;   // tests / tuning: force a stream variant where it is applicable
 
 // A 4-channel image without padding: the S4 16-byte chunks (4 pixels each) of a filter row
 // are contiguous bytes, i.e. the layer is an R x 1 convolution over 16*S4 "channels" whose
@@ -95,11 +94,12 @@ bool stream_capable(const q8_conv_desc* d) {
 // Its extended build (unsigned codes, per-channel scales) is kept to K > 32.
 bool ext_capable(const q8_conv_desc* d) { return stream_capable(d) && d->K > 32; }
 
-int pick_variant(const q8_conv_desc* d) {
+// `forced`: -1, or a variant of the main kernel to use where that kernel is applicable.
+int pick_variant(const q8_conv_desc* d, int forced = -1) {
   const int mode = conv_mode(d);
   const int tile = d->K > 64 ? 0 : d->K > 32 ? 1 : 2;      // 128x128, 256x64, 256x32
   if (!stream_capable(d)) return kRegBase + 3 * mode + tile;
-  if (g_variant_override >= 0) return g_variant_override;
+  if (forced >= 0) return forced;
   if (mode == 1) return d->K <= 64 ? 8 : 4;   // short reduction: small tiles, many per CU
   const int red = d->R * d->S * d->C;
   const int nk = (red + 63) / 64;     // reduction steps of 64 bytes
@@ -192,6 +192,7 @@ struct U8Flags {
   const float* m_vec = nullptr;     // per-output-channel scales (replace q_x * q_w / q_out)
   float* y_f32 = nullptr;           // real-valued output instead of int8 codes
   const PairArgs* pair = nullptr;   // a second, 1x1 layer on the output while it is on chip
+  int variant = -1;                 // tile variant of the main kernel to use (tests, tuning)
 };
 
 // Checks the arguments of one layer and fills the kernels' parameter block.  *empty: the
@@ -368,7 +369,7 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
     p.vec16_2 = aligned2(16) ? 1 : 0;
     return q8::launch_pair_variant(p, s);
   }
-  const int variant = pick_variant(d);
+  const int variant = pick_variant(d, u.variant);
   if (variant >= kRegBase) return q8::launch_reg_variant(variant - kRegBase, p, s);
   return q8::launch_stream_variant(variant, p, s);
 }
@@ -504,10 +505,17 @@ int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32
   return q8_launch_status();
 }
 
-int q8_conv_force_variant(int index) {
-  if (index < -1 || index >= q8::num_stream_variants()) return Q8_EINVAL;
-  g_variant_override = index;
-  return Q8_OK;
+int q8_conv_num_variants(void) { return q8::num_stream_variants(); }
+
+int q8_conv_int8_variant(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                         const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                         const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
+                         int variant, void* stream) {
+  Q8_REQUIRE(variant >= -1 && variant < q8::num_stream_variants(), Q8_EINVAL);
+  U8Flags u{0, 0, 0, nullptr};
+  u.variant = variant;
+  return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual, q_res, z_y,
+                     acc_dump, stream);
 }
 
 const char* q8_conv_variant(const q8_conv_desc* d) {

@@ -342,6 +342,8 @@ float q8_qfactor(float maxabs, int p) {
   return q;
 }
 
+float q8_sum_factor(float q1, float q2) { return q1 > q2 ? q1 : q2; }
+
 int q8_calibrate_maxabs(const float* x_dev, size_t n, float* maxabs_dev, void* stream) {
   Q8_REQUIRE(maxabs_dev != nullptr, Q8_EINVAL);
   if (n == 0) return Q8_OK;

@@ -462,8 +462,10 @@ int q8_maxpool_i8(const int8_t* x_dev, int N, int H, int W, int C, int R, int S,
   return maxpool_launch<int8_t>(x_dev, N, H, W, C, R, S, stride, pad, Ho, Wo, y_dev, stream);
 }
 int q8_pool_i8(const int8_t* x_dev, int N, int H, int W, int C, int mode, int R, int S, int stride,
-               int pad, int Ho, int Wo, float m, int8_t* y_dev, int out_c_stride, int out_c_off,
-               void* stream) {
+               int pad, int Ho, int Wo, float q_in, float q_out, int8_t* y_dev, int out_c_stride,
+               int out_c_off, void* stream) {
+  Q8_REQUIRE(q8_finite_pos(q_in) && q8_finite_pos(q_out), Q8_EINVAL);
+  const float m = q_in / q_out;        // the rescale of Eq. A' between two factors, one fp32 division
   Q8_REQUIRE(N >= 0 && H >= 1 && W >= 1 && C >= 1 && R >= 1 && S >= 1 && stride >= 1 && pad >= 0 &&
                  Ho >= 0 && Wo >= 0 && (mode == 0 || mode == 1), Q8_EINVAL);
   Q8_REQUIRE(pad < R && pad < S && q8_finite_pos(m), Q8_EINVAL);

@@ -229,7 +229,7 @@ class Engine:
         for op in self.net.ops:
             if (op.kind == "conv" and op.res is not None and not self.unsigned
                     and not self.own_sum_factor):
-                q[op.dst] = max(q[op.name + ":branch"], q[op.res])   # the + rule
+                q[op.dst] = B.sum_factor(q[op.name + ":branch"], q[op.res])   # Eq. +
             if op.kind == "pool" and self.net.tensors[op.dst].C == self.net.tensors[op.src].C:
                 q[op.dst] = q[op.src]       # a stand-alone pool keeps its input's factor
         self.q = q
@@ -317,8 +317,8 @@ class Engine:
                                          op.stride, op.pad, d.H, d.W, dst.data_ptr(),
                                          B._stream()))
         else:
-            B.pool_i8(src, op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W,
-                      self.scale32(q_in, q_out), out=dst, out_c_off=op.dst_c_off)
+            B.pool_i8(src, op.mode, op.R, op.S, op.stride, op.pad, d.H, d.W, q_in, q_out,
+                      out=dst, out_c_off=op.dst_c_off)
 
     def conv_desc(self, op, n):
         """Descriptor of ``op`` over ``n`` images (the whole batch or one part of it)."""
@@ -329,15 +329,15 @@ class Engine:
             self.part_desc[key] = self._desc(op, n)
         return self.part_desc[key]
 
-    def run_conv(self, op, lo=0, n=None, acc_dump=None):
+    def run_conv(self, op, lo=0, n=None, acc_dump=None, fuse=True):
         n = self.N if n is None else n
         packed, bias = self.wq[op.name]
         res = self.act[op.res][lo:lo + n] if op.res else None
         q_res = self.q[op.res] if op.res else 0.0
         U = self.unsigned
-        if op.name in self.paired and acc_dump is None:
+        if op.name in self.paired and fuse:
             return                       # ran with the layer in front of it
-        if op.name in self.pairs and acc_dump is None:
+        if op.name in self.pairs and fuse:
             b = self.pairs[op.name]
             packed2, bias2 = self.wq[b.name]
             res2 = self.act[b.res][lo:lo + n] if b.res else None
@@ -429,11 +429,6 @@ class Engine:
                 self.run_ops([ops[i]], 0, self.N)
                 i += 1
 
-    @staticmethod
-    def scale32(q_in, q_out):
-        """q_in / q_out rounded once to fp32 (both factors are fp32 values)."""
-        return float(np.float32(q_in) / np.float32(q_out))
-
     def run_step(self, x=None, dequant=None, serial=False):
         """One pass over the batch: Eq. Q on ``x`` (if given), every layer, Eq. D on the
         tensors named in ``dequant`` ({name: fp32 output buffer}).  With two streams the
@@ -464,11 +459,13 @@ class Engine:
         """Every layer on the codes already in the input buffer.  ``acc_dump``
         ({conv name: int32 buffer}): whole-batch launches that also store the accumulators."""
         if acc_dump:
+            # every layer on its own in this pass (no fused pairs): a dumped layer needs its
+            # input tensor written, whether or not the layer in front of it is dumped too
             for op in self.net.ops:
                 if op.kind == "pool":
                     self.run_pool(op)
                 else:
-                    self.run_conv(op, acc_dump=acc_dump.get(op.name))
+                    self.run_conv(op, acc_dump=acc_dump.get(op.name), fuse=False)
             return
         self.run_step(serial=serial)
 

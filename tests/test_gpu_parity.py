@@ -167,7 +167,7 @@ CONV_CASES = [
 ]
 
 
-def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=0):
+def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=0, variant=-1):
     g = orc.ConvGeom(**geom)
     rng = np.random.default_rng(seed)
     Cs = 4 if g.C < 4 else g.C                      # stored channels of the input
@@ -198,7 +198,7 @@ def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=
     dump = torch.zeros((g.N, Ho, Wo, g.K), dtype=torch.int32, device="cuda")
     B.conv_int8(d, dev(x), packed, None if b is None else dev(b), float(q_x), float(q_w),
                 float(q_out), None if res is None else dev(res), float(q_res), out=out,
-                acc_dump=dump)
+                acc_dump=dump, variant=variant)
     assert np.array_equal(host(dump), acc_o), "int32 accumulators differ"
     got = host(out)
     assert np.array_equal(got, want), "int8 outputs differ"
@@ -226,18 +226,12 @@ VARIANT_CASES = [
 def test_conv_every_kernel_variant(B):
     """Every tile / ring variant of the main kernel gives the same bits (integer sums are
     order-independent; the epilogue is one fixed fp32 sequence)."""
-    n = 0
-    while B.lib.q8_conv_force_variant(n) == 0:
-        n += 1
+    n = B.conv_num_variants()
     assert n >= 10
-    try:
-        for v in range(n):
-            B.conv_force_variant(v)
-            for k, geom in enumerate(VARIANT_CASES):
-                _run_conv_case(B, geom, relu=bool(k % 2), with_res=bool((k + v) % 2),
-                               with_bias=True, seed=100 * v + k)
-    finally:
-        B.conv_force_variant(-1)
+    for v in range(n):
+        for k, geom in enumerate(VARIANT_CASES):
+            _run_conv_case(B, geom, relu=bool(k % 2), with_res=bool((k + v) % 2),
+                           with_bias=True, seed=100 * v + k, variant=v)
 
 
 @pytest.mark.parametrize("geom", [
@@ -700,8 +694,13 @@ def test_pool_i8(B, mode, shape, win, m, slice_):
     Cd, off = slice_
     Cd = Cd or shape[3]
     base = rng.integers(-128, 128, size=(shape[0], Ho, Wo, Cd), dtype=np.int8)
-    want = orc.pool_i8(x, mode, R, R, stride, pad, Ho, Wo, m, out=base.copy(), out_c_off=off)
-    got = B.pool_i8(dev(x), mode, R, R, stride, pad, Ho, Wo, float(np.float32(m)),
+    # the library forms the rescale itself from the two factors, one fp32 division
+    q_out = np.float32(0.0071)
+    q_in = np.float32(m) * q_out
+    m_used = orc.residual_scale(q_in, q_out)
+    assert abs(float(m_used) - m) <= 1e-6 * m
+    want = orc.pool_i8(x, mode, R, R, stride, pad, Ho, Wo, m_used, out=base.copy(), out_c_off=off)
+    got = B.pool_i8(dev(x), mode, R, R, stride, pad, Ho, Wo, float(q_in), float(q_out),
                     out=dev(base), out_c_off=off)
     assert np.array_equal(host(got), want)
 
@@ -831,7 +830,11 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
     qparams = onet.quantize_params(net, folded, q, per_channel=per_channel)
     x = wl.input_batch(cfg_id, net, batch, 0)
     z_in = orc.Q(x[picks], q[net.input], 7)
-    acts = onet.forward_i8(net, qparams, q, z_in, unsigned=U)
+    plain = not (unsigned or per_channel or real_outputs or own_sum_factor)
+    if plain:
+        acts, accs = onet.forward_i8(net, qparams, q, z_in, keep_acc=True)
+    else:
+        acts = onet.forward_i8(net, qparams, q, z_in, unsigned=U)
 
     def codes(name, a):       # the GPU's bytes as the oracle's codes
         return (a.astype(np.int16) + 128).astype(np.uint8) if name in U else a
@@ -902,6 +905,26 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
             continue
         want = orc.D_u8(acts[o], q[o]) if o in U else orc.D(acts[o], q[o])
         assert np.all(np.abs(r - want) <= 1e-5 * np.abs(want)), o
+    if plain and not chain:
+        # the int32 accumulators of every layer on the sampled images (run as a small batch of
+        # their own from the same int8 input codes), against the oracle's
+        small = Engine(net, len(picks), fuse_pairs=fuse_pairs)
+        small.load_params(params)
+        small.fold()
+        small.set_factors(q)
+        small.quantize_weights()
+        small.allocate()
+        small.input_codes().copy_(eng.input_codes()[picks])
+        dumps = {op.name: torch.zeros((len(picks), net.tensors[op.dst].H, net.tensors[op.dst].W,
+                                       op.K), dtype=torch.int32, device="cuda")
+                 for op in net.convs()}
+        some = {k: v for i, (k, v) in enumerate(dumps.items()) if i % 2 == 0} if fuse_pairs else dumps
+        small.run_layers(acc_dump=some)
+        for name in some:
+            assert np.array_equal(host(dumps[name]), accs[name]), name
+        for op in net.ops:
+            assert np.array_equal(host(small.act[op.dst]), acts[op.dst]), op.name
+        del small, dumps
     # replays of the captured HIP graph, with eager work between them: same bits each time
     eng.capture(xd)
     for rep in range(3):
@@ -947,7 +970,7 @@ def test_config4_inception_v3_batch64_sampled_images(B):
     _sampled_images_check(B, 4, 64, [0, 21, 63], n_cal=4, cal_batch=8)
 
 
-@pytest.mark.parametrize("batch,picks", [(1, [0]), (64, [0, 63])])
+@pytest.mark.parametrize("batch,picks", [(1, [0]), (64, [0, 32, 63])])
 def test_config5_ssd300_vgg16_sampled_images(B, batch, picks):
     # 3x3 stack at 300x300, ceil-mode pooling, dilation 6, head convolutions with
     # K in {16, 24, 84, 126}, twelve int8 outputs

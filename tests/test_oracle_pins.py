@@ -603,6 +603,26 @@ def test_requant_mixed_against_exact_rational():
                              out_unsigned=True).ravel().tolist() == [2, 255, 0, 255]
 
 
+def test_dequantize_u8_hand_worked():
+    """Eq. D on unsigned codes: the hand-worked values of tests/golden/eq_D_u8.txt (exact where
+    the product is a binary fraction, else within one fp32 rounding of q * z), the identity
+    Q(D(z)) = z on all 256 codes, and agreement with the signed form on the shared range."""
+    for name, c in golden_io.load("eq_D_u8.txt").items():
+        got = orc.D_u8(np.array(c["z"], np.uint8), c["q"])
+        want = np.array(c["r"], np.float64)
+        assert got.dtype == np.float32
+        assert np.all(np.abs(got.astype(np.float64) - want) <= 2.0 ** -23 * np.abs(want)), name
+        if name == "halves":
+            assert got.tolist() == c["r"]
+    z = np.arange(256, dtype=np.uint8)
+    for q in (0.5, 0.02, 0.0371):
+        r = orc.D_u8(z, q)
+        assert np.all(np.diff(r) > 0) and r[0] == 0.0
+        back = np.clip(np.rint(r.astype(np.float64) / np.float32(q)), 0, 255)
+        assert np.array_equal(back.astype(np.uint8), z)
+        assert np.array_equal(r[:128], orc.D(z[:128].astype(np.int8), q))
+
+
 def test_unsigned_network_reading_on_a_small_resnet():
     """Unsigned codes halve the quantisation step of the ReLU outputs: the int8 network's
     dequantised output is closer to the fp32 network's with them than without."""
