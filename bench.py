@@ -83,6 +83,8 @@ def main():
                          "reported as its own workload")
     ap.add_argument("--fuse-pairs", action="store_true",
                     help="a convolution and the 1x1 layer that alone reads it run as one launch")
+    ap.add_argument("--fuse-duals", action="store_true",
+                    help="two independent convolutions on the same input run as one launch")
     ap.add_argument("--own-sum-factor", action="store_true",
                     help="a fused sum's output factor from its own max-abs instead of the "
                          "max(q1, q2) rule; reported as its own workload")
@@ -122,7 +124,8 @@ def main():
     params = {op.name: wl.conv_params(args.config, i, op) for i, op in enumerate(convs)}
     eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations,
                  per_channel_weights=args.per_channel_weights, real_outputs=args.real_output,
-                 own_sum_factor=args.own_sum_factor, fuse_pairs=args.fuse_pairs)
+                 own_sum_factor=args.own_sum_factor, fuse_pairs=args.fuse_pairs,
+                 fuse_duals=args.fuse_duals)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -332,11 +335,15 @@ def main():
             helpers.append(dict(name=op.name, mode=op.mode, H=s_t.H, C=s_t.C, R=op.R, stride=op.stride,
                                 us=round(us, 2), gbs=round(byts / us / 1e3, 1), launches=n_launch))
             continue
-        if op.name in eng.paired:
+        if op.name in eng.paired or op.name in eng.dualed:
             continue                      # counted with the layer in front of it
         n_launch = len(eng.parts) if i >= eng.n_unsplit else 1
         n_img = eng.parts[0][1] if i >= eng.n_unsplit else N
         ops, byts = conv_work(net, op, N)
+        if op.name in eng.duals:          # one launch for two layers on the same input
+            ops2, byts2 = conv_work(net, eng.duals[op.name], N)
+            s_t = net.tensors[op.src]
+            ops, byts = ops + ops2, byts + byts2
         if op.name in eng.pairs:          # one launch for two layers: the tensor between
             ops2, byts2 = conv_work(net, eng.pairs[op.name], N)     # them is not moved
             mid = net.tensors[op.dst]

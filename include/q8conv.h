@@ -232,6 +232,22 @@ int q8_conv_pair_int8(const q8_conv_desc *d1, const int8_t *z_x, const void *w1_
                       float q_w2, float q_out, const int8_t *residual, float q_res,
                       int8_t *z_y, void *stream);
 
+/* Two layers that do not depend on each other (typically the projection branch and the first
+ * 1x1 of a residual stage, which read the same tensor) in ONE launch: each is Eq. A' exactly
+ * as q8_conv_int8 computes it, arguments as there, results bit-identical to two calls.  Saves
+ * one launch boundary on the critical path.  Supported (q8_conv_dual_supported returns 1):
+ * both layers have C % 64 == 0, K > 32 and at most 32 taps, and their sizes map to one of
+ * the tile-shape pairs the library was built with; otherwise Q8_EUNSUPPORTED (call the two
+ * layers one after the other).  The outputs must be distinct tensors that neither layer
+ * reads.                                                                                  */
+int q8_conv_dual_supported(const q8_conv_desc *d1, const q8_conv_desc *d2);
+int q8_conv_dual_int8(const q8_conv_desc *d1, const int8_t *z_x1, const void *w1_packed,
+                      const int32_t *bias1, float q_x1, float q_w1, float q_out1,
+                      const int8_t *residual1, float q_res1, int8_t *z_y1,
+                      const q8_conv_desc *d2, const int8_t *z_x2, const void *w2_packed,
+                      const int32_t *bias2, float q_x2, float q_w2, float q_out2,
+                      const int8_t *residual2, float q_res2, int8_t *z_y2, void *stream);
+
 /* ---- a list of layers in one launch (cross-layer fusion, "Model Optimization" section) --
  * q8_conv_chain_int8 runs a list of convolution layers, each one Eq. A' exactly as
  * q8_conv_int8 computes it (bias, scale, fused residual sum of Eq. +, ReLU, Round, clamp, one
@@ -307,6 +323,7 @@ const char *q8_conv_variant(const q8_conv_desc *d);
  * main kernel can take the geometry (C % 16 == 0, R*S <= 32) and ignored otherwise.  The
  * results are identical for every variant.                                              */
 int q8_conv_num_variants(void);
+const char *q8_conv_variant_name(int variant);   /* as in a profiler's kernel trace */
 int q8_conv_int8_variant(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
                          const int32_t *bias_i32, float q_x, float q_w, float q_out,
                          const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,

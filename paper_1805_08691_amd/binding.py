@@ -26,11 +26,11 @@ EXPORTS = [
     "q8_u8_prepare", "q8_conv_u8", "q8_quantize_weights_per_channel",
     "q8_quantize_bias_per_channel", "q8_requant_scales", "q8_conv_int8_per_channel", "q8_conv_int8_real_output", "q8_conv_pair_supported", "q8_conv_pair_int8", "q8_dequantize",
     "q8_fold_bn", "q8_packed_weight_bytes", "q8_pack_weights", "q8_conv_int8",
-    "q8_conv_chain_supported", "q8_conv_chain_plan_bytes", "q8_conv_chain_plan",
+    "q8_conv_dual_supported", "q8_conv_dual_int8", "q8_conv_chain_supported", "q8_conv_chain_plan_bytes", "q8_conv_chain_plan",
     "q8_conv_chain_workspace_bytes", "q8_conv_chain_int8",
     "q8_conv_chain_static_workspace_limit", "q8_conv_chain_int8_static",
     "q8_conv_chain_static_status",
-    "q8_conv_variant", "q8_conv_num_variants", "q8_conv_int8_variant", "q8_sum_factor",
+    "q8_conv_variant", "q8_conv_num_variants", "q8_conv_variant_name", "q8_conv_int8_variant", "q8_sum_factor",
     "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
@@ -77,6 +77,8 @@ class ChainLayer(C.Structure):
 _vp, _sz, _f, _i = C.c_void_p, C.c_size_t, C.c_float, C.c_int
 _dp = C.POINTER(ConvDesc)
 lib.q8_conv_chain_supported.argtypes = [_dp]
+lib.q8_conv_dual_supported.argtypes = [_dp, _dp]
+lib.q8_conv_dual_int8.argtypes = ([_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp] * 2) + [_vp]
 lib.q8_conv_chain_plan_bytes.restype = C.c_size_t
 lib.q8_conv_chain_plan_bytes.argtypes = [C.POINTER(ChainLayer), _i]
 lib.q8_conv_chain_plan.argtypes = [C.POINTER(ChainLayer), _i, _vp, _sz]
@@ -118,6 +120,8 @@ lib.q8_dequantize_u8.argtypes = [_vp, _sz, _f, _vp, _vp]
 lib.q8_conv_variant.restype = C.c_char_p
 lib.q8_conv_variant.argtypes = [_dp]
 lib.q8_conv_num_variants.argtypes = []
+lib.q8_conv_variant_name.restype = C.c_char_p
+lib.q8_conv_variant_name.argtypes = [_i]
 lib.q8_conv_int8_variant.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _i, _vp]
 lib.q8_sum_factor.restype = _f
 lib.q8_sum_factor.argtypes = [_f, _f]
@@ -346,6 +350,20 @@ def conv_pair_int8(d1, z_x, w1_packed, bias1, q_x, q_w1, q_mid, d2, w2_packed, b
                                  _ptr(residual, torch.int8), q_res, _ptr(out, torch.int8),
                                  _stream()))
     return out
+
+
+def conv_dual_supported(d1, d2):
+    return bool(lib.q8_conv_dual_supported(C.byref(d1), C.byref(d2)))
+
+
+def conv_dual_int8(a, b):
+    """Two independent layers in one launch; ``a`` and ``b`` are tuples (desc, z_x, w_packed,
+    bias, q_x, q_w, q_out, residual, q_res, out)."""
+    args = []
+    for (d, x, w, bias, q_x, q_w, q_out, res, q_res, out) in (a, b):
+        args += [C.byref(d), _ptr(x, torch.int8), _ptr(w, torch.int8), _ptr(bias, torch.int32), q_x,
+                 q_w, q_out, _ptr(res, torch.int8), q_res, _ptr(out, torch.int8)]
+    _check(lib.q8_conv_dual_int8(*args, _stream()))
 
 
 def conv_chain_supported(desc):

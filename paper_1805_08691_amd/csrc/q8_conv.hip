@@ -19,7 +19,14 @@
 
 namespace q8 {
 int num_stream_variants();
+int num_ring_variants();
+int first_pw_variant();
+int launch_dual_variant(ConvParams& p1, ConvParams& p2, hipStream_t stream);   // q8_conv_dual.hip
+bool dual_shapes_supported(const ConvParams& p1, const ConvParams& p2);
 }
+#ifdef Q8_TRACE
+namespace { unsigned long long* g_trace = nullptr; unsigned long long g_trace_cap = 0; }
+#endif
 
 namespace {
 
@@ -94,6 +101,30 @@ bool stream_capable(const q8_conv_desc* d) {
 // Its extended build (unsigned codes, per-channel scales) is kept to K > 32.
 bool ext_capable(const q8_conv_desc* d) { return stream_capable(d) && d->K > 32; }
 
+// The 3x3 tile family (q8_conv_halo_kernel.h) for a padded 3x3 stride-1 layer over two or more
+// 64-channel chunks (with one chunk the patch is not reused across chunks and the generic
+// kernel is as fast): the largest tile that still gives every CU a tile and a half, else the
+// smallest one the map's width allows.  -1: the generic kernel.  Fitted to a sweep over the
+// 3x3 layers of the three benchmark networks.
+int pick_halo3(const q8_conv_desc* d) {
+  if (d->R != 3 || d->S != 3 || d->stride_h != 1 || d->stride_w != 1 || d->dil_h != 1 ||
+      d->dil_w != 1 || d->pad_h != 1 || d->pad_w != 1 || d->C % 64 != 0 || d->C < 128 || d->K <= 32)
+    return -1;
+  struct Shape { int index, bp, bc, max_w; };
+  // by falling tile size; the order of q8_conv_halo.hip's table is the index
+  static const Shape shapes[] = {{2, 256, 128, 127}, {3, 256, 128, 383}, {1, 128, 128, 63},
+                                 {0, 128, 64, 63},   {4, 128, 64, 191},  {6, 64, 64, 31}};
+  const long M = (long)d->N * d->H * d->W;
+  int smallest = -1;
+  for (const Shape& s : shapes) {
+    if (d->W > s.max_w || (s.bc == 128 && d->K <= 64)) continue;
+    const long tiles = ((M + s.bp - 1) / s.bp) * ((d->K + s.bc - 1) / s.bc);
+    if (tiles >= 360) return s.index;
+    smallest = s.index;
+  }
+  return smallest;
+}
+
 // `forced`: -1, or a variant of the main kernel to use where that kernel is applicable.
 int pick_variant(const q8_conv_desc* d, int forced = -1) {
   const int mode = conv_mode(d);
@@ -101,7 +132,15 @@ int pick_variant(const q8_conv_desc* d, int forced = -1) {
   if (!stream_capable(d)) return kRegBase + 3 * mode + tile;
   if (forced >= 0) return forced;
   if (mode == 1) return d->K <= 64 ? 8 : 4;   // short reduction: small tiles, many per CU
+  const int halo = pick_halo3(d);
+  if (halo >= 0) return q8::num_ring_variants() + halo;
   const int red = d->R * d->S * d->C;
+  // pointwise layers on 64 channels with many pixel tiles: persistent workgroups (a layer the
+  // build cannot take -- odd strides, a dump of the accumulators -- goes to the generic kernel)
+  if (d->R * d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 && d->pad_w == 0 &&
+      d->C == 64 && (d->K & 15) == 0 && (long)d->N * d->H * d->W >= 128L * 512 &&
+      getenv("Q8_NO_PW") == nullptr)
+    return q8::first_pw_variant();
   const int nk = (red + 63) / 64;     // reduction steps of 64 bytes
   const long M = (long)d->N * out_extent(d->H, d->pad_h, d->dil_h, d->R, d->stride_h) *
                  out_extent(d->W, d->pad_w, d->dil_w, d->S, d->stride_w);
@@ -262,6 +301,7 @@ int conv_fill(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const 
     p.w_bytes = (int)wb;
   }
   p.x = z_x; p.w = (const int8_t*)z_w_packed; p.bias = bias_i32; p.res = residual; p.y = z_y;
+  p.res_bytes = (residual && M * (long)p.res_cs < 0x7fffffffL) ? (int)(M * (long)p.res_cs) : 0;
   p.acc_dump = acc_dump;
   p.M = (int)M;
   p.in_u8 = u.in_u8; p.out_u8 = u.out_u8; p.res_u8 = u.res_u8;
@@ -311,6 +351,10 @@ int conv_fill(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const 
   p.vec4 = aligned_to(4) ? 1 : 0;
   p.vec16 = aligned_to(16) ? 1 : 0;
   p.y_f32 = u.y_f32;
+#ifdef Q8_TRACE
+  p.trace = g_trace;
+  p.trace_cap = g_trace_cap;
+#endif
   p.f32_vec4 =
       (u.y_f32 && p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(u.y_f32, 16)) ? 1 : 0;
 
@@ -482,6 +526,46 @@ int q8_conv_pair_int8(const q8_conv_desc* d1, const int8_t* z_x, const void* w1_
                      stream);
 }
 
+// Both layers must take the uniform-tap build of the main kernel (C % 64 == 0, at most 32
+// taps, K > 32) and a supported pair of tile shapes; the library tries and reports.
+int q8_conv_dual_int8(const q8_conv_desc* d1, const int8_t* z_x1, const void* w1_packed,
+                      const int32_t* bias1, float q_x1, float q_w1, float q_out1,
+                      const int8_t* residual1, float q_res1, int8_t* z_y1,
+                      const q8_conv_desc* d2, const int8_t* z_x2, const void* w2_packed,
+                      const int32_t* bias2, float q_x2, float q_w2, float q_out2,
+                      const int8_t* residual2, float q_res2, int8_t* z_y2, void* stream) {
+  Q8_REQUIRE(q8_conv_dual_supported(d1, d2), Q8_EUNSUPPORTED);
+  ConvParams p1, p2;
+  bool e1 = false, e2 = false;
+  int rc = conv_fill(d1, U8Flags{0, 0, 0, nullptr}, z_x1, w1_packed, bias1, q_x1, q_w1, q_out1,
+                     residual1, q_res1, z_y1, nullptr, p1, &e1);
+  if (rc != Q8_OK) return rc;
+  rc = conv_fill(d2, U8Flags{0, 0, 0, nullptr}, z_x2, w2_packed, bias2, q_x2, q_w2, q_out2,
+                 residual2, q_res2, z_y2, nullptr, p2, &e2);
+  if (rc != Q8_OK) return rc;
+  if (e1 || e2) return Q8_EUNSUPPORTED;
+  // the outputs must not overlap each other nor an input of the other layer
+  Q8_REQUIRE(z_y1 != z_y2 && (const int8_t*)z_y1 != z_x2 && (const int8_t*)z_y2 != z_x1 &&
+                 (const int8_t*)z_y1 != residual2 && (const int8_t*)z_y2 != residual1, Q8_EINVAL);
+  return q8::launch_dual_variant(p1, p2, (hipStream_t)stream);
+}
+
+int q8_conv_dual_supported(const q8_conv_desc* d1, const q8_conv_desc* d2) {
+  for (const q8_conv_desc* d : {d1, d2}) {
+    if (!desc_sane(d) || conv_mode(d) != 0 || d->C % 64 != 0 || d->R * d->S > 32 || d->K <= 32) return 0;
+  }
+  // probe the shape table with the two layers' sizes (no launch)
+  ConvParams p1{}, p2{};
+  const q8_conv_desc* ds[2] = {d1, d2};
+  ConvParams* ps[2] = {&p1, &p2};
+  for (int i = 0; i < 2; ++i) {
+    ps[i]->M = (int)((long)ds[i]->N * q8_conv_out_h(ds[i]) * q8_conv_out_w(ds[i]));
+    ps[i]->K = ds[i]->K;
+    ps[i]->red_len = ds[i]->R * ds[i]->S * ds[i]->C;
+  }
+  return q8::dual_shapes_supported(p1, p2) ? 1 : 0;
+}
+
 int q8_conv_pair_supported(const q8_conv_desc* d1, const q8_conv_desc* d2) {
   if (!desc_sane(d1) || !desc_sane(d2) || conv_mode(d1) != 0 || !stream_capable(d1)) return 0;
   if (d1->C % 64 != 0 || (d1->K != 64 && d1->K != 128) || d2->K % d1->K != 0) return 0;
@@ -506,6 +590,7 @@ int q8_u8_prepare(const q8_conv_desc* d, const int8_t* z_w_krsc_dev, const int32
 }
 
 int q8_conv_num_variants(void) { return q8::num_stream_variants(); }
+const char* q8_conv_variant_name(int variant) { return q8::stream_variant_name(variant); }
 
 int q8_conv_int8_variant(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
                          const int32_t* bias_i32, float q_x, float q_w, float q_out,
@@ -526,3 +611,11 @@ const char* q8_conv_variant(const q8_conv_desc* d) {
 }
 
 }  // extern "C"
+
+#ifdef Q8_TRACE
+// Measurement build only (never part of the product library): where the workgroups log.
+extern "C" void q8_trace_set(unsigned long long* buf_dev, unsigned long long cap) {
+  g_trace = buf_dev;
+  g_trace_cap = cap;
+}
+#endif

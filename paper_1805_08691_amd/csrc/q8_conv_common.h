@@ -35,6 +35,7 @@ struct ConvParams {
   int S4;         // 4-channel mode: 16-byte chunks per filter row (ceil(S/4))
   int n_ptiles, n_ctiles;
   int x_bytes, w_bytes;   // sizes of the activation and filter tensors (buffer descriptors)
+  int res_bytes;          // size of the residual tensor, 0 if none or beyond 2 GiB
   unsigned div_img_m, div_img_s;   // division of a pixel index by Ho*Wo (see fast_div)
   unsigned div_row_m, div_row_s;   // division by Wo
   // unsigned p = 8 activation codes (0..255), stored as code - 128 (= code ^ 0x80) so that
@@ -60,6 +61,10 @@ struct ConvParams {
   int out_cs2, out_off2, res_cs2, res_off2;
   float m2, m_r2;
   int relu2, vec4_2, vec16_2;
+#ifdef Q8_TRACE
+  unsigned long long* trace;      // measurement build only: workgroup log
+  unsigned long long trace_cap;
+#endif
 };
 
 // x / d for 0 <= x < 2^31 with host-made constants s = ceil(log2 d), m = ceil(2^(31+s) / d):
@@ -358,6 +363,17 @@ __device__ __forceinline__ int swz(int row, int chunk) {
     // eight row pairs a quarter-wave touches
     return chunk ^ ((row >> 1) & (CHUNKS - 1));
   }
+}
+
+// Staging tile of the coalesced epilogue: rows of SLOTS 16-byte channel groups, one row per
+// pixel; the slot of group g in row r is g ^ swz_out(r), so that both the lanes of an MFMA
+// tile (32 consecutive rows, one group) and a linear sweep over the tile touch all banks.
+template <int SLOTS>
+__device__ __forceinline__ int swz_out(int row) {
+  static_assert(SLOTS == 2 || SLOTS == 4 || SLOTS == 8 || SLOTS == 16, "16-byte groups per row");
+  if constexpr (SLOTS == 4) return (row >> 2) & 3;        // 64-byte rows: four rows per bank sweep
+  else if constexpr (SLOTS == 2) return (row >> 3) & 1;
+  else return (row >> 1) & (SLOTS - 1) & 7;               // 128-byte rows and wider
 }
 
 // s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,

@@ -25,6 +25,7 @@
 // on by BK / C taps per step, so a lane adds a constant to a scalar.  UNIFORM = 0: each
 // lane tracks its own tap.
 #pragma once
+#include <stdlib.h>
 #include <type_traits>
 #include "q8_common.h"
 #include "q8_conv_common.h"
@@ -33,6 +34,72 @@ namespace q8 {
 namespace {
 
 constexpr int kOobOffset = (int)0x80000000;   // >= any descriptor size (tensors are < 2 GiB)
+
+#ifdef Q8_TRACE
+// Measurement build only: every workgroup logs (start, end) on the 100 MHz clock and what
+// identifies its launch into p.trace (word 0 = number of records, 3 words per record).
+__device__ __forceinline__ void q8_trace_record(const ConvParams& p, unsigned long long t0) {
+  if (threadIdx.x == 0 && p.trace && (blockIdx.x & 15) == 0) {     // one workgroup in 16
+    const unsigned long long t1 = __builtin_amdgcn_s_memrealtime();
+    const unsigned long long slot = atomicAdd(p.trace, 1ull);
+    if (slot < p.trace_cap) {
+      p.trace[1 + 3 * slot] = t0;
+      p.trace[2 + 3 * slot] = t1;
+      p.trace[3 + 3 * slot] = ((unsigned long long)(((uintptr_t)p.y >> 12) & 0x7ffff) << 45) |
+                              ((unsigned long long)(unsigned)p.M << 26) |
+                              ((unsigned long long)(unsigned)p.K << 14) | ((unsigned)p.C << 2) |
+                              (p.R == 3 ? 1u : 0u) | (p.res ? 2u : 0u);
+    }
+  }
+}
+#endif
+
+// Epilogue of one tile (tail of Eq. A' with the fused sum): acc[i][j] = the 32 x 32 MFMA tiles of
+// this wavefront (channel tile i, pixel tile j; a lane holds 16 consecutive channels of one
+// pixel), res_w the residual codes fetched for them.  A complete tile with aligned rows takes
+// the branch-free path (complete in pixels; in channels either complete or K a multiple of
+// the 16-channel group a lane holds, the groups beyond K being skipped).
+template <int TP, int TC, int U8>
+__device__ __forceinline__ void finish_tile(const ConvParams& p, const v16i (&acc)[TC][TP],
+                                            const int (&res_w)[TC][TP][4], const int pix0,
+                                            const int ch0, const int BP, const int BC,
+                                            const int wave_p, const int wave_c, const int lane) {
+  const bool fast_tile = p.vec16 && !p.acc_dump && !p.y_f32 && pix0 + BP <= p.M &&
+                         (ch0 + BC <= p.K || (p.K & 15) == 0);
+  auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
+    // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
+    // residual, signed residual, unsigned residual); 6, 7: fast with per-channel scales
+    // (no residual, residual)
+    constexpr int MODE = decltype(mode_c)::value;
+#pragma unroll
+    for (int i = 0; i < TC; ++i) {
+      const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
+      if (ch >= p.K) continue;
+      float mv[16] = {};
+      if constexpr (MODE >= 6) load_scale16(p, ch, mv);
+#pragma unroll
+      for (int j = 0; j < TP; ++j) {
+        const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
+        if (MODE == 0 && pix >= p.M) continue;
+        int v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
+        if constexpr (MODE == 0) finish16(p, pix, ch, v, res_w[i][j]);
+        else if constexpr (MODE <= 2) finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j], mv);
+        else if constexpr (MODE <= 5)
+          finish16_fast<MODE >= 4, true, MODE == 5>(p, pix, ch, v, res_w[i][j], mv);
+        else finish16_fast<MODE == 7, false, false, true>(p, pix, ch, v, res_w[i][j], mv);
+      }
+    }
+  };
+  if (!fast_tile) finish_all(std::integral_constant<int, 0>{});
+  else if (U8 && p.m_vec) {
+    if (p.res) finish_all(std::integral_constant<int, 7>{});
+    else finish_all(std::integral_constant<int, 6>{});
+  } else if (!p.res) finish_all(std::integral_constant<int, U8 ? 3 : 1>{});
+  else if (U8 && p.res_u8) finish_all(std::integral_constant<int, 5>{});
+  else finish_all(std::integral_constant<int, U8 ? 4 : 2>{});
+}
 
 // U8 = 1: the extended build of the kernel: unsigned activation codes (border correction,
 // unsigned residual / output) and per-output-channel scales; kept apart so that the plain
@@ -618,44 +685,7 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
     return;
   }
 
-  // ---- epilogue.  A complete tile with aligned rows takes the branch-free path.
-  // (complete in pixels; in channels either complete or K a multiple of the 16-channel group
-  // a lane holds, the groups beyond K being skipped)
-  const bool fast_tile = p.vec16 && !p.acc_dump && !p.y_f32 && pix0 + BP <= p.M &&
-                         (ch0 + BC <= p.K || (p.K & 15) == 0);
-  auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
-    // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no
-    // residual, signed residual, unsigned residual); 6, 7: fast with per-channel scales
-    // (no residual, residual)
-    constexpr int MODE = decltype(mode_c)::value;
-#pragma unroll
-    for (int i = 0; i < TC; ++i) {
-      const int ch = ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5);
-      if (ch >= p.K) continue;
-      float mv[16] = {};
-      if constexpr (MODE >= 6) load_scale16(p, ch, mv);
-#pragma unroll
-      for (int j = 0; j < TP; ++j) {
-        const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);
-        if (MODE == 0 && pix >= p.M) continue;
-        int v[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = acc[i][j][e];
-        if constexpr (MODE == 0) finish16(p, pix, ch, v, res_w[i][j]);
-        else if constexpr (MODE <= 2) finish16_fast<MODE == 2>(p, pix, ch, v, res_w[i][j], mv);
-        else if constexpr (MODE <= 5)
-          finish16_fast<MODE >= 4, true, MODE == 5>(p, pix, ch, v, res_w[i][j], mv);
-        else finish16_fast<MODE == 7, false, false, true>(p, pix, ch, v, res_w[i][j], mv);
-      }
-    }
-  };
-  if (!fast_tile) finish_all(std::integral_constant<int, 0>{});
-  else if (U8 && p.m_vec) {
-    if (p.res) finish_all(std::integral_constant<int, 7>{});
-    else finish_all(std::integral_constant<int, 6>{});
-  } else if (!p.res) finish_all(std::integral_constant<int, U8 ? 3 : 1>{});
-  else if (U8 && p.res_u8) finish_all(std::integral_constant<int, 5>{});
-  else finish_all(std::integral_constant<int, U8 ? 4 : 2>{});
+  finish_tile<TP, TC, U8>(p, acc, res_w, pix0, ch0, BP, BC, wave_p, wave_c, lane);
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
@@ -673,8 +703,14 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     const int base = nblk / kNumXcd, rem = nblk % kNumXcd;
     bid = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(p, bid / p.n_ctiles,
-                                                                bid % p.n_ctiles, lds);
+#ifdef Q8_TRACE
+  const unsigned long long q8_t0 = __builtin_amdgcn_s_memrealtime();
+#endif
+  conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(
+      p, bid / p.n_ctiles, bid % p.n_ctiles, lds);
+#ifdef Q8_TRACE
+  q8_trace_record(p, q8_t0);
+#endif
 #endif
 }
 

@@ -33,8 +33,14 @@ class Engine:
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
                  per_channel_weights=False, real_outputs=False, own_sum_factor=False,
-                 fuse_pairs=False, chain=False):
+                 fuse_pairs=False, chain=False, fuse_duals=False):
         self.net = net
+        # fuse_duals: two consecutive convolutions that read the same tensor and do not depend on
+        # each other (a stage's projection branch and its first 1x1) run as one launch where
+        # the library has a tile-shape pair for them
+        self.fuse_duals = fuse_duals
+        self.duals = {}       # first conv name -> second conv
+        self.dualed = set()
         # chain: every run of consecutive convolutions the library can take as a list runs as
         # ONE persistent launch (q8_conv_chain_int8: the batch split over the XCDs, tiles
         # started by the completion of the tiles they read) instead of one launch per layer
@@ -117,6 +123,24 @@ class Engine:
         if fuse_pairs:
             assert not (unsigned_activations or per_channel_weights)
             self._find_pairs()
+        if fuse_duals:
+            assert not (unsigned_activations or per_channel_weights or real_outputs)
+            self._find_duals()
+
+    def _find_duals(self):
+        ops = self.net.ops
+        n_part = self.parts[0][1]
+        for a, b in zip(ops, ops[1:]):
+            if a.kind != "conv" or b.kind != "conv" or a.src != b.src:
+                continue
+            if a.name in self.dualed or a.name in self.pairs or b.name in self.pairs or \
+                    a.name in self.paired or b.name in self.paired:
+                continue
+            if a.dst in (b.src, b.res) or b.dst in (a.src, a.res) or a.dst == b.dst:
+                continue
+            if B.conv_dual_supported(self.conv_desc(a, n_part), self.conv_desc(b, n_part)):
+                self.duals[a.name] = b
+                self.dualed.add(b.name)
 
     def _find_pairs(self):
         net = self.net
@@ -335,8 +359,19 @@ class Engine:
         res = self.act[op.res][lo:lo + n] if op.res else None
         q_res = self.q[op.res] if op.res else 0.0
         U = self.unsigned
-        if op.name in self.paired and fuse:
+        if (op.name in self.paired or op.name in self.dualed) and fuse:
             return                       # ran with the layer in front of it
+        if op.name in self.duals and fuse:
+            b = self.duals[op.name]
+
+            def args(o):
+                w, bias = self.wq[o.name]
+                return (self.conv_desc(o, n), self.act[o.src][lo:lo + n], w, bias, self.q[o.src],
+                        self.qw[o.name], self.q[o.dst],
+                        self.act[o.res][lo:lo + n] if o.res else None,
+                        self.q[o.res] if o.res else 0.0, self.act[o.dst][lo:lo + n])
+            B.conv_dual_int8(args(op), args(b))
+            return
         if op.name in self.pairs and fuse:
             b = self.pairs[op.name]
             packed2, bias2 = self.wq[b.name]
@@ -445,11 +480,16 @@ class Engine:
                 self.run_ops(self.net.ops, lo, n)
         else:
             main = torch.cuda.current_stream()
-            for side, part in zip(self.side, self.parts[1:]):
+            for side in self.side:
                 side.wait_stream(main)
-                with torch.cuda.stream(side):
-                    self.run_ops(self.net.ops, *part)
-            self.run_ops(self.net.ops, *self.parts[0])
+            # layer by layer, alternating between the pipelines: a captured graph hands its
+            # nodes to the GPU in the order they were recorded, and a pipeline recorded whole
+            # before the next one starts that much earlier and runs alone meanwhile
+            for op in self.net.ops:
+                for side, part in zip(self.side, self.parts[1:]):
+                    with torch.cuda.stream(side):
+                        self.run_ops([op], *part)
+                self.run_ops([op], *self.parts[0])
             for side in self.side:
                 main.wait_stream(side)
         for name, out in (dequant or {}).items():

@@ -167,7 +167,8 @@ CONV_CASES = [
 ]
 
 
-def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=0, variant=-1):
+def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=0, variant=-1,
+                   dump_acc=True):
     g = orc.ConvGeom(**geom)
     rng = np.random.default_rng(seed)
     Cs = 4 if g.C < 4 else g.C                      # stored channels of the input
@@ -198,8 +199,9 @@ def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=
     dump = torch.zeros((g.N, Ho, Wo, g.K), dtype=torch.int32, device="cuda")
     B.conv_int8(d, dev(x), packed, None if b is None else dev(b), float(q_x), float(q_w),
                 float(q_out), None if res is None else dev(res), float(q_res), out=out,
-                acc_dump=dump, variant=variant)
-    assert np.array_equal(host(dump), acc_o), "int32 accumulators differ"
+                acc_dump=dump if dump_acc else None, variant=variant)
+    if dump_acc:
+        assert np.array_equal(host(dump), acc_o), "int32 accumulators differ"
     got = host(out)
     assert np.array_equal(got, want), "int8 outputs differ"
     frac_sat = np.mean(np.abs(want[..., out_off:out_off + g.K].astype(int)) >= 127)
@@ -232,6 +234,63 @@ def test_conv_every_kernel_variant(B):
         for k, geom in enumerate(VARIANT_CASES):
             _run_conv_case(B, geom, relu=bool(k % 2), with_res=bool((k + v) % 2),
                            with_bias=True, seed=100 * v + k, variant=v)
+
+
+HALO_CASES = [   # 3x3, stride 1, padding 1, C % 64 == 0: the shapes the 3x3 tile family takes
+    dict(N=3, H=7, W=7, C=64, K=64),          # several images inside one pixel tile
+    dict(N=5, H=7, W=7, C=512, K=128),        # eight channel chunks, ragged last pixel tile
+    dict(N=2, H=14, W=14, C=128, K=128),
+    dict(N=1, H=28, W=28, C=64, K=256),
+    dict(N=2, H=9, W=31, C=192, K=96),        # three chunks, K ends inside a channel tile
+    dict(N=1, H=5, W=63, C=64, K=64),         # the widest map of the narrow patch buffers
+    dict(N=1, H=3, W=100, C=64, K=128),       # only the wide patch buffers take it
+    dict(N=1, H=2, W=300, C=64, K=64),        # only the widest one
+    dict(N=1, H=1, W=1, C=64, K=64),          # one pixel: only the centre tap is inside
+    dict(N=2, H=1, W=17, C=64, K=64),         # one row: no tap above or below
+]
+
+
+@pytest.mark.parametrize("idx", range(len(HALO_CASES)))
+def test_conv_3x3_tile_family(B, idx):
+    """Every build of the 3x3 tile family (activation patch with halo staged once per channel
+    chunk, nine taps as nine row offsets) against the oracle; a build whose patch buffer is too
+    narrow for the map hands the layer to the generic kernel, which must give the same bits."""
+    geom = dict(R=3, S=3, pad_h=1, pad_w=1, **HALO_CASES[idx])
+    n = B.conv_num_variants()
+    names = [B.lib.q8_conv_variant_name(v).decode() for v in range(n)]
+    halo = [v for v in range(n) if "halo3" in names[v]]
+    assert len(halo) >= 4
+    for k, v in enumerate(halo):
+        _run_conv_case(B, geom, relu=bool(k % 2), with_res=bool((k + idx) % 2), with_bias=True,
+                       seed=1000 * idx + v, variant=v)
+
+
+PW_CASES = [     # 1x1, stride 1, no padding, C in {64, 128, 256}: what the pointwise family takes
+    dict(N=2, H=56, W=56, C=64, K=256),       # many pixel tiles per workgroup, ragged last tile
+    dict(N=1, H=28, W=28, C=128, K=512),
+    dict(N=3, H=19, W=23, C=256, K=64),
+    dict(N=1, H=9, W=9, C=64, K=64),          # fewer pixel tiles than workgroups
+    dict(N=2, H=31, W=17, C=128, K=96),       # K ends inside a channel tile
+    dict(N=40, H=28, W=28, C=64, K=128),      # more pixel tiles than one round of workgroups
+    dict(N=1, H=1, W=1, C=256, K=320),
+]
+
+
+@pytest.mark.parametrize("idx", range(len(PW_CASES)))
+def test_conv_pointwise_tile_family(B, idx):
+    """Every build of the pointwise tile family (persistent workgroups, filters resident in LDS,
+    the next pixel tile's operands in flight while the current one is computed) against the
+    oracle; a build made for another channel count hands the layer to the generic kernel."""
+    geom = dict(R=1, S=1, **PW_CASES[idx])
+    n = B.conv_num_variants()
+    names = [B.lib.q8_conv_variant_name(v).decode() for v in range(n)]
+    pw = [v for v in range(n) if "pw_kernel" in names[v]]
+    assert len(pw) >= 4
+    for k, v in enumerate(pw):
+        for with_res in (False, True):
+            _run_conv_case(B, geom, relu=bool((k + with_res) % 2), with_res=with_res,
+                           with_bias=True, seed=3000 * idx + 2 * v + with_res, variant=v,
+                           out_pad=16 * (k % 2), out_off=16 * (k % 2), dump_acc=False)
 
 
 @pytest.mark.parametrize("geom", [
@@ -815,7 +874,7 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
                           per_channel=False, real_outputs=False, own_sum_factor=False,
-                          fuse_pairs=False, chain=False, chain_variants=None):
+                          fuse_pairs=False, chain=False, chain_variants=None, fuse_duals=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -841,7 +900,8 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
 
     eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned,
                  per_channel_weights=per_channel, real_outputs=real_outputs,
-                 fuse_pairs=fuse_pairs, chain=chain)
+                 fuse_pairs=fuse_pairs, chain=chain, fuse_duals=fuse_duals)
+    assert bool(eng.duals) == fuse_duals
     assert eng.unsigned == U
     assert bool(eng.pairs) == fuse_pairs
     unwritten = {op.dst for op in net.convs() if op.name in eng.pairs}   # stay on chip
@@ -981,6 +1041,15 @@ def test_resnet50_with_fused_layer_pairs(B):
     # every bottleneck's 3x3 -> 1x1 whose 3x3 has 64 or 128 filters runs as one launch, in
     # the benchmark's launch configuration
     _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, fuse_pairs=True)
+
+
+def test_resnet50_with_dual_launches(B):
+    # the projection branch and the first 1x1 of each of the four stages as one launch, in the
+    # benchmark's launch configuration (two half-batch pipelines), also together with the fused
+    # 3x3 -> 1x1 pairs
+    _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, fuse_duals=True)
+    _sampled_images_check(B, 3, 16, [0, 7, 8, 15], n_cal=2, cal_batch=8, fuse_duals=True,
+                          fuse_pairs=True)
 
 
 def test_resnet50_as_one_chained_launch(B):
