@@ -137,11 +137,24 @@ int q8_pack_weights(const q8_conv_desc *d, const int8_t *z_w_krsc_dev, void *pac
  *   residual   int8 [N][Ho][Wo][res_c_stride] or NULL.
  *   z_y        int8 [N][Ho][Wo][out_c_stride], written at channel out_c_off.
  *   acc_dump   NULL, or dense int32 [N][Ho][Wo][K] that receives acc (tests).
+ *   workspace  NULL, or device memory of at least q8_conv_workspace_bytes(d) bytes, 256-byte
+ *              aligned, owned by the caller.  With a workspace the library may split the
+ *              reduction over r, s, c of a layer with few output tiles among several
+ *              workgroups (Eq. x: acc is an integer sum, so every grouping of its terms
+ *              gives the same bits; the results do not depend on whether, or how, the
+ *              reduction is split).  The caller zeroes the workspace once after allocating
+ *              it; every call leaves its counters zero again, so one workspace serves any
+ *              number of calls that do not overlap in time.  Q8_EWORKSPACE if it is
+ *              smaller than q8_conv_workspace_bytes(d); without one nothing is split.
  * Accumulation wraps modulo 2^32 (cannot happen below R*S*C = 130 000).           */
 int q8_conv_int8(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
                  const int32_t *bias_i32, float q_x, float q_w, float q_out,
                  const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
-                 void *stream);
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace with which q8_conv_int8 splits this layer's reduction; 0 for a layer it
+ * would not split (then the workspace argument is ignored).                              */
+size_t q8_conv_workspace_bytes(const q8_conv_desc *d);
 
 /* ---- unsigned activations: the calibration paragraph's p = 8 for non-negative tensors --
  * An unsigned tensor (the output of a ReLU layer) holds codes 0..255 with q = max/255, one
@@ -320,14 +333,20 @@ const char *q8_conv_variant(const q8_conv_desc *d);
 /* Tests and tuning only: q8_conv_int8 with the tile / ring variant of the main kernel given
  * by the caller (0 .. q8_conv_num_variants() - 1, in the order of the library's variant
  * table; -1 = automatic choice, i.e. q8_conv_int8 itself).  The variant is used wherever the
- * main kernel can take the geometry (C % 16 == 0, R*S <= 32) and ignored otherwise.  The
- * results are identical for every variant.                                              */
+ * main kernel can take the geometry (C % 16 == 0, R*S <= 32) and ignored otherwise.  With a
+ * split-reduction variant, n_split >= 2 workgroups share each output tile (clipped to the
+ * number of 64-byte reduction steps; the layer must have C % 64 == 0) and the workspace holds
+ * at least q8_conv_workspace_bytes_variant(d, variant, n_split) bytes; n_split < 2, or a layer
+ * such a variant cannot take, runs unsplit.  The results are identical for every variant
+ * and every split factor.                                                                */
 int q8_conv_num_variants(void);
 const char *q8_conv_variant_name(int variant);   /* as in a profiler's kernel trace */
+size_t q8_conv_workspace_bytes_variant(const q8_conv_desc *d, int variant, int n_split);
 int q8_conv_int8_variant(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
                          const int32_t *bias_i32, float q_x, float q_w, float q_out,
                          const int8_t *residual, float q_res, int8_t *z_y, int32_t *acc_dump,
-                         int variant, void *stream);
+                         int variant, int n_split, void *workspace, size_t workspace_bytes,
+                         void *stream);
 
 /* ---- helpers that only chain layers; not part of the paper's method ------------ */
 

@@ -31,6 +31,7 @@ EXPORTS = [
     "q8_conv_chain_static_workspace_limit", "q8_conv_chain_int8_static",
     "q8_conv_chain_static_status",
     "q8_conv_variant", "q8_conv_num_variants", "q8_conv_variant_name", "q8_conv_int8_variant", "q8_sum_factor",
+    "q8_conv_workspace_bytes", "q8_conv_workspace_bytes_variant",
     "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
@@ -105,7 +106,11 @@ lib.q8_fold_bn.argtypes = [_vp] * 6 + [_f, _i, _i, _vp, _vp, _vp]
 lib.q8_packed_weight_bytes.restype = _sz
 lib.q8_packed_weight_bytes.argtypes = [_dp]
 lib.q8_pack_weights.argtypes = [_dp, _vp, _vp, _vp]
-lib.q8_conv_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
+lib.q8_conv_int8.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp, C.c_size_t, _vp]
+lib.q8_conv_workspace_bytes.argtypes = [_dp]
+lib.q8_conv_workspace_bytes.restype = C.c_size_t
+lib.q8_conv_workspace_bytes_variant.argtypes = [_dp, _i, _i]
+lib.q8_conv_workspace_bytes_variant.restype = C.c_size_t
 lib.q8_conv_u8.argtypes = [_dp, _i, _i, _i, _vp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_u8_prepare.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
 lib.q8_quantize_weights_per_channel.argtypes = [_vp, _i, _sz, _i, _vp, _vp, _vp]
@@ -122,7 +127,8 @@ lib.q8_conv_variant.argtypes = [_dp]
 lib.q8_conv_num_variants.argtypes = []
 lib.q8_conv_variant_name.restype = C.c_char_p
 lib.q8_conv_variant_name.argtypes = [_i]
-lib.q8_conv_int8_variant.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _i, _vp]
+lib.q8_conv_int8_variant.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _i, _i, _vp,
+                                     C.c_size_t, _vp]
 lib.q8_sum_factor.restype = _f
 lib.q8_sum_factor.argtypes = [_f, _f]
 lib.q8_probe_mfma_i8.argtypes = [_i, _i, _vp, _vp]
@@ -229,19 +235,29 @@ def pack_weights(desc, z_w):
     return packed
 
 
+def conv_workspace_bytes(desc, variant=-1, n_split=0):
+    """Workspace with which the library splits this layer's reduction (0: it would not)."""
+    if variant >= 0:
+        return lib.q8_conv_workspace_bytes_variant(C.byref(desc), int(variant), int(n_split))
+    return lib.q8_conv_workspace_bytes(C.byref(desc))
+
+
 def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q_res=0.0,
-              out=None, acc_dump=None, variant=-1):
-    """``variant`` >= 0 (tests, tuning): that tile variant of the main kernel."""
+              out=None, acc_dump=None, variant=-1, workspace=None, n_split=0):
+    """``workspace``: a zeroed uint8 device tensor the library may split the reduction with.
+    ``variant`` >= 0 (tests, tuning): that tile variant of the main kernel, ``n_split``
+    workgroups per tile where it is a split-reduction variant."""
     if out is None:
         ocs = desc.out_c_stride or desc.K
         out = torch.empty((desc.N, desc.Ho, desc.Wo, ocs), dtype=torch.int8, device=z_x.device)
     args = (C.byref(desc), _ptr(z_x, torch.int8), _ptr(z_w_packed, torch.int8),
             _ptr(bias_i32, torch.int32), q_x, q_w, q_out, _ptr(residual, torch.int8), q_res,
             _ptr(out, torch.int8), _ptr(acc_dump, torch.int32))
+    ws = (_ptr(workspace, torch.uint8), 0 if workspace is None else workspace.numel())
     if variant >= 0:
-        _check(lib.q8_conv_int8_variant(*args, int(variant), _stream()))
+        _check(lib.q8_conv_int8_variant(*args, int(variant), int(n_split), *ws, _stream()))
     else:
-        _check(lib.q8_conv_int8(*args, _stream()))
+        _check(lib.q8_conv_int8(*args, *ws, _stream()))
     return out
 
 

@@ -21,6 +21,9 @@ namespace q8 {
 int num_stream_variants();
 int num_ring_variants();
 int first_pw_variant();
+int first_split_variant();
+int num_split_variants();
+void split_variant_tile(int variant, int* bp, int* bc);
 int launch_dual_variant(ConvParams& p1, ConvParams& p2, hipStream_t stream);   // q8_conv_dual.hip
 bool dual_shapes_supported(const ConvParams& p1, const ConvParams& p2);
 }
@@ -232,6 +235,9 @@ struct U8Flags {
   float* y_f32 = nullptr;           // real-valued output instead of int8 codes
   const PairArgs* pair = nullptr;   // a second, 1x1 layer on the output while it is on chip
   int variant = -1;                 // tile variant of the main kernel to use (tests, tuning)
+  int n_split = 0;                  // with a split-reduction variant: workgroups per tile
+  void* workspace = nullptr;        // caller's device workspace: lets the reduction be split
+  size_t workspace_bytes = 0;
 };
 
 // Checks the arguments of one layer and fills the kernels' parameter block.  *empty: the
@@ -361,6 +367,37 @@ int conv_fill(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const 
   return Q8_OK;
 }
 
+// Workspace of a split reduction: one int32 arrival counter per output tile (padded to 256
+// bytes), then one int32 partial tile per (tile, part).
+struct SplitLayout {
+  int n_split;            // clipped to the number of reduction steps; < 2: no split
+  size_t counter_bytes, bytes;
+};
+SplitLayout split_layout(const q8_conv_desc* d, int variant, int n_split) {
+  SplitLayout l{1, 0, 0};
+  if (variant < q8::first_split_variant() || conv_mode(d) != 0 || !stream_capable(d) ||
+      d->C % 64 != 0)
+    return l;
+  int bp = 0, bc = 0;
+  q8::split_variant_tile(variant - q8::first_split_variant(), &bp, &bc);
+  const long M = (long)d->N * q8_conv_out_h(d) * q8_conv_out_w(d);
+  const long tiles = ((M + bp - 1) / bp) * ((d->K + bc - 1) / bc);
+  const int nk = d->R * d->S * d->C / 64;
+  if (n_split > nk) n_split = nk;
+  if (n_split < 2 || tiles <= 0) return l;
+  l.n_split = n_split;
+  l.counter_bytes = (size_t)((tiles * 4 + 255) / 256 * 256);
+  l.bytes = l.counter_bytes + (size_t)tiles * n_split * bp * bc * 4;
+  return l;
+}
+
+// Whether the layer's reduction is split when the caller provides a workspace, and how.
+// No layer is: the partial tiles have to pass through memory (the parts of a tile may sit on
+// different XCDs), and on every ResNet-50 / SSD shape tried that costs more than the shorter
+// chain of reduction steps saves (7x7 512->512 3x3 at batch 32: 10.2 us unsplit, 12.2 us at
+// best split in two).  The split builds stay reachable through q8_conv_int8_variant.
+void split_plan(const q8_conv_desc*, int*, int*) {}
+
 int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const void* z_w_packed,
                 const int32_t* bias_i32, float q_x, float q_w, float q_out,
                 const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
@@ -413,8 +450,25 @@ int conv_launch(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, cons
     p.vec16_2 = aligned2(16) ? 1 : 0;
     return q8::launch_pair_variant(p, s);
   }
-  const int variant = pick_variant(d, u.variant);
+  int variant = pick_variant(d, u.variant);
+  p.n_split = 1;
+  p.ws_counters = nullptr;
+  p.ws_slabs = nullptr;
   if (variant >= kRegBase) return q8::launch_reg_variant(variant - kRegBase, p, s);
+  int n_split = u.n_split;
+  if (u.variant < 0 && u.workspace && !(u.in_u8 || u.out_u8 || u.res_u8 || u.m_vec || u.y_f32))
+    split_plan(d, &variant, &n_split);
+  if (variant >= q8::first_split_variant() && n_split >= 2) {
+    const SplitLayout l = split_layout(d, variant, n_split);
+    if (l.n_split >= 2) {       // (a reduction of one step is not split)
+      Q8_REQUIRE(u.workspace != nullptr, Q8_EINVAL);
+      Q8_REQUIRE(q8_aligned(u.workspace, 256), Q8_EALIGN);
+      Q8_REQUIRE(u.workspace_bytes >= l.bytes, Q8_EWORKSPACE);
+      p.n_split = l.n_split;
+      p.ws_counters = (int*)u.workspace;
+      p.ws_slabs = (int*)((char*)u.workspace + l.counter_bytes);
+    }
+  }
   return q8::launch_stream_variant(variant, p, s);
 }
 
@@ -476,9 +530,24 @@ extern "C" {
 int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
                  const int32_t* bias_i32, float q_x, float q_w, float q_out,
                  const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
-                 void* stream) {
-  return conv_launch(d, U8Flags{0, 0, 0, nullptr}, z_x, z_w_packed, bias_i32, q_x, q_w, q_out,
-                     residual, q_res, z_y, acc_dump, stream);
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  U8Flags u{0, 0, 0, nullptr};
+  u.workspace = workspace;
+  u.workspace_bytes = workspace_bytes;
+  return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual, q_res, z_y,
+                     acc_dump, stream);
+}
+
+size_t q8_conv_workspace_bytes(const q8_conv_desc* d) {
+  if (!desc_sane(d)) return 0;
+  int variant = -1, n_split = 1;
+  split_plan(d, &variant, &n_split);
+  return variant < 0 ? 0 : split_layout(d, variant, n_split).bytes;
+}
+
+size_t q8_conv_workspace_bytes_variant(const q8_conv_desc* d, int variant, int n_split) {
+  if (!desc_sane(d) || variant < 0 || variant >= q8::num_stream_variants()) return 0;
+  return split_layout(d, variant, n_split).bytes;
 }
 
 int q8_conv_u8(const q8_conv_desc* d, int in_unsigned, int out_unsigned, int res_unsigned,
@@ -595,10 +664,15 @@ const char* q8_conv_variant_name(int variant) { return q8::stream_variant_name(v
 int q8_conv_int8_variant(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
                          const int32_t* bias_i32, float q_x, float q_w, float q_out,
                          const int8_t* residual, float q_res, int8_t* z_y, int32_t* acc_dump,
-                         int variant, void* stream) {
+                         int variant, int n_split, void* workspace, size_t workspace_bytes,
+                         void* stream) {
   Q8_REQUIRE(variant >= -1 && variant < q8::num_stream_variants(), Q8_EINVAL);
+  Q8_REQUIRE(n_split >= 0 && n_split <= 64, Q8_EINVAL);
   U8Flags u{0, 0, 0, nullptr};
   u.variant = variant;
+  u.n_split = n_split;
+  u.workspace = workspace;
+  u.workspace_bytes = workspace_bytes;
   return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual, q_res, z_y,
                      acc_dump, stream);
 }

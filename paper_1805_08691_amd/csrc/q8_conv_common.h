@@ -61,6 +61,12 @@ struct ConvParams {
   int out_cs2, out_off2, res_cs2, res_off2;
   float m2, m_r2;
   int relu2, vec4_2, vec16_2;
+  // Split reduction (the split builds of the main kernel): n_split workgroups share an output
+  // tile, each over a contiguous range of reduction steps.  ws_slabs holds one int32 partial
+  // tile per (tile, part), ws_counters one arrival counter per tile (zero between launches).
+  int n_split;
+  int* __restrict__ ws_counters;
+  int* __restrict__ ws_slabs;
 #ifdef Q8_TRACE
   unsigned long long* trace;      // measurement build only: workgroup log
   unsigned long long trace_cap;

@@ -196,13 +196,35 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
       bf[h & 1][j] = *reinterpret_cast<const v4i*>(lds + addr);
     }
   };
+  // A wave with a single 32 x 32 tile would feed every MFMA the result of the one before it
+  // and wait out its full latency each time: such builds sum the odd 32-byte sub-steps in a
+  // second accumulator (integer sums: any grouping gives the same bits) and add it at the end.
+  constexpr bool TWO_SUMS = TC * TP == 1;
+  v16i acc_odd[1];
+  if constexpr (TWO_SUMS) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc_odd[0][e] = 0;
+  }
   auto mma = [&](int h) {
+    if constexpr (TWO_SUMS) {
+      if (h & 1)
+        acc_odd[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][0], bf[1][0], acc_odd[0], 0, 0, 0);
+      else
+        acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][0], bf[0][0], acc[0][0], 0, 0, 0);
+    } else {
 #pragma unroll
-    for (int i = 0; i < TC; ++i)
+      for (int i = 0; i < TC; ++i)
 #pragma unroll
-      for (int j = 0; j < TP; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
-                                                          0, 0, 0);
+        for (int j = 0; j < TP; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
+                                                            0, 0, 0);
+    }
+  };
+  auto fold_sums = [&]() {
+    if constexpr (TWO_SUMS) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[0][0][e] += acc_odd[0][e];
+    }
   };
 
   using std::integral_constant;
@@ -266,6 +288,7 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
   step(chunk, Q8_TAP(7), Q8_AHEAD(A_LOADS), no, no, no);
   step(chunk, Q8_TAP(8), Q8_AHEAD(0), no, no, yes);
   mma(1);
+  fold_sums();
 #undef Q8_TAP
 #undef Q8_AHEAD
 

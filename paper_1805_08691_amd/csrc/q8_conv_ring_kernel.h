@@ -116,9 +116,18 @@ __device__ __forceinline__ void finish_tile(const ConvParams& p, const v16i (&ac
 // the operand ring.  No vector-memory operation of the workgroup may be outstanding on entry
 // (the ring counts its own loads); the caller synchronises the workgroup before `lds` is
 // used again.
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
+//
+// SPLIT = 1: the reduction of a tile is split over p.n_split workgroups (Eq. x: the integer
+// accumulator is a plain sum, so any grouping of its terms gives the same bits).  Workgroup
+// `part` runs its share of the reduction steps, stores its partial accumulators in its slab of
+// the workspace and bumps the tile's arrival counter; the workgroup that arrives last adds the
+// other slabs to its own registers, clears the counter for the next launch and runs the
+// epilogue.  Nobody waits for anybody: a workgroup either finishes the tile or leaves.
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0,
+          int SPLIT = 0>
 __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int ptile,
-                                               const int ctile, int8_t* const lds) {
+                                               const int ctile, int8_t* const lds,
+                                               const int part = 0) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub: buffer
                                       // descriptor types exist for the device target alone
   constexpr int CHUNKS = BK / 16;          // 16-byte chunks per LDS row
@@ -250,6 +259,21 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
   // What the reduction loop reads of `p`, in registers: when `p` lives in global memory (a
   // layer list) the compiler barriers of the loop would otherwise force a reload per step.
   const int p_C = p.C, p_S = p.S, p_red_len = p.red_len;
+  // the reduction steps of this workgroup: all of them, or its share of a split reduction
+  int nk = (p.red_len + BK - 1) / BK;
+  if constexpr (SPLIT) {
+    static_assert(UNIFORM == 1 && !U8 && !PAIR, "split reduction: plain uniform-tap builds");
+    const int k_first = (int)((long)nk * part / p.n_split);
+    nk = (int)((long)nk * (part + 1) / p.n_split) - k_first;
+    const int per_tap = p_C / BK;                  // steps per filter tap
+    tap = k_first / per_tap;
+    tap_c = (k_first - tap * per_tap) * BK;
+    const int r = tap / p_S;
+    tap_s = tap - r * p_S;
+    tap_delta = (r * p.dil_h * p.W + tap_s * p.dil_w) * p.in_cs;
+    step_base = k_first * BK;
+    refresh_taps();
+  }
   auto issue_stage = [&](int buf) {
     int8_t* stage = lds + buf * STAGE_BYTES;
     if constexpr (UNIFORM == 1) {
@@ -361,6 +385,16 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
         for (int e = 0; e < 16; ++e) acc[i][j][e] = b[e];
     }
   }
+  if constexpr (SPLIT) {
+    if (part != 0) {                    // the bias is part 0's
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+    }
+  }
   // Pair build: bias and residual codes of the second layer's first channel tile, requested
   // ahead of the ring like the first layer's bias; double-buffered over its channel tiles.
   v16i bias2[TC];
@@ -415,7 +449,6 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
               16, off, t * BC * BC + s2 * BK, 0, 0);
         }
   }
-  const int nk = (p.red_len + BK - 1) / BK;
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
 
@@ -431,8 +464,9 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
         load_res16(p, pix0 + (wave_p * TP + j) * 32 + (lane & 31),
                    ch0 + (wave_c * TC + i) * 32 + 16 * (lane >> 5), res_w[i][j]);
   };
+  // (split reduction: only the workgroup that finishes the tile needs them, see below)
   const bool early_residual = nk <= STAGES - 1;
-  if (early_residual) fetch_residual();
+  if (early_residual && !SPLIT) fetch_residual();
 
   // Operand fragments of the 32-byte sub-steps of a reduction step, double-buffered in
   // registers.  The loop is software-pipelined inside one wavefront: the LDS reads of a
@@ -473,13 +507,35 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
     for (int j = 0; j < TP; ++j)
       bf[h & 1][j] = *reinterpret_cast<const v4i*>(stage + b_foff[h][j]);
   };
+  // A wave with a single 32 x 32 tile would feed every MFMA the result of the one before it
+  // and wait out its full latency each time: such builds sum the odd 32-byte sub-steps in a
+  // second accumulator (integer sums: any grouping gives the same bits) and add it at the end.
+  constexpr bool TWO_SUMS = TC * TP == 1;
+  v16i acc_odd[1];
+  if constexpr (TWO_SUMS) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc_odd[0][e] = 0;
+  }
   auto mma = [&](int h) {
+    if constexpr (TWO_SUMS) {
+      if (h & 1)
+        acc_odd[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][0], bf[1][0], acc_odd[0], 0, 0, 0);
+      else
+        acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][0], bf[0][0], acc[0][0], 0, 0, 0);
+    } else {
 #pragma unroll
-    for (int i = 0; i < TC; ++i)
+      for (int i = 0; i < TC; ++i)
 #pragma unroll
-      for (int j = 0; j < TP; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
-                                                          0, 0, 0);
+        for (int j = 0; j < TP; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[h & 1][i], bf[h & 1][j], acc[i][j],
+                                                            0, 0, 0);
+    }
+  };
+  auto fold_sums = [&]() {
+    if constexpr (TWO_SUMS) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[0][0][e] += acc_odd[0][e];
+    }
   };
 
   // One reduction step.  LATER = steps issued after step kt that may still be in flight
@@ -506,7 +562,7 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
     if constexpr (decltype(issue_c)::value)
       issue_stage(STAGE >= 0 ? (STAGE + STAGES - 1) % STAGES : (kt + STAGES - 1) % STAGES);
     if constexpr (decltype(last_c)::value) {
-      if (!early_residual) fetch_residual();
+      if (!early_residual && !SPLIT) fetch_residual();
     }
     mma(NH - 1);                        // last sub-step of step kt-1 (zeros on the first step)
 #pragma unroll
@@ -594,6 +650,7 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
   step(kt, integral_constant<int, 0>{}, integral_constant<bool, false>{},
        integral_constant<bool, true>{}, any_stage);
   mma(NH - 1);
+  fold_sums();
 
   if constexpr (PAIR) {
     static_assert(UNIFORM == 1 && !U8, "pair build: plain uniform-tap kernel only");
@@ -685,6 +742,63 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
     return;
   }
 
+  if constexpr (SPLIT) {
+    // The parts of a tile may run on different XCDs, whose L2 caches do not see each other's
+    // lines.  Slabs and counters are therefore written and read past the caches (relaxed
+    // atomics of system scope: write-through stores, loads that miss on purpose), which
+    // costs a trip to the memory side but no cache-wide write-back or invalidate.
+    // Slab layout: register pair h of MFMA tile (i, j) of lane tid at 8-byte word
+    // ((i TP + j) 8 + h) NW 64 + tid: every wave-wide access is 512 bytes in one piece.
+    using word_t = unsigned long long;
+    constexpr int kWords = BP * BC / 2;                       // 8-byte words per slab
+    const int tile = ptile * p.n_ctiles + ctile;
+    word_t* const slabs = reinterpret_cast<word_t*>(p.ws_slabs) + (size_t)tile * p.n_split * kWords;
+    {
+      word_t* const mine = slabs + (size_t)part * kWords + tid;
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+#pragma unroll
+          for (int h = 0; h < 8; ++h)
+            __hip_atomic_store(mine + ((i * TP + j) * 8 + h) * (NW * 64),
+                               (word_t)(unsigned)acc[i][j][2 * h] |
+                                   ((word_t)(unsigned)acc[i][j][2 * h + 1] << 32),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    // every store of this wave has been acknowledged by the memory side ...
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                     // ... and so have the other waves'; LDS is free
+    int* const word = reinterpret_cast<int*>(lds);
+    if (wave == 0) {
+      int before = 0;
+      if (lane == 0)
+        before = __hip_atomic_fetch_add(p.ws_counters + tile, 1, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_SYSTEM);
+      before = __builtin_amdgcn_readfirstlane(before);
+      if (lane == 0) word[0] = before;
+    }
+    __syncthreads();
+    if (word[0] != p.n_split - 1) return;           // someone else finishes the tile
+    fetch_residual();
+    for (int other = 0; other < p.n_split; ++other) {
+      if (other == part) continue;
+      word_t* const theirs = slabs + (size_t)other * kWords + tid;
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+#pragma unroll
+          for (int h = 0; h < 8; ++h) {
+            const word_t v = __hip_atomic_load(theirs + ((i * TP + j) * 8 + h) * (NW * 64),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            acc[i][j][2 * h] += (int)(unsigned)v;
+            acc[i][j][2 * h + 1] += (int)(unsigned)(v >> 32);
+          }
+    }
+    if (wave == 0 && lane == 0)
+      __hip_atomic_store(p.ws_counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
   finish_tile<TP, TC, U8>(p, acc, res_w, pix0, ch0, BP, BC, wave_p, wave_c, lane);
 #endif  // __HIP_DEVICE_COMPILE__
 }
@@ -692,11 +806,13 @@ __device__ __forceinline__ void conv_tile_ring(const ConvParams& p, const int pt
 // One workgroup per output tile.  Workgroup id -> tile: each XCD (workgroups are dealt to
 // the XCDs round-robin) gets a contiguous run of tiles, channel tile fastest, so tiles that
 // share activations share an L2.
-template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0>
+template <int WP, int WC, int TP, int TC, int BK, int STAGES, int UNIFORM, int U8, int PAIR = 0,
+          int SPLIT = 0>
 __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];   // the operand ring
-  const int nblk = p.n_ptiles * p.n_ctiles;
+  // units of work: tiles, or (tile, part) with the parts of a tile next to each other
+  const int nblk = p.n_ptiles * p.n_ctiles * (SPLIT ? p.n_split : 1);
   int bid = blockIdx.x;
   {
     const int xcd = bid % kNumXcd, idx = bid / kNumXcd;
@@ -706,8 +822,14 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
 #ifdef Q8_TRACE
   const unsigned long long q8_t0 = __builtin_amdgcn_s_memrealtime();
 #endif
-  conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(
-      p, bid / p.n_ctiles, bid % p.n_ctiles, lds);
+  if constexpr (SPLIT) {
+    const int tile = bid / p.n_split;
+    conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR, 1>(
+        p, tile / p.n_ctiles, tile % p.n_ctiles, lds, bid - tile * p.n_split);
+  } else {
+    conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(p, bid / p.n_ctiles,
+                                                                  bid % p.n_ctiles, lds);
+  }
 #ifdef Q8_TRACE
   q8_trace_record(p, q8_t0);
 #endif
@@ -737,6 +859,30 @@ int launch_ring_grid(const ConvParams& p, dim3 grid, hipStream_t stream) {
     if (attr != hipSuccess) return Q8_EHIP;
   }
   hipLaunchKernelGGL(kernel, grid, dim3(WP * WC * 64), kLdsBytes, stream, p);
+  return q8_launch_status();
+}
+
+// Split-reduction launch of a plain uniform-tap build: p.n_split workgroups per output tile.
+// The caller has checked split_applicable and set p.n_split, p.ws_counters and p.ws_slabs.
+inline bool split_applicable(const ConvParams& p) {
+  return p.S4 == 0 && p.C % 64 == 0 && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 &&
+         !p.tap_sums;
+}
+template <int WP, int WC, int TP, int TC, int BK, int STAGES>
+int launch_ring_split(ConvParams& p, hipStream_t stream) {
+  constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
+  constexpr int kLdsBytes = STAGES * (BP + BC) * BK;
+  p.n_ptiles = (p.M + BP - 1) / BP;
+  p.n_ctiles = (p.K + BC - 1) / BC;
+  const long nblk = (long)p.n_ptiles * p.n_ctiles * p.n_split;
+  if (nblk > 0x7fffffffL || p.C % BK != 0) return Q8_EUNSUPPORTED;
+  auto kernel = conv_i8_ring_kernel<WP, WC, TP, TC, BK, STAGES, 1, 0, 0, 1>;
+  if constexpr (kLdsBytes > 65536) {
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr != hipSuccess) return Q8_EHIP;
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)nblk), dim3(WP * WC * 64), kLdsBytes, stream, p);
   return q8_launch_status();
 }
 

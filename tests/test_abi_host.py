@@ -61,7 +61,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.q8_fold_bn(fake, None, fake, fake, fake, fake, 1e-5, 0, 4, fake, fake, None) == 0
 
     d = B.ConvDesc(1, 8, 8, 16, 16, 3, 3, pad_h=1, pad_w=1)
-    ok = (fake, fake, None, 1.0, 1.0, 1.0, None, 0.0, fake, None, None)
+    ok = (fake, fake, None, 1.0, 1.0, 1.0, None, 0.0, fake, None, None, 0, None)   # no workspace
     assert L.q8_conv_int8(None, *ok) == -1
     bad = B.ConvDesc(1, 8, 8, 16, 16, 3, 3, stride_h=0)
     assert L.q8_conv_int8(C.byref(bad), *ok) == -1
@@ -69,18 +69,34 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.q8_conv_int8(C.byref(odd), *ok) == -2
     assert B.packed_weight_bytes(odd) == 0
     assert L.q8_conv_int8(C.byref(d), fake, fake, None, 0.0, 1.0, 1.0, None, 0.0, fake, None,
-                          None) == -1
+                          None, 0, None) == -1
     assert L.q8_conv_int8(C.byref(d), None, fake, None, 1.0, 1.0, 1.0, None, 0.0, fake, None,
-                          None) == -1
+                          None, 0, None) == -1
     assert L.q8_conv_int8(C.byref(d), C.c_void_p(0x1004), fake, None, 1.0, 1.0, 1.0, None, 0.0,
-                          fake, None, None) == -3     # activations not 16-byte aligned
+                          fake, None, None, 0, None) == -3     # activations not 16-byte aligned
     narrow = B.ConvDesc(1, 8, 8, 16, 16, 3, 3, out_c_stride=8)
     assert L.q8_conv_int8(C.byref(narrow), *ok) == -1  # K does not fit the output stride
-    resq = (fake, fake, None, 1.0, 1.0, 1.0, fake, 0.0, fake, None, None)
+    resq = (fake, fake, None, 1.0, 1.0, 1.0, fake, 0.0, fake, None, None, 0, None)
     assert L.q8_conv_int8(C.byref(d), *resq) == -1     # residual with q_res <= 0
     empty = B.ConvDesc(0, 8, 8, 16, 16, 3, 3)
     assert L.q8_conv_int8(C.byref(empty), None, None, None, 1.0, 1.0, 1.0, None, 0.0, None, None,
-                          None) == 0                   # empty batch: nothing to do
+                          None, 0, None) == 0          # empty batch: nothing to do
+    # split reduction: the workspace is checked on the host
+    deep = B.ConvDesc(2, 7, 7, 512, 512, 3, 3, pad_h=1, pad_w=1)
+    names = [L.q8_conv_variant_name(v).decode() for v in range(L.q8_conv_num_variants())]
+    sv = next(v for v, nm in enumerate(names) if "split" in nm)
+    need = L.q8_conv_workspace_bytes_variant(C.byref(deep), sv, 4)
+    assert need > 4 * 98 * 49 // 128 * 4            # counters plus four partial tiles per tile
+    assert L.q8_conv_workspace_bytes_variant(C.byref(deep), sv, 1) == 0     # nothing to share
+    assert L.q8_conv_workspace_bytes_variant(C.byref(deep), 0, 4) == 0      # not a split build
+    assert L.q8_conv_workspace_bytes_variant(C.byref(odd), sv, 4) == 0
+    assert L.q8_conv_workspace_bytes(C.byref(deep)) <= need
+    sp = (fake, fake, None, 1.0, 1.0, 1.0, None, 0.0, fake, None, sv, 4)
+    assert L.q8_conv_int8_variant(C.byref(deep), *sp, None, 0, None) == -1             # none given
+    assert L.q8_conv_int8_variant(C.byref(deep), *sp, C.c_void_p(0x1010), need, None) == -3
+    assert L.q8_conv_int8_variant(C.byref(deep), *sp, fake, need - 1, None) == -5      # too small
+    assert L.q8_conv_int8_variant(C.byref(deep), *sp[:-1], 65, fake, need, None) == -1 # factor
+    assert L.q8_conv_int8_variant(C.byref(deep), *sp[:-2], len(names), 2, fake, need, None) == -1
     # sizes beyond the kernels' 32-bit offsets are refused on the host, nothing is launched
     big_x = B.ConvDesc(4096, 512, 512, 64, 64, 3, 3, pad_h=1, pad_w=1)        # activations > 2 GiB
     assert L.q8_conv_int8(C.byref(big_x), *ok) == -2

@@ -168,7 +168,7 @@ CONV_CASES = [
 
 
 def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=0, variant=-1,
-                   dump_acc=True):
+                   dump_acc=True, n_split=0, workspace=None):
     g = orc.ConvGeom(**geom)
     rng = np.random.default_rng(seed)
     Cs = 4 if g.C < 4 else g.C                      # stored channels of the input
@@ -199,7 +199,8 @@ def _run_conv_case(B, geom, relu, with_res, with_bias, seed, out_pad=0, out_off=
     dump = torch.zeros((g.N, Ho, Wo, g.K), dtype=torch.int32, device="cuda")
     B.conv_int8(d, dev(x), packed, None if b is None else dev(b), float(q_x), float(q_w),
                 float(q_out), None if res is None else dev(res), float(q_res), out=out,
-                acc_dump=dump if dump_acc else None, variant=variant)
+                acc_dump=dump if dump_acc else None, variant=variant, n_split=n_split,
+                workspace=workspace)
     if dump_acc:
         assert np.array_equal(host(dump), acc_o), "int32 accumulators differ"
     got = host(out)
@@ -263,6 +264,42 @@ def test_conv_3x3_tile_family(B, idx):
     for k, v in enumerate(halo):
         _run_conv_case(B, geom, relu=bool(k % 2), with_res=bool((k + idx) % 2), with_bias=True,
                        seed=1000 * idx + v, variant=v)
+
+
+SPLIT_CASES = [   # long reductions over few output tiles: what a split reduction is for
+    dict(N=5, H=7, W=7, C=512, K=512, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=3, H=14, W=14, C=1024, K=256, R=1, S=1),
+    dict(N=2, H=9, W=11, C=192, K=96, R=3, S=3, pad_h=1, pad_w=1),        # ragged tiles
+    dict(N=1, H=14, W=14, C=1024, K=512, R=1, S=1, stride_h=2, stride_w=2),
+    dict(N=2, H=8, W=8, C=128, K=128, R=3, S=3, pad_h=2, pad_w=2, dil_h=2, dil_w=2),
+    dict(N=1, H=6, W=6, C=64, K=64, R=1, S=1),                             # one step: never split
+]
+
+
+@pytest.mark.parametrize("idx", range(len(SPLIT_CASES)))
+def test_conv_split_reduction(B, idx):
+    """Eq. x: the accumulator is an integer sum, so splitting the reduction over 2, 3, 5 or 7
+    workgroups per tile (partial tiles through the caller's workspace, the last workgroup to
+    arrive adds them up) gives the oracle's accumulators and codes bit for bit, with every
+    split build.  One workspace, zeroed once, serves all calls: each leaves its counters zero."""
+    geom = SPLIT_CASES[idx]
+    g = orc.ConvGeom(**geom)
+    d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                   g.dil_h, g.dil_w)
+    n = B.conv_num_variants()
+    names = [B.lib.q8_conv_variant_name(v).decode() for v in range(n)]
+    split = [v for v in range(n) if "split" in names[v]]
+    assert len(split) >= 4
+    factors = (2, 3, 5, 7)
+    need = max(B.conv_workspace_bytes(d, v, f) for v in split for f in factors)
+    ws = torch.zeros(max(need, 256), dtype=torch.uint8, device="cuda")
+    for k, v in enumerate(split):
+        for f in factors:
+            _run_conv_case(B, geom, relu=bool((k + f) % 2), with_res=bool(k % 2), with_bias=True,
+                           seed=7000 + 100 * idx + 10 * k + f, variant=v, n_split=f, workspace=ws)
+    if need:
+        words = B.conv_workspace_bytes(d, split[0], 2)      # (an upper bound on the counters)
+        assert not host(ws[:min(words, 4096)]).view(np.int32)[:16].any()
 
 
 PW_CASES = [     # 1x1, stride 1, no padding, C in {64, 128, 256}: what the pointwise family takes
