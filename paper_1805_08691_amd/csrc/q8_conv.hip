@@ -141,8 +141,7 @@ int pick_variant(const q8_conv_desc* d, int forced = -1) {
   // pointwise layers on 64 channels with many pixel tiles: persistent workgroups (a layer the
   // build cannot take -- odd strides, a dump of the accumulators -- goes to the generic kernel)
   if (d->R * d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 && d->pad_w == 0 &&
-      d->C == 64 && (d->K & 15) == 0 && (long)d->N * d->H * d->W >= 128L * 512 &&
-      getenv("Q8_NO_PW") == nullptr)
+      d->C == 64 && (d->K & 15) == 0 && (long)d->N * d->H * d->W >= 128L * 512)
     return q8::first_pw_variant();
   const int nk = (red + 63) / 64;     // reduction steps of 64 bytes
   const long M = (long)d->N * out_extent(d->H, d->pad_h, d->dil_h, d->R, d->stride_h) *
@@ -305,6 +304,10 @@ int conv_fill(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const 
     Q8_REQUIRE(xb + lead < 0x7fffffffL && wb < 0x7fffffffL, Q8_EUNSUPPORTED);
     p.x_bytes = (int)xb;
     p.w_bytes = (int)wb;
+    // tile order over the XCDs: filters larger than the activations the layer reads -> every
+    // XCD keeps a slice of the filters and sees all pixels, else the other way round
+    const long x_read = (d->R * d->S == 1) ? xb / ((long)d->stride_h * d->stride_w) : xb;
+    p.ptile_fastest = x_read < wb ? 1 : 0;
   }
   p.x = z_x; p.w = (const int8_t*)z_w_packed; p.bias = bias_i32; p.res = residual; p.y = z_y;
   p.res_bytes = (residual && M * (long)p.res_cs < 0x7fffffffL) ? (int)(M * (long)p.res_cs) : 0;

@@ -80,8 +80,6 @@ struct ChainHeader {
   int n_items[kNumXcd];
   int item_off[kNumXcd];                   // first entry of XCD x in the item array
   int head_off[kNumXcd];                   // word of XCD x's queue head in the workspace
-  int trace_off[kNumXcd];                  // 0, or word of XCD x's trace records (4 per queue entry:
-                                           // 100 MHz clock at claim / inputs ready / done, HW_ID)
 };
 
 // item: layer << 24 | ctile << 16 | ptile
@@ -173,9 +171,6 @@ __global__ __launch_bounds__(kChainThreads, kWgPerCu) void conv_chain_kernel(
     const int li = item >> 24, ctile = (item >> 16) & 255, ptile = item & 0xffff;
     const ChainLayerDev& L = layers[li];
     const ConvParams& p = params[li * kNumXcd + x];
-    const int trace = hd.trace_off[x];
-    int t_claim = 0;
-    if (trace) t_claim = (int)__builtin_amdgcn_s_memrealtime();
     if (wave == 0) {
       const int pix0 = ptile * L.bp;
       const int pix1 = min(pix0 + L.bp, p.M) - 1;
@@ -195,8 +190,6 @@ __global__ __launch_bounds__(kChainThreads, kWgPerCu) void conv_chain_kernel(
       if (!ok) __hip_atomic_fetch_max(ws + kWsStatus, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();      // the producers' results are in the L2; nothing of them is in this L1
-    int t_ready = 0;
-    if (trace) t_ready = (int)__builtin_amdgcn_s_memrealtime();
     switch (L.variant) {
       case 0: q8::conv_tile_ring<2, 2, 2, 2, 64, 3, 1, 0>(p, ptile, ctile, lds); break;
       case 1: q8::conv_tile_ring<2, 2, 2, 1, 64, 4, 1, 0>(p, ptile, ctile, lds); break;
@@ -207,17 +200,9 @@ __global__ __launch_bounds__(kChainThreads, kWgPerCu) void conv_chain_kernel(
     q8::wait_vmcnt<0>();
     __syncthreads();
     if (wave == 0) {
-      if (lane == 0) {
+      if (lane == 0)
         __hip_atomic_fetch_add(ws + L.done_off[x] + ptile, 1, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (trace) {
-          int* rec = ws + trace + 4 * idx;
-          rec[0] = t_claim;
-          rec[1] = t_ready;
-          rec[2] = (int)__builtin_amdgcn_s_memrealtime();
-          rec[3] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);     // HW_ID
-        }
-      }
     }
   }
 #endif
@@ -345,12 +330,6 @@ int chain_layout(const q8_chain_layer* layers, int n, std::vector<ChainLayerDev>
     ws_words += (region_words[x] + 31) & ~31L;
     Q8_REQUIRE(ws_words < 0x3fffffffL, Q8_EUNSUPPORTED);
   }
-  if (getenv("Q8_CHAIN_TRACE")) {          // measurement: a record per queue entry
-    for (int x = 0; x < kNumXcd; ++x) {
-      hd->trace_off[x] = (int)ws_words;
-      ws_words += (4 * n_items[x] + 31) & ~31L;
-    }
-  }
   long total_items = 0;
   for (int x = 0; x < kNumXcd; ++x) {
     Q8_REQUIRE(n_items[x] < 0x7fffffffL, Q8_EUNSUPPORTED);
@@ -440,10 +419,6 @@ int q8_conv_chain_plan(const q8_chain_layer* layers, int n_layers, void* plan_ho
       n_cu = prop.multiProcessorCount;
   }
   hd.grid = n_cu * kWgPerCu;
-  if (const char* e = getenv("Q8_CHAIN_WGS")) {      // experiments: fewer workgroups per CU
-    const int w = atoi(e);
-    if (w >= 1 && w <= kWgPerCu) hd.grid = n_cu * w;
-  }
   memcpy(out, &hd, sizeof(hd));
   memcpy(out + sz.layers_off, L.data(), L.size() * sizeof(ChainLayerDev));
   ConvParams* params = (ConvParams*)(out + sz.params_off);

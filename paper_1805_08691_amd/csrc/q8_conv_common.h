@@ -34,6 +34,11 @@ struct ConvParams {
   int red_len;    // reduction bytes per filter (R*S*C, or R*S4*16 in the 4-channel mode)
   int S4;         // 4-channel mode: 16-byte chunks per filter row (ceil(S/4))
   int n_ptiles, n_ctiles;
+  // Which tiles an XCD works on (each XCD has an L2 of its own and takes a contiguous run of
+  // the tile order).  0: channel tile fastest -- an XCD holds few pixel tiles and every filter;
+  // 1: pixel tile fastest -- an XCD holds few channel tiles and every pixel.  The host picks
+  // what fetches fewer bytes over all eight L2s (filters 8 times, or activations 8 times).
+  int ptile_fastest;
   int x_bytes, w_bytes;   // sizes of the activation and filter tensors (buffer descriptors)
   int res_bytes;          // size of the residual tensor, 0 if none or beyond 2 GiB
   unsigned div_img_m, div_img_s;   // division of a pixel index by Ho*Wo (see fast_div)

@@ -310,7 +310,9 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_halo3_kernel(const ConvP
 #ifdef Q8_TRACE
   const unsigned long long q8_t0 = __builtin_amdgcn_s_memrealtime();
 #endif
-  conv_tile_halo3<WP, WC, TP, TC, PL>(p, bid / p.n_ctiles, bid % p.n_ctiles, lds);
+  const int ptile = p.ptile_fastest ? bid % p.n_ptiles : bid / p.n_ctiles;
+  const int ctile = p.ptile_fastest ? bid / p.n_ptiles : bid % p.n_ctiles;
+  conv_tile_halo3<WP, WC, TP, TC, PL>(p, ptile, ctile, lds);
 #ifdef Q8_TRACE
   q8_trace_record(p, q8_t0);
 #endif

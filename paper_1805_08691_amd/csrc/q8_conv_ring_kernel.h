@@ -827,8 +827,9 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_ring_kernel(const ConvPa
     conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR, 1>(
         p, tile / p.n_ctiles, tile % p.n_ctiles, lds, bid - tile * p.n_split);
   } else {
-    conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(p, bid / p.n_ctiles,
-                                                                  bid % p.n_ctiles, lds);
+    const int ptile = p.ptile_fastest ? bid % p.n_ptiles : bid / p.n_ctiles;
+    const int ctile = p.ptile_fastest ? bid / p.n_ptiles : bid % p.n_ctiles;
+    conv_tile_ring<WP, WC, TP, TC, BK, STAGES, UNIFORM, U8, PAIR>(p, ptile, ctile, lds);
   }
 #ifdef Q8_TRACE
   q8_trace_record(p, q8_t0);

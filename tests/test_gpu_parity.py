@@ -156,6 +156,8 @@ CONV_CASES = [
     dict(N=1, H=3, W=3, C=256, K=16, R=3, S=3),
     dict(N=4, H=1, W=1, C=256, K=84, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=2, H=37, W=41, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
+    dict(N=2, H=37, W=40, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),  # rows of
+    dict(N=3, H=9, W=12, C=3, K=64, R=3, S=3, pad_h=1, pad_w=1),     # whole 4-pixel groups
     dict(N=1, H=20, W=20, C=3, K=32, R=3, S=3, stride_h=2, stride_w=2),
     dict(N=1, H=16, W=16, C=4, K=8, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=1, H=7, W=7, C=512, K=2048 // 8, R=1, S=1),
