@@ -332,6 +332,38 @@ def test_conv_pointwise_tile_family(B, idx):
                            out_pad=16 * (k % 2), out_off=16 * (k % 2), dump_acc=False)
 
 
+@pytest.mark.parametrize("q", [0.03, 0.0078125, 1.0 / 3.0, 0.0123456789, 5.5e-3])
+def test_quantize_image_next_to_ties(B, q):
+    """Eq. Q on values whose quotient r/q lies on, and within a few ulps of, every tie k + 1/2
+    and every integer k of the code range (and beyond its ends): the image kernel, which only
+    divides where a product with 1/q cannot decide the rounding, must give the oracle's codes."""
+    q = np.float32(q)
+    ks = np.arange(-131, 131, dtype=np.float64)
+    centres = np.concatenate([ks + 0.5, ks]) * np.float64(q)
+    vals = []
+    for c in centres.astype(np.float32):
+        v = c
+        for _ in range(6):
+            v = np.nextafter(v, np.float32(-np.inf), dtype=np.float32)
+        for _ in range(13):
+            vals.append(v)
+            v = np.nextafter(v, np.float32(np.inf), dtype=np.float32)
+    vals = np.array(vals, dtype=np.float32)
+    n_pix = -(-vals.size // 3)
+    W = 8
+    Hh = -(-n_pix // W)
+    r = np.zeros((1, Hh, W, 3), np.float32)
+    r.reshape(-1)[:vals.size] = vals
+    want = orc.Q(r, q, 7)
+    ties = np.abs(np.abs(vals.astype(np.float64) / np.float64(q)) % 1.0 - 0.5) < 1e-4
+    assert ties.sum() > 2000                                 # the cases are what they claim to be
+    frame = torch.zeros((1, Hh, W, 4), dtype=torch.int8, device="cuda")
+    B.quantize_image(dev(r), float(q), 7, frame, 0, 0)
+    got = host(frame)
+    assert np.array_equal(got[..., :3], want)
+    assert not got[..., 3].any()
+
+
 @pytest.mark.parametrize("geom", [
     dict(N=2, H=37, W=41, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
     dict(N=1, H=39, W=39, C=3, K=64, R=3, S=3, stride_h=2, stride_w=2),
