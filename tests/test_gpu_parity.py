@@ -268,6 +268,33 @@ def test_conv_3x3_tile_family(B, idx):
                        seed=1000 * idx + v, variant=v)
 
 
+P3_CASES = [     # 3x3, stride 1, padding 1, C = 64, K <= 64: what the persistent 3x3 family takes
+    dict(N=2, H=56, W=56, C=64, K=64),        # several tiles per workgroup? no: one pass, ragged end
+    dict(N=40, H=28, W=28, C=64, K=64),       # more tiles than resident workgroups: two passes
+    dict(N=3, H=7, W=7, C=64, K=64),          # several images inside one pixel tile
+    dict(N=1, H=5, W=63, C=64, K=48),         # the widest map of the narrow patch, K short of the tile
+    dict(N=1, H=3, W=100, C=64, K=64),        # only the wide patch takes it
+    dict(N=1, H=1, W=1, C=64, K=16),          # one pixel
+    dict(N=2, H=1, W=17, C=64, K=32),         # one row: no tap above or below
+]
+
+
+@pytest.mark.parametrize("idx", range(len(P3_CASES)))
+def test_conv_persistent_3x3_family(B, idx):
+    """Every build of the persistent 3x3 family (all filters resident in LDS, workgroups walk
+    over pixel tiles with the next tile's activation patch in flight) against the oracle; a
+    build whose patch is too narrow for the map hands the layer to the generic kernel."""
+    geom = dict(R=3, S=3, pad_h=1, pad_w=1, **P3_CASES[idx])
+    n = B.conv_num_variants()
+    names = [B.lib.q8_conv_variant_name(v).decode() for v in range(n)]
+    p3 = [v for v in range(n) if "p3_kernel" in names[v]]
+    assert len(p3) >= 2
+    for k, v in enumerate(p3):
+        _run_conv_case(B, geom, relu=bool(k % 2), with_res=False, with_bias=True,
+                       seed=5000 * idx + v, variant=v, out_pad=16 * (k % 2), out_off=16 * (k % 2),
+                       dump_acc=False)
+
+
 SPLIT_CASES = [   # long reductions over few output tiles: what a split reduction is for
     dict(N=5, H=7, W=7, C=512, K=512, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=3, H=14, W=14, C=1024, K=256, R=1, S=1),
