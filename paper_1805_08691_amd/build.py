@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.environ.get("Q8_OBJ_DIR") or os.path.join(HERE, "_build")
 LIB = os.environ.get("Q8_LIB_OUT") or os.path.join(HERE, "libq8conv.so")
 SOURCES = ["q8_conv_ring.hip", "q8_conv_ring_ext.hip", "q8_conv_ring_pair.hip", "q8_conv_chain.hip",
-           "q8_conv_halo.hip", "q8_conv_dual.hip", "q8_conv_pw.hip", "q8_conv_split.hip", "q8_conv_p3.hip",
+           "q8_conv_halo.hip", "q8_conv_dual.hip", "q8_conv_pw.hip", "q8_conv_split.hip", "q8_conv_p3.hip", "q8_conv_stem.hip",
            "q8_conv.hip", "q8_conv_reg.hip", "q8_elementwise.hip", "q8_helpers.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

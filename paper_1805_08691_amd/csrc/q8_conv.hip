@@ -22,6 +22,7 @@ int num_stream_variants();
 int num_ring_variants();
 int first_pw_variant();
 int first_p3_variant();
+int first_stem_variant();
 int first_split_variant();
 int num_split_variants();
 void split_variant_tile(int variant, int* bp, int* bc);
@@ -135,7 +136,17 @@ int pick_variant(const q8_conv_desc* d, int forced = -1) {
   const int tile = d->K > 64 ? 0 : d->K > 32 ? 1 : 2;      // 128x128, 256x64, 256x32
   if (!stream_capable(d)) return kRegBase + 3 * mode + tile;
   if (forced >= 0) return forced;
-  if (mode == 1) return d->K <= 64 ? 8 : 4;   // short reduction: small tiles, many per CU
+  if (mode == 1) {
+    // a first layer with up to eight taps per filter row, a stride and short output rows: the
+    // image's rows are the operand as they lie in memory (q8_conv_stem_kernel.h)
+    const int wo = out_extent(d->W, 0, 1, d->S, d->stride_w);
+    const int ho = out_extent(d->H, 0, 1, d->R, d->stride_h);
+    if (d->S > 4 && d->S <= 8 && d->R <= 8 && d->K <= 64 && (d->K & 15) == 0 && wo <= 128 &&
+        d->W <= 240 && d->stride_h <= 4 && d->stride_w <= 2 &&
+        (long)d->N * ho * wo >= 128L * 256 && wo >= 64)
+      return q8::first_stem_variant();
+    return d->K <= 64 ? 8 : 4;   // short reduction: small tiles, many per CU
+  }
   // 3x3 / stride 1 / padding 1 on 64 channels with K <= 64 and many pixel tiles: persistent
   // workgroups with every filter resident (narrow patch: maps up to 63 pixels wide)
   if (d->R == 3 && d->S == 3 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 1 &&

@@ -54,17 +54,25 @@ int num_p3_variants();
 int launch_p3_variant(int variant, ConvParams& p, hipStream_t stream);
 const char* p3_variant_name(int variant);
 
+// ... and the image-row family (q8_conv_stem.hip)
+int num_stem_variants();
+int launch_stem_variant(int variant, ConvParams& p, hipStream_t stream);
+const char* stem_variant_name(int variant);
+
 int num_ring_variants() { return kNumRingVariants; }
 int first_pw_variant() { return kNumRingVariants + num_halo_variants(); }
 int first_split_variant() { return first_pw_variant() + num_pw_variants(); }
 int first_p3_variant() { return first_split_variant() + num_split_variants(); }
-int num_stream_variants() { return first_p3_variant() + num_p3_variants(); }
+int first_stem_variant() { return first_p3_variant() + num_p3_variants(); }
+int num_stream_variants() { return first_stem_variant() + num_stem_variants(); }
 int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
   if (variant < 0 || variant >= num_stream_variants()) return Q8_EINVAL;
   if (p.in_u8 | p.out_u8 | p.res_u8 | (p.m_vec != nullptr)) {
     // variants without an extended build fall back to the 128 x 128 ring of 3
     return launch_ring_ext_variant(variant < kNumRingExtVariants ? variant : 1, p, stream);
   }
+  if (variant >= first_stem_variant())
+    return launch_stem_variant(variant - first_stem_variant(), p, stream);
   if (variant >= first_p3_variant()) return launch_p3_variant(variant - first_p3_variant(), p, stream);
   if (variant >= first_split_variant())
     return launch_split_variant(variant - first_split_variant(), p, stream);
@@ -73,6 +81,7 @@ int launch_stream_variant(int variant, ConvParams& p, hipStream_t stream) {
   return kRingVariants[variant].launch(p, stream);
 }
 const char* stream_variant_name(int variant) {
+  if (variant >= first_stem_variant()) return stem_variant_name(variant - first_stem_variant());
   if (variant >= first_p3_variant()) return p3_variant_name(variant - first_p3_variant());
   if (variant >= first_split_variant()) return split_variant_name(variant - first_split_variant());
   if (variant >= first_pw_variant()) return pw_variant_name(variant - first_pw_variant());

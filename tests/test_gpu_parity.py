@@ -295,6 +295,38 @@ def test_conv_persistent_3x3_family(B, idx):
                        dump_acc=False)
 
 
+STEM_CASES = [   # unpadded 4-channel images, 5..8 taps per filter row: the image-row family
+    dict(N=2, H=43, W=47, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2),
+    dict(N=3, H=230, W=230, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2),   # ResNet-50's first layer
+    dict(N=3, H=20, W=240, C=4, K=48, R=5, S=8, stride_h=1, stride_w=2),    # the widest image, K short
+    dict(N=1, H=12, W=100, C=3, K=16, R=3, S=5),                            # stride 1
+    dict(N=2, H=40, W=60, C=2, K=32, R=8, S=6, stride_h=4, stride_w=2),     # 8 + 4 rows in the ring
+    dict(N=37, H=19, W=33, C=1, K=64, R=7, S=7, stride_h=2, stride_w=2),    # many images, short strips
+    dict(N=1, H=9, W=200, C=3, K=64, R=3, S=5),                             # rows too long: generic kernel
+]
+
+
+@pytest.mark.parametrize("idx", range(len(STEM_CASES)))
+def test_conv_image_row_family(B, idx):
+    """The image-row family (filters resident, a ring of image rows in LDS as the activation
+    operand, workgroups walking down strips of output rows) against the oracle, with and
+    without ReLU and with a strided output; ResNet-50's first layer also picks it by itself."""
+    geom = STEM_CASES[idx]
+    n = B.conv_num_variants()
+    names = [B.lib.q8_conv_variant_name(v).decode() for v in range(n)]
+    stem = [v for v in range(n) if "stem_kernel" in names[v]]
+    assert len(stem) == 1
+    for k in range(2):
+        _run_conv_case(B, geom, relu=bool(k), with_res=False, with_bias=bool(k), seed=7000 + 10 * idx + k,
+                       variant=stem[0], out_pad=16 * k, out_off=16 * k, dump_acc=False)
+    if idx == 1:
+        g = orc.ConvGeom(**geom)
+        d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, 0, 0, 1, 1,
+                       relu=1, in_c_stride=4)
+        assert "stem_kernel" in B.conv_variant(d)
+        _run_conv_case(B, geom, relu=True, with_res=False, with_bias=True, seed=7777, dump_acc=False)
+
+
 SPLIT_CASES = [   # long reductions over few output tiles: what a split reduction is for
     dict(N=5, H=7, W=7, C=512, K=512, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=3, H=14, W=14, C=1024, K=256, R=1, S=1),
