@@ -330,6 +330,33 @@ int q8_conv_chain_static_status(int32_t *status_host);
  * For measurement code that groups launches by kernel.                              */
 const char *q8_conv_variant(const q8_conv_desc *d);
 
+/* The head of a network as ONE launch: Eq. Q on the real-valued image, the first layer on the
+ * codes (Eq. x / Eq. A' with bias, ReLU and requantisation as q8_conv_int8) and, with pool = 1,
+ * the 3x3 / stride 2 / padding 1 max-pool behind it (the maximum of codes, which keeps q_out).
+ * The result is, bit for bit, that of q8_quantize_image into a zero frame, q8_conv_int8 on the
+ * frame and q8_maxpool_i8 on its output; the int8 image and, with pool = 1, the layer's own
+ * output are never written to memory.
+ *   d      the layer over the zero frame, as it would be given to q8_conv_int8 after
+ *          q8_quantize_image: d->H x d->W the frame, no padding, d->C = C <= 4,
+ *          in_c_stride 4 (or 0); out_c_stride / out_c_off place the output channels;
+ *   r_dev  device, fp32 [N][H][W][C], 4-byte aligned; pixel (n, h, w) lies at pixel
+ *          (top + h, left + w) of the frame, whose other pixels are zeros;
+ *   q_x, p Eq. Q's factor and bit count (1 <= p <= 7);  z_w_packed, bias_i32, q_w, q_out as
+ *          q8_conv_int8 (filters packed by q8_pack_weights for d);
+ *   z_y    device, int8 [N][Ho][Wo][out_c_stride], or with pool = 1
+ *          [N][(Ho-1)/2+1][(Wo-1)/2+1][out_c_stride]; 16-byte aligned, strides % 16 == 0.
+ * Layers taken: 5 .. 8 filter columns, at most 8 filter rows, stride 1 or 2 (pool: vertical
+ * stride 2), K <= 64 with K % 16 == 0, output rows of at most 128 pixels, frames at most 240
+ * pixels wide.  Q8_EUNSUPPORTED otherwise (q8_conv_image_f32_supported says so beforehand:
+ * 1 / 0); the caller then makes the three calls.  Q8_EINVAL for an image that does not fit
+ * the frame or C != d->C, Q8_EALIGN as q8_conv_int8.                                       */
+int q8_conv_image_f32_supported(const q8_conv_desc *d, int H, int W, int C, int top, int left,
+                                int pool);
+int q8_conv_image_f32_int8(const q8_conv_desc *d, const float *r_dev, int H, int W, int C,
+                           int top, int left, float q_x, int p, const void *z_w_packed,
+                           const int32_t *bias_i32, float q_w, float q_out, int pool,
+                           int8_t *z_y, void *stream);
+
 /* Tests and tuning only: q8_conv_int8 with the tile / ring variant of the main kernel given
  * by the caller (0 .. q8_conv_num_variants() - 1, in the order of the library's variant
  * table; -1 = automatic choice, i.e. q8_conv_int8 itself).  The variant is used wherever the

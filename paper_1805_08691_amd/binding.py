@@ -32,6 +32,7 @@ EXPORTS = [
     "q8_conv_chain_static_status",
     "q8_conv_variant", "q8_conv_num_variants", "q8_conv_variant_name", "q8_conv_int8_variant", "q8_sum_factor",
     "q8_conv_workspace_bytes", "q8_conv_workspace_bytes_variant",
+    "q8_conv_image_f32_supported", "q8_conv_image_f32_int8",
     "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
@@ -129,6 +130,8 @@ lib.q8_conv_variant_name.restype = C.c_char_p
 lib.q8_conv_variant_name.argtypes = [_i]
 lib.q8_conv_int8_variant.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _i, _i, _vp,
                                      C.c_size_t, _vp]
+lib.q8_conv_image_f32_supported.argtypes = [_dp, _i, _i, _i, _i, _i, _i]
+lib.q8_conv_image_f32_int8.argtypes = [_dp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _vp, _f, _f, _i, _vp, _vp]
 lib.q8_sum_factor.restype = _f
 lib.q8_sum_factor.argtypes = [_f, _f]
 lib.q8_probe_mfma_i8.argtypes = [_i, _i, _vp, _vp]
@@ -258,6 +261,25 @@ def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q
         _check(lib.q8_conv_int8_variant(*args, int(variant), int(n_split), *ws, _stream()))
     else:
         _check(lib.q8_conv_int8(*args, *ws, _stream()))
+    return out
+
+
+def conv_image_f32_supported(desc, H, W, Cc, top, left, pool=0):
+    return bool(lib.q8_conv_image_f32_supported(C.byref(desc), H, W, Cc, top, left, int(pool)))
+
+
+def conv_image_f32(desc, r, top, left, q_x, p, z_w_packed, bias_i32, q_w, q_out, pool=0, out=None):
+    """Eq. Q on the fp32 image r [N,H,W,C<=4], the layer ``desc`` (given over the zero frame
+    that holds r at (top, left)) and, with ``pool``, the 3x3/2 max-pool, as one launch."""
+    N, H, W, Cc = r.shape
+    assert N == desc.N
+    if out is None:
+        Ho, Wo = ((desc.Ho - 1) // 2 + 1, (desc.Wo - 1) // 2 + 1) if pool else (desc.Ho, desc.Wo)
+        out = torch.empty((N, Ho, Wo, desc.out_c_stride or desc.K), dtype=torch.int8, device=r.device)
+    _check(lib.q8_conv_image_f32_int8(C.byref(desc), _ptr(r, torch.float32), H, W, Cc, top, left,
+                                      q_x, p, _ptr(z_w_packed, torch.int8),
+                                      _ptr(bias_i32, torch.int32), q_w, q_out, int(pool),
+                                      _ptr(out, torch.int8), _stream()))
     return out
 
 

@@ -23,6 +23,7 @@ int num_ring_variants();
 int first_pw_variant();
 int first_p3_variant();
 int first_stem_variant();
+int launch_stem_image(ConvParams& p, const StemImage& im, int pool, bool dry_run, hipStream_t stream);
 int first_split_variant();
 int num_split_variants();
 void split_variant_tile(int variant, int* bp, int* bc);
@@ -142,7 +143,7 @@ int pick_variant(const q8_conv_desc* d, int forced = -1) {
     const int wo = out_extent(d->W, 0, 1, d->S, d->stride_w);
     const int ho = out_extent(d->H, 0, 1, d->R, d->stride_h);
     if (d->S > 4 && d->S <= 8 && d->R <= 8 && d->K <= 64 && (d->K & 15) == 0 && wo <= 128 &&
-        d->W <= 240 && d->stride_h <= 4 && d->stride_w <= 2 &&
+        d->W <= 240 && d->stride_h <= 2 && d->stride_w <= 2 &&
         (long)d->N * ho * wo >= 128L * 256 && wo >= 64)
       return q8::first_stem_variant();
     return d->K <= 64 ? 8 : 4;   // short reduction: small tiles, many per CU
@@ -557,6 +558,50 @@ int q8_conv_int8(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packe
   u.workspace_bytes = workspace_bytes;
   return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual, q_res, z_y,
                      acc_dump, stream);
+}
+
+// Eq. Q on the image + its first layer (+ max-pool): see include/q8conv.h.  dry_run: checks only.
+static int conv_image_f32(const q8_conv_desc* d, const float* r_dev, int H, int W, int C, int top,
+                          int left, float q_x, int p_bits, const void* z_w_packed,
+                          const int32_t* bias_i32, float q_w, float q_out, int pool, int8_t* z_y,
+                          bool dry_run, void* stream) {
+  Q8_REQUIRE(desc_sane(d) && p_bits >= 1 && p_bits <= 7 && (pool == 0 || pool == 1), Q8_EINVAL);
+  Q8_REQUIRE(H >= 1 && W >= 1 && C >= 1 && C <= 4 && C == d->C && top >= 0 && left >= 0 &&
+                 d->H >= top + H && d->W >= left + W, Q8_EINVAL);
+  if (!image_rows_contiguous(d)) return Q8_EUNSUPPORTED;
+  Q8_REQUIRE(r_dev != nullptr && q8_aligned(r_dev, 4), r_dev ? Q8_EALIGN : Q8_EINVAL);
+  q8::ConvParams p;
+  bool empty = false;
+  // the layer over the zero frame; its int8 input pointer only stands in (never read)
+  const int rc = conv_fill(d, U8Flags{0, 0, 0, nullptr}, reinterpret_cast<const int8_t*>(r_dev),
+                           z_w_packed, bias_i32, q_x, q_w, q_out, nullptr, 0.0f, z_y, nullptr, p,
+                           &empty);
+  if (rc != Q8_OK || empty) return rc;
+  q8::StemImage im;
+  im.r = r_dev; im.H = H; im.W = W; im.C = C; im.top = top; im.left = left;
+  im.q = q_x;
+  im.hi = (float)((1 << p_bits) - 1);
+  im.lo = -(float)(1 << p_bits);
+  im.Hp = (p.Ho - 1) / 2 + 1;
+  im.Wp = (p.Wo - 1) / 2 + 1;
+  return q8::launch_stem_image(p, im, pool, dry_run, (hipStream_t)stream);
+}
+
+int q8_conv_image_f32_int8(const q8_conv_desc* d, const float* r_dev, int H, int W, int C, int top,
+                           int left, float q_x, int p, const void* z_w_packed,
+                           const int32_t* bias_i32, float q_w, float q_out, int pool, int8_t* z_y,
+                           void* stream) {
+  return conv_image_f32(d, r_dev, H, W, C, top, left, q_x, p, z_w_packed, bias_i32, q_w, q_out,
+                        pool, z_y, false, stream);
+}
+
+int q8_conv_image_f32_supported(const q8_conv_desc* d, int H, int W, int C, int top, int left,
+                                int pool) {
+  // stand-in pointers with the alignment a caller's buffers must have
+  const auto fake = [](uintptr_t a) { return reinterpret_cast<void*>(a); };
+  return conv_image_f32(d, static_cast<const float*>(fake(256)), H, W, C, top, left, 1.0f, 7,
+                        fake(512), nullptr, 1.0f, 1.0f, pool, static_cast<int8_t*>(fake(768)), true,
+                        nullptr) == Q8_OK ? 1 : 0;
 }
 
 size_t q8_conv_workspace_bytes(const q8_conv_desc* d) {

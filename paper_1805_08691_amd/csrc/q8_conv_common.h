@@ -78,6 +78,16 @@ struct ConvParams {
 #endif
 };
 
+// The real-valued image of the image-row family's fused builds (pixel (h, w) of image n lies
+// at pixel (top + h, left + w) of the zero frame the layer's descriptor describes) and the
+// extent of the pooled output.
+struct StemImage {
+  const float* r;     // [N][H][W][C] fp32
+  int H, W, C, top, left;
+  float q, lo, hi;    // Eq. Q: factor and code range
+  int Hp, Wp;         // with the max-pool: pooled rows and columns
+};
+
 // x / d for 0 <= x < 2^31 with host-made constants s = ceil(log2 d), m = ceil(2^(31+s) / d):
 // m * d exceeds 2^(31+s) by less than d <= 2^s, so x * m / 2^(31+s) exceeds x / d by less
 // than 1/d and has the same integer part.

@@ -10,18 +10,25 @@
 //  * keeps all filters in LDS (K rows of R x 32 bytes, 272-byte pitch so that 16 lanes on 16
 //    consecutive rows hit 16 distinct bank groups),
 //  * walks down a strip of output rows of one image with a ring of 16 input rows in LDS:
-//    each new output row needs only stride_h new input rows, which are requested
-//    (global -> LDS, one wave-wide load per row) while the current row is computed,
+//    each new output row needs only stride_h new input rows, which are requested ahead,
 //  * computes one output row per pass: wave w owns pixels 32 w .. 32 w + 31 and all 64
 //    channels, R x 2 MFMAs, operands straight from LDS (activations as two 8-byte reads),
 //  * writes the row's codes through a row-ordered staging tile: an output row is one
 //    contiguous run of Wo x K bytes in NHWC.
-// The generic kernel spends ~450 vector instructions per wave on this layer's addressing;
-// here the addressing of a whole row is a handful of scalar operations.
+// Two options turn the layer into the whole head of a network in one launch:
+//  F32IN: the input is the real-valued image [N][H][W][C <= 4]; the workgroup applies Eq. Q to
+//         the rows it loads and builds the zero frame in LDS -- the int8 image never exists
+//         in memory;
+//  POOL:  the 3x3 / stride 2 / padding 1 max-pool behind the layer: the maximum over three
+//         output rows is kept in registers (on the rounded, clamped fp32 values, whose order
+//         is that of the codes), the maximum over three columns is taken on the codes in the
+//         staging tile, and only the pooled rows are written.
 #pragma once
 #include "q8_conv_ring_kernel.h"
+#include "q8_quant.h"
 
 namespace q8 {
+
 namespace {
 
 struct StemShape {
@@ -34,8 +41,30 @@ struct StemShape {
   static constexpr int LDS_BYTES = FILT_BYTES + RING_BYTES + S_BYTES;
 };
 
-// p.n_ptiles = strips per image, p.n_ctiles = output rows per strip (set by launch_stem).
-__global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p) {
+// Bytewise maximum of signed bytes flipped to unsigned order (x ^ 0x80 per byte), on the
+// even and the odd bytes of a word as two pairs of 16-bit lanes.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+struct SplitBytes { u16x2 even, odd; };
+__device__ __forceinline__ SplitBytes split_bytes(unsigned w) {
+  SplitBytes s;
+  s.even = __builtin_bit_cast(u16x2, w & 0x00ff00ffu);
+  s.odd = __builtin_bit_cast(u16x2, (w >> 8) & 0x00ff00ffu);
+  return s;
+}
+__device__ __forceinline__ SplitBytes max_bytes(SplitBytes a, SplitBytes b) {
+  SplitBytes m;
+  m.even = __builtin_elementwise_max(a.even, b.even);
+  m.odd = __builtin_elementwise_max(a.odd, b.odd);
+  return m;
+}
+__device__ __forceinline__ unsigned join_bytes(SplitBytes s) {
+  return __builtin_bit_cast(unsigned, s.even) | (__builtin_bit_cast(unsigned, s.odd) << 8);
+}
+
+// p.n_ptiles = strips per image, p.n_ctiles = output rows (POOL: pooled rows) per strip, set by
+// launch_stem.  SH: the vertical stride (the number of image rows a new output row adds).
+template <int SH, bool F32IN, bool POOL>
+__global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, const StemImage im) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using Sh = StemShape;
   constexpr int NW = Sh::NW, BP = Sh::BP, BC = Sh::BC, SLOTS = BC / 16;
@@ -46,16 +75,23 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int R = p.R, sh = p.stride_h;
+  const int R = p.R;
+  constexpr int sh = SH;
   const int strips = p.n_ptiles, rows_per_strip = p.n_ctiles;
   const int n = blockIdx.x / strips;
-  const int ho_first = (blockIdx.x - n * strips) * rows_per_strip;
-  const int ho_end = min(ho_first + rows_per_strip, p.Ho);
+  // output rows [ho_first, ho_end) of image n; POOL: those under pooled rows [j_first, j_end)
+  const int j_first = (blockIdx.x - n * strips) * rows_per_strip;
+  const int j_end = min(j_first + rows_per_strip, POOL ? im.Hp : p.Ho);
+  const int ho_first = POOL ? max(2 * j_first - 1, 0) : j_first;
+  const int ho_end = POOL ? min(2 * j_end, p.Ho) : j_end;
 
   const __amdgpu_buffer_rsrc_t rsrc_w =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, p.w_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, p.x_bytes, 0x00020000);
+  const int y_rows = POOL ? p.N * im.Hp * im.Wp : p.M;
+  const __amdgpu_buffer_rsrc_t rsrc_y =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.y, 0, y_rows * p.out_cs, 0x00020000);
 
   // ---- filters, once: LDS row rho (272 bytes: the R * 32 filter bytes, then padding) holds
   // channel (rho & ~31) + row_to_channel(rho & 31); 16-byte cell number i * 64 + lane of load i
@@ -74,18 +110,71 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p) {
       }
     }
   }
-  // ---- input rows: row hi of image n goes to ring slot hi % 16, requested by wave hi % 4 as
-  // one wave-wide load of 1 KB (the bytes behind the row's end belong to the next row, or read
-  // as zeros past the tensor: they only meet pixels that are not stored)
+
+  // ---- input rows: row hi of the frame goes to ring slot hi % 16.
+  // Codes in memory: every wave requests a quarter of the row (64 lanes x 4 bytes), so that all
+  // waves have the same number of requests in flight.  The bytes behind the row's end belong to
+  // the next row, or read as zeros past the tensor: they only meet zero filter bytes or pixels
+  // that are not stored.
   const int row_bytes = p.W * 4;
-  const int img_off = n * p.H * row_bytes;
+  const int lane_off = n * p.H * row_bytes + wave * 256 + lane * 4;
   auto issue_row = [&](int hi) {
-    if ((hi & 3) == wave && hi < p.H)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          rsrc_x, (__attribute__((address_space(3))) void*)(ring + (hi & 15) * Sh::ROW_BYTES), 16,
-          img_off + hi * row_bytes + lane * 16, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        rsrc_x,
+        (__attribute__((address_space(3))) void*)(ring + (hi & 15) * Sh::ROW_BYTES + wave * 256), 4,
+        lane_off + hi * row_bytes, 0, 0, 0);
   };
-  for (int r = 0; r < R; ++r) issue_row(ho_first * sh + r);
+  // Real-valued image: thread t holds pixel t of a row.  A row of the frame above or below the
+  // image is a row of zeros (Q(0) = 0); the frame's columns left and right of the image are
+  // zeroed once, below, and never written again.
+  const float inv_q = F32IN ? __fdiv_rn(1.0f, im.q) : 0.0f;
+  auto load_row = [&](int hi, float (&f)[4]) {
+    const int h = hi - im.top;
+    const bool inside = (unsigned)h < (unsigned)im.H && tid < im.W;
+    const float* const src = im.r + ((size_t)(n * im.H + (inside ? h : 0)) * im.W + (inside ? tid : 0)) * im.C;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) f[c] = 0.0f;
+    if (inside) {
+      if (im.C == 3) {
+        f[0] = src[0]; f[1] = src[1]; f[2] = src[2];
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (c < im.C) f[c] = src[c];
+      }
+    }
+  };
+  auto store_row = [&](int hi, const float (&f)[4]) {
+    int z[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) z[c] = quant1_fast(f[c], im.q, inv_q, im.lo, im.hi);
+    if (tid < im.W)
+      *reinterpret_cast<unsigned*>(ring + (hi & 15) * Sh::ROW_BYTES + (im.left + tid) * 4) =
+          pack4(z[0], z[1], z[2], z[3]);
+  };
+
+  if constexpr (F32IN) {
+    for (int c = tid; c < Sh::RING_BYTES / 16; c += NW * 64)
+      *reinterpret_cast<v4i*>(ring + c * 16) = v4i{0, 0, 0, 0};
+    __syncthreads();
+#pragma unroll
+    for (int r0 = 0; r0 < 8; r0 += 4) {          // the first output row's image rows, four at a time
+      if (r0 < R) {
+        float f[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (r0 + r < R) load_row(ho_first * sh + r0 + r, f[r]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (r0 + r < R) store_row(ho_first * sh + r0 + r, f[r]);
+      }
+    }
+  } else {
+    // the rows of the strip's first output row, and what the second one adds
+    for (int r = 0; r < R; ++r) issue_row(ho_first * sh + r);
+    if (ho_first + 1 < ho_end)
+      for (int r = R - sh; r < R; ++r) issue_row((ho_first + 1) * sh + r);
+  }
 
   // ---- fragments.  Filters: LDS row tc * 32 + (lane & 31), bytes r * 32 + 16 * (lane >> 5).
   // Activations: pixel 32 wave + (lane & 31) of the output row, same half.
@@ -95,14 +184,34 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p) {
   int bias_v[2][16];
 #pragma unroll
   for (int tc = 0; tc < 2; ++tc) load_bias16(p, tc * 32 + 16 * frag_half, bias_v[tc]);
-  const float no_scales[16] = {};
+  const float code_lo = p.relu ? 0.0f : -128.0f;          // ReLU folded into the lower bound
+  constexpr float kMagic = 12582912.0f;                   // 1.5 * 2^23: t + kMagic rounds t to an
+                                                          // integer, held in the low mantissa bits
+  // POOL: running maximum over the output rows of the open pooling window
+  float win[2][16];
+#pragma unroll
+  for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) win[tc][e] = kMagic - 128.0f;
 
   wait_vmcnt<0>();
   __syncthreads();
   for (int ho = ho_first; ho < ho_end; ++ho) {
-    // the rows the NEXT output row adds (their slots were last read eight or more rows ago)
-    if (ho + 1 < ho_end)
-      for (int r = R - sh; r < R; ++r) issue_row((ho + 1) * sh + r);
+    // Requests ahead.  Codes: the rows the output row after the next adds (R + 2 SH <= 16:
+    // their slots hold rows that no wave reads any more); in flight, oldest first: the next
+    // row's SH requests, the stores of the row before, these SH requests.  Real-valued image:
+    // the rows the next output row adds, into registers; they are quantised into the ring
+    // behind this row's arithmetic.
+    const bool ahead = F32IN ? ho + 1 < ho_end : ho + 2 < ho_end;
+    float pre[SH][4];
+    if (ahead) {
+      if constexpr (F32IN) {
+#pragma unroll
+        for (int s = 0; s < SH; ++s) load_row((ho + 1) * sh + R - sh + s, pre[s]);
+      } else {
+        for (int r = R - sh; r < R; ++r) issue_row((ho + 2) * sh + r);
+      }
+    }
 
     v16i acc[2];
 #pragma unroll
@@ -136,53 +245,122 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p) {
       }
     }
 
-    // ---- epilogue through the staging tile
-    {
+    // ---- epilogue (the fixed fp32 sequence of the layer's tail: convert, scale, clamp with
+    // ReLU as the lower bound, Round by adding 1.5 * 2^23), then through the staging tile.
+    // POOL: an even output row 2j joins the window of pooled row j; an odd row 2j + 1 closes
+    // it -- the window's maximum is what goes to the staging tile -- and opens the next one.
+    bool emit = true;
+    int y_row = ho;                                    // the output row the staging tile holds
+    float t[2][16];
+#pragma unroll
+    for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        t[tc][e] = __builtin_amdgcn_fmed3f((float)acc[tc][e] * p.m, code_lo, 127.0f) + kMagic;
+    if constexpr (POOL) {
+      const bool odd = ho & 1;
+      emit = (odd && ho != ho_first) || (!odd && ho == p.Ho - 1);
+      y_row = ho >> 1;
+#pragma unroll
+      for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float m = fmaxf(win[tc][e], t[tc][e]);
+          win[tc][e] = odd ? t[tc][e] : m;
+          t[tc][e] = m;
+        }
+    }
+    if (emit) {
       const int row = wave * 32 + frag_row;
 #pragma unroll
       for (int tc = 0; tc < 2; ++tc) {
         const int slot = tc * 2 + frag_half;
-        int v[16];
+        v4i out;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = acc[tc][e];
-        const int rw[4] = {0, 0, 0, 0};
-        *reinterpret_cast<v4i*>(stage + row * BC + ((slot ^ swz_out<SLOTS>(row)) << 4)) =
-            codes16_fast<false>(p, v, rw, no_scales);
+        for (int a = 0; a < 4; ++a) {
+          const unsigned w01 = __builtin_amdgcn_perm(__float_as_uint(t[tc][4 * a + 1]),
+                                                     __float_as_uint(t[tc][4 * a]), 0x0c0c0400u);
+          const unsigned w23 = __builtin_amdgcn_perm(__float_as_uint(t[tc][4 * a + 3]),
+                                                     __float_as_uint(t[tc][4 * a + 2]), 0x0c0c0400u);
+          out[a] = (int)__builtin_amdgcn_perm(w23, w01, 0x05040100u);
+        }
+        *reinterpret_cast<v4i*>(stage + row * BC + ((slot ^ swz_out<SLOTS>(row)) << 4)) = out;
       }
     }
-    // the rows requested above have landed (so have the stores of the row before, long ago)
-    wait_vmcnt<0>();
-    __syncthreads();
-    {
-      int8_t* const y0 = p.y + ((size_t)(n * p.Ho + ho) * p.Wo) * p.out_cs + p.out_off;
+    if constexpr (F32IN) {
+      if (ahead) {
 #pragma unroll
-      for (int c = tid; c < BP * SLOTS; c += NW * 64) {      // two stores per lane
-        const int row = c / SLOTS, g = c % SLOTS;
-        if (row < p.Wo && g * 16 < p.K)
-          *reinterpret_cast<v4i*>(y0 + (size_t)row * p.out_cs + g * 16) =
-              *reinterpret_cast<const v4i*>(stage + row * BC + ((g ^ swz_out<SLOTS>(row)) << 4));
+        for (int s = 0; s < SH; ++s) store_row((ho + 1) * sh + R - sh + s, pre[s]);
       }
+    } else {
+      // the next output row's image rows have landed; the stores of the row before and the
+      // requests made above may still be in flight
+      if (ahead) wait_vmcnt<2 + SH>(); else wait_vmcnt<2>();
     }
-    // every wave has read the staging tile (its stores took the data) before the next row's
-    // codes are written into it; the stores themselves stay in flight
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wave's LDS writes are done
     __builtin_amdgcn_s_barrier();
+    if (emit) {
+      // exactly two store instructions per wave (what the counts above rely on): a lane with
+      // nothing to store issues its store out of the buffer's range, where it is dropped
+      if constexpr (POOL) {
+        // thread = (pooled pixel, 16-channel group): the maximum over columns 2w-1, 2w, 2w+1
+        const int wp = tid / SLOTS, g = tid % SLOTS;
+        SplitBytes m[4];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          int col = 2 * wp - 1 + k;
+          col = col < 0 ? 0 : (col >= p.Wo ? 2 * wp : col);     // outside: repeat a column inside
+          col = col >= BP ? BP - 1 : col;                       // (threads beyond the row: any)
+          const v4i cell =
+              *reinterpret_cast<const v4i*>(stage + col * BC + ((g ^ swz_out<SLOTS>(col)) << 4));
+#pragma unroll
+          for (int a = 0; a < 4; ++a) {
+            const SplitBytes s = split_bytes((unsigned)cell[a] ^ 0x80808080u);
+            m[a] = k == 0 ? s : max_bytes(m[a], s);
+          }
+        }
+        v4i codes;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) codes[a] = (int)(join_bytes(m[a]) ^ 0x80808080u);
+        const int y_off = ((n * im.Hp + y_row) * im.Wp) * p.out_cs + p.out_off;
+        const int off = (wp < im.Wp && g * 16 < p.K) ? y_off + wp * p.out_cs + g * 16 : kOobOffset;
+        __builtin_amdgcn_raw_buffer_store_b128(codes, rsrc_y, off, 0, 0);
+      } else {
+        const int y_off = ((n * p.Ho + y_row) * p.Wo) * p.out_cs + p.out_off;
+#pragma unroll
+        for (int k = 0; k < BP * SLOTS / (NW * 64); ++k) {
+          const int c = tid + k * NW * 64;
+          const int row = c / SLOTS, g = c % SLOTS;
+          const v4i codes =
+              *reinterpret_cast<const v4i*>(stage + row * BC + ((g ^ swz_out<SLOTS>(row)) << 4));
+          const int off = (row < p.Wo && g * 16 < p.K) ? y_off + row * p.out_cs + g * 16 : kOobOffset;
+          __builtin_amdgcn_raw_buffer_store_b128(codes, rsrc_y, off, 0, 0);
+        }
+      }
+      // every wave has read the staging tile (its stores took the data) before the next
+      // row's codes are written into it; the stores themselves stay in flight
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+    }
   }
   wait_vmcnt<0>();
 #endif
 }
 
-inline bool stem_applicable(const ConvParams& p) {
-  return p.S4 == 2 && p.S == 1 && p.C == 32 && p.in_cs == 4 && p.R <= 8 && p.K <= 64 &&
-         (p.K & 15) == 0 && p.Wo <= 128 && p.W <= 240 && p.stride_h >= 1 && p.stride_h <= 4 && p.stride_w <= 2 &&
-         p.R + p.stride_h <= 12 && p.pad_h == 0 && p.pad_w == 0 && p.vec16 && !p.res &&
-         !p.acc_dump && !p.y_f32 && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 &&
-         !p.tap_sums && (long)p.N * p.H * p.W * 4 < 0x7fffffffL;
+// Layers the family takes (codes in memory; the F32IN / POOL entry adds its own conditions).
+template <int SH>
+bool stem_applicable(const ConvParams& p) {
+  return p.stride_h == SH && p.R + 2 * SH <= 16 && p.S4 == 2 && p.S == 1 && p.C == 32 &&
+         p.in_cs == 4 && p.R <= 8 && p.K <= 64 && (p.K & 15) == 0 && p.Wo <= 128 && p.W <= 240 &&
+         p.stride_w <= 2 && p.pad_h == 0 && p.pad_w == 0 && p.vec16 && !p.res && !p.acc_dump &&
+         !p.y_f32 && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 && !p.tap_sums &&
+         (long)p.N * p.H * p.W * 4 < 0x7fffffffL && (long)p.M * p.out_cs < 0x7fffffffL;
 }
 
-inline int launch_stem(ConvParams& p, hipStream_t stream) {
+template <int SH, bool F32IN, bool POOL>
+int launch_stem(ConvParams& p, const StemImage& im, hipStream_t stream) {
   using Sh = StemShape;
-  auto kernel = conv_i8_stem_kernel;
+  auto kernel = conv_i8_stem_kernel<SH, F32IN, POOL>;
   static const hipError_t attr = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
       Sh::LDS_BYTES);
@@ -198,16 +376,18 @@ inline int launch_stem(ConvParams& p, hipStream_t stream) {
     return per_cu * cus;
   }();
   // strips per image: about as many workgroups as stay resident, at least four rows each
+  // (POOL: three pooled rows, i.e. seven output rows of which one is computed twice)
+  const int rows = POOL ? im.Hp : p.Ho, least = POOL ? 3 : 4;
   int strips = (resident + p.N - 1) / p.N;
-  if (strips > (p.Ho + 3) / 4) strips = (p.Ho + 3) / 4;
+  if (strips > (rows + least - 1) / least) strips = (rows + least - 1) / least;
   if (strips < 1) strips = 1;
-  const int rows_per_strip = (p.Ho + strips - 1) / strips;
-  strips = (p.Ho + rows_per_strip - 1) / rows_per_strip;
+  const int rows_per_strip = (rows + strips - 1) / strips;
+  strips = (rows + rows_per_strip - 1) / rows_per_strip;
   p.n_ptiles = strips;
   p.n_ctiles = rows_per_strip;
   const long grid = (long)p.N * strips;
   if (grid > 0x7fffffffL) return Q8_EUNSUPPORTED;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), Sh::LDS_BYTES, stream, p);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), Sh::LDS_BYTES, stream, p, im);
   return q8_launch_status();
 }
 

@@ -327,6 +327,71 @@ def test_conv_image_row_family(B, idx):
         _run_conv_case(B, geom, relu=True, with_res=False, with_bias=True, seed=7777, dump_acc=False)
 
 
+HEAD_CASES = [   # image (N, H, W, C), filter, strides, padding = the zero frame around the image
+    dict(N=2, H=37, W=41, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),
+    dict(N=3, H=224, W=224, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),  # ResNet-50
+    dict(N=1, H=24, W=20, C=1, K=48, R=5, S=5, stride_h=2, stride_w=2, pad_h=2, pad_w=2),
+    dict(N=2, H=33, W=232, C=4, K=32, R=8, S=8, stride_h=2, stride_w=2, pad_h=4, pad_w=4),   # widest frame
+    dict(N=35, H=19, W=33, C=2, K=16, R=3, S=6, stride_h=2, stride_w=1, pad_h=1, pad_w=2),
+    dict(N=1, H=3, W=9, C=3, K=64, R=7, S=7, stride_h=2, stride_w=2, pad_h=3, pad_w=3),       # one or two rows
+    dict(N=2, H=18, W=30, C=3, K=64, R=5, S=7, stride_h=1, stride_w=1, pad_h=2, pad_w=3),     # stride 1: no pool
+]
+
+
+@pytest.mark.parametrize("idx", range(len(HEAD_CASES)))
+def test_conv_image_f32_head(B, idx):
+    """Eq. Q on the real-valued image, the first layer and the 3x3 / 2 max-pool as one launch
+    against the oracle's three steps (quantise, padded convolution + requantisation, max-pool
+    of the codes); values next to rounding ties and beyond the code range are in the image."""
+    geom = HEAD_CASES[idx]
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(900 + idx)
+    r = rng.standard_normal((g.N, g.H, g.W, g.C)).astype(np.float32)
+    q_x = orc.qfactor(np.float32(2.9), 7)                       # |r| > 2.9 saturates
+    flat = r.reshape(-1)
+    where = rng.choice(flat.size, flat.size // 7, replace=False)
+    ties = ((rng.integers(-130, 130, where.size).astype(np.float32) + np.float32(0.5)) * q_x).astype(np.float32)
+    toward = np.float32([-np.inf, 0.0, np.inf])[rng.integers(0, 3, where.size)]
+    flat[where] = np.nextafter(ties, toward)                    # a tie or an fp32 neighbour of it
+    z_x = orc.Q(r, q_x, 7)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-2000, 2000, g.K).astype(np.int32)
+    q_w = np.float32(0.004)
+    q_out = np.float32(q_x * q_w * 74 * 40 * np.sqrt(g.R * g.S * g.C) / 40.0)
+    Hs, Ws = g.H + 2 * g.pad_h, g.W + 2 * g.pad_w
+    d = B.ConvDesc(g.N, Hs, Ws, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, 0, 0, 1, 1,
+                   relu=1, in_c_stride=4)
+    packed = B.pack_weights(d, dev(w))
+    for relu in (1, 0):
+        d.relu = relu
+        conv = orc.requant(orc.conv_i8(g, z_x, w, b), orc.requant_scale(q_x, q_w, q_out), bool(relu))
+        for pool in (0, 1):
+            ok = B.conv_image_f32_supported(d, g.H, g.W, g.C, g.pad_h, g.pad_w, pool)
+            assert ok == (not (pool and g.stride_h != 2))
+            if not ok:
+                continue
+            want = orc.maxpool_i8(conv, 3, 3, 2, 1, (g.Ho - 1) // 2 + 1, (g.Wo - 1) // 2 + 1) if pool else conv
+            out = torch.full(want.shape, 77, dtype=torch.int8, device="cuda")
+            B.conv_image_f32(d, dev(r), g.pad_h, g.pad_w, float(q_x), 7, packed, dev(b), float(q_w),
+                             float(q_out), pool=pool, out=out)
+            assert np.array_equal(host(out), want), f"relu={relu} pool={pool}"
+
+
+def test_conv_image_f32_head_rejects(B):
+    """Host checks of the fused head: a layer outside the family is unsupported, an image that
+    does not fit its frame is invalid."""
+    d = B.ConvDesc(1, 30, 30, 3, 64, 3, 3, 1, 1, 0, 0, 1, 1, relu=1, in_c_stride=4)   # 3 columns
+    assert not B.conv_image_f32_supported(d, 28, 28, 3, 1, 1, 0)
+    d = B.ConvDesc(1, 30, 30, 3, 64, 7, 7, 2, 2, 0, 0, 1, 1, relu=1, in_c_stride=4)
+    assert B.conv_image_f32_supported(d, 24, 24, 3, 3, 3, 1)
+    assert not B.conv_image_f32_supported(d, 28, 24, 3, 3, 3, 1)                     # 3 + 28 > 30
+    assert not B.conv_image_f32_supported(d, 24, 24, 4, 3, 3, 1)                     # C != d.C
+    r = torch.zeros((1, 28, 24, 3), dtype=torch.float32, device="cuda")
+    w = torch.zeros((64, 7, 7, 3), dtype=torch.int8, device="cuda")
+    with pytest.raises(B.Q8Error):
+        B.conv_image_f32(d, r, 3, 3, 0.02, 7, B.pack_weights(d, w), None, 0.01, 0.5)
+
+
 SPLIT_CASES = [   # long reductions over few output tiles: what a split reduction is for
     dict(N=5, H=7, W=7, C=512, K=512, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=3, H=14, W=14, C=1024, K=256, R=1, S=1),
