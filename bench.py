@@ -89,6 +89,9 @@ def main():
     ap.add_argument("--no-cold", action="store_true",
                     help="skip the per-layer timing with caches flushed before every layer")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
+    ap.add_argument("--no-fuse-head", action="store_true",
+                    help="quantise the input, run the first layer and its max-pool as three "
+                         "launches instead of one")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2, 3, 4),
                     help="number of concurrent part-batch pipelines the layers run as (2: two "
                          "half-batch pipelines, the default and the headline configuration)")
@@ -150,7 +153,9 @@ def main():
     eng = Engine(net, N, n_streams=args.streams, unsigned_activations=args.unsigned_activations,
                  per_channel_weights=args.per_channel_weights, real_outputs=args.real_output,
                  own_sum_factor=args.own_sum_factor, fuse_pairs=args.fuse_pairs,
-                 fuse_duals=args.fuse_duals)
+                 fuse_duals=args.fuse_duals,
+                 fuse_head=not (args.no_fuse_head or args.unsigned_activations
+                                or args.per_channel_weights))
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -263,7 +268,7 @@ def main():
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(ops_list) + 3)]
         torch.cuda._sleep(20_000_000)
         ev[0].record()
-        eng.quantize_input(x)
+        eng.set_input(x)                  # Eq. Q now, or inside the first layer's launches
         ev[1].record()
         for i, op in enumerate(ops_list):
             # the launches of one layer (one per half-batch when split) back to back on
@@ -274,6 +279,7 @@ def main():
         for name, buf in dequant.items():
             eng.dequantize(name, out=buf)
         ev[-1].record()
+        eng._x = None
         torch.cuda.synchronize()
         for i in range(len(ops_list) + 2):
             dur[r, i] = ev[i].elapsed_time(ev[i + 1]) * 1e3      # us
@@ -296,6 +302,7 @@ def main():
         cold_reps = 5
         cdur = np.zeros((cold_reps, len(ops_list)))
         for r in range(cold_reps):
+            eng._x = x if eng.head else None
             e0 = [torch.cuda.Event(enable_timing=True) for _ in ops_list]
             e1 = [torch.cuda.Event(enable_timing=True) for _ in ops_list]
             for i, op in enumerate(ops_list):
@@ -304,6 +311,7 @@ def main():
                 for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
                     eng.run_ops([op], lo, n)
                 e1[i].record()
+            eng._x = None
             torch.cuda.synchronize()
             for i in range(len(ops_list)):
                 cdur[r, i] = e0[i].elapsed_time(e1[i]) * 1e3
@@ -344,9 +352,12 @@ def main():
     del big
     n_in = x.numel()
     n_out = out_f32.numel()
+    # with the fused head Eq. Q on the input is not a launch of the step: timed on its own
+    t_qin = timed_us(lambda: eng.quantize_input(x)) if eng.head else float(med[0])
     passes = {
         "maxabs": dict(bytes=4 * 64 * 112 * 112 * 64, us=round(t_maxabs, 2)),
-        "quantize_input": dict(bytes=5 * n_in + n_in // 3, us=round(float(med[0]), 2)),
+        "quantize_input": dict(bytes=5 * n_in + n_in // 3, us=round(t_qin, 2),
+                               in_step=not eng.head),
         "dequantize_output": dict(bytes=5 * n_out, us=round(float(med[-1]), 2)),
     }
     if args.real_output:
@@ -363,6 +374,8 @@ def main():
     roof_us = 0.0
     helpers = []          # the pooling launches between convolutions (not the paper's method)
     for i, op in enumerate(ops_list):
+        if eng.head and op is eng.head[1]:
+            continue                      # ran inside the first layer's launch
         if op.kind != "conv":
             n_launch = len(eng.parts) if i >= eng.n_unsplit else 1
             s_t, d_t = net.tensors[op.src], net.tensors[op.dst]
@@ -384,10 +397,18 @@ def main():
             ops2, byts2 = conv_work(net, eng.pairs[op.name], N)     # them is not moved
             mid = net.tensors[op.dst]
             ops, byts = ops + ops2, byts + byts2 - 2 * N * mid.H * mid.W * mid.C
+        fused_head = bool(eng.head and op is eng.head[0])
+        if fused_head:                    # reads the fp32 image, writes the pooled tensor
+            t_img = net.tensors[net.input]
+            out_t = net.tensors[eng.head[1].dst] if eng.head[1] else net.tensors[op.dst]
+            byts = (4 * N * t_img.H * t_img.W * t_img.C + N * out_t.H * out_t.W * op.K
+                    + op.K * op.R * op.S * op.C + 4 * op.K)
         ops, byts = ops / n_launch, byts / n_launch          # per launch
         us = float(med[i + 1]) / n_launch
         us_cold = float(cold[i]) / n_launch
         variant = B.conv_variant(eng.conv_desc(op, n_img)) + ("+pair" if op.name in eng.pairs else "")
+        if fused_head:
+            variant += "<Q" + (",pool>" if eng.head[1] else ">")
         bound = "mfma" if ops / byts > RIDGE else "hbm"
         t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)) * 1e6
         layers.append(dict(name=op.name, C=op.C, K=op.K, R=op.R, S=op.S, stride=op.stride,

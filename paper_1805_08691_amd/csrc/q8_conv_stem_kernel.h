@@ -64,7 +64,7 @@ __device__ __forceinline__ unsigned join_bytes(SplitBytes s) {
 // p.n_ptiles = strips per image, p.n_ctiles = output rows (POOL: pooled rows) per strip, set by
 // launch_stem.  SH: the vertical stride (the number of image rows a new output row adds).
 template <int SH, bool F32IN, bool POOL>
-__global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, const StemImage im) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_i8_stem_kernel(const ConvParams p, const StemImage im) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using Sh = StemShape;
   constexpr int NW = Sh::NW, BP = Sh::BP, BC = Sh::BC, SLOTS = BC / 16;
@@ -145,9 +145,10 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, c
     }
   };
   auto store_row = [&](int hi, const float (&f)[4]) {
-    int z[4];
+    int z[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < 4; ++c) z[c] = quant1_fast(f[c], im.q, inv_q, im.lo, im.hi);
+    for (int c = 0; c < 4; ++c)
+      if (c < im.C) z[c] = quant1_fast(f[c], im.q, inv_q, im.lo, im.hi);
     if (tid < im.W)
       *reinterpret_cast<unsigned*>(ring + (hi & 15) * Sh::ROW_BYTES + (im.left + tid) * 4) =
           pack4(z[0], z[1], z[2], z[3]);
@@ -181,51 +182,65 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, c
   const int frag_row = lane & 31, frag_half = lane >> 5;
   const int a_off = frag_row * Sh::FILT_PITCH + 16 * frag_half;
   const int b_off = (wave * 32 + frag_row) * (p.stride_w * 4) + 16 * frag_half;
-  int bias_v[2][16];
+  v16i bias_v[2];
 #pragma unroll
-  for (int tc = 0; tc < 2; ++tc) load_bias16(p, tc * 32 + 16 * frag_half, bias_v[tc]);
+  for (int tc = 0; tc < 2; ++tc) {
+    int b[16];
+    load_bias16(p, tc * 32 + 16 * frag_half, b);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) bias_v[tc][e] = b[e];
+  }
   const float code_lo = p.relu ? 0.0f : -128.0f;          // ReLU folded into the lower bound
   constexpr float kMagic = 12582912.0f;                   // 1.5 * 2^23: t + kMagic rounds t to an
                                                           // integer, held in the low mantissa bits
-  // POOL: running maximum over the output rows of the open pooling window
-  float win[2][16];
+  // POOL: running maximum of the ACCUMULATORS over the output rows of the open pooling window.
+  // The layer's tail (scale by m > 0, clamp, Round) never decreases when the accumulator
+  // grows, so the maximum of the codes is the code of the maximum: the tail runs once per
+  // pooled row, on the window's maximum.
+  v16i win[2];
 #pragma unroll
   for (int tc = 0; tc < 2; ++tc)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) win[tc][e] = kMagic - 128.0f;
+    for (int e = 0; e < 16; ++e) win[tc][e] = (int)0x80000000;
 
   wait_vmcnt<0>();
   __syncthreads();
-  for (int ho = ho_first; ho < ho_end; ++ho) {
-    // Requests ahead.  Codes: the rows the output row after the next adds (R + 2 SH <= 16:
-    // their slots hold rows that no wave reads any more); in flight, oldest first: the next
-    // row's SH requests, the stores of the row before, these SH requests.  Real-valued image:
-    // the rows the next output row adds, into registers; they are quantised into the ring
-    // behind this row's arithmetic.
-    const bool ahead = F32IN ? ho + 1 < ho_end : ho + 2 < ho_end;
-    float pre[SH][4];
-    if (ahead) {
-      if constexpr (F32IN) {
+
+  // Real-valued image: two register buffers of image rows, each requested two passes before
+  // it is quantised into the ring (pre_a: what output rows ho_first + 1, + 3, ... add).
+  float pre_a[SH][4], pre_b[SH][4];
+  auto new_row = [&](int ho, int s) { return ho * sh + R - sh + s; };   // s-th row that ho adds
+  if constexpr (F32IN) {
+    if (ho_first + 1 < ho_end) {
 #pragma unroll
-        for (int s = 0; s < SH; ++s) load_row((ho + 1) * sh + R - sh + s, pre[s]);
-      } else {
+      for (int s = 0; s < SH; ++s) load_row(new_row(ho_first + 1, s), pre_a[s]);
+    }
+    if (ho_first + 2 < ho_end) {
+#pragma unroll
+      for (int s = 0; s < SH; ++s) load_row(new_row(ho_first + 2, s), pre_b[s]);
+    }
+  }
+
+  // One output row.  pre (real-valued image): the rows output row ho + 1 adds.
+  auto row_pass = [&](int ho, float (&pre)[SH][4]) {
+    if constexpr (!F32IN) {
+      // Codes: request the rows the output row after the next adds (R + 2 SH <= 16: their
+      // slots hold rows that no wave reads any more).  In flight, oldest first: the next
+      // row's SH requests, the stores of the row before, these SH requests.
+      if (ho + 2 < ho_end)
         for (int r = R - sh; r < R; ++r) issue_row((ho + 2) * sh + r);
-      }
     }
 
+    // a few filter rows at a time: their fragments are requested together (rows beyond R read
+    // valid LDS and are not used); the bias is the first MFMA's addend
+    constexpr int GR = POOL ? 2 : 4;                   // POOL holds 32 more registers
     v16i acc[2];
 #pragma unroll
-    for (int tc = 0; tc < 2; ++tc)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[tc][e] = bias_v[tc][e];
-    // four filter rows at a time: their fragments are requested together (rows beyond R read
-    // valid LDS and are not used)
-#pragma unroll
-    for (int r0 = 0; r0 < 8; r0 += 4) {
+    for (int r0 = 0; r0 < 8; r0 += GR) {
       if (r0 < R) {
-        v4i af[4][2], bf[4];
+        v4i af[GR][2], bf[GR];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < GR; ++r) {
           const int8_t* const row = ring + ((ho * sh + r0 + r) & 15) * Sh::ROW_BYTES + b_off;
           const long long b0 = *reinterpret_cast<const long long*>(row);
           const long long b1 = *reinterpret_cast<const long long*>(row + 8);
@@ -236,66 +251,77 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, c
                                                       (r0 + r) * 32);
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < GR; ++r)
           if (r0 + r < R) {
 #pragma unroll
             for (int tc = 0; tc < 2; ++tc)
-              acc[tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][tc], bf[r], acc[tc], 0, 0, 0);
+              acc[tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                  af[r][tc], bf[r], (r0 + r == 0) ? bias_v[tc] : acc[tc], 0, 0, 0);
           }
       }
     }
 
-    // ---- epilogue (the fixed fp32 sequence of the layer's tail: convert, scale, clamp with
-    // ReLU as the lower bound, Round by adding 1.5 * 2^23), then through the staging tile.
-    // POOL: an even output row 2j joins the window of pooled row j; an odd row 2j + 1 closes
-    // it -- the window's maximum is what goes to the staging tile -- and opens the next one.
+    // ---- POOL: an even output row 2j joins the window of pooled row j; an odd row 2j + 1
+    // closes it -- the window's maximum is what goes on -- and opens the next one.
     bool emit = true;
     int y_row = ho;                                    // the output row the staging tile holds
-    float t[2][16];
-#pragma unroll
-    for (int tc = 0; tc < 2; ++tc)
-#pragma unroll
-      for (int e = 0; e < 16; ++e)
-        t[tc][e] = __builtin_amdgcn_fmed3f((float)acc[tc][e] * p.m, code_lo, 127.0f) + kMagic;
     if constexpr (POOL) {
       const bool odd = ho & 1;
       emit = (odd && ho != ho_first) || (!odd && ho == p.Ho - 1);
       y_row = ho >> 1;
+      if (odd) {
 #pragma unroll
-      for (int tc = 0; tc < 2; ++tc)
+        for (int tc = 0; tc < 2; ++tc)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float m = fmaxf(win[tc][e], t[tc][e]);
-          win[tc][e] = odd ? t[tc][e] : m;
-          t[tc][e] = m;
-        }
+          for (int e = 0; e < 16; ++e) {
+            const int a = acc[tc][e];
+            acc[tc][e] = max(win[tc][e], a);
+            win[tc][e] = a;
+          }
+      } else {
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[tc][e] = win[tc][e] = max(win[tc][e], acc[tc][e]);
+      }
     }
+    // ---- the layer's tail (the fixed fp32 sequence: convert, scale, clamp with ReLU as the
+    // lower bound, Round by adding 1.5 * 2^23, low byte = code) into the staging tile
     if (emit) {
       const int row = wave * 32 + frag_row;
 #pragma unroll
       for (int tc = 0; tc < 2; ++tc) {
         const int slot = tc * 2 + frag_half;
+        unsigned t[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          t[e] = __float_as_uint(
+              __builtin_amdgcn_fmed3f((float)acc[tc][e] * p.m, code_lo, 127.0f) + kMagic);
         v4i out;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-          const unsigned w01 = __builtin_amdgcn_perm(__float_as_uint(t[tc][4 * a + 1]),
-                                                     __float_as_uint(t[tc][4 * a]), 0x0c0c0400u);
-          const unsigned w23 = __builtin_amdgcn_perm(__float_as_uint(t[tc][4 * a + 3]),
-                                                     __float_as_uint(t[tc][4 * a + 2]), 0x0c0c0400u);
+          const unsigned w01 = __builtin_amdgcn_perm(t[4 * a + 1], t[4 * a], 0x0c0c0400u);
+          const unsigned w23 = __builtin_amdgcn_perm(t[4 * a + 3], t[4 * a + 2], 0x0c0c0400u);
           out[a] = (int)__builtin_amdgcn_perm(w23, w01, 0x05040100u);
         }
         *reinterpret_cast<v4i*>(stage + row * BC + ((slot ^ swz_out<SLOTS>(row)) << 4)) = out;
       }
     }
     if constexpr (F32IN) {
-      if (ahead) {
+      // the next output row's image rows into the ring (R + SH <= 16: slots nobody reads);
+      // the buffer then takes what the row three further down adds
+      if (ho + 1 < ho_end) {
 #pragma unroll
-        for (int s = 0; s < SH; ++s) store_row((ho + 1) * sh + R - sh + s, pre[s]);
+        for (int s = 0; s < SH; ++s) store_row(new_row(ho + 1, s), pre[s]);
+      }
+      if (ho + 3 < ho_end) {
+#pragma unroll
+        for (int s = 0; s < SH; ++s) load_row(new_row(ho + 3, s), pre[s]);
       }
     } else {
       // the next output row's image rows have landed; the stores of the row before and the
       // requests made above may still be in flight
-      if (ahead) wait_vmcnt<2 + SH>(); else wait_vmcnt<2>();
+      if (ho + 2 < ho_end) wait_vmcnt<2 + SH>(); else wait_vmcnt<2>();
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wave's LDS writes are done
     __builtin_amdgcn_s_barrier();
@@ -315,8 +341,8 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, c
               *reinterpret_cast<const v4i*>(stage + col * BC + ((g ^ swz_out<SLOTS>(col)) << 4));
 #pragma unroll
           for (int a = 0; a < 4; ++a) {
-            const SplitBytes s = split_bytes((unsigned)cell[a] ^ 0x80808080u);
-            m[a] = k == 0 ? s : max_bytes(m[a], s);
+            const SplitBytes sb = split_bytes((unsigned)cell[a] ^ 0x80808080u);
+            m[a] = k == 0 ? sb : max_bytes(m[a], sb);
           }
         }
         v4i codes;
@@ -342,6 +368,10 @@ __global__ __launch_bounds__(256) void conv_i8_stem_kernel(const ConvParams p, c
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
     }
+  };
+  for (int ho = ho_first; ho < ho_end; ho += 2) {
+    row_pass(ho, pre_a);
+    if (ho + 1 < ho_end) row_pass(ho + 1, pre_b);
   }
   wait_vmcnt<0>();
 #endif

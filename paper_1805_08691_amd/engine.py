@@ -33,8 +33,15 @@ class Engine:
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
                  per_channel_weights=False, real_outputs=False, own_sum_factor=False,
-                 fuse_pairs=False, chain=False, fuse_duals=False):
+                 fuse_pairs=False, chain=False, fuse_duals=False, fuse_head=False):
         self.net = net
+        # fuse_head: Eq. Q on the input image, the first convolution and the max-pool behind it
+        # run as one launch per pipeline where the library has a build for them (same
+        # results; the image's codes and the convolution's own output are then not written
+        # in a step that starts from the real-valued batch)
+        self.fuse_head = fuse_head
+        self.head = None      # (first conv, the pool fused into it or None)
+        self._x = None        # the real-valued batch of the running step (fused head)
         # fuse_duals: two consecutive convolutions that read the same tensor and do not depend on
         # each other (a stage's projection branch and its first 1x1) run as one launch where
         # the library has a tile-shape pair for them
@@ -123,9 +130,36 @@ class Engine:
         if fuse_pairs:
             assert not (unsigned_activations or per_channel_weights)
             self._find_pairs()
+        if fuse_head:
+            assert not (unsigned_activations or per_channel_weights or chain)
+            self._find_head()
         if fuse_duals:
             assert not (unsigned_activations or per_channel_weights or real_outputs)
             self._find_duals()
+
+    def _find_head(self):
+        ops, t_in = self.net.ops, self.net.tensors[self.net.input]
+        if not self.in_frame or not ops or ops[0].kind != "conv" or ops[0].src != self.net.input:
+            return
+        conv = ops[0]
+        if conv.res or conv.dst_c_off or conv.name in self.pairs or conv.name in self.duals \
+                or conv.dst in self.real:
+            return
+        top, left = self.in_frame[:2]
+        pool = None
+        if len(ops) > 1 and ops[1].kind == "pool" and ops[1].src == conv.dst:
+            o = ops[1]
+            others = [u for u in ops[2:] if u.src == conv.dst or (u.kind == "conv" and u.res == conv.dst)]
+            s, d = self.net.tensors[o.src], self.net.tensors[o.dst]
+            if (o.mode == "max" and (o.R, o.S, o.stride, o.pad) == (3, 3, 2, 1) and not others
+                    and conv.dst not in self.net.outputs and d.C == s.C and o.dst_c_off == 0
+                    and (d.H, d.W) == ((s.H - 1) // 2 + 1, (s.W - 1) // 2 + 1)):
+                pool = o
+        for cand in ((pool,) if pool is None else (pool, None)):
+            if B.conv_image_f32_supported(self.desc[conv.name], t_in.H, t_in.W, t_in.C, top, left,
+                                          1 if cand else 0):
+                self.head = (conv, cand)
+                return
 
     def _find_duals(self):
         ops = self.net.ops
@@ -330,6 +364,23 @@ class Engine:
         else:
             B.quantize(x, self.q[self.net.input], P_ACT, out=z)
 
+    def set_input(self, x):
+        """The real-valued batch of the next layers: with a fused head it is only remembered
+        (the head's launches apply Eq. Q), otherwise Eq. Q runs on it now."""
+        if self.head:
+            self._x = x
+        else:
+            self.quantize_input(x)
+
+    def run_head(self, lo, n):
+        conv, pool = self.head
+        packed, bias = self.wq[conv.name]
+        dst = pool.dst if pool else conv.dst
+        B.conv_image_f32(self.conv_desc(conv, n), self._x[lo:lo + n], self.in_frame[0],
+                         self.in_frame[1], self.q[self.net.input], P_ACT, packed, bias,
+                         self.qw[conv.name], self.q[conv.dst], pool=1 if pool else 0,
+                         out=self.act[dst][lo:lo + n])
+
     def run_pool(self, op, lo=0, n=None):
         n = self.N if n is None else n
         s, d = self.net.tensors[op.src], self.net.tensors[op.dst]
@@ -404,6 +455,12 @@ class Engine:
 
     def run_ops(self, ops, lo, n):
         for op in ops:
+            if self._x is not None and self.head:
+                if op is self.head[0]:
+                    self.run_head(lo, n)
+                    continue
+                if op is self.head[1]:
+                    continue             # ran inside the head's launch
             if op.kind == "pool":
                 self.run_pool(op, lo, n)
             else:
@@ -471,8 +528,9 @@ class Engine:
         quantise and dequantise launches -- splitting those two as well was slower;
         ``serial`` issues the same launches one pipeline after the other on the caller's
         stream."""
+        self._x = None
         if x is not None:
-            self.quantize_input(x)
+            self.set_input(x)
         if self.chain:
             self.run_chained()
         elif self.n_streams == 1 or serial:
@@ -492,6 +550,7 @@ class Engine:
                 self.run_ops([op], *self.parts[0])
             for side in self.side:
                 main.wait_stream(side)
+        self._x = None
         for name, out in (dequant or {}).items():
             self.dequantize(name, out=out)
 

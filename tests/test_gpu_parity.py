@@ -1069,7 +1069,8 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
                           per_channel=False, real_outputs=False, own_sum_factor=False,
-                          fuse_pairs=False, chain=False, chain_variants=None, fuse_duals=False):
+                          fuse_pairs=False, chain=False, chain_variants=None, fuse_duals=False,
+                          fuse_head=False):
     """Whole network at ``batch`` in the launch configuration the benchmark times; the
     oracle evaluates the images in ``picks`` (batch elements are independent once the
     factor table is frozen) and every tensor of the chain is compared bit for bit."""
@@ -1095,11 +1096,14 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
 
     eng = Engine(net, batch, n_streams=n_streams, unsigned_activations=unsigned,
                  per_channel_weights=per_channel, real_outputs=real_outputs,
-                 fuse_pairs=fuse_pairs, chain=chain, fuse_duals=fuse_duals)
+                 fuse_pairs=fuse_pairs, chain=chain, fuse_duals=fuse_duals, fuse_head=fuse_head)
+    assert bool(eng.head) == fuse_head
     assert bool(eng.duals) == fuse_duals
     assert eng.unsigned == U
     assert bool(eng.pairs) == fuse_pairs
     unwritten = {op.dst for op in net.convs() if op.name in eng.pairs}   # stay on chip
+    if eng.head and eng.head[1]:
+        unwritten.add(eng.head[0].dst)       # pooled inside the first layer's launch
     # outputs that leave the quantised domain as fp32 straight from their convolution
     real_want = {}
     if real_outputs:
@@ -1134,6 +1138,11 @@ def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2
     if chain:
         torch.cuda.synchronize()
         assert [c.status() for _, _, c in eng.chains] == [0] * len(eng.chains)
+    if eng.head:
+        # the head's launches quantised the image on the way in; the stand-alone Eq. Q (which
+        # the small-batch check below starts from) is checked here all the same
+        assert not host(eng.act[net.input]).any()
+        eng.quantize_input(xd)
     zi = host(eng.input_codes())
     if z_in.shape[-1] == 3:              # an image: stored with a zero fourth channel
         assert np.array_equal(zi[picks][..., :3], z_in) and np.all(zi[..., 3] == 0)
@@ -1236,6 +1245,13 @@ def test_resnet50_with_fused_layer_pairs(B):
     # every bottleneck's 3x3 -> 1x1 whose 3x3 has 64 or 128 filters runs as one launch, in
     # the benchmark's launch configuration
     _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, fuse_pairs=True)
+
+
+def test_resnet50_with_fused_head(B):
+    # Eq. Q on the image, the 7x7 / 2 layer and the 3x3 / 2 max-pool as one launch per half
+    # batch: the launch configuration the benchmark times
+    _sampled_images_check(B, 3, 64, [0, 31, 32, 63], n_cal=4, cal_batch=8, fuse_head=True)
+    _sampled_images_check(B, 3, 5, [0, 2, 4], n_cal=2, cal_batch=8, fuse_head=True, n_streams=1)
 
 
 def test_resnet50_with_dual_launches(B):
