@@ -125,30 +125,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         lane_off + hi * row_bytes, 0, 0, 0);
   };
   // Real-valued image: thread t holds pixel t of a row.  A row of the frame above or below the
-  // image is a row of zeros (Q(0) = 0); the frame's columns left and right of the image are
-  // zeroed once, below, and never written again.
+  // image is a row of zeros; the frame's columns left and right of the image are zeroed once,
+  // below, and never written again.  Every request is made unconditionally, from an address
+  // clamped into the image (what it brings is dropped when the row is quantised): the number
+  // of requests in flight is then the same in every pass and the waits can be exact.
   const float inv_q = F32IN ? __fdiv_rn(1.0f, im.q) : 0.0f;
+  const int c_off1 = min(1, im.C - 1), c_off2 = min(2, im.C - 1), c_off3 = min(3, im.C - 1);
+  const float* const img = im.r + ((size_t)n * im.H * im.W + min(tid, im.W - 1)) * im.C;
   auto load_row = [&](int hi, float (&f)[4]) {
-    const int h = hi - im.top;
-    const bool inside = (unsigned)h < (unsigned)im.H && tid < im.W;
-    const float* const src = im.r + ((size_t)(n * im.H + (inside ? h : 0)) * im.W + (inside ? tid : 0)) * im.C;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) f[c] = 0.0f;
-    if (inside) {
-      if (im.C == 3) {
-        f[0] = src[0]; f[1] = src[1]; f[2] = src[2];
-      } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (c < im.C) f[c] = src[c];
-      }
-    }
+    const int h = min(max(hi - im.top, 0), im.H - 1);
+    const float* const src = img + (size_t)h * im.W * im.C;
+    f[0] = src[0];
+    f[1] = src[c_off1];
+    f[2] = src[c_off2];
+    f[3] = src[c_off3];
   };
   auto store_row = [&](int hi, const float (&f)[4]) {
+    const bool row_inside = (unsigned)(hi - im.top) < (unsigned)im.H;
     int z[4] = {0, 0, 0, 0};
+    if (row_inside) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (c < im.C) z[c] = quant1_fast(f[c], im.q, inv_q, im.lo, im.hi);
+      for (int c = 0; c < 3; ++c) z[c] = quant1_fast(f[c], im.q, inv_q, im.lo, im.hi);
+      if (im.C > 3) z[3] = quant1_fast(f[3], im.q, inv_q, im.lo, im.hi);
+      if (im.C < 3) z[2] = 0;
+      if (im.C < 2) z[1] = 0;
+    }
     if (tid < im.W)
       *reinterpret_cast<unsigned*>(ring + (hi & 15) * Sh::ROW_BYTES + (im.left + tid) * 4) =
           pack4(z[0], z[1], z[2], z[3]);
@@ -163,8 +164,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
       if (r0 < R) {
         float f[4][4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (r0 + r < R) load_row(ho_first * sh + r0 + r, f[r]);
+        for (int r = 0; r < 4; ++r) load_row(ho_first * sh + r0 + r, f[r]);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
           if (r0 + r < R) store_row(ho_first * sh + r0 + r, f[r]);
@@ -211,14 +211,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   float pre_a[SH][4], pre_b[SH][4];
   auto new_row = [&](int ho, int s) { return ho * sh + R - sh + s; };   // s-th row that ho adds
   if constexpr (F32IN) {
-    if (ho_first + 1 < ho_end) {
 #pragma unroll
-      for (int s = 0; s < SH; ++s) load_row(new_row(ho_first + 1, s), pre_a[s]);
-    }
-    if (ho_first + 2 < ho_end) {
+    for (int s = 0; s < SH; ++s) load_row(new_row(ho_first + 1, s), pre_a[s]);
 #pragma unroll
-      for (int s = 0; s < SH; ++s) load_row(new_row(ho_first + 2, s), pre_b[s]);
-    }
+    for (int s = 0; s < SH; ++s) load_row(new_row(ho_first + 2, s), pre_b[s]);
   }
 
   // One output row.  pre (real-valued image): the rows output row ho + 1 adds.
@@ -314,10 +310,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
         for (int s = 0; s < SH; ++s) store_row(new_row(ho + 1, s), pre[s]);
       }
-      if (ho + 3 < ho_end) {
 #pragma unroll
-        for (int s = 0; s < SH; ++s) load_row(new_row(ho + 3, s), pre[s]);
-      }
+      for (int s = 0; s < SH; ++s) load_row(new_row(ho + 3, s), pre[s]);
     } else {
       // the next output row's image rows have landed; the stores of the row before and the
       // requests made above may still be in flight
