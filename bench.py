@@ -89,6 +89,10 @@ def main():
     ap.add_argument("--no-cold", action="store_true",
                     help="skip the per-layer timing with caches flushed before every layer")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of a HIP graph")
+    ap.add_argument("--fuse-dequant", action="store_true",
+                    help="Eq. D on the output inside the last layer's launches instead of a pass "
+                         "of its own (same values; measured slower on ResNet-50: the layer then "
+                         "takes the general epilogue and writes five times the bytes)")
     ap.add_argument("--no-fuse-head", action="store_true",
                     help="quantise the input, run the first layer and its max-pool as three "
                          "launches instead of one")
@@ -155,7 +159,8 @@ def main():
                  own_sum_factor=args.own_sum_factor, fuse_pairs=args.fuse_pairs,
                  fuse_duals=args.fuse_duals,
                  fuse_head=not (args.no_fuse_head or args.unsigned_activations
-                                or args.per_channel_weights))
+                                or args.per_channel_weights),
+                 fuse_dequant=args.fuse_dequant)
     eng.load_params(params)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -254,6 +259,7 @@ def main():
     # The host enqueues a whole chained pass behind a spin kernel so the GPU runs the
     # layers back to back; events between launches give each kernel's duration.
     ops_list = [o for o in net.ops]
+    fused_deq = {k: v for k, v in dequant.items() if eng._dequant_writer(k)}
     reps = 7
     # an event record costs GPU time of its own: measure the interval between back-to-back
     # records on the busy stream and take it off every interval below
@@ -269,6 +275,7 @@ def main():
         torch.cuda._sleep(20_000_000)
         ev[0].record()
         eng.set_input(x)                  # Eq. Q now, or inside the first layer's launches
+        eng._deq = dict(fused_deq)        # Eq. D inside the last layer's launches, or below
         ev[1].record()
         for i, op in enumerate(ops_list):
             # the launches of one layer (one per half-batch when split) back to back on
@@ -277,9 +284,10 @@ def main():
                 eng.run_ops([op], lo, n)
             ev[i + 2].record()
         for name, buf in dequant.items():
-            eng.dequantize(name, out=buf)
+            if name not in fused_deq:
+                eng.dequantize(name, out=buf)
         ev[-1].record()
-        eng._x = None
+        eng._x, eng._deq = None, {}
         torch.cuda.synchronize()
         for i in range(len(ops_list) + 2):
             dur[r, i] = ev[i].elapsed_time(ev[i + 1]) * 1e3      # us
@@ -303,6 +311,7 @@ def main():
         cdur = np.zeros((cold_reps, len(ops_list)))
         for r in range(cold_reps):
             eng._x = x if eng.head else None
+            eng._deq = dict(fused_deq)
             e0 = [torch.cuda.Event(enable_timing=True) for _ in ops_list]
             e1 = [torch.cuda.Event(enable_timing=True) for _ in ops_list]
             for i, op in enumerate(ops_list):
@@ -311,7 +320,7 @@ def main():
                 for lo, n in (eng.parts if i >= eng.n_unsplit else [(0, N)]):
                     eng.run_ops([op], lo, n)
                 e1[i].record()
-            eng._x = None
+            eng._x, eng._deq = None, {}
             torch.cuda.synchronize()
             for i in range(len(ops_list)):
                 cdur[r, i] = e0[i].elapsed_time(e1[i]) * 1e3
@@ -358,7 +367,9 @@ def main():
         "maxabs": dict(bytes=4 * 64 * 112 * 112 * 64, us=round(t_maxabs, 2)),
         "quantize_input": dict(bytes=5 * n_in + n_in // 3, us=round(t_qin, 2),
                                in_step=not eng.head),
-        "dequantize_output": dict(bytes=5 * n_out, us=round(float(med[-1]), 2)),
+        "dequantize_output": dict(bytes=5 * n_out, in_step=not fused_deq,
+                                  us=round(timed_us(lambda: eng.dequantize(out_name, out=out_f32))
+                                           if fused_deq else float(med[-1]), 2)),
     }
     if args.real_output:
         del passes["dequantize_output"]
@@ -403,12 +414,16 @@ def main():
             out_t = net.tensors[eng.head[1].dst] if eng.head[1] else net.tensors[op.dst]
             byts = (4 * N * t_img.H * t_img.W * t_img.C + N * out_t.H * out_t.W * op.K
                     + op.K * op.R * op.S * op.C + 4 * op.K)
+        if op.dst in fused_deq:           # also writes the fp32 values of its codes
+            byts += 4 * N * net.tensors[op.dst].H * net.tensors[op.dst].W * op.K
         ops, byts = ops / n_launch, byts / n_launch          # per launch
         us = float(med[i + 1]) / n_launch
         us_cold = float(cold[i]) / n_launch
         variant = B.conv_variant(eng.conv_desc(op, n_img)) + ("+pair" if op.name in eng.pairs else "")
         if fused_head:
             variant += "<Q" + (",pool>" if eng.head[1] else ">")
+        if op.dst in fused_deq:
+            variant += "+D"
         bound = "mfma" if ops / byts > RIDGE else "hbm"
         t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)) * 1e6
         layers.append(dict(name=op.name, C=op.C, K=op.K, R=op.R, S=op.S, stride=op.stride,

@@ -330,6 +330,18 @@ int q8_conv_chain_static_status(int32_t *status_host);
  * For measurement code that groups launches by kernel.                              */
 const char *q8_conv_variant(const q8_conv_desc *d);
 
+/* q8_conv_int8 that also applies Eq. D to its own output in the same launch, for a layer whose
+ * output leaves the quantised domain as fp32 AND is kept as codes: besides z_y it writes
+ *   r_y[i] = q_out * fp32(z_y[i])      (one fp32 multiplication, the arithmetic of q8_dequantize)
+ * for every element it writes of z_y, r_y being fp32 [N][Ho][Wo][out_c_stride] laid out like
+ * z_y (4-byte aligned; 16-byte aligned with strides % 4 == 0 for vector stores).  Saves the
+ * separate pass over the tensor.  Signed codes only; other arguments and errors as
+ * q8_conv_int8 (no accumulator dump, no workspace).                                        */
+int q8_conv_int8_dequantized(const q8_conv_desc *d, const int8_t *z_x, const void *z_w_packed,
+                             const int32_t *bias_i32, float q_x, float q_w, float q_out,
+                             const int8_t *residual, float q_res, int8_t *z_y, float *r_y,
+                             void *stream);
+
 /* The head of a network as ONE launch: Eq. Q on the real-valued image, the first layer on the
  * codes (Eq. x / Eq. A' with bias, ReLU and requantisation as q8_conv_int8) and, with pool = 1,
  * the 3x3 / stride 2 / padding 1 max-pool behind it (the maximum of codes, which keeps q_out).

@@ -32,7 +32,7 @@ EXPORTS = [
     "q8_conv_chain_static_status",
     "q8_conv_variant", "q8_conv_num_variants", "q8_conv_variant_name", "q8_conv_int8_variant", "q8_sum_factor",
     "q8_conv_workspace_bytes", "q8_conv_workspace_bytes_variant",
-    "q8_conv_image_f32_supported", "q8_conv_image_f32_int8",
+    "q8_conv_image_f32_supported", "q8_conv_image_f32_int8", "q8_conv_int8_dequantized",
     "q8_probe_mfma_i8",
     "q8_conv_f32_ref", "q8_maxpool_i8", "q8_maxpool_f32", "q8_pool_i8", "q8_pool_f32",
 ]
@@ -130,6 +130,7 @@ lib.q8_conv_variant_name.restype = C.c_char_p
 lib.q8_conv_variant_name.argtypes = [_i]
 lib.q8_conv_int8_variant.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _i, _i, _vp,
                                      C.c_size_t, _vp]
+lib.q8_conv_int8_dequantized.argtypes = [_dp, _vp, _vp, _vp, _f, _f, _f, _vp, _f, _vp, _vp, _vp]
 lib.q8_conv_image_f32_supported.argtypes = [_dp, _i, _i, _i, _i, _i, _i]
 lib.q8_conv_image_f32_int8.argtypes = [_dp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _vp, _f, _f, _i, _vp, _vp]
 lib.q8_sum_factor.restype = _f
@@ -262,6 +263,22 @@ def conv_int8(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q
     else:
         _check(lib.q8_conv_int8(*args, *ws, _stream()))
     return out
+
+
+def conv_int8_dequantized(desc, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual=None, q_res=0.0,
+                          out=None, out_f32=None):
+    """conv_int8 that also writes Eq. D of its output codes: -> (codes, fp32)."""
+    shape = (desc.N, desc.Ho, desc.Wo, desc.out_c_stride or desc.K)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.int8, device=z_x.device)
+    if out_f32 is None:
+        out_f32 = torch.empty(shape, dtype=torch.float32, device=z_x.device)
+    _check(lib.q8_conv_int8_dequantized(C.byref(desc), _ptr(z_x, torch.int8),
+                                        _ptr(z_w_packed, torch.int8), _ptr(bias_i32, torch.int32),
+                                        q_x, q_w, q_out, _ptr(residual, torch.int8), q_res,
+                                        _ptr(out, torch.int8), _ptr(out_f32, torch.float32),
+                                        _stream()))
+    return out, out_f32
 
 
 def conv_image_f32_supported(desc, H, W, Cc, top, left, pool=0):

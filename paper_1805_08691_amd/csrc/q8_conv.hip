@@ -251,6 +251,7 @@ struct U8Flags {
   const int32_t* tap_sums;
   const float* m_vec = nullptr;     // per-output-channel scales (replace q_x * q_w / q_out)
   float* y_f32 = nullptr;           // real-valued output instead of int8 codes
+  float* y_deq = nullptr;           // Eq. D of the output codes, written beside them
   const PairArgs* pair = nullptr;   // a second, 1x1 layer on the output while it is on chip
   int variant = -1;                 // tile variant of the main kernel to use (tests, tuning)
   int n_split = 0;                  // with a split-reduction variant: workgroups per tile
@@ -379,12 +380,20 @@ int conv_fill(const q8_conv_desc* d, const U8Flags& u, const int8_t* z_x, const 
   p.vec4 = aligned_to(4) ? 1 : 0;
   p.vec16 = aligned_to(16) ? 1 : 0;
   p.y_f32 = u.y_f32;
+  p.y_deq = u.y_deq;
+  p.q_deq = q_out;
+  if (u.y_deq) {
+    Q8_REQUIRE(!(u.in_u8 || u.out_u8 || u.res_u8 || u.m_vec || u.y_f32 || u.pair) && z_y,
+               Q8_EUNSUPPORTED);
+    Q8_REQUIRE(q8_aligned(u.y_deq, 4), Q8_EALIGN);
+  }
 #ifdef Q8_TRACE
   p.trace = g_trace;
   p.trace_cap = g_trace_cap;
 #endif
   p.f32_vec4 =
-      (u.y_f32 && p.out_cs % 4 == 0 && p.out_off % 4 == 0 && q8_aligned(u.y_f32, 16)) ? 1 : 0;
+      ((u.y_f32 || u.y_deq) && p.out_cs % 4 == 0 && p.out_off % 4 == 0 &&
+       q8_aligned(u.y_f32 ? u.y_f32 : u.y_deq, 16)) ? 1 : 0;
 
   return Q8_OK;
 }
@@ -646,6 +655,17 @@ int q8_conv_int8_real_output(const q8_conv_desc* d, const int8_t* z_x, const voi
   U8Flags u{0, 0, 0, nullptr};
   u.y_f32 = y_dev;            // null: rejected by the shared checks unless the output is empty
   return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, 1.0f, residual, q_res, nullptr,
+                     nullptr, stream);
+}
+
+int q8_conv_int8_dequantized(const q8_conv_desc* d, const int8_t* z_x, const void* z_w_packed,
+                             const int32_t* bias_i32, float q_x, float q_w, float q_out,
+                             const int8_t* residual, float q_res, int8_t* z_y, float* r_y,
+                             void* stream) {
+  Q8_REQUIRE(r_y != nullptr || (d && d->N == 0), Q8_EINVAL);
+  U8Flags u{0, 0, 0, nullptr};
+  u.y_deq = r_y;
+  return conv_launch(d, u, z_x, z_w_packed, bias_i32, q_x, q_w, q_out, residual, q_res, z_y,
                      nullptr, stream);
 }
 

@@ -26,6 +26,10 @@ struct ConvParams {
   // instead of y; then m is the accumulator's factor q_x*q_w and m_r the residual's q_res
   float* __restrict__ y_f32;
   int f32_vec4;   // 1: fp32 output addresses of 4-channel groups are 16-byte aligned
+  // Eq. D on the layer's own output codes in the same launch: fp32 [M][out_cs] laid out like
+  // y, y_deq[i] = q_deq * code[i]; null: codes only
+  float* __restrict__ y_deq;
+  float q_deq;
   int N, H, W, C, K, R, S;
   int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
   int Ho, Wo;
@@ -294,6 +298,23 @@ __device__ __forceinline__ void finish16(const ConvParams& p, int pix, int ch, c
     if (p.relu) u = fmaxf(u, 0.0f);
     u = fminf(fmaxf(u, lo), hi);
     zw[e >> 2] |= ((unsigned)((int)rintf(u) - out_sub) & 0xffu) << (8 * (e & 3));
+  }
+  if (p.y_deq) {      // Eq. D on the codes just made (signed codes only)
+    float* r = p.y_deq + (size_t)pix * p.out_cs + p.out_off + ch;
+    float dq[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      dq[e] = p.q_deq * (float)(int8_t)((zw[e >> 2] >> (8 * (e & 3))) & 0xff);
+    if (full && p.f32_vec4) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        *reinterpret_cast<float4*>(r + 4 * a) =
+            float4{dq[4 * a], dq[4 * a + 1], dq[4 * a + 2], dq[4 * a + 3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e < nvalid) r[e] = dq[e];
+    }
   }
   int8_t* o = p.y + (size_t)pix * p.out_cs + p.out_off + ch;
   if (full && p.vec16) {

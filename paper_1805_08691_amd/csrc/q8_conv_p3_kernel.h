@@ -201,7 +201,7 @@ bool p3_applicable(const ConvParams& p) {
   return p.R == 3 && p.S == 3 && p.stride_h == 1 && p.stride_w == 1 && p.dil_h == 1 &&
          p.dil_w == 1 && p.pad_h == 1 && p.pad_w == 1 && p.C == 64 && p.S4 == 0 && p.K <= 64 &&
          (p.K & 15) == 0 && p.W <= P3Shape<PL>::max_w() && p.vec16 && !p.res && !p.acc_dump &&
-         !p.y_f32 && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 && !p.tap_sums;
+         !p.y_f32 && !p.y_deq && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 && !p.tap_sums;
 }
 
 template <int PL>

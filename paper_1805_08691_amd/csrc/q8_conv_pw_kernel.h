@@ -229,7 +229,7 @@ bool pw_applicable(const ConvParams& p) {
   const bool pointwise = p.R == 1 && p.S == 1 && p.stride_h == 1 && p.stride_w == 1 &&
                          p.pad_h == 0 && p.pad_w == 0;
   return pointwise && p.S4 == 0 && p.C == KS * 64 && (p.K & 15) == 0 && p.vec16 && !p.acc_dump &&
-         !p.y_f32 && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 &&
+         !p.y_f32 && !p.y_deq && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 &&
          (!p.res || (p.res_bytes > 0 && (long)p.M * p.res_cs < 0x7fffffffL)) &&
          (long)p.M * p.in_cs < 0x7fffffffL;
 }

@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void conv_i8_kernel(const ConvParams p) {
   // ---- epilogue: a lane holds 16 consecutive channels of pixel column (lane & 31).
   // A complete tile with aligned rows takes the branch-free path.
   const bool fast_tile =
-      p.vec16 && !p.acc_dump && !p.y_f32 && ch0 + BC <= p.K && pix0 + BP <= p.M;
+      p.vec16 && !p.acc_dump && !p.y_f32 && !p.y_deq && ch0 + BC <= p.K && pix0 + BP <= p.M;
 #pragma unroll
   for (int j = 0; j < TP; ++j) {
     const int pix = pix0 + (wave_p * TP + j) * 32 + (lane & 31);

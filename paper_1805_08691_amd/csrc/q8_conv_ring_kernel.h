@@ -64,7 +64,7 @@ __device__ __forceinline__ void finish_tile(const ConvParams& p, const v16i (&ac
                                             const int (&res_w)[TC][TP][4], const int pix0,
                                             const int ch0, const int BP, const int BC,
                                             const int wave_p, const int wave_c, const int lane) {
-  const bool fast_tile = p.vec16 && !p.acc_dump && !p.y_f32 && pix0 + BP <= p.M &&
+  const bool fast_tile = p.vec16 && !p.acc_dump && !p.y_f32 && !p.y_deq && pix0 + BP <= p.M &&
                          (ch0 + BC <= p.K || (p.K & 15) == 0);
   auto finish_all = [&](auto mode_c) __attribute__((always_inline)) {
     // 0 general; 1 fast; 2 fast + residual; 3, 4, 5: fast with unsigned codes (no

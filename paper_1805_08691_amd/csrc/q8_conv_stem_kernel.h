@@ -377,7 +377,7 @@ bool stem_applicable(const ConvParams& p) {
   return p.stride_h == SH && p.R + 2 * SH <= 16 && p.S4 == 2 && p.S == 1 && p.C == 32 &&
          p.in_cs == 4 && p.R <= 8 && p.K <= 64 && (p.K & 15) == 0 && p.Wo <= 128 && p.W <= 240 &&
          p.stride_w <= 2 && p.pad_h == 0 && p.pad_w == 0 && p.vec16 && !p.res && !p.acc_dump &&
-         !p.y_f32 && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 && !p.tap_sums &&
+         !p.y_f32 && !p.y_deq && !p.in_u8 && !p.out_u8 && !p.res_u8 && !p.m_vec && !p.w2 && !p.tap_sums &&
          (long)p.N * p.H * p.W * 4 < 0x7fffffffL && (long)p.M * p.out_cs < 0x7fffffffL;
 }
 

@@ -33,8 +33,14 @@ class Engine:
 
     def __init__(self, net, batch, device="cuda", n_streams=1, unsigned_activations=False,
                  per_channel_weights=False, real_outputs=False, own_sum_factor=False,
-                 fuse_pairs=False, chain=False, fuse_duals=False, fuse_head=False):
+                 fuse_pairs=False, chain=False, fuse_duals=False, fuse_head=False,
+                 fuse_dequant=False):
         self.net = net
+        # fuse_dequant: where run_step is asked for Eq. D of a tensor that one convolution writes
+        # whole, that convolution writes the fp32 values beside its codes (same values; no
+        # separate pass over the tensor)
+        self.fuse_dequant = fuse_dequant
+        self._deq = {}        # tensor name -> fp32 buffer of the running step (fused Eq. D)
         # fuse_head: Eq. Q on the input image, the first convolution and the max-pool behind it
         # run as one launch per pipeline where the library has a build for them (same
         # results; the image's codes and the convolution's own output are then not written
@@ -364,6 +370,22 @@ class Engine:
         else:
             B.quantize(x, self.q[self.net.input], P_ACT, out=z)
 
+    def _dequant_writer(self, name):
+        """The convolution that can write Eq. D of tensor ``name`` beside its codes, or None."""
+        if not self.fuse_dequant or self.unsigned or self.per_channel or name in self.real:
+            return None
+        writers = [o for o in self.net.ops if o.dst == name]
+        if len(writers) != 1 or writers[0].kind != "conv":
+            return None
+        o = writers[0]
+        if o.dst_c_off or self.net.tensors[name].C != o.K or _pad_c(o.K) != o.K:
+            return None
+        if o.name in self.paired or o.name in self.dualed or o.name in self.pairs or o.name in self.duals:
+            return None
+        if self.head and o is self.head[0]:
+            return None
+        return o
+
     def set_input(self, x):
         """The real-valued batch of the next layers: with a fused head it is only remembered
         (the head's launches apply Eq. Q), otherwise Eq. Q runs on it now."""
@@ -449,6 +471,12 @@ class Engine:
                       self.q[op.src], self.qw[op.name], self.q[op.dst], res, q_res,
                       out=self.act[op.dst][lo:lo + n], acc_dump=acc_dump)
             return
+        if op.dst in self._deq and acc_dump is None:
+            B.conv_int8_dequantized(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed, bias,
+                                    self.q[op.src], self.qw[op.name], self.q[op.dst], res, q_res,
+                                    out=self.act[op.dst][lo:lo + n],
+                                    out_f32=self._deq[op.dst][lo:lo + n])
+            return
         B.conv_int8(self.conv_desc(op, n), self.act[op.src][lo:lo + n], packed, bias,
                     self.q[op.src], self.qw[op.name], self.q[op.dst], res, q_res,
                     out=self.act[op.dst][lo:lo + n], acc_dump=acc_dump)
@@ -531,6 +559,9 @@ class Engine:
         self._x = None
         if x is not None:
             self.set_input(x)
+        # Eq. D inside the launch that writes the tensor, where there is such a launch
+        self._deq = {name: out for name, out in (dequant or {}).items()
+                     if out is not None and not self.chain and self._dequant_writer(name)}
         if self.chain:
             self.run_chained()
         elif self.n_streams == 1 or serial:
@@ -551,8 +582,10 @@ class Engine:
             for side in self.side:
                 main.wait_stream(side)
         self._x = None
+        done, self._deq = self._deq, {}
         for name, out in (dequant or {}).items():
-            self.dequantize(name, out=out)
+            if name not in done:
+                self.dequantize(name, out=out)
 
     def run_layers(self, acc_dump=None, serial=False):
         """Every layer on the codes already in the input buffer.  ``acc_dump``

@@ -377,6 +377,46 @@ def test_conv_image_f32_head(B, idx):
             assert np.array_equal(host(out), want), f"relu={relu} pool={pool}"
 
 
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=7, W=7, C=512, K=2048, R=1, S=1),                          # ResNet-50's last layer
+    dict(N=1, H=9, W=11, C=64, K=40, R=3, S=3, pad_h=1, pad_w=1),          # K ends inside a group
+    dict(N=3, H=5, W=5, C=3, K=24, R=3, S=3, pad_h=1, pad_w=1),            # the small-channel kernel
+])
+def test_conv_with_dequantized_output(B, geom):
+    """Eq. A' and Eq. D in one launch: the codes equal the oracle's, and the fp32 tensor is
+    Eq. D of those codes (one fp32 multiplication, bit for bit); channels outside the
+    layer's slice of a wider tensor are left alone."""
+    g = orc.ConvGeom(**geom)
+    rng = np.random.default_rng(4242 + g.K)
+    Cs = 4 if g.C < 4 else g.C
+    x = rng.integers(-128, 128, (g.N, g.H, g.W, Cs)).astype(np.int8)
+    w = rng.integers(-128, 128, (g.K, g.R, g.S, g.C)).astype(np.int8)
+    b = rng.integers(-20000, 20000, g.K).astype(np.int32)
+    res = rng.integers(-128, 128, (g.N, g.Ho, g.Wo, g.K)).astype(np.int8)
+    q_x, q_w = np.float32(0.021), np.float32(0.0017)
+    q_out = np.float32(q_x * q_w * 5476.0 * np.sqrt(g.R * g.S * g.C) / 40.0)
+    q_res = np.float32(0.3) * q_out
+    go = orc.ConvGeom(**{**geom, "in_c_stride": Cs})
+    acc = orc.conv_i8(go, x, w, b)
+    for with_res, pad in ((True, 0), (False, 8)):
+        ocs = g.K + pad
+        want = np.full((g.N, g.Ho, g.Wo, ocs), 77, np.int8)
+        orc.requant(acc, orc.requant_scale(q_x, q_w, q_out), True, res if with_res else None,
+                    orc.residual_scale(q_res, q_out) if with_res else 0.0, out=want,
+                    out_c_stride=ocs, out_c_off=pad)
+        d = B.ConvDesc(g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.stride_h, g.stride_w, g.pad_h, g.pad_w,
+                       g.dil_h, g.dil_w, relu=1, in_c_stride=Cs, out_c_stride=ocs, out_c_off=pad)
+        out = torch.full(want.shape, 77, dtype=torch.int8, device="cuda")
+        out_f = torch.full(want.shape, -5.0, dtype=torch.float32, device="cuda")
+        B.conv_int8_dequantized(d, dev(x), B.pack_weights(d, dev(w)), dev(b), float(q_x), float(q_w),
+                                float(q_out), dev(res) if with_res else None, float(q_res),
+                                out=out, out_f32=out_f)
+        assert np.array_equal(host(out), want)
+        want_f = np.full(want.shape, -5.0, np.float32)
+        want_f[..., pad:] = orc.D(want[..., pad:], q_out)
+        assert np.array_equal(host(out_f), want_f)
+
+
 def test_conv_image_f32_head_rejects(B):
     """Host checks of the fused head: a layer outside the family is unsupported, an image that
     does not fit its frame is invalid."""
@@ -1048,8 +1088,9 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
     net, params, x, folded, q, qparams, z_in, acts, accs = _oracle_pipeline(cfg_id, batch, True)
     o = net.outputs[0]
     want = orc.D(acts[o], q[o])
-    for n_streams, serial in ((1, False), (2, False), (2, True), (3, False)):
-        eng = Engine(net, batch, n_streams=n_streams)
+    for n_streams, serial, fuse_deq in ((1, False, False), (2, False, False), (2, True, False),
+                                        (3, False, False), (2, False, True), (1, False, True)):
+        eng = Engine(net, batch, n_streams=n_streams, fuse_dequant=fuse_deq)
         eng.load_params(params)
         eng.fold()
         eng.set_factors(q)
@@ -1063,8 +1104,10 @@ def test_run_step_one_and_two_pipelines_and_serial(B):
         eng.run_step(dev(x), {o: out}, serial=serial)
         torch.cuda.synchronize()
         assert np.array_equal(host(eng.act[o]), acts[o]), (n_streams, serial)
+        assert bool(eng._dequant_writer(o)) == fuse_deq
         got = host(out)
-        assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want)), (n_streams, serial)
+        assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want)), (n_streams, serial, fuse_deq)
+        assert np.array_equal(got, host(eng.dequantize(o)))       # fused or not: the same bits
 
 
 def _sampled_images_check(B, cfg_id, batch, picks, n_cal, cal_batch, n_streams=2, unsigned=False,
