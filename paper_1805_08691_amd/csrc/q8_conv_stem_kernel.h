@@ -357,10 +357,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
           __builtin_amdgcn_raw_buffer_store_b128(codes, rsrc_y, off, 0, 0);
         }
       }
-      // every wave has read the staging tile (its stores took the data) before the next
-      // row's codes are written into it; the stores themselves stay in flight
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();
+      // Every wave has read the staging tile (its stores took the data) before the next
+      // codes are written into it; the stores themselves stay in flight.  POOL: the tile is
+      // written again two passes later at the earliest, behind the next pass's barrier --
+      // except when the image's last output row is an even one and closes a window by itself.
+      if (!POOL || ho + 2 == p.Ho) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+      }
     }
   };
   for (int ho = ho_first; ho < ho_end; ho += 2) {
