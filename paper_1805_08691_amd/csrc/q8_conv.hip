@@ -128,6 +128,14 @@ int pick_halo3(const q8_conv_desc* d) {
     if (tiles >= 360) return s.index;
     smallest = s.index;
   }
+  // Down at the 64 x 64 tile there are at most a tile or two per CU and a tile's time is its
+  // chain of reduction steps: with an even number of 64-channel chunks two groups of
+  // wavefronts share the chain (builds 8 and 9 of the family's table), on 64 x 128 tiles
+  // where those still give most CUs one.
+  if (smallest == 6 && d->C % 128 == 0) {
+    const long tiles_wide = ((M + 63) / 64) * ((d->K + 127) / 128);
+    return d->K > 64 && tiles_wide >= 192 ? 9 : 8;
+  }
   return smallest;
 }
 

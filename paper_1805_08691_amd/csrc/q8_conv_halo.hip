@@ -6,9 +6,12 @@
 namespace q8 {
 namespace {
 
-template <int WP, int WC, int TP, int TC, int PL>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
 int launch_halo3_or_generic(ConvParams& p, hipStream_t stream) {
-  if (halo3_applicable<WP, WC, TP, TC, PL>(p)) return launch_halo3<WP, WC, TP, TC, PL>(p, stream);
+  if (halo3_applicable<WP, WC, TP, TC, PL, KW>(p))
+    return launch_halo3<WP, WC, TP, TC, PL, KW>(p, stream);
+  if (KW > 1 && halo3_applicable<WP, WC, TP, TC, PL>(p))      // an odd number of chunks
+    return launch_halo3<WP, WC, TP, TC, PL>(p, stream);
   return launch_ring<2, 2, 2, 2, 64, 3, 0>(p, stream);
 }
 
@@ -30,6 +33,13 @@ const HaloVariant kHaloVariants[] = {
     Q8_HALO_ROW(4, 1, 2, 2, 14)    // 5: 256 x 64, maps up to 319 wide
     Q8_HALO_ROW(2, 2, 1, 1, 2)     // 6: 64 x 64, maps up to 31 wide
     Q8_HALO_ROW(2, 2, 1, 2, 2)     // 7: 64 x 128, maps up to 31 wide
+    // the reduction split over two groups of four wavefronts
+    { "conv_i8_halo3_kernel<2,2,1,1,2,2>", &launch_halo3_or_generic<2, 2, 1, 1, 2, 2>, 64, 64,
+      HaloShape<2, 2, 1, 1, 2, 2>::max_w() },                   // 8: 64 x 64
+    { "conv_i8_halo3_kernel<2,2,1,2,2,2>", &launch_halo3_or_generic<2, 2, 1, 2, 2, 2>, 64, 128,
+      HaloShape<2, 2, 1, 2, 2, 2>::max_w() },                   // 9: 64 x 128
+    { "conv_i8_halo3_kernel<2,2,2,1,4,2>", &launch_halo3_or_generic<2, 2, 2, 1, 4, 2>, 128, 64,
+      HaloShape<2, 2, 2, 1, 4, 2>::max_w() },                   // 10: 128 x 64
 };
 #undef Q8_HALO_ROW
 constexpr int kNumHaloVariants = sizeof(kHaloVariants) / sizeof(kHaloVariants[0]);

@@ -31,24 +31,34 @@ namespace {
 
 // PL = patch loads per wavefront and chunk (a wavefront-wide load fills 16 rows): the patch
 // buffer holds PL * NW * 16 rows, which must cover BP + 2W + 2.
-template <int WP, int WC, int TP, int TC, int PL>
+//
+// KW = 2: the reduction of a tile is split over two groups of WP * WC wavefronts inside the
+// workgroup (Eq. x: integer sums regroup freely).  Group g runs the loop above on the channel
+// chunks g, g + 2, ... with a filter ring and patch buffers of its own; both groups meet at
+// every step's barrier, so a workgroup passes half as many barriers per tile -- what counts
+// when a layer has few tiles per CU and a tile's time is its chain of steps.  At the end group
+// 1 hands its accumulators to group 0 through LDS and group 0 runs the layer's tail.
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
 struct HaloShape {
-  static constexpr int NW = WP * WC;
+  static constexpr int NW = WP * WC;                       // wavefronts per group
   static constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
   static constexpr int STAGES = 3;
   static constexpr int A_BYTES = BC * 64;                  // one filter slab
   static constexpr int PATCH_ROWS = PL * NW * 16;
   static constexpr int PATCH_BYTES = PATCH_ROWS * 64;
-  static constexpr int ZERO_OFF = STAGES * A_BYTES + 2 * PATCH_BYTES;   // a row of zeros
-  static constexpr int LDS_BYTES = ZERO_OFF + 64;
+  static constexpr int GROUP_BYTES = STAGES * A_BYTES + 2 * PATCH_BYTES;   // ring + patches
+  static constexpr int ZERO_OFF = KW * GROUP_BYTES;        // a row of zeros
+  static constexpr int XCH_OFF = ZERO_OFF + 1024;          // KW = 2: accumulators of group 1
+  static constexpr int XCH_BYTES = KW > 1 ? NW * TC * TP * 4096 : 0;
+  static constexpr int LDS_BYTES = KW > 1 ? XCH_OFF + XCH_BYTES : ZERO_OFF + 64;
   static constexpr int max_w() { return (PATCH_ROWS - BP - 2) / 2; }
 };
 
-template <int WP, int WC, int TP, int TC, int PL>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
 __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int ptile,
                                                 const int ctile, int8_t* const lds) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  using Sh = HaloShape<WP, WC, TP, TC, PL>;
+  using Sh = HaloShape<WP, WC, TP, TC, PL, KW>;
   constexpr int NW = Sh::NW, BP = Sh::BP, BC = Sh::BC, STAGES = Sh::STAGES;
   constexpr int A_BYTES = Sh::A_BYTES, PATCH_BYTES = Sh::PATCH_BYTES;
   constexpr int A_LOADS = BC / 16 / NW;          // filter loads per wavefront and step
@@ -60,19 +70,22 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
   const int ch0 = ctile * BC;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kgroup = KW > 1 ? wave_all / NW : 0;           // which share of the reduction
+  const int wave = KW > 1 ? wave_all % NW : wave_all;      // wavefront inside its group
   const int wave_p = wave % WP;
   const int wave_c = wave / WP;
   const int W = p.W;
-  const int n_chunks = p.C >> 6;
+  const int n_chunks = (p.C >> 6) / KW;                    // chunks of this group
+  const int gbase = kgroup * Sh::GROUP_BYTES;              // the group's ring and patches
 
   const __amdgpu_buffer_rsrc_t rsrc_w =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, p.w_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, p.x_bytes, 0x00020000);
 
-  int8_t* const ring = lds;
-  int8_t* const patch = lds + STAGES * A_BYTES;
+  int8_t* const ring = lds + gbase;
+  int8_t* const patch = ring + STAGES * A_BYTES;
   // the row of zeros that masked taps read
   if (tid < 16) reinterpret_cast<int*>(lds + Sh::ZERO_OFF)[tid] = 0;
 
@@ -130,10 +143,11 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
 #pragma unroll
     for (int j = 0; j < TP; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = b[e];
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = kgroup == 0 ? b[e] : 0;
   }
   int res_w[TC][TP][4];
   auto fetch_residual = [&]() {
+    if (KW > 1 && kgroup != 0) return;
 #pragma unroll
     for (int i = 0; i < TC; ++i)
 #pragma unroll
@@ -143,13 +157,14 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
   };
 
   const int p_C = p.C;
+  // `chunk` counts the group's own chunks: its c-th chunk is channel chunk c * KW + kgroup
   auto issue_patch = [&](int chunk) {        // the patch of `chunk` into buffer chunk & 1
     int8_t* buf = patch + (chunk & 1) * PATCH_BYTES;
 #pragma unroll
     for (int j = 0; j < PL; ++j)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
           rsrc_x, (__attribute__((address_space(3))) void*)(buf + (wave + NW * j) * 1024), 16,
-          b_off[j], chunk * 64, 0, 0);
+          b_off[j], (chunk * KW + kgroup) * 64, 0, 0);
   };
   auto issue_filters = [&](int chunk, int tap, int stage) {     // the slab of one step
     int8_t* buf = ring + stage * A_BYTES;
@@ -157,7 +172,7 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
     for (int j = 0; j < A_LOADS; ++j)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
           rsrc_w, (__attribute__((address_space(3))) void*)(buf + (wave + NW * j) * 1024), 16,
-          a_off[j], tap * p_C + chunk * 64, 0, 0);
+          a_off[j], tap * p_C + (chunk * KW + kgroup) * 64, 0, 0);
   };
 
   // ---- operand fragments: filters as in the generic kernel, activations from the patch
@@ -186,7 +201,7 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
     for (int i = 0; i < TC; ++i)
       af[h & 1][i] = *reinterpret_cast<const v4i*>(a_base + a_foff[h][i]);
     const int delta = (TAP / 3) * W + (TAP % 3);
-    const int pbase = STAGES * A_BYTES + (chunk & 1) * PATCH_BYTES;
+    const int pbase = gbase + STAGES * A_BYTES + (chunk & 1) * PATCH_BYTES;
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
       const int rho = prow[j] + delta;
@@ -292,12 +307,43 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
 #undef Q8_TAP
 #undef Q8_AHEAD
 
+  if constexpr (KW > 1) {
+    // group 1's accumulators through LDS to group 0 (lane-major 16-byte cells: no conflicts)
+    int8_t* const xch = lds + Sh::XCH_OFF + wave * (TC * TP * 4096);
+    if (kgroup != 0) {
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<v4i*>(xch + (((i * TP + j) * 4 + q) * 64 + lane) * 16) =
+                v4i{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                    acc[i][j][4 * q + 3]};
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kgroup != 0) return;
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < TP; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const v4i o = *reinterpret_cast<const v4i*>(xch + (((i * TP + j) * 4 + q) * 64 + lane) * 16);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[i][j][4 * q + k] += o[k];
+        }
+  }
+
   finish_tile<TP, TC, 0>(p, acc, res_w, pix0, ch0, BP, BC, wave_p, wave_c, lane);
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int WP, int WC, int TP, int TC, int PL>
-__global__ __launch_bounds__(WP * WC * 64) void conv_i8_halo3_kernel(const ConvParams p) {
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
+__global__ __launch_bounds__(WP * WC * KW * 64) void conv_i8_halo3_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
   const int nblk = p.n_ptiles * p.n_ctiles;
@@ -312,7 +358,7 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_halo3_kernel(const ConvP
 #endif
   const int ptile = p.ptile_fastest ? bid % p.n_ptiles : bid / p.n_ctiles;
   const int ctile = p.ptile_fastest ? bid / p.n_ptiles : bid % p.n_ctiles;
-  conv_tile_halo3<WP, WC, TP, TC, PL>(p, ptile, ctile, lds);
+  conv_tile_halo3<WP, WC, TP, TC, PL, KW>(p, ptile, ctile, lds);
 #ifdef Q8_TRACE
   q8_trace_record(p, q8_t0);
 #endif
@@ -320,29 +366,29 @@ __global__ __launch_bounds__(WP * WC * 64) void conv_i8_halo3_kernel(const ConvP
 }
 
 // Whether the 3x3 family takes this layer with this shape (else the generic kernel does).
-template <int WP, int WC, int TP, int TC, int PL>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
 bool halo3_applicable(const ConvParams& p) {
-  return p.R == 3 && p.S == 3 && p.stride_h == 1 && p.stride_w == 1 && p.dil_h == 1 &&
+  return (p.C / 64) % KW == 0 && p.R == 3 && p.S == 3 && p.stride_h == 1 && p.stride_w == 1 && p.dil_h == 1 &&
          p.dil_w == 1 && p.pad_h == 1 && p.pad_w == 1 && p.C % 64 == 0 && p.S4 == 0 &&
          p.W <= HaloShape<WP, WC, TP, TC, PL>::max_w() && !p.in_u8 && !p.out_u8 && !p.res_u8 &&
          !p.m_vec && !p.w2;
 }
 
-template <int WP, int WC, int TP, int TC, int PL>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
 int launch_halo3(ConvParams& p, hipStream_t stream) {
-  using Sh = HaloShape<WP, WC, TP, TC, PL>;
+  using Sh = HaloShape<WP, WC, TP, TC, PL, KW>;
   p.n_ptiles = (p.M + Sh::BP - 1) / Sh::BP;
   p.n_ctiles = (p.K + Sh::BC - 1) / Sh::BC;
   const long nblk = (long)p.n_ptiles * p.n_ctiles;
   if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
-  auto kernel = conv_i8_halo3_kernel<WP, WC, TP, TC, PL>;
+  auto kernel = conv_i8_halo3_kernel<WP, WC, TP, TC, PL, KW>;
   if constexpr (Sh::LDS_BYTES > 65536) {
     static const hipError_t attr = hipFuncSetAttribute(
         reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
         Sh::LDS_BYTES);
     if (attr != hipSuccess) return Q8_EHIP;
   }
-  hipLaunchKernelGGL(kernel, dim3((unsigned)nblk), dim3(Sh::NW * 64), Sh::LDS_BYTES, stream, p);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)nblk), dim3(Sh::NW * KW * 64), Sh::LDS_BYTES, stream, p);
   return q8_launch_status();
 }
 
