@@ -134,7 +134,7 @@ int pick_halo3(const q8_conv_desc* d) {
   // where those still give most CUs one.
   if (smallest == 6 && d->C % 128 == 0) {
     const long tiles_wide = ((M + 63) / 64) * ((d->K + 127) / 128);
-    return d->K > 64 && tiles_wide >= 192 ? 9 : 8;
+    return d->K > 64 && tiles_wide >= 192 ? 9 : 12;
   }
   return smallest;
 }
@@ -194,8 +194,11 @@ int pick_variant(const q8_conv_desc* d, int forced = -1) {
     return 8;
   }
   if (d->K >= 256 && tiles128 >= 1024 && nk > 4) return 13;
-  if (tiles128 <= 64) return 7;
-  if (tiles128 <= 128) return d->R * d->S == 1 ? 5 : 9;
+  // (pointwise layers with at most 128 such tiles: measured inside the network, where their
+  // filters come from HBM in every pass, 64 x 64 tiles with 128 reduction bytes per step beat
+  // the wider tiles that win on a warm cache)
+  if (tiles128 <= 64) return d->R * d->S == 1 && nk % 2 == 0 ? 21 : 7;
+  if (tiles128 <= 128) return d->R * d->S == 1 ? (nk % 2 == 0 ? 21 : 5) : 9;
   if (nk <= 4) return tiles128 >= 512 ? 8 : 4;
   return tiles128 <= 256 ? 11 : 1;    // 11: eight wavefronts on a 128 x 128 tile, ring of 4
 }

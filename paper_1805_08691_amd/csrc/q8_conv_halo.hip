@@ -6,12 +6,12 @@
 namespace q8 {
 namespace {
 
-template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1, int ST = 3>
 int launch_halo3_or_generic(ConvParams& p, hipStream_t stream) {
   if (halo3_applicable<WP, WC, TP, TC, PL, KW>(p))
-    return launch_halo3<WP, WC, TP, TC, PL, KW>(p, stream);
+    return launch_halo3<WP, WC, TP, TC, PL, KW, ST>(p, stream);
   if (KW > 1 && halo3_applicable<WP, WC, TP, TC, PL>(p))      // an odd number of chunks
-    return launch_halo3<WP, WC, TP, TC, PL>(p, stream);
+    return launch_halo3<WP, WC, TP, TC, PL, 1, ST>(p, stream);
   return launch_ring<2, 2, 2, 2, 64, 3, 0>(p, stream);
 }
 
@@ -40,6 +40,13 @@ const HaloVariant kHaloVariants[] = {
       HaloShape<2, 2, 1, 2, 2, 2>::max_w() },                   // 9: 64 x 128
     { "conv_i8_halo3_kernel<2,2,2,1,4,2>", &launch_halo3_or_generic<2, 2, 2, 1, 4, 2>, 128, 64,
       HaloShape<2, 2, 2, 1, 4, 2>::max_w() },                   // 10: 128 x 64
+    // a filter ring of nine slabs (eight in flight)
+    { "conv_i8_halo3_kernel<2,2,1,1,2,1,9>", &launch_halo3_or_generic<2, 2, 1, 1, 2, 1, 9>, 64, 64,
+      HaloShape<2, 2, 1, 1, 2>::max_w() },                      // 11: 64 x 64
+    { "conv_i8_halo3_kernel<2,2,1,1,2,2,9>", &launch_halo3_or_generic<2, 2, 1, 1, 2, 2, 9>, 64, 64,
+      HaloShape<2, 2, 1, 1, 2>::max_w() },                      // 12: 64 x 64, two groups
+    { "conv_i8_halo3_kernel<2,2,1,2,2,1,9>", &launch_halo3_or_generic<2, 2, 1, 2, 2, 1, 9>, 64, 128,
+      HaloShape<2, 2, 1, 2, 2>::max_w() },                      // 13: 64 x 128
 };
 #undef Q8_HALO_ROW
 constexpr int kNumHaloVariants = sizeof(kHaloVariants) / sizeof(kHaloVariants[0]);

@@ -38,11 +38,15 @@ namespace {
 // every step's barrier, so a workgroup passes half as many barriers per tile -- what counts
 // when a layer has few tiles per CU and a tile's time is its chain of steps.  At the end group
 // 1 hands its accumulators to group 0 through LDS and group 0 runs the layer's tail.
-template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
+//
+// ST = ring depth of the filter slabs, 3 or 9 (the stage of a step is known at compile time:
+// ST divides the nine taps).  Nine keeps eight slabs in flight per group: for the late layers,
+// whose filters come from HBM in every pass and whose tiles are chains of 36 ... 72 steps.
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1, int ST = 3>
 struct HaloShape {
   static constexpr int NW = WP * WC;                       // wavefronts per group
   static constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
-  static constexpr int STAGES = 3;
+  static constexpr int STAGES = ST;
   static constexpr int A_BYTES = BC * 64;                  // one filter slab
   static constexpr int PATCH_ROWS = PL * NW * 16;
   static constexpr int PATCH_BYTES = PATCH_ROWS * 64;
@@ -54,12 +58,13 @@ struct HaloShape {
   static constexpr int max_w() { return (PATCH_ROWS - BP - 2) / 2; }
 };
 
-template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1, int ST = 3>
 __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int ptile,
                                                 const int ctile, int8_t* const lds) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  using Sh = HaloShape<WP, WC, TP, TC, PL, KW>;
+  using Sh = HaloShape<WP, WC, TP, TC, PL, KW, ST>;
   constexpr int NW = Sh::NW, BP = Sh::BP, BC = Sh::BC, STAGES = Sh::STAGES;
+  static_assert(STAGES == 3 || STAGES == 9, "the ring depth divides the nine taps");
   constexpr int A_BYTES = Sh::A_BYTES, PATCH_BYTES = Sh::PATCH_BYTES;
   constexpr int A_LOADS = BC / 16 / NW;          // filter loads per wavefront and step
   static_assert(NW == 4 || NW == 8, "four or eight wavefronts per block");
@@ -258,9 +263,9 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
     load_frags(chunk, tap_c, STAGE, 0);
     if constexpr (decltype(patch_c)::value) issue_patch(chunk + 1);
     if constexpr (decltype(issue_c)::value) {
-      // step + 2: tap TAP + 2 of this chunk, or tap TAP - 7 of the next
-      constexpr int T2 = (TAP + 2) % 9;
-      issue_filters(TAP + 2 >= 9 ? chunk + 1 : chunk, T2, (STAGE + 2) % STAGES);
+      // step + STAGES - 1: a later tap of this chunk, or an early one of the next
+      constexpr int T2 = (TAP + STAGES - 1) % 9;
+      issue_filters(TAP + STAGES - 1 >= 9 ? chunk + 1 : chunk, T2, T2 % STAGES);
     }
     if constexpr (decltype(last_c)::value) fetch_residual();
     mma(1);                                  // second half of the previous step
@@ -273,35 +278,30 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
 #define Q8_TAP(T) integral_constant<int, (T)>{}
 #define Q8_AHEAD(N) integral_constant<int, (N)>{}
 
-  // prologue: patch of chunk 0, slabs of steps 0 and 1
+  // prologue: patch of chunk 0, slabs of the first STAGES - 1 steps (of the first chunk, or
+  // with a deep ring and one chunk... a chunk has nine steps, so always of the first chunk)
   issue_patch(0);
-  issue_filters(0, 0, 0);
-  issue_filters(0, 1, 1);
+#pragma unroll
+  for (int t = 0; t < STAGES - 1; ++t) issue_filters(0, t, t);
   __builtin_amdgcn_s_waitcnt(0xc07f);
-  // every chunk but the last: each step requests the slab two steps ahead; the first one
-  // also the next chunk's patch (PL more loads behind the slab it waits for)
+  // Loads this wave issued after the slab of (chunk, tap) and that may still be in flight
+  // when that step starts.  Every chunk but the last: each step requests the slab STAGES - 1
+  // steps ahead, so STAGES - 2 slabs are younger; the first step also requests the next
+  // chunk's patch, in front of its slab: those PL loads are younger than the slabs of taps
+  // 1 .. STAGES - 2.  Last chunk: nothing beyond its ninth slab is requested.
   int chunk = 0;
+#define Q8_MID(T) step(chunk, Q8_TAP(T), \
+    Q8_AHEAD((STAGES - 2) * A_LOADS + (((T) >= 1 && (T) <= STAGES - 2) ? PL : 0)), yes, \
+    integral_constant<bool, (T) == 0>{}, no)
+#define Q8_END(T) step(chunk, Q8_TAP(T), \
+    Q8_AHEAD((((T) + STAGES - 2 < 8 ? (T) + STAGES - 2 : 8) - (T)) * A_LOADS), \
+    integral_constant<bool, ((T) + STAGES - 1 <= 8)>{}, no, integral_constant<bool, (T) == 8>{})
   for (; chunk + 1 < n_chunks; ++chunk) {
-    step(chunk, Q8_TAP(0), Q8_AHEAD(A_LOADS), yes, yes, no);
-    step(chunk, Q8_TAP(1), Q8_AHEAD(A_LOADS + PL), yes, no, no);
-    step(chunk, Q8_TAP(2), Q8_AHEAD(A_LOADS), yes, no, no);
-    step(chunk, Q8_TAP(3), Q8_AHEAD(A_LOADS), yes, no, no);
-    step(chunk, Q8_TAP(4), Q8_AHEAD(A_LOADS), yes, no, no);
-    step(chunk, Q8_TAP(5), Q8_AHEAD(A_LOADS), yes, no, no);
-    step(chunk, Q8_TAP(6), Q8_AHEAD(A_LOADS), yes, no, no);
-    step(chunk, Q8_TAP(7), Q8_AHEAD(A_LOADS), yes, no, no);
-    step(chunk, Q8_TAP(8), Q8_AHEAD(A_LOADS), yes, no, no);
+    Q8_MID(0); Q8_MID(1); Q8_MID(2); Q8_MID(3); Q8_MID(4); Q8_MID(5); Q8_MID(6); Q8_MID(7); Q8_MID(8);
   }
-  // the last chunk: no further patch, the last two steps request nothing
-  step(chunk, Q8_TAP(0), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(1), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(2), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(3), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(4), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(5), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(6), Q8_AHEAD(A_LOADS), yes, no, no);
-  step(chunk, Q8_TAP(7), Q8_AHEAD(A_LOADS), no, no, no);
-  step(chunk, Q8_TAP(8), Q8_AHEAD(0), no, no, yes);
+  Q8_END(0); Q8_END(1); Q8_END(2); Q8_END(3); Q8_END(4); Q8_END(5); Q8_END(6); Q8_END(7); Q8_END(8);
+#undef Q8_MID
+#undef Q8_END
   mma(1);
   fold_sums();
 #undef Q8_TAP
@@ -342,7 +342,7 @@ __device__ __forceinline__ void conv_tile_halo3(const ConvParams& p, const int p
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1, int ST = 3>
 __global__ __launch_bounds__(WP * WC * KW * 64) void conv_i8_halo3_kernel(const ConvParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(WP * WC * KW * 64) void conv_i8_halo3_kernel(const 
 #endif
   const int ptile = p.ptile_fastest ? bid % p.n_ptiles : bid / p.n_ctiles;
   const int ctile = p.ptile_fastest ? bid / p.n_ptiles : bid % p.n_ctiles;
-  conv_tile_halo3<WP, WC, TP, TC, PL, KW>(p, ptile, ctile, lds);
+  conv_tile_halo3<WP, WC, TP, TC, PL, KW, ST>(p, ptile, ctile, lds);
 #ifdef Q8_TRACE
   q8_trace_record(p, q8_t0);
 #endif
@@ -374,14 +374,14 @@ bool halo3_applicable(const ConvParams& p) {
          !p.m_vec && !p.w2;
 }
 
-template <int WP, int WC, int TP, int TC, int PL, int KW = 1>
+template <int WP, int WC, int TP, int TC, int PL, int KW = 1, int ST = 3>
 int launch_halo3(ConvParams& p, hipStream_t stream) {
-  using Sh = HaloShape<WP, WC, TP, TC, PL, KW>;
+  using Sh = HaloShape<WP, WC, TP, TC, PL, KW, ST>;
   p.n_ptiles = (p.M + Sh::BP - 1) / Sh::BP;
   p.n_ctiles = (p.K + Sh::BC - 1) / Sh::BC;
   const long nblk = (long)p.n_ptiles * p.n_ctiles;
   if (nblk > 0x7fffffffL) return Q8_EUNSUPPORTED;
-  auto kernel = conv_i8_halo3_kernel<WP, WC, TP, TC, PL, KW>;
+  auto kernel = conv_i8_halo3_kernel<WP, WC, TP, TC, PL, KW, ST>;
   if constexpr (Sh::LDS_BYTES > 65536) {
     static const hipError_t attr = hipFuncSetAttribute(
         reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
