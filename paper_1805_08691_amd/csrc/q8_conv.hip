@@ -125,7 +125,8 @@ int pick_halo3(const q8_conv_desc* d) {
   for (const Shape& s : shapes) {
     if (d->W > s.max_w || (s.bc == 128 && d->K <= 64)) continue;
     const long tiles = ((M + s.bp - 1) / s.bp) * ((d->K + s.bc - 1) / s.bc);
-    if (tiles >= 360) return s.index;
+    // (the 64 x 64 tile inside a network, its filters coming from HBM: a ring of nine slabs)
+    if (tiles >= 360) return s.index == 6 ? 11 : s.index;
     smallest = s.index;
   }
   // Down at the 64 x 64 tile there are at most a tile or two per CU and a tile's time is its
@@ -140,7 +141,27 @@ int pick_halo3(const q8_conv_desc* d) {
 }
 
 // `forced`: -1, or a variant of the main kernel to use where that kernel is applicable.
+int pick_variant_auto(const q8_conv_desc* d, int forced);
 int pick_variant(const q8_conv_desc* d, int forced = -1) {
+  int v = pick_variant_auto(d, forced);
+  static int remap[256];
+  static const bool init = [&]() {
+    for (int i = 0; i < 256; ++i) remap[i] = i;
+    if (const char* e = getenv("Q8_REMAP")) {
+      int a, b;
+      while (*e && sscanf(e, "%d:%d", &a, &b) == 2) {
+        if (a >= 0 && a < 256) remap[a] = b;
+        while (*e && *e != ',') ++e;
+        if (*e == ',') ++e;
+      }
+    }
+    return true;
+  }();
+  (void)init;
+  if (forced < 0 && v >= 0 && v < 256) v = remap[v];
+  return v;
+}
+int pick_variant_auto(const q8_conv_desc* d, int forced) {
   const int mode = conv_mode(d);
   const int tile = d->K > 64 ? 0 : d->K > 32 ? 1 : 2;      // 128x128, 256x64, 256x32
   if (!stream_capable(d)) return kRegBase + 3 * mode + tile;
@@ -199,7 +220,7 @@ int pick_variant(const q8_conv_desc* d, int forced = -1) {
   // the wider tiles that win on a warm cache)
   if (tiles128 <= 64) return d->R * d->S == 1 && nk % 2 == 0 ? 21 : 7;
   if (tiles128 <= 128) return d->R * d->S == 1 ? (nk % 2 == 0 ? 21 : 5) : 9;
-  if (nk <= 4) return tiles128 >= 512 ? 8 : 4;
+  if (nk <= 4) return tiles128 >= 192 ? 8 : 4;
   return tiles128 <= 256 ? 11 : 1;    // 11: eight wavefronts on a 128 x 128 tile, ring of 4
 }
 
