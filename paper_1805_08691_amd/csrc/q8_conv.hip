@@ -221,11 +221,11 @@ int pick_variant_auto(const q8_conv_desc* d, int forced) {
   if (tiles128 <= 64) return d->R * d->S == 1 && nk % 2 == 0 ? 21 : 7;
   if (tiles128 <= 128) return d->R * d->S == 1 ? (nk % 2 == 0 ? 21 : 5) : 9;
   if (nk <= 4) return tiles128 >= 192 ? 8 : 4;
-  // at most a 128 x 128 tile per CU: eight wavefronts on such a tile with a ring of 4, or,
+  // at most two 128 x 128 tiles per CU: eight wavefronts on such a tile with a ring of 4, or,
   // where those tiles would leave a third of the CUs idle (the 17 x 17 maps of an
   // Inception-shaped stack), 128 x 64 tiles with a ring of 4
   if (tiles128 <= 160) return 9;
-  return tiles128 <= 256 ? 11 : 1;
+  return tiles128 <= 512 ? 11 : 1;
 }
 
 }  // namespace
