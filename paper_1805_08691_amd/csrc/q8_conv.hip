@@ -211,14 +211,14 @@ int pick_variant_auto(const q8_conv_desc* d, int forced) {
     if (tiles128 >= 16384) return 3;
     // a long reduction on a small map (a detector's box head): at most a workgroup or two
     // per CU, so the ring has to cover the memory latency by itself
-    if (nk >= 16 && tiles128 <= 512) return tiles128 <= 128 ? 7 : 9;
+    if (nk >= 16 && tiles128 <= 512) return tiles128 <= 128 ? (nk % 2 == 0 ? 21 : 7) : 9;
     return 8;
   }
   if (d->K >= 256 && tiles128 >= 1024 && nk > 4) return 13;
-  // (pointwise layers with at most 128 such tiles: measured inside the network, where their
-  // filters come from HBM in every pass, 64 x 64 tiles with 128 reduction bytes per step beat
-  // the wider tiles that win on a warm cache)
-  if (tiles128 <= 64) return d->R * d->S == 1 && nk % 2 == 0 ? 21 : 7;
+  // (layers with at most 128 such tiles: measured inside the networks, where their filters
+  // come from HBM in every pass, 64 x 64 tiles with 128 reduction bytes per step beat the
+  // 64-byte steps and the wider tiles that win on a warm cache)
+  if (tiles128 <= 64) return nk % 2 == 0 ? 21 : 7;
   if (tiles128 <= 128) return d->R * d->S == 1 ? (nk % 2 == 0 ? 21 : 5) : 9;
   if (nk <= 4) return tiles128 >= 192 ? 8 : 4;
   // at most two 128 x 128 tiles per CU: eight wavefronts on such a tile with a ring of 4, or,
