@@ -141,27 +141,7 @@ int pick_halo3(const q8_conv_desc* d) {
 }
 
 // `forced`: -1, or a variant of the main kernel to use where that kernel is applicable.
-int pick_variant_auto(const q8_conv_desc* d, int forced);
 int pick_variant(const q8_conv_desc* d, int forced = -1) {
-  int v = pick_variant_auto(d, forced);
-  static int remap[256];
-  static const bool init = [&]() {
-    for (int i = 0; i < 256; ++i) remap[i] = i;
-    if (const char* e = getenv("Q8_REMAP")) {
-      int a, b;
-      while (*e && sscanf(e, "%d:%d", &a, &b) == 2) {
-        if (a >= 0 && a < 256) remap[a] = b;
-        while (*e && *e != ',') ++e;
-        if (*e == ',') ++e;
-      }
-    }
-    return true;
-  }();
-  (void)init;
-  if (forced < 0 && v >= 0 && v < 256) v = remap[v];
-  return v;
-}
-int pick_variant_auto(const q8_conv_desc* d, int forced) {
   const int mode = conv_mode(d);
   const int tile = d->K > 64 ? 0 : d->K > 32 ? 1 : 2;      // 128x128, 256x64, 256x32
   if (!stream_capable(d)) return kRegBase + 3 * mode + tile;
