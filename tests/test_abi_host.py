@@ -191,6 +191,45 @@ def _chain_layers(n_img=16, bad=None):
     return arr
 
 
+def test_fused_head_and_dequantized_output_host_checks():
+    """q8_conv_image_f32_supported and the argument checks of q8_conv_image_f32_int8 /
+    q8_conv_int8_dequantized run on the host: nothing is launched here."""
+    L = B.lib
+    fake = C.c_void_p(0x1000)
+    # ResNet-50's first layer over its zero frame, with and without the max-pool
+    d = B.ConvDesc(32, 230, 230, 3, 64, 7, 7, 2, 2, 0, 0, 1, 1, relu=1, in_c_stride=4)
+    assert B.conv_image_f32_supported(d, 224, 224, 3, 3, 3, 0)
+    assert B.conv_image_f32_supported(d, 224, 224, 3, 3, 3, 1)
+    assert not B.conv_image_f32_supported(d, 228, 224, 3, 3, 3, 1)      # does not fit the frame
+    assert not B.conv_image_f32_supported(d, 224, 224, 4, 3, 3, 1)      # C != d.C
+    # outside the family: 3 filter columns; rows of more than 128 output pixels; K > 64;
+    # the pool needs a vertical stride of 2
+    assert not B.conv_image_f32_supported(
+        B.ConvDesc(1, 301, 301, 3, 32, 3, 3, 2, 2, 0, 0, 1, 1, in_c_stride=4), 299, 299, 3, 1, 1, 0)
+    assert not B.conv_image_f32_supported(
+        B.ConvDesc(1, 200, 240, 3, 64, 7, 7, 1, 1, 0, 0, 1, 1, in_c_stride=4), 194, 234, 3, 3, 3, 0)
+    assert not B.conv_image_f32_supported(
+        B.ConvDesc(1, 70, 70, 3, 96, 7, 7, 2, 2, 0, 0, 1, 1, in_c_stride=4), 64, 64, 3, 3, 3, 0)
+    d1 = B.ConvDesc(1, 70, 70, 3, 64, 7, 7, 1, 2, 0, 0, 1, 1, in_c_stride=4)
+    assert B.conv_image_f32_supported(d1, 64, 64, 3, 3, 3, 0)
+    assert not B.conv_image_f32_supported(d1, 64, 64, 3, 3, 3, 1)
+    args = lambda dd, r, H, W, Cc, top, left, q, p, pool, y: L.q8_conv_image_f32_int8(
+        C.byref(dd), r, H, W, Cc, top, left, q, p, fake, None, 0.01, 0.5, pool, y, None)
+    assert args(d, fake, 224, 224, 3, 3, 3, 0.02, 7, 2, fake) == -1       # pool flag
+    assert args(d, fake, 224, 224, 3, 3, 3, 0.02, 8, 1, fake) == -1       # p out of range
+    assert args(d, fake, 230, 224, 3, 3, 3, 0.02, 7, 1, fake) == -1       # image beyond the frame
+    assert args(d, None, 224, 224, 3, 3, 3, 0.02, 7, 1, fake) == -1       # no image
+    assert args(d, C.c_void_p(0x1002), 224, 224, 3, 3, 3, 0.02, 7, 1, fake) == -3   # misaligned
+    assert args(d, fake, 224, 224, 3, 3, 3, -1.0, 7, 1, fake) == -1       # factor
+    d3 = B.ConvDesc(1, 30, 30, 3, 64, 3, 3, 1, 1, 0, 0, 1, 1, in_c_stride=4)
+    assert args(d3, fake, 28, 28, 3, 1, 1, 0.02, 7, 0, fake) == -2        # not in the family
+    dd = B.ConvDesc(2, 7, 7, 512, 2048, 1, 1)
+    deq = lambda r_y: L.q8_conv_int8_dequantized(C.byref(dd), fake, fake, None, 0.02, 0.01, 0.5, None,
+                                                 0.0, fake, r_y, None)
+    assert deq(None) == -1
+    assert deq(C.c_void_p(0x1002)) == -3
+
+
 def test_chain_plan_accepts_a_block_and_sizes_its_workspace():
     arr = _chain_layers()
     n = B.lib.q8_conv_chain_plan_bytes(arr, 3)
