@@ -403,13 +403,17 @@ int launch_stem(ConvParams& p, const StemImage& im, hipStream_t stream) {
       per_cu = 1;
     return per_cu * cus;
   }();
-  // strips per image: about as many workgroups as stay resident, at least four rows each
-  // (POOL: three pooled rows, i.e. seven output rows of which one is computed twice)
-  const int rows = POOL ? im.Hp : p.Ho, least = POOL ? 3 : 4;
-  int strips = (resident + p.N - 1) / p.N;
-  if (strips > (rows + least - 1) / least) strips = (rows + least - 1) / least;
+  // Strips per image: about as many workgroups as HALF the resident slots -- the layer's
+  // other part-batch launch runs beside this one (two pipelines), and a second round of
+  // workgroups costs more than longer strips do (ResNet-50's head at 2 x 32 images: 0.711 ->
+  // 0.700 ms per step with 5 instead of 3 pooled rows per strip) -- between four and six rows
+  // each (POOL: three to six pooled rows, i.e. 7 .. 13 output rows of which one is computed
+  // twice).
+  const int rows = POOL ? im.Hp : p.Ho, least = POOL ? 3 : 4, most = 6;
+  int strips = (resident / 2 + p.N - 1) / p.N;
   if (strips < 1) strips = 1;
-  const int rows_per_strip = (rows + strips - 1) / strips;
+  int rows_per_strip = (rows + strips - 1) / strips;
+  rows_per_strip = rows_per_strip < least ? least : (rows_per_strip > most ? most : rows_per_strip);
   strips = (rows + rows_per_strip - 1) / rows_per_strip;
   p.n_ptiles = strips;
   p.n_ctiles = rows_per_strip;
