@@ -1,6 +1,8 @@
-// The builds of the persistent 3x3 tile family (see q8_conv_p3_kernel.h) and their table.  A
+// The builds of the persistent 3x3 tile family (see q8_conv_p3_kernel.h, q8_conv_p3b_kernel.h)
+// and their table.  A
 // build asked for a layer it cannot take hands the layer to the generic kernel.
 #include "q8_conv_p3_kernel.h"
+#include "q8_conv_p3b_kernel.h"
 
 namespace q8 {
 namespace {
@@ -11,6 +13,11 @@ int launch_p3_or_generic(ConvParams& p, hipStream_t stream) {
   return launch_ring<2, 2, 2, 2, 64, 3, 0>(p, stream);
 }
 
+int launch_p3b_or_generic(ConvParams& p, hipStream_t stream) {
+  if (p3b_applicable(p)) return launch_p3b(p, stream);
+  return launch_ring<2, 2, 2, 2, 64, 3, 0>(p, stream);
+}
+
 struct P3Variant {
   const char* name;
   int (*launch)(ConvParams&, hipStream_t);
@@ -18,6 +25,7 @@ struct P3Variant {
 const P3Variant kP3Variants[] = {
     {"conv_i8_p3_kernel<4>", &launch_p3_or_generic<4>},     // maps up to 63 pixels wide
     {"conv_i8_p3_kernel<6>", &launch_p3_or_generic<6>},     // up to 127
+    {"conv_i8_p3b_kernel", &launch_p3b_or_generic},         // 8 x 16 blocks: maps of any width
 };
 constexpr int kNumP3Variants = sizeof(kP3Variants) / sizeof(kP3Variants[0]);
 

@@ -276,6 +276,8 @@ P3_CASES = [     # 3x3, stride 1, padding 1, C = 64, K <= 64: what the persisten
     dict(N=1, H=3, W=100, C=64, K=64),        # only the wide patch takes it
     dict(N=1, H=1, W=1, C=64, K=16),          # one pixel
     dict(N=2, H=1, W=17, C=64, K=32),         # one row: no tap above or below
+    dict(N=2, H=19, W=301, C=64, K=64),       # a wide map: only the block-tiled build takes it
+    dict(N=3, H=9, W=16, C=64, K=16),         # blocks: a ragged last block row, exact columns
 ]
 
 
@@ -287,8 +289,8 @@ def test_conv_persistent_3x3_family(B, idx):
     geom = dict(R=3, S=3, pad_h=1, pad_w=1, **P3_CASES[idx])
     n = B.conv_num_variants()
     names = [B.lib.q8_conv_variant_name(v).decode() for v in range(n)]
-    p3 = [v for v in range(n) if "p3_kernel" in names[v]]
-    assert len(p3) >= 2
+    p3 = [v for v in range(n) if "p3_kernel" in names[v] or "p3b_kernel" in names[v]]
+    assert len(p3) >= 3
     for k, v in enumerate(p3):
         _run_conv_case(B, geom, relu=bool(k % 2), with_res=False, with_bias=True,
                        seed=5000 * idx + v, variant=v, out_pad=16 * (k % 2), out_off=16 * (k % 2),
